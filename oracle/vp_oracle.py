@@ -1,0 +1,180 @@
+"""ctypes front end of the CPU oracle (``vp_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``, by the smoke check and by the
+benchmark's ``cpu_baseline`` leg, never by the product package.  It shares no
+code with the HIP library and does not import it.
+
+All array arguments are numpy arrays; fp16 data is passed as its raw bits.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "vp_oracle.c")
+_SO = os.path.join(_HERE, "libvp_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile vp_oracle.c with gcc (plain -O2 loops, OpenMP over rows only)."""
+    stale = (not os.path.exists(_SO)) or os.path.getmtime(_SO) < os.path.getmtime(_SRC)
+    if force or stale:
+        tmp = _SO + ".tmp.%d" % os.getpid()
+        subprocess.check_call(
+            ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-o", tmp, _SRC, "-lm"]
+        )
+        os.replace(tmp, _SO)
+    return _SO
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_SO)
+        lib.vpo_half_to_double.restype = ctypes.c_double
+        lib.vpo_half_to_double.argtypes = [ctypes.c_uint16]
+        lib.vpo_log_softmax.restype = ctypes.c_double
+        _lib = lib
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _bits(a) -> np.ndarray:
+    """fp16 array (or raw uint16 bits) -> contiguous uint16 bit patterns."""
+    a = np.asarray(a)
+    if a.dtype == np.float16:
+        a = a.view(np.uint16)
+    if a.dtype != np.uint16:
+        raise TypeError("oracle inputs must be float16 or uint16 bit patterns, got %s" % a.dtype)
+    return np.ascontiguousarray(a)
+
+
+def half_to_double(bits: int) -> float:
+    return float(_load().vpo_half_to_double(ctypes.c_uint16(int(bits))))
+
+
+def cnorm(C) -> np.ndarray:
+    C = _bits(C)
+    K, d = C.shape
+    out = np.empty(K, np.float64)
+    _load().vpo_cnorm(_p(C), ctypes.c_int(K), ctypes.c_int(d), _p(out))
+    return out
+
+
+def assign(H, C, return_scores: bool = False):
+    """Eq. 2: cluster id of every row (and optionally all N*K scores)."""
+    H, C = _bits(H), _bits(C)
+    N, d = H.shape
+    K = C.shape[0]
+    assert C.shape[1] == d
+    cn = cnorm(C)
+    g = np.empty(N, np.int32)
+    scores = np.empty((N, K), np.float64) if return_scores else None
+    _load().vpo_assign(_p(H), ctypes.c_int(N), ctypes.c_int(d), _p(C), ctypes.c_int(K),
+                       _p(cn), _p(g), _p(scores))
+    return (g, scores) if return_scores else g
+
+
+def logits_row(W, b, h, ids=None) -> np.ndarray:
+    """Eq. 1 for one row over the listed token ids (all V when ids is None)."""
+    W, b, h = _bits(W), _bits(b), _bits(h)
+    d, V = W.shape
+    if ids is not None:
+        ids = np.ascontiguousarray(ids, np.int32)
+        n = ids.shape[0]
+    else:
+        n = V
+    z = np.empty(n, np.float64)
+    _load().vpo_logits_row(_p(W), _p(b), ctypes.c_int(d), ctypes.c_int(V), _p(h), _p(ids),
+                           ctypes.c_int(n), _p(z))
+    return z
+
+
+def log_softmax(z):
+    z = np.ascontiguousarray(z, np.float64)
+    logp = np.empty_like(z)
+    lse = _load().vpo_log_softmax(_p(z), ctypes.c_int(z.shape[0]), _p(logp))
+    return logp, float(lse)
+
+
+def topk(z, k: int) -> np.ndarray:
+    z = np.ascontiguousarray(z, np.float64)
+    pos = np.empty(k, np.int32)
+    _load().vpo_topk(_p(z), ctypes.c_int(z.shape[0]), ctypes.c_int(k), _p(pos))
+    return pos
+
+
+def project(W, b, C, cand_off, cand_ids, H, k: int, forced_g=None, want_all: bool = False):
+    """Clustered projection.  Returns a dict with g, ids, logp, z, lse and, if
+    want_all, all_off / all_z (every candidate logit of every row)."""
+    W, b, C, H = _bits(W), _bits(b), _bits(C), _bits(H)
+    d, V = W.shape
+    K = C.shape[0]
+    N = H.shape[0]
+    cand_off = np.ascontiguousarray(cand_off, np.int64)
+    cand_ids = np.ascontiguousarray(cand_ids, np.int32)
+    assert cand_off.shape[0] == K + 1
+    g = np.empty(N, np.int32)
+    ids = np.empty((N, k), np.int32)
+    logp = np.empty((N, k), np.float64)
+    z = np.empty((N, k), np.float64)
+    lse = np.empty(N, np.float64)
+    fg = None if forced_g is None else np.ascontiguousarray(forced_g, np.int32)
+    all_off = all_z = None
+    if want_all:
+        # the row's cluster is needed to size the buffer: run Eq. 2 first
+        g0 = assign(H, C)
+        if fg is not None:
+            g0 = np.where(fg >= 0, fg, g0).astype(np.int32)
+        sizes = (cand_off[1:] - cand_off[:-1])[g0]
+        all_off = np.zeros(N + 1, np.int64)
+        np.cumsum(sizes, out=all_off[1:])
+        all_z = np.empty(int(all_off[-1]), np.float64)
+    _load().vpo_project(_p(W), _p(b), ctypes.c_int(d), ctypes.c_int(V), _p(C), ctypes.c_int(K),
+                        _p(cand_off), _p(cand_ids), _p(H), ctypes.c_int(N), ctypes.c_int(k),
+                        _p(fg), _p(g), _p(ids), _p(logp), _p(z), _p(lse), _p(all_off), _p(all_z))
+    out = dict(g=g, ids=ids, logp=logp, z=z, lse=lse)
+    if want_all:
+        out["all_off"] = all_off
+        out["all_z"] = all_z
+    return out
+
+
+def project_full(W, b, H, k: int, want_all: bool = False):
+    """Full-vocabulary projection, log-softmax over V and top-k."""
+    W, b, H = _bits(W), _bits(b), _bits(H)
+    d, V = W.shape
+    N = H.shape[0]
+    ids = np.empty((N, k), np.int32)
+    logp = np.empty((N, k), np.float64)
+    z = np.empty((N, k), np.float64)
+    lse = np.empty(N, np.float64)
+    all_z = np.empty((N, V), np.float64) if want_all else None
+    _load().vpo_project_full(_p(W), _p(b), ctypes.c_int(d), ctypes.c_int(V), _p(H),
+                             ctypes.c_int(N), ctypes.c_int(k), _p(ids), _p(logp), _p(z), _p(lse),
+                             _p(all_z))
+    out = dict(ids=ids, logp=logp, z=z, lse=lse)
+    if want_all:
+        out["all_z"] = all_z
+    return out
+
+
+def logit_points(W, b, H, rows, toks) -> np.ndarray:
+    """Eq. 1 for single (row, token) pairs."""
+    W, b, H = _bits(W), _bits(b), _bits(H)
+    d, V = W.shape
+    rows = np.ascontiguousarray(rows, np.int32)
+    toks = np.ascontiguousarray(toks, np.int32)
+    z = np.empty(rows.shape[0], np.float64)
+    _load().vpo_logit_points(_p(W), _p(b), ctypes.c_int(d), ctypes.c_int(V), _p(H), _p(rows),
+                             _p(toks), ctypes.c_int(rows.shape[0]), _p(z))
+    return z
