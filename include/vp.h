@@ -1,0 +1,153 @@
+/*
+ * vp.h - C ABI of the clustered vocabulary projection library for MI355X
+ * (gfx950), after "Fast Vocabulary Projection Method via Clustering for
+ * Multilingual Machine Translation on GPU" (arxiv 2208.06874).
+ *
+ * At each decode step a hidden row h picks its nearest k-means centroid
+ * (section 2.3, Eq. 2), is projected only onto that cluster's active-token
+ * columns of the output embedding (Eq. 1 of section 2.1 restricted as in step
+ * 3 of the inference list of section 2.3), and a log-softmax over those
+ * candidates (steps 4-5: excluded tokens are at -infinity) plus a descending
+ * top-k (section 2.1) are returned.  Unlike the paper's own GPU design, which
+ * unions the active sets of a batch and runs one gathered GEMM, rows are
+ * bucketed by cluster and each bucket streams its cluster's pre-packed slab.
+ *
+ * Conventions
+ *  - "device" pointers are HIP device memory of the current device, "host"
+ *    pointers ordinary memory.  The caller owns every device byte: the arena
+ *    that holds the packed index and the per-call workspace.  The library
+ *    allocates no device memory.
+ *  - hip_stream is a hipStream_t passed as void* (NULL = the null stream).
+ *  - vp_project* only enqueue kernels: no host synchronisation, no device to
+ *    host copy, no allocation.  Argument errors are found on the host before
+ *    anything is launched and leave the outputs untouched.
+ *  - All calls return a vp_status; vp_last_error() gives the message of the
+ *    calling thread's last failure.
+ *  - Results are deterministic: equal inputs give bit-identical outputs.
+ *  - fp16 inputs, fp32 accumulation; logits are never rounded to fp16.
+ */
+#ifndef VP_H
+#define VP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct vp_index vp_index; /* opaque host-side handle */
+
+typedef enum {
+    VP_OK = 0,
+    VP_ERR_INVALID_ARG = 1, /* null/misaligned pointer, bad id list, size out of range */
+    VP_ERR_UNSUPPORTED = 2, /* a shape the kernels do not handle (see limits below)    */
+    VP_ERR_WORKSPACE = 3,   /* arena / workspace / output capacity too small           */
+    VP_ERR_HIP = 4          /* a HIP runtime call or kernel launch failed               */
+} vp_status;
+
+/* Limits: d % 8 == 0, 8 <= d <= 4096; 1 <= K <= 4096; 1 <= V < 2^31 - 16;
+ * 1 <= k <= k_max <= 32; every active set non-empty; N <= 65536 per call. */
+#define VP_MAX_TOPK 32
+#define VP_MAX_CLUSTERS 4096
+#define VP_MAX_ROWS 65536
+#define VP_MAX_DIM 4096
+
+typedef struct {
+    int32_t d;             /* embedding dimension                                        */
+    int32_t V;             /* vocabulary size                                            */
+    int32_t K;             /* number of clusters (the paper's r)                         */
+    const void *W;         /* device, fp16, W[d, V] row-major as in section 2.1          */
+    const void *bias;      /* device, fp16, b[V]                                         */
+    const void *centroids; /* device, fp16, C[K, d] row-major                            */
+    const int64_t *cand_offsets; /* host, [K+1], cand_offsets[0] = 0, increasing         */
+    const int32_t *cand_ids;     /* host, active sets A_j (section 2.2) back to back;
+                                    each strictly ascending, ids in [0, V)               */
+    void *arena;           /* device, 256-byte aligned, >= vp_build_bytes()              */
+    size_t arena_bytes;
+    int32_t k_max;         /* largest top-k that will be requested                       */
+    uint32_t flags;        /* must be 0                                                  */
+} vp_build_desc;
+
+typedef struct {
+    int32_t d, V, K, k_max;
+    int32_t d_pad;            /* d rounded up to the packed k-extent                    */
+    int32_t n_min, n_max;     /* smallest / largest active set                          */
+    int64_t n_total;          /* sum of active-set sizes                                */
+    int64_t slab_bytes;       /* packed per-cluster slabs                               */
+    int64_t full_bytes;       /* packed copy of the whole W                             */
+    int64_t arena_bytes_used;
+} vp_index_info;
+
+/* Bytes of arena vp_build needs for this description (device pointers are not
+ * read).  Returns 0 and sets the error message if the description is invalid. */
+size_t vp_build_bytes(const vp_build_desc *desc);
+
+/* Packs the index into the arena: ||C_j||^2 per centroid (the precomputed term
+ * of Eq. 2), centroids and W re-tiled for the matrix cores, and per cluster a
+ * slab with its active tokens' columns, their bias and their ids.  W, bias and
+ * centroids are only read during this call (the index keeps its own copies);
+ * the arena must outlive the index.  Synchronises the stream before returning.
+ * Unsorted, duplicate or out-of-range ids: VP_ERR_INVALID_ARG.  Empty active
+ * set, d % 8 != 0, limits exceeded: VP_ERR_UNSUPPORTED. */
+vp_status vp_build(const vp_build_desc *desc, void *hip_stream, vp_index **out);
+
+vp_status vp_get_info(const vp_index *idx, vp_index_info *info);
+
+/* Tuning knobs (host side, take effect on the next call):
+ *   "target_items"  work items the projection is split into (default 8192)
+ *   "rstar"         buckets with at most this many rows use the dot-product
+ *                   GEMV loop, larger ones the MFMA loop (default 0, max 4)
+ *   "full_target_items"  same as target_items for vp_project_full
+ * Unknown name or out-of-range value: VP_ERR_INVALID_ARG. */
+vp_status vp_set_option(vp_index *idx, const char *name, int64_t value);
+
+/* Workspace bytes vp_project / vp_project_full / vp_project_debug_logits need
+ * for up to N_max rows with the current options.  0 on error. */
+size_t vp_workspace_bytes(const vp_index *idx, int32_t N_max);
+
+/* Clustered projection of N hidden rows.
+ *   hidden       device, fp16 [N, d] row-major, 16-byte aligned
+ *   out_ids      device, int32 [N, k]: token ids by (logit descending, token id
+ *                ascending); -1 where the row's active set has fewer than k tokens
+ *   out_logp     device, fp32 [N, k]: logit minus log-sum-exp over the row's
+ *                active set; -inf in padded slots
+ *   out_cluster  device, int32 [N] or NULL: Eq. 2 cluster of each row (ties to
+ *                the lowest index)
+ *   workspace    device, 256-byte aligned, >= vp_workspace_bytes(idx, N)
+ * N == 0 is a no-op returning VP_OK.  Calls that share a workspace must be
+ * ordered on one stream. */
+vp_status vp_project(const vp_index *idx, const void *hidden, int32_t N, int32_t k,
+                     int32_t *out_ids, float *out_logp, int32_t *out_cluster,
+                     void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* The default projection of section 2.1 over all V tokens (log-softmax over V,
+ * top-k), same output contract; the baseline the speed-up is quoted against. */
+vp_status vp_project_full(const vp_index *idx, const void *hidden, int32_t N, int32_t k,
+                          int32_t *out_ids, float *out_logp,
+                          void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Parity/debug entry, not part of the timed path: every candidate logit.
+ *   full == 0: row r's logits over its cluster's active set, in list order, at
+ *              out_logits[out_row_offsets[r] .. out_row_offsets[r+1]);
+ *              out_cluster (required) receives the clusters.
+ *   full != 0: all V logits of row r at out_logits[r * V ..]; out_cluster may be
+ *              NULL; out_row_offsets[r] = r * V.
+ *   out_row_offsets  device, int64 [N+1]
+ *   out_logits       device, fp32, capacity in elements must be >= N * n_max
+ *                    (full == 0) or N * V (full != 0), else VP_ERR_WORKSPACE. */
+vp_status vp_project_debug_logits(const vp_index *idx, const void *hidden, int32_t N, int32_t full,
+                                  int32_t *out_cluster, int64_t *out_row_offsets,
+                                  float *out_logits, size_t out_logits_capacity,
+                                  void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Frees the host handle only; the arena stays the caller's. */
+void vp_destroy(vp_index *idx);
+
+/* Message of the calling thread's last non-OK status ("" if none). */
+const char *vp_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VP_H */

@@ -1,0 +1,92 @@
+// Centroid selection, Eq. 2 of section 2.3:
+//     g[r] = argmin_j ( ||C_j||^2 - 2 <h_r, C_j> ),  ties to the lowest j,
+// with ||C_j||^2 precomputed at build time.  The inner products of 16 rows
+// with 16 centroids are one v_mfma_f32_16x16x32_f16 per 32 k-values; every
+// lane then holds 4 scores of one row, keeps a running (min, argmin) and the
+// four lane groups of the wavefront are reduced with cross-lane shuffles.
+// The centroids are split into `parts` ranges handled by different
+// wavefronts so that small batches still fill the chip; the planning kernel
+// reduces the per-part minima.
+#include <hip/hip_runtime.h>
+#include "vp_kernels.h"
+
+namespace {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+union Frag {
+    uint4 u;
+    half8 h;
+};
+
+__device__ inline bool score_less(float s, int j, float s2, int j2)
+{
+    return s < s2 || (s == s2 && j < j2);
+}
+
+__global__ __launch_bounds__(256) void centroid_kernel(
+    const uint4 *__restrict__ hidden, int N, int d, const uint4 *__restrict__ cp,
+    const float *__restrict__ cnorm, int K, int kt_count, int ctiles, int tiles_per_part, int parts,
+    int2 *__restrict__ cpart)
+{
+    const int wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int n = lane & 15;
+    const int q = lane >> 4;
+    const int part = blockIdx.y * 4 + wave;
+    if (part >= parts) return;
+    const int row = blockIdx.x * 16 + n;
+    const bool valid_row = row < N;
+    const int t0 = part * tiles_per_part;
+    const int t1 = min(t0 + tiles_per_part, ctiles);
+    const int pieces_per_row = d >> 3;   // 16-byte pieces
+    const uint4 *hrow = hidden + (size_t)(valid_row ? row : 0) * pieces_per_row;
+
+    float best_s = __builtin_inff();
+    int best_j = VP_IDX_NONE;
+    for (int t = t0; t < t1; ++t) {
+        floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+        const uint4 *ap = cp + (size_t)t * kt_count * 64 + lane;
+#pragma unroll 8
+        for (int kt = 0; kt < kt_count; ++kt) {
+            Frag a, b;
+            a.u = ap[(size_t)kt * 64];
+            const int piece = kt * 4 + q;
+            b.u = make_uint4(0, 0, 0, 0);
+            if (valid_row && piece < pieces_per_row) b.u = hrow[piece];
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a.h, b.h, acc, 0, 0, 0);
+        }
+        const float4 cn = *reinterpret_cast<const float4 *>(cnorm + t * 16 + q * 4);
+        const float cnv[4] = {cn.x, cn.y, cn.z, cn.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int j = t * 16 + q * 4 + i;
+            const float s = cnv[i] - 2.0f * acc[i];
+            if (j < K && s < best_s) {   // j ascends within a lane: strict < keeps the lowest
+                best_s = s;
+                best_j = j;
+            }
+        }
+    }
+#pragma unroll
+    for (int off = 16; off <= 32; off <<= 1) {
+        const float s2 = __shfl_xor(best_s, off);
+        const int j2 = __shfl_xor(best_j, off);
+        if (score_less(s2, j2, best_s, best_j)) {
+            best_s = s2;
+            best_j = j2;
+        }
+    }
+    if (q == 0 && valid_row) cpart[(size_t)row * parts + part] = make_int2(__float_as_int(best_s), best_j);
+}
+
+}  // namespace
+
+void vpk_centroid(const void *hidden, int N, int d, const void *cp, const float *cnorm, int K, int kt,
+                  int ctiles, int tiles_per_part, int parts, void *cpart, hipStream_t st)
+{
+    dim3 grid((N + 15) / 16, (parts + 3) / 4);
+    hipLaunchKernelGGL(centroid_kernel, grid, dim3(256), 0, st, (const uint4 *)hidden, N, d, (const uint4 *)cp,
+                       cnorm, K, kt, ctiles, tiles_per_part, parts, (int2 *)cpart);
+}

@@ -1,0 +1,265 @@
+// Row bucketing by cluster and work planning (one workgroup, all in LDS).
+//
+// The paper unions the active sets of a batch (section 2.3); here each row is
+// instead projected against its own cluster's slab, so rows are first grouped
+// by cluster: histogram of the cluster ids -> exclusive prefix scan -> scatter
+// of the row numbers into bucket order.  The same kernel finishes Eq. 2 (it
+// reduces the per-part minima of the centroid kernel) and cuts the projection
+// work into items of equal slab bytes: (bucket, group of up to 16 rows, range
+// of candidate tiles).  The number of tiles per item adapts to the total work
+// so that any batch, from one row to thousands, yields about `target_items`
+// items.  The order of rows inside a bucket is the order in which the LDS
+// atomics happen to be served; each row's result is independent of its slot.
+#include <hip/hip_runtime.h>
+#include "vp_kernels.h"
+
+namespace {
+
+constexpr int PLAN_THREADS = 1024;
+
+// Exclusive prefix sum over the workgroup; returns this thread's prefix and the
+// total to everyone.  wsum: LDS scratch of PLAN_THREADS / 64 + 1 elements.
+template <typename T>
+__device__ T block_exscan(T v, T *total, T *wsum)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    T inc = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        T up = __shfl_up(inc, off);
+        if (lane >= off) inc += up;
+    }
+    __syncthreads();   // wsum may still be read from a previous call
+    if (lane == 63) wsum[wave] = inc;
+    __syncthreads();
+    if (wave == 0) {
+        const int nw = blockDim.x >> 6;
+        T w = lane < nw ? wsum[lane] : T(0);
+        T winc = w;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            T up = __shfl_up(winc, off);
+            if (lane >= off) winc += up;
+        }
+        if (lane < nw) wsum[lane] = winc - w;
+        if (lane == nw - 1) wsum[nw] = winc;
+    }
+    __syncthreads();
+    *total = wsum[blockDim.x >> 6];
+    return wsum[wave] + inc - v;
+}
+
+__device__ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+__global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(
+    const int2 *__restrict__ cpart, int parts, int N, int K, const int32_t *__restrict__ n_cand,
+    const int32_t *__restrict__ tile_off, int target_items, int max_items, int32_t *__restrict__ g,
+    int32_t *__restrict__ out_cluster, int32_t *__restrict__ perm, int32_t *__restrict__ row_item0,
+    int32_t *__restrict__ row_stride, int32_t *__restrict__ row_nit, VpItem *__restrict__ items,
+    VpPlanHeader *__restrict__ hdr, int64_t *__restrict__ dbg_row_off)
+{
+    extern __shared__ int lds[];
+    int *cnt = lds;             // [K]   rows per cluster, later the scatter cursor
+    int *off = cnt + K;         // [K+1] first perm position of each bucket
+    int *ioff = off + K + 1;    // [K+1] first item of each bucket
+    __shared__ int wsum[PLAN_THREADS / 64 + 1];
+    __shared__ long long wsum64[PLAN_THREADS / 64 + 1];
+    const int tid = threadIdx.x;
+
+    for (int j = tid; j < K; j += PLAN_THREADS) cnt[j] = 0;
+    __syncthreads();
+
+    // finish Eq. 2: minimum over the centroid parts, ties to the lowest index
+    for (int r = tid; r < N; r += PLAN_THREADS) {
+        float bs = __builtin_inff();
+        int bj = VP_IDX_NONE;
+        for (int p = 0; p < parts; ++p) {
+            const int2 e = cpart[(size_t)r * parts + p];
+            const float s = __int_as_float(e.x);
+            if (s < bs || (s == bs && e.y < bj)) {
+                bs = s;
+                bj = e.y;
+            }
+        }
+        if (bj < 0 || bj >= K) bj = 0;   // non-finite scores: keep every index in range
+        g[r] = bj;
+        if (out_cluster) out_cluster[r] = bj;
+        atomicAdd(&cnt[bj], 1);
+    }
+    __syncthreads();
+
+    // exclusive scan of the histogram -> bucket offsets; total candidate tiles of all row groups
+    int carry = 0;
+    int my_tiles = 0;
+    for (int base = 0; base < K; base += PLAN_THREADS) {
+        const int j = base + tid;
+        const int c = j < K ? cnt[j] : 0;
+        int tot;
+        const int ex = block_exscan<int>(c, &tot, wsum);
+        if (j < K) {
+            off[j] = carry + ex;
+            my_tiles += ceil_div(c, VP_ROWS_PER_ITEM) * (tile_off[j + 1] - tile_off[j]);
+        }
+        carry += tot;
+    }
+    if (tid == 0) off[K] = carry;
+    int total_tiles;
+    block_exscan<int>(my_tiles, &total_tiles, wsum);
+    const int tpw = max(1, ceil_div(total_tiles, VP_WG_WAVES * max(1, target_items)));
+    const int tpi = tpw * VP_WG_WAVES;
+
+    // items per bucket -> item offsets
+    carry = 0;
+    for (int base = 0; base < K; base += PLAN_THREADS) {
+        const int j = base + tid;
+        int c = 0;
+        if (j < K) c = ceil_div(cnt[j], VP_ROWS_PER_ITEM) * ceil_div(tile_off[j + 1] - tile_off[j], tpi);
+        int tot;
+        const int ex = block_exscan<int>(c, &tot, wsum);
+        if (j < K) ioff[j] = carry + ex;
+        carry += tot;
+    }
+    if (tid == 0) ioff[K] = carry;
+    __syncthreads();
+    const int total_items = min(ioff[K], max_items);
+
+    // scatter rows into bucket order (cnt becomes the per-bucket cursor)
+    for (int j = tid; j < K; j += PLAN_THREADS) cnt[j] = 0;
+    __syncthreads();
+    for (int r = tid; r < N; r += PLAN_THREADS) {
+        const int j = g[r];
+        const int pos = atomicAdd(&cnt[j], 1);
+        perm[off[j] + pos] = r;
+    }
+    __syncthreads();
+
+    // where the merge kernel finds the partial results of each row
+    for (int p = tid; p < N; p += PLAN_THREADS) {
+        const int j = g[perm[p]];
+        const int rgs = ceil_div(off[j + 1] - off[j], VP_ROWS_PER_ITEM);
+        row_item0[p] = ioff[j] + (p - off[j]) / VP_ROWS_PER_ITEM;
+        row_stride[p] = rgs;
+        row_nit[p] = ceil_div(tile_off[j + 1] - tile_off[j], tpi);
+    }
+
+    // the items: for each bucket, candidate ranges outermost and row groups
+    // innermost, so items that re-read the same tiles sit next to each other
+    for (int it = tid; it < total_items; it += PLAN_THREADS) {
+        int lo = 0, hi = K;   // largest j with ioff[j] <= it (empty buckets have empty ranges)
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (ioff[mid] <= it) lo = mid; else hi = mid;
+        }
+        const int j = lo;
+        const int rows = off[j + 1] - off[j];
+        const int rgs = ceil_div(rows, VP_ROWS_PER_ITEM);
+        const int local = it - ioff[j];
+        const int ch = local / rgs;
+        const int rg = local - ch * rgs;
+        const int tiles = tile_off[j + 1] - tile_off[j];
+        VpItem v;
+        v.cluster = j;
+        v.perm_start = off[j] + rg * VP_ROWS_PER_ITEM;
+        v.nrows = min(VP_ROWS_PER_ITEM, rows - rg * VP_ROWS_PER_ITEM);
+        v.tile0 = ch * tpi;
+        v.ntiles = min(tpi, tiles - ch * tpi);
+        v.pad[0] = v.pad[1] = v.pad[2] = 0;
+        items[it] = v;
+    }
+    if (tid == 0) {
+        hdr->total_items = total_items;
+        hdr->tiles_per_wave = tpw;
+        hdr->overflow = ioff[K] > max_items;
+        hdr->total_tiles = total_tiles;
+    }
+
+    // debug entry only: where each row's candidate logits start
+    if (dbg_row_off) {
+        long long carry64 = 0;
+        for (int base = 0; base < N; base += PLAN_THREADS) {
+            const int r = base + tid;
+            const long long c = r < N ? (long long)n_cand[g[r]] : 0;
+            long long tot;
+            const long long ex = block_exscan<long long>(c, &tot, wsum64);
+            if (r < N) dbg_row_off[r] = carry64 + ex;
+            carry64 += tot;
+        }
+        if (tid == 0) dbg_row_off[N] = carry64;
+    }
+}
+
+// Plan of the full-vocabulary projection: one bucket holding every row in
+// order, one slab holding every token.  Nothing depends on device data.
+__global__ __launch_bounds__(256) void plan_full_kernel(
+    int N, int V, int vtiles, int target_items, int max_items, int32_t *__restrict__ perm,
+    int32_t *__restrict__ row_item0, int32_t *__restrict__ row_stride, int32_t *__restrict__ row_nit,
+    VpItem *__restrict__ items, VpPlanHeader *__restrict__ hdr, int64_t *__restrict__ dbg_row_off)
+{
+    const int rgs = ceil_div(N, VP_ROWS_PER_ITEM);
+    const long long total_tiles = (long long)rgs * vtiles;
+    const int tpw = (int)max(1LL, (total_tiles + (long long)VP_WG_WAVES * target_items - 1) /
+                                      ((long long)VP_WG_WAVES * target_items));
+    const int tpi = tpw * VP_WG_WAVES;
+    const int chunks = ceil_div(vtiles, tpi);
+    const int total_items = min(chunks * rgs, max_items);
+    const int gtid = blockIdx.x * blockDim.x + threadIdx.x;
+    const int gsize = gridDim.x * blockDim.x;
+    for (int p = gtid; p < N; p += gsize) {
+        perm[p] = p;
+        row_item0[p] = p / VP_ROWS_PER_ITEM;
+        row_stride[p] = rgs;
+        row_nit[p] = chunks;
+        if (dbg_row_off) dbg_row_off[p] = (int64_t)p * V;
+    }
+    for (int it = gtid; it < total_items; it += gsize) {
+        const int ch = it / rgs;
+        const int rg = it - ch * rgs;
+        VpItem v;
+        v.cluster = 0;
+        v.perm_start = rg * VP_ROWS_PER_ITEM;
+        v.nrows = min(VP_ROWS_PER_ITEM, N - rg * VP_ROWS_PER_ITEM);
+        v.tile0 = ch * tpi;
+        v.ntiles = min(tpi, vtiles - ch * tpi);
+        v.pad[0] = v.pad[1] = v.pad[2] = 0;
+        items[it] = v;
+    }
+    if (gtid == 0) {
+        hdr->total_items = total_items;
+        hdr->tiles_per_wave = tpw;
+        hdr->overflow = chunks * rgs > max_items;
+        hdr->total_tiles = (int)min(total_tiles, 2147483647LL);
+        if (dbg_row_off) dbg_row_off[N] = (int64_t)N * V;
+    }
+}
+
+}  // namespace
+
+size_t vpk_plan_lds_bytes(int K) { return (size_t)(3 * K + 2) * sizeof(int); }
+
+hipError_t vpk_plan_prepare()
+{
+    // clusters up to VP_MAX_CLUSTERS need 48 KiB of dynamic LDS; allow it explicitly
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(plan_kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024);
+}
+
+void vpk_plan(const void *cpart, int parts, int N, int K, const int32_t *n_cand, const int32_t *tile_off,
+              int target_items, int max_items, int32_t *g, int32_t *out_cluster, int32_t *perm,
+              int32_t *row_item0, int32_t *row_stride, int32_t *row_nit, VpItem *items, VpPlanHeader *hdr,
+              int64_t *dbg_row_off, hipStream_t st)
+{
+    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(PLAN_THREADS), vpk_plan_lds_bytes(K), st, (const int2 *)cpart,
+                       parts, N, K, n_cand, tile_off, target_items, max_items, g, out_cluster, perm, row_item0,
+                       row_stride, row_nit, items, hdr, dbg_row_off);
+}
+
+void vpk_plan_full(int N, int V, int vtiles, int target_items, int max_items, int32_t *perm, int32_t *row_item0,
+                   int32_t *row_stride, int32_t *row_nit, VpItem *items, VpPlanHeader *hdr,
+                   int64_t *dbg_row_off, hipStream_t st)
+{
+    const int work = max(N, max_items);
+    const int blocks = min(64, (work + 255) / 256);
+    hipLaunchKernelGGL(plan_full_kernel, dim3(blocks), dim3(256), 0, st, N, V, vtiles, target_items, max_items,
+                       perm, row_item0, row_stride, row_nit, items, hdr, dbg_row_off);
+}

@@ -1,0 +1,326 @@
+// Gathered per-cluster projection with the fused candidate log-softmax / top-k.
+//
+// For each work item (up to 16 rows of one bucket x a range of candidate tiles
+// of that bucket's slab) this computes Eq. 1 of section 2.1 restricted to the
+// cluster's active tokens (step 3 of the inference list in section 2.3),
+//     z[r, c] = sum_i h[r, i] * S_j[c, i] + b_j[c],
+// and folds the logits straight into the pieces of steps 4-5 (softmax over the
+// listed tokens only; the rest are at -infinity) and of the descending sort of
+// section 2.1: a running maximum, a running sum of exponentials and the k best
+// (logit, candidate position) pairs.  Logits never leave the registers.
+//
+// Each of the 4 wavefronts streams its own contiguous run of packed tiles
+// (vp_layout.h) with 1 KiB loads, 8 loads in flight.  Two inner loops share
+// everything else:
+//   MFMA: v_mfma_f32_16x16x32_f16 with the slab tile as the A operand and the
+//         16 hidden rows (staged once in LDS, in operand order) as B.  Lane l
+//         then owns row l % 16 and candidates 4 * (l / 16) .. + 3 of the tile.
+//   GEMV: buckets of at most `rstar` (<= 4) rows: v_dot2_f32_f16 against the
+//         rows held row-major in LDS, partial sums of the four k-slices added
+//         with cross-lane shuffles.
+// Both stream the slab exactly once at full load width; which is faster for a
+// given bucket size is a measured choice.
+#include <hip/hip_runtime.h>
+#include "vp_kernels.h"
+
+namespace {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+union Frag {
+    uint4 u;
+    half8 h;
+    half2v p[4];
+};
+
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr int PF = 8;   // tile loads in flight per wavefront
+
+__device__ inline float fast_exp(float x) { return __builtin_amdgcn_exp2f(x * LOG2E); }
+
+// Per-lane running state of one row over the candidates this lane has seen.
+struct RowState {
+    float m;     // running maximum of the logits
+    float s;     // sum of exp(z - m)
+    float thr;   // logit of the lane's current k-th best (+inf: lane inactive)
+};
+
+// Lane-private sorted list of the k best (logit, position) pairs, kept in LDS
+// as [slot][lane] so that the 64 lanes of a wavefront hit 64 different banks.
+struct LaneList {
+    float *val;
+    int *idx;
+    __device__ inline float &v(int slot) { return val[slot * 64]; }
+    __device__ inline int &i(int slot) { return idx[slot * 64]; }
+};
+
+// Folds the four logits a lane holds for its row into the running state.
+// z[i] belongs to candidate position c0 + i; positions ascend call after call,
+// so on equal logits the entry already listed (smaller position = smaller
+// token id) stays ahead.
+__device__ inline void fold_logits(const float z[4], int c0, int k, RowState &st, LaneList list)
+{
+    const float tmax = fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3]));
+    const float mn = fmaxf(st.m, tmax);
+    st.s = st.s * fast_exp(st.m - mn) + fast_exp(z[0] - mn) + fast_exp(z[1] - mn) + fast_exp(z[2] - mn) +
+           fast_exp(z[3] - mn);
+    st.m = mn;
+    if (tmax > st.thr) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float v = z[i];
+            if (v > st.thr) {
+                int p = k - 1;
+                while (p > 0 && list.v(p - 1) < v) {
+                    list.v(p) = list.v(p - 1);
+                    list.i(p) = list.i(p - 1);
+                    --p;
+                }
+                list.v(p) = v;
+                list.i(p) = c0 + i;
+                st.thr = list.v(k - 1);
+            }
+        }
+    }
+}
+
+// (logit descending, position ascending) order used by every merge level.
+__device__ inline bool entry_before(float v, int i, float v2, int i2) { return v > v2 || (v == v2 && i < i2); }
+
+__global__ __launch_bounds__(VP_WG_THREADS) void project_kernel(
+    VpSlabSet set, const uint4 *__restrict__ hidden, int d, const int32_t *__restrict__ perm,
+    const VpItem *__restrict__ items, const VpPlanHeader *__restrict__ hdr, int k, int rstar,
+    float *__restrict__ partials, float *__restrict__ dbg_logits, const int64_t *__restrict__ dbg_row_off)
+{
+    const int it = blockIdx.x;
+    if (it >= hdr->total_items) return;
+    const VpItem item = items[it];
+    const int tpw = hdr->tiles_per_wave;
+    const int KT = set.kt;
+    const int X = KT * 4;                       // 16-byte pieces per padded row
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6;
+    const int lane = tid & 63;
+    const int n = lane & 15;                    // row slot this lane owns in the epilogue
+    const int q = lane >> 4;
+    const bool gemv = item.nrows <= rstar;
+
+    extern __shared__ uint4 lds[];
+    uint4 *ldsA = lds;                                                  // KT KiB: the hidden rows
+    float *list_val = reinterpret_cast<float *>(lds + (size_t)KT * 64);  // [4 waves][k][64]
+    int *list_idx = reinterpret_cast<int *>(list_val + VP_WG_WAVES * k * 64);
+    float *hdr_m = reinterpret_cast<float *>(list_idx + VP_WG_WAVES * k * 64);   // [4][16]
+    float *hdr_s = hdr_m + VP_WG_WAVES * 16;
+    int *rowid = reinterpret_cast<int *>(hdr_s + VP_WG_WAVES * 16);             // [16]
+
+    if (tid < VP_ROWS_PER_ITEM) rowid[tid] = tid < item.nrows ? perm[item.perm_start + tid] : -1;
+    for (int e = tid; e < VP_WG_WAVES * k * 64; e += VP_WG_THREADS) {
+        list_val[e] = -__builtin_inff();
+        list_idx[e] = VP_IDX_NONE;
+    }
+    __syncthreads();
+
+    // stage the hidden rows: MFMA operand order, or row-major for the GEMV loop
+    {
+        const int pieces_per_row = d >> 3;
+        const int rows_to_stage = gemv ? item.nrows : VP_ROWS_PER_ITEM;
+        for (int e = tid; e < rows_to_stage * X; e += VP_WG_THREADS) {
+            const int r = e / X;
+            const int x = e - r * X;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            const int row = rowid[r];
+            if (row >= 0 && x < pieces_per_row) v = hidden[(size_t)row * pieces_per_row + x];
+            if (gemv) ldsA[r * X + x] = v;
+            else ldsA[(x >> 2) * 64 + (x & 3) * 16 + r] = v;
+        }
+    }
+    __syncthreads();
+
+    const int ncand = set.n_cand[item.cluster];
+    const int toff = set.tile_off[item.cluster];
+    const uint4 *slab = reinterpret_cast<const uint4 *>(set.tiles) + (size_t)toff * KT * 64;
+    const float *bias = set.bias + (size_t)toff * VP_TILE_ITEMS;
+
+    const int tb = item.tile0 + wave * tpw;
+    const int te = min(tb + tpw, item.tile0 + item.ntiles);
+    const bool row_valid = n < item.nrows;
+    RowState st;
+    st.m = VP_NEG_BIG;
+    st.s = 0.f;
+    st.thr = row_valid ? -__builtin_inff() : __builtin_inff();
+    LaneList list;
+    list.val = list_val + wave * k * 64 + lane;
+    list.idx = list_idx + wave * k * 64 + lane;
+    const int64_t dbg_base = (dbg_logits && row_valid) ? dbg_row_off[rowid[n]] : 0;
+
+    if (tb < te) {
+        const uint4 *sp = slab + (size_t)tb * KT * 64 + lane;
+        const int S = (te - tb) * KT;   // 1 KiB steps; KT % 8 == 0
+        uint4 buf[PF];
+#pragma unroll
+        for (int u = 0; u < PF; ++u) buf[u] = sp[(size_t)u * 64];
+        int kt = 0;
+        int tile = tb;
+        float4 bcur = *reinterpret_cast<const float4 *>(bias + tile * VP_TILE_ITEMS + q * 4);
+        floatx4 acc = {0.f, 0.f, 0.f, 0.f};        // MFMA: 4 candidates of row n
+        float ga[VP_GEMV_MAX_ROWS] = {0.f, 0.f, 0.f, 0.f};   // GEMV: candidate n, k-slice q, rows 0..3
+
+        for (int s0 = 0; s0 < S; s0 += PF) {
+#pragma unroll
+            for (int u = 0; u < PF; ++u) {
+                Frag a;
+                a.u = buf[u];
+                const int nx = s0 + PF + u;
+                if (nx < S) buf[u] = sp[(size_t)nx * 64];
+                if (!gemv) {
+                    Frag b;
+                    b.u = ldsA[(kt + u) * 64 + lane];
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a.h, b.h, acc, 0, 0, 0);
+                } else {
+#pragma unroll
+                    for (int r = 0; r < VP_GEMV_MAX_ROWS; ++r) {
+                        if (r < item.nrows) {
+                            Frag b;
+                            b.u = ldsA[r * X + (kt + u) * 4 + q];
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) ga[r] = __builtin_amdgcn_fdot2(a.p[e], b.p[e], ga[r], false);
+                        }
+                    }
+                }
+            }
+            kt += PF;
+            if (kt == KT) {
+                // a group of 16 candidates is complete for all rows
+                float z[4];
+                if (!gemv) {
+                    z[0] = acc[0]; z[1] = acc[1]; z[2] = acc[2]; z[3] = acc[3];
+                    acc = floatx4{0.f, 0.f, 0.f, 0.f};
+                } else {
+                    float full[VP_GEMV_MAX_ROWS];
+#pragma unroll
+                    for (int r = 0; r < VP_GEMV_MAX_ROWS; ++r) {
+                        float t = ga[r];
+                        t += __shfl_xor(t, 16);
+                        t += __shfl_xor(t, 32);
+                        full[r] = t;     // every lane with the same (lane & 15) holds candidate (lane & 15) of row r
+                        ga[r] = 0.f;
+                    }
+                    // hand lane (n, q) the logits of row n for candidates 4q .. 4q+3
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int src = q * 4 + i;
+                        const float t0 = __shfl(full[0], src);
+                        const float t1 = __shfl(full[1], src);
+                        const float t2 = __shfl(full[2], src);
+                        const float t3 = __shfl(full[3], src);
+                        z[i] = n == 0 ? t0 : n == 1 ? t1 : n == 2 ? t2 : t3;
+                    }
+                }
+                const int c0 = tile * VP_TILE_ITEMS + q * 4;
+                const float bz[4] = {bcur.x, bcur.y, bcur.z, bcur.w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) z[i] = (c0 + i < ncand) ? z[i] + bz[i] : -__builtin_inff();
+                if (dbg_logits && row_valid) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if (c0 + i < ncand) dbg_logits[dbg_base + c0 + i] = z[i];
+                }
+                fold_logits(z, c0, k, st, list);
+                kt = 0;
+                ++tile;
+                if (tile < te) bcur = *reinterpret_cast<const float4 *>(bias + tile * VP_TILE_ITEMS + q * 4);
+            }
+        }
+    }
+
+    // the four lanes that own a row (one per candidate quarter) -> one (m, s)
+#pragma unroll
+    for (int off = 16; off <= 32; off <<= 1) {
+        const float m2 = __shfl_xor(st.m, off);
+        const float s2 = __shfl_xor(st.s, off);
+        const float mn = fmaxf(st.m, m2);
+        st.s = st.s * fast_exp(st.m - mn) + s2 * fast_exp(m2 - mn);
+        st.m = mn;
+    }
+    if (q == 0) {
+        hdr_m[wave * 16 + n] = st.m;
+        hdr_s[wave * 16 + n] = st.s;
+    }
+    __syncthreads();
+
+    // Combine the workgroup's 16 lane lists per row (4 wavefronts x 4 lanes) into one
+    // partial result per (item, row): k rounds of "best entry after the previous winner".
+    const int PFL = vp_partial_floats(k);
+    for (int r = wave; r < item.nrows; r += VP_WG_WAVES) {
+        float M = hdr_m[r];
+#pragma unroll
+        for (int w = 1; w < VP_WG_WAVES; ++w) M = fmaxf(M, hdr_m[w * 16 + r]);
+        float Ssum = 0.f;
+#pragma unroll
+        for (int w = 0; w < VP_WG_WAVES; ++w) Ssum += hdr_s[w * 16 + r] * fast_exp(hdr_m[w * 16 + r] - M);
+        float *out = partials + ((size_t)it * VP_ROWS_PER_ITEM + r) * PFL;
+        if (lane == 0) {
+            out[0] = M;
+            out[1] = Ssum;
+        }
+        // lane -> one of the 16 source lists and a residue class of its slots
+        const int src = lane & 15;
+        const int sw = src >> 2, sq = src & 3;
+        const float *sv = list_val + sw * k * 64 + (sq * 16 + r);
+        const int *si = list_idx + sw * k * 64 + (sq * 16 + r);
+        float pv = __builtin_inff();
+        int pi = -1;
+        for (int t = 0; t < k; ++t) {
+            float bv = -__builtin_inff();
+            int bi = VP_IDX_NONE;
+            for (int p = lane >> 4; p < k; p += 4) {
+                const float v = sv[p * 64];
+                const int i = si[p * 64];
+                const bool after_prev = v < pv || (v == pv && i > pi);
+                if (after_prev && entry_before(v, i, bv, bi)) {
+                    bv = v;
+                    bi = i;
+                }
+            }
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const float v2 = __shfl_xor(bv, off);
+                const int i2 = __shfl_xor(bi, off);
+                if (entry_before(v2, i2, bv, bi)) {
+                    bv = v2;
+                    bi = i2;
+                }
+            }
+            if (lane == 0) {
+                out[2 + t] = bv;
+                out[2 + k + t] = __int_as_float(bi);
+            }
+            pv = bv;
+            pi = bi;
+        }
+    }
+}
+
+}  // namespace
+
+size_t vpk_project_lds_bytes(int kt, int k)
+{
+    return (size_t)kt * VP_TILE_BYTES + (size_t)VP_WG_WAVES * k * 64 * 8 + VP_WG_WAVES * 16 * 8 + 64;
+}
+
+hipError_t vpk_project_prepare()
+{
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(project_kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+}
+
+void vpk_project(const VpSlabSet &set, const void *hidden, int d, const int32_t *perm, const VpItem *items,
+                 const VpPlanHeader *hdr, int grid_items, int k, int rstar, float *partials, float *dbg_logits,
+                 const int64_t *dbg_row_off, hipStream_t st)
+{
+    hipLaunchKernelGGL(project_kernel, dim3(grid_items), dim3(VP_WG_THREADS), vpk_project_lds_bytes(set.kt, k), st,
+                       set, (const uint4 *)hidden, d, perm, items, hdr, k, rstar, partials, dbg_logits,
+                       dbg_row_off);
+}

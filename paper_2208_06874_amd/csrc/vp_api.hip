@@ -1,0 +1,430 @@
+// Host side of the C ABI declared in include/vp.h: argument validation, arena
+// and workspace carving, kernel sequencing.  No device memory is allocated
+// here; every buffer is carved from memory the caller supplies.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "vp.h"
+#include "vp_kernels.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+vp_status fail(vp_status st, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+constexpr size_t ALIGN = 256;
+constexpr size_t LDS_LIMIT = 160 * 1024;
+inline size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
+inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+inline int ceil_div(long a, long b) { return (int)((a + b - 1) / b); }
+
+// Byte offsets of the index sections inside the arena.
+struct ArenaLayout {
+    int d_pad, kt, vtiles, ctiles;
+    long total_groups;     // candidate groups (of 16) over all clusters
+    long n_total;
+    int n_min, n_max, max_tiles;
+    size_t wp, biasf, cp, cnorm, full_meta, tile_off, n_cand, ids_pad, sbias, slabs, total;
+};
+
+}  // namespace
+
+struct vp_index {
+    int d, V, K, k_max;
+    ArenaLayout L;
+    char *arena;
+    VpSlabSet clusters;
+    VpSlabSet full;
+    const void *cp;
+    const float *cnorm;
+    int target_items, full_target_items, rstar;
+};
+
+namespace {
+
+// Checks everything in the description that lives on the host and computes the layout.
+vp_status plan_arena(const vp_build_desc *D, bool check_ids, ArenaLayout *L)
+{
+    if (!D) return fail(VP_ERR_INVALID_ARG, "vp_build: null description");
+    if (D->flags != 0) return fail(VP_ERR_INVALID_ARG, "vp_build: flags must be 0");
+    if (D->d < 8 || D->d > VP_MAX_DIM || D->d % 8 != 0)
+        return fail(VP_ERR_UNSUPPORTED, "vp_build: d = %d must be a multiple of 8 in [8, %d]", D->d, VP_MAX_DIM);
+    if (D->K < 1 || D->K > VP_MAX_CLUSTERS)
+        return fail(VP_ERR_UNSUPPORTED, "vp_build: K = %d must be in [1, %d]", D->K, VP_MAX_CLUSTERS);
+    if (D->V < 1 || D->V > 2147483647 - 16) return fail(VP_ERR_UNSUPPORTED, "vp_build: V = %d out of range", D->V);
+    if (D->k_max < 1 || D->k_max > VP_MAX_TOPK)
+        return fail(VP_ERR_UNSUPPORTED, "vp_build: k_max = %d must be in [1, %d]", D->k_max, VP_MAX_TOPK);
+    if (!D->cand_offsets || !D->cand_ids) return fail(VP_ERR_INVALID_ARG, "vp_build: null candidate lists");
+    if (D->cand_offsets[0] != 0) return fail(VP_ERR_INVALID_ARG, "vp_build: cand_offsets[0] must be 0");
+
+    L->d_pad = (D->d + VP_KPAD - 1) / VP_KPAD * VP_KPAD;
+    L->kt = L->d_pad / VP_TILE_K;
+    if (vpk_project_lds_bytes(L->kt, D->k_max) > LDS_LIMIT)
+        return fail(VP_ERR_UNSUPPORTED, "vp_build: d = %d with k_max = %d needs more than %zu bytes of LDS", D->d,
+                    D->k_max, LDS_LIMIT);
+    L->vtiles = ceil_div(D->V, VP_TILE_ITEMS);
+    L->ctiles = ceil_div(D->K, VP_TILE_ITEMS);
+    long groups = 0, total = 0;
+    int n_min = 2147483647, n_max = 0;
+    for (int j = 0; j < D->K; ++j) {
+        const int64_t a = D->cand_offsets[j], b = D->cand_offsets[j + 1];
+        if (b < a) return fail(VP_ERR_INVALID_ARG, "vp_build: cand_offsets decreases at cluster %d", j);
+        const int64_t n = b - a;
+        if (n == 0) return fail(VP_ERR_UNSUPPORTED, "vp_build: cluster %d has an empty active set", j);
+        if (n > D->V) return fail(VP_ERR_INVALID_ARG, "vp_build: cluster %d lists %lld > V tokens", j, (long long)n);
+        if (check_ids) {
+            const int32_t *ids = D->cand_ids + a;
+            if (ids[0] < 0 || ids[n - 1] >= D->V)
+                return fail(VP_ERR_INVALID_ARG, "vp_build: cluster %d has a token id outside [0, V)", j);
+            for (int64_t c = 1; c < n; ++c)
+                if (ids[c] <= ids[c - 1])
+                    return fail(VP_ERR_INVALID_ARG,
+                                "vp_build: active set of cluster %d is not strictly ascending at position %lld", j,
+                                (long long)c);
+        }
+        groups += (n + VP_TILE_ITEMS - 1) / VP_TILE_ITEMS;
+        total += n;
+        n_min = std::min<int64_t>(n_min, n);
+        n_max = std::max<int64_t>(n_max, n);
+    }
+    if (groups > 2147483647L / 2) return fail(VP_ERR_UNSUPPORTED, "vp_build: active sets too large in total");
+    L->total_groups = groups;
+    L->n_total = total;
+    L->n_min = n_min;
+    L->n_max = n_max;
+    L->max_tiles = ceil_div(n_max, VP_TILE_ITEMS);
+
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
+    const size_t group_bytes = (size_t)L->kt * VP_TILE_BYTES;
+    L->wp = take((size_t)L->vtiles * group_bytes);
+    L->biasf = take((size_t)L->vtiles * VP_TILE_ITEMS * sizeof(float));
+    L->cp = take((size_t)L->ctiles * group_bytes);
+    L->cnorm = take((size_t)L->ctiles * VP_TILE_ITEMS * sizeof(float));
+    L->full_meta = take(4 * sizeof(int32_t));
+    L->tile_off = take((size_t)(D->K + 1) * sizeof(int32_t));
+    L->n_cand = take((size_t)D->K * sizeof(int32_t));
+    L->ids_pad = take((size_t)groups * VP_TILE_ITEMS * sizeof(int32_t));
+    L->sbias = take((size_t)groups * VP_TILE_ITEMS * sizeof(float));
+    L->slabs = take((size_t)groups * group_bytes);
+    L->total = o;
+    return VP_OK;
+}
+
+// Byte offsets of the per-call scratch inside the workspace.
+struct WsLayout {
+    int max_items;
+    size_t hdr, cpart, g, perm, row_item0, row_stride, row_nit, items, partials, total;
+};
+
+int max_items_clustered(const vp_index *I, int N)
+{
+    return I->target_items + ceil_div(N, VP_ROWS_PER_ITEM) + std::min(N, I->K) + 2;
+}
+int max_items_full(const vp_index *I, int N) { return I->full_target_items + ceil_div(N, VP_ROWS_PER_ITEM) + 2; }
+
+WsLayout plan_workspace(const vp_index *I, int N)
+{
+    WsLayout W;
+    W.max_items = std::max(max_items_clustered(I, N), max_items_full(I, N));
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
+    const size_t n = (size_t)std::max(N, 1);
+    W.hdr = take(sizeof(VpPlanHeader));
+    W.cpart = take(n * I->L.ctiles * 8);
+    W.g = take(n * 4);
+    W.perm = take(n * 4);
+    W.row_item0 = take(n * 4);
+    W.row_stride = take(n * 4);
+    W.row_nit = take(n * 4);
+    W.items = take((size_t)W.max_items * sizeof(VpItem));
+    W.partials = take((size_t)W.max_items * VP_ROWS_PER_ITEM * vp_partial_floats(I->k_max) * sizeof(float));
+    W.total = o;
+    return W;
+}
+
+vp_status check_call(const char *fn, const vp_index *I, const void *hidden, int N, int k, const void *out_ids,
+                     const void *out_logp, const void *ws, size_t ws_bytes, bool need_outputs)
+{
+    if (!I) return fail(VP_ERR_INVALID_ARG, "%s: null index", fn);
+    if (N < 0 || N > VP_MAX_ROWS) return fail(VP_ERR_INVALID_ARG, "%s: N = %d must be in [0, %d]", fn, N, VP_MAX_ROWS);
+    if (k < 1 || k > I->k_max)
+        return fail(VP_ERR_UNSUPPORTED, "%s: k = %d must be in [1, k_max = %d]", fn, k, I->k_max);
+    if (N == 0) return VP_OK;
+    if (!hidden || !aligned(hidden, 16)) return fail(VP_ERR_INVALID_ARG, "%s: hidden is null or not 16-byte aligned", fn);
+    if (need_outputs && (!out_ids || !out_logp)) return fail(VP_ERR_INVALID_ARG, "%s: null output pointer", fn);
+    if (!ws || !aligned(ws, ALIGN)) return fail(VP_ERR_INVALID_ARG, "%s: workspace is null or not 256-byte aligned", fn);
+    const WsLayout W = plan_workspace(I, N);
+    if (ws_bytes < W.total)
+        return fail(VP_ERR_WORKSPACE, "%s: workspace of %zu bytes, %zu needed for N = %d", fn, ws_bytes, W.total, N);
+    return VP_OK;
+}
+
+vp_status launch_status(const char *fn)
+{
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(VP_ERR_HIP, "%s: kernel launch failed: %s", fn, hipGetErrorString(e));
+    return VP_OK;
+}
+
+// The kernel sequence shared by vp_project and the clustered debug entry.
+vp_status run_clustered(const char *fn, const vp_index *I, const void *hidden, int N, int k, int32_t *out_ids,
+                        float *out_logp, int32_t *out_cluster, char *ws, int64_t *dbg_row_off, float *dbg_logits,
+                        hipStream_t st)
+{
+    const WsLayout W = plan_workspace(I, N);
+    VpPlanHeader *hdr = reinterpret_cast<VpPlanHeader *>(ws + W.hdr);
+    void *cpart = ws + W.cpart;
+    int32_t *g = reinterpret_cast<int32_t *>(ws + W.g);
+    int32_t *perm = reinterpret_cast<int32_t *>(ws + W.perm);
+    int32_t *row_item0 = reinterpret_cast<int32_t *>(ws + W.row_item0);
+    int32_t *row_stride = reinterpret_cast<int32_t *>(ws + W.row_stride);
+    int32_t *row_nit = reinterpret_cast<int32_t *>(ws + W.row_nit);
+    VpItem *items = reinterpret_cast<VpItem *>(ws + W.items);
+    float *partials = reinterpret_cast<float *>(ws + W.partials);
+
+    // Eq. 2 in parts so that a handful of rows still occupies many wavefronts
+    const int row_tiles = ceil_div(N, 16);
+    int parts = std::max(1, std::min(I->L.ctiles, ceil_div(1024, row_tiles)));
+    const int tpp = ceil_div(I->L.ctiles, parts);
+    parts = ceil_div(I->L.ctiles, tpp);
+    vpk_centroid(hidden, N, I->d, I->cp, I->cnorm, I->K, I->L.kt, I->L.ctiles, tpp, parts, cpart, st);
+
+    const int max_items = max_items_clustered(I, N);
+    vpk_plan(cpart, parts, N, I->K, I->clusters.n_cand, I->clusters.tile_off, I->target_items, max_items, g,
+             out_cluster, perm, row_item0, row_stride, row_nit, items, hdr, dbg_row_off, st);
+
+    const long row_groups = (long)row_tiles + std::min(N, I->K);
+    const long by_tiles = row_groups * ceil_div(I->L.max_tiles, VP_WG_WAVES);
+    const int grid_items = (int)std::min<long>(max_items, by_tiles);
+    vpk_project(I->clusters, hidden, I->d, perm, items, hdr, grid_items, k, I->rstar, partials, dbg_logits,
+                dbg_row_off, st);
+    if (out_ids)
+        vpk_merge(I->clusters, perm, g, row_item0, row_stride, row_nit, items, partials, k, N, out_ids, out_logp, st);
+    return launch_status(fn);
+}
+
+vp_status run_full(const char *fn, const vp_index *I, const void *hidden, int N, int k, int32_t *out_ids,
+                   float *out_logp, char *ws, int64_t *dbg_row_off, float *dbg_logits, hipStream_t st)
+{
+    const WsLayout W = plan_workspace(I, N);
+    VpPlanHeader *hdr = reinterpret_cast<VpPlanHeader *>(ws + W.hdr);
+    int32_t *perm = reinterpret_cast<int32_t *>(ws + W.perm);
+    int32_t *row_item0 = reinterpret_cast<int32_t *>(ws + W.row_item0);
+    int32_t *row_stride = reinterpret_cast<int32_t *>(ws + W.row_stride);
+    int32_t *row_nit = reinterpret_cast<int32_t *>(ws + W.row_nit);
+    VpItem *items = reinterpret_cast<VpItem *>(ws + W.items);
+    float *partials = reinterpret_cast<float *>(ws + W.partials);
+
+    const int max_items = max_items_full(I, N);
+    vpk_plan_full(N, I->V, I->L.vtiles, I->full_target_items, max_items, perm, row_item0, row_stride, row_nit,
+                  items, hdr, dbg_row_off, st);
+    const long row_groups = ceil_div(N, VP_ROWS_PER_ITEM);
+    const long by_tiles = row_groups * ceil_div(I->L.vtiles, VP_WG_WAVES);
+    const int grid_items = (int)std::min<long>(max_items, by_tiles);
+    // the GEMV loop is reserved for the clustered buckets; the full projection keeps its rows in one bucket
+    vpk_project(I->full, hidden, I->d, perm, items, hdr, grid_items, k, N <= I->rstar ? I->rstar : 0, partials,
+                dbg_logits, dbg_row_off, st);
+    if (out_ids)
+        vpk_merge(I->full, perm, nullptr, row_item0, row_stride, row_nit, items, partials, k, N, out_ids, out_logp,
+                  st);
+    return launch_status(fn);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *vp_last_error(void) { return g_err; }
+
+size_t vp_build_bytes(const vp_build_desc *desc)
+{
+    ArenaLayout L;
+    if (plan_arena(desc, false, &L) != VP_OK) return 0;
+    return L.total;
+}
+
+vp_status vp_build(const vp_build_desc *D, void *hip_stream, vp_index **out)
+{
+    if (!out) return fail(VP_ERR_INVALID_ARG, "vp_build: null output handle");
+    *out = nullptr;
+    ArenaLayout L;
+    vp_status s = plan_arena(D, true, &L);
+    if (s != VP_OK) return s;
+    if (!D->W || !D->bias || !D->centroids) return fail(VP_ERR_INVALID_ARG, "vp_build: null W, bias or centroids");
+    if (!aligned(D->W, 2) || !aligned(D->bias, 2) || !aligned(D->centroids, 16))
+        return fail(VP_ERR_INVALID_ARG, "vp_build: W/bias must be 2-byte and centroids 16-byte aligned");
+    if (!D->arena || !aligned(D->arena, ALIGN)) return fail(VP_ERR_INVALID_ARG, "vp_build: arena is null or not 256-byte aligned");
+    if (D->arena_bytes < L.total)
+        return fail(VP_ERR_WORKSPACE, "vp_build: arena of %zu bytes, %zu needed", D->arena_bytes, L.total);
+
+    hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+    hipError_t e = vpk_plan_prepare();
+    if (e == hipSuccess) e = vpk_project_prepare();
+    if (e != hipSuccess) return fail(VP_ERR_HIP, "vp_build: cannot configure kernels: %s", hipGetErrorString(e));
+
+    // host-side metadata: candidate groups per cluster, ids padded to whole groups
+    std::vector<int32_t> tile_off(D->K + 1), n_cand(D->K);
+    std::vector<int32_t> ids_pad((size_t)L.total_groups * VP_TILE_ITEMS, -1);
+    tile_off[0] = 0;
+    for (int j = 0; j < D->K; ++j) {
+        const int64_t a = D->cand_offsets[j];
+        const int n = (int)(D->cand_offsets[j + 1] - a);
+        n_cand[j] = n;
+        tile_off[j + 1] = tile_off[j] + (n + VP_TILE_ITEMS - 1) / VP_TILE_ITEMS;
+        std::memcpy(ids_pad.data() + (size_t)tile_off[j] * VP_TILE_ITEMS, D->cand_ids + a, (size_t)n * sizeof(int32_t));
+    }
+    const int32_t full_meta[4] = {0, L.vtiles, D->V, 0};   // tile_off[2], n_cand[1]
+
+    char *A = static_cast<char *>(D->arena);
+    auto up = [&](size_t at, const void *src, size_t bytes) {
+        if (e == hipSuccess) e = hipMemcpyAsync(A + at, src, bytes, hipMemcpyHostToDevice, st);
+    };
+    up(L.tile_off, tile_off.data(), tile_off.size() * sizeof(int32_t));
+    up(L.n_cand, n_cand.data(), n_cand.size() * sizeof(int32_t));
+    up(L.ids_pad, ids_pad.data(), ids_pad.size() * sizeof(int32_t));
+    up(L.full_meta, full_meta, sizeof(full_meta));
+    if (e != hipSuccess) return fail(VP_ERR_HIP, "vp_build: upload failed: %s", hipGetErrorString(e));
+
+    vpk_pack_w(D->W, D->d, D->V, L.kt, A + L.wp, st);
+    vpk_bias_full(D->bias, D->V, L.vtiles * VP_TILE_ITEMS, reinterpret_cast<float *>(A + L.biasf), st);
+    vpk_pack_rows(D->centroids, D->K, D->d, L.kt, A + L.cp, st);
+    vpk_cnorm(D->centroids, D->K, D->d, L.ctiles * VP_TILE_ITEMS, reinterpret_cast<float *>(A + L.cnorm), st);
+    vpk_gather_slabs(A + L.wp, D->bias, L.kt, reinterpret_cast<const int32_t *>(A + L.ids_pad), L.total_groups,
+                     A + L.slabs, reinterpret_cast<float *>(A + L.sbias), st);
+    s = launch_status("vp_build");
+    if (s != VP_OK) return s;
+    e = hipStreamSynchronize(st);
+    if (e != hipSuccess) return fail(VP_ERR_HIP, "vp_build: %s", hipGetErrorString(e));
+
+    vp_index *I = new (std::nothrow) vp_index();
+    if (!I) return fail(VP_ERR_INVALID_ARG, "vp_build: out of host memory");
+    I->d = D->d;
+    I->V = D->V;
+    I->K = D->K;
+    I->k_max = D->k_max;
+    I->L = L;
+    I->arena = A;
+    I->cp = A + L.cp;
+    I->cnorm = reinterpret_cast<const float *>(A + L.cnorm);
+    I->clusters.tiles = A + L.slabs;
+    I->clusters.bias = reinterpret_cast<const float *>(A + L.sbias);
+    I->clusters.ids = reinterpret_cast<const int32_t *>(A + L.ids_pad);
+    I->clusters.tile_off = reinterpret_cast<const int32_t *>(A + L.tile_off);
+    I->clusters.n_cand = reinterpret_cast<const int32_t *>(A + L.n_cand);
+    I->clusters.entries = D->K;
+    I->clusters.kt = L.kt;
+    I->full.tiles = A + L.wp;
+    I->full.bias = reinterpret_cast<const float *>(A + L.biasf);
+    I->full.ids = nullptr;
+    I->full.tile_off = reinterpret_cast<const int32_t *>(A + L.full_meta);
+    I->full.n_cand = reinterpret_cast<const int32_t *>(A + L.full_meta) + 2;
+    I->full.entries = 1;
+    I->full.kt = L.kt;
+    I->target_items = 8192;
+    I->full_target_items = 2048;
+    I->rstar = 0;
+    *out = I;
+    return VP_OK;
+}
+
+vp_status vp_get_info(const vp_index *I, vp_index_info *info)
+{
+    if (!I || !info) return fail(VP_ERR_INVALID_ARG, "vp_get_info: null argument");
+    info->d = I->d;
+    info->V = I->V;
+    info->K = I->K;
+    info->k_max = I->k_max;
+    info->d_pad = I->L.d_pad;
+    info->n_min = I->L.n_min;
+    info->n_max = I->L.n_max;
+    info->n_total = I->L.n_total;
+    info->slab_bytes = (int64_t)I->L.total_groups * I->L.kt * VP_TILE_BYTES;
+    info->full_bytes = (int64_t)I->L.vtiles * I->L.kt * VP_TILE_BYTES;
+    info->arena_bytes_used = (int64_t)I->L.total;
+    return VP_OK;
+}
+
+vp_status vp_set_option(vp_index *I, const char *name, int64_t value)
+{
+    if (!I || !name) return fail(VP_ERR_INVALID_ARG, "vp_set_option: null argument");
+    if (!std::strcmp(name, "target_items") || !std::strcmp(name, "full_target_items")) {
+        if (value < 1 || value > (1 << 20))
+            return fail(VP_ERR_INVALID_ARG, "vp_set_option: %s = %lld must be in [1, 2^20]", name, (long long)value);
+        (name[0] == 't' ? I->target_items : I->full_target_items) = (int)value;
+        return VP_OK;
+    }
+    if (!std::strcmp(name, "rstar")) {
+        if (value < 0 || value > VP_GEMV_MAX_ROWS)
+            return fail(VP_ERR_INVALID_ARG, "vp_set_option: rstar = %lld must be in [0, %d]", (long long)value,
+                        VP_GEMV_MAX_ROWS);
+        I->rstar = (int)value;
+        return VP_OK;
+    }
+    return fail(VP_ERR_INVALID_ARG, "vp_set_option: unknown option '%s'", name);
+}
+
+size_t vp_workspace_bytes(const vp_index *I, int32_t N_max)
+{
+    if (!I || N_max < 0 || N_max > VP_MAX_ROWS) {
+        fail(VP_ERR_INVALID_ARG, "vp_workspace_bytes: bad index or N_max");
+        return 0;
+    }
+    return plan_workspace(I, N_max).total;
+}
+
+vp_status vp_project(const vp_index *I, const void *hidden, int32_t N, int32_t k, int32_t *out_ids, float *out_logp,
+                     int32_t *out_cluster, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    vp_status s = check_call("vp_project", I, hidden, N, k, out_ids, out_logp, workspace, workspace_bytes, true);
+    if (s != VP_OK || N == 0) return s;
+    return run_clustered("vp_project", I, hidden, N, k, out_ids, out_logp, out_cluster, static_cast<char *>(workspace),
+                         nullptr, nullptr, reinterpret_cast<hipStream_t>(hip_stream));
+}
+
+vp_status vp_project_full(const vp_index *I, const void *hidden, int32_t N, int32_t k, int32_t *out_ids,
+                          float *out_logp, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    vp_status s = check_call("vp_project_full", I, hidden, N, k, out_ids, out_logp, workspace, workspace_bytes, true);
+    if (s != VP_OK || N == 0) return s;
+    return run_full("vp_project_full", I, hidden, N, k, out_ids, out_logp, static_cast<char *>(workspace), nullptr,
+                    nullptr, reinterpret_cast<hipStream_t>(hip_stream));
+}
+
+vp_status vp_project_debug_logits(const vp_index *I, const void *hidden, int32_t N, int32_t full,
+                                  int32_t *out_cluster, int64_t *out_row_offsets, float *out_logits,
+                                  size_t out_logits_capacity, void *workspace, size_t workspace_bytes,
+                                  void *hip_stream)
+{
+    const char *fn = "vp_project_debug_logits";
+    vp_status s = check_call(fn, I, hidden, N, 1, nullptr, nullptr, workspace, workspace_bytes, false);
+    if (s != VP_OK) return s;
+    if (!out_row_offsets || (N > 0 && !out_logits)) return fail(VP_ERR_INVALID_ARG, "%s: null output pointer", fn);
+    if (!full && !out_cluster) return fail(VP_ERR_INVALID_ARG, "%s: out_cluster is required when full == 0", fn);
+    if (N == 0) return VP_OK;
+    const size_t need = (size_t)N * (full ? (size_t)I->V : (size_t)I->L.n_max);
+    if (out_logits_capacity < need)
+        return fail(VP_ERR_WORKSPACE, "%s: out_logits holds %zu elements, %zu needed", fn, out_logits_capacity, need);
+    hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+    if (full) return run_full(fn, I, hidden, N, 1, nullptr, nullptr, static_cast<char *>(workspace), out_row_offsets, out_logits, st);
+    return run_clustered(fn, I, hidden, N, 1, nullptr, nullptr, out_cluster, static_cast<char *>(workspace),
+                         out_row_offsets, out_logits, st);
+}
+
+void vp_destroy(vp_index *I) { delete I; }
+
+}  // extern "C"

@@ -1,0 +1,41 @@
+// Host-callable launchers of the HIP kernels (internal to the library).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+#include "vp_layout.h"
+
+// index building
+void vpk_pack_w(const void *W, int d, int V, int kt, void *out, hipStream_t st);
+void vpk_pack_rows(const void *M, int rows, int d, int kt, void *out, hipStream_t st);
+void vpk_cnorm(const void *C, int K, int d, int K_pad, float *cnorm, hipStream_t st);
+void vpk_bias_full(const void *b, int V, int V_pad, float *out, hipStream_t st);
+void vpk_gather_slabs(const void *wp, const void *b, int kt, const int32_t *ids_pad, long total_groups,
+                      void *slabs, float *sbias, hipStream_t st);
+
+// centroid selection (Eq. 2)
+void vpk_centroid(const void *hidden, int N, int d, const void *cp, const float *cnorm, int K, int kt,
+                  int ctiles, int tiles_per_part, int parts, void *cpart, hipStream_t st);
+
+// bucketing + planning
+size_t vpk_plan_lds_bytes(int K);
+hipError_t vpk_plan_prepare();
+void vpk_plan(const void *cpart, int parts, int N, int K, const int32_t *n_cand, const int32_t *tile_off,
+              int target_items, int max_items, int32_t *g, int32_t *out_cluster, int32_t *perm,
+              int32_t *row_item0, int32_t *row_stride, int32_t *row_nit, VpItem *items, VpPlanHeader *hdr,
+              int64_t *dbg_row_off, hipStream_t st);
+void vpk_plan_full(int N, int V, int vtiles, int target_items, int max_items, int32_t *perm, int32_t *row_item0,
+                   int32_t *row_stride, int32_t *row_nit, VpItem *items, VpPlanHeader *hdr,
+                   int64_t *dbg_row_off, hipStream_t st);
+
+// projection + fused log-softmax / top-k partials
+size_t vpk_project_lds_bytes(int kt, int k);
+hipError_t vpk_project_prepare();
+void vpk_project(const VpSlabSet &set, const void *hidden, int d, const int32_t *perm, const VpItem *items,
+                 const VpPlanHeader *hdr, int grid_items, int k, int rstar, float *partials, float *dbg_logits,
+                 const int64_t *dbg_row_off, hipStream_t st);
+
+// per-row merge
+void vpk_merge(const VpSlabSet &set, const int32_t *perm, const int32_t *g, const int32_t *row_item0,
+               const int32_t *row_stride, const int32_t *row_nit, const VpItem *items, const float *partials,
+               int k, int N, int32_t *out_ids, float *out_logp, hipStream_t st);

@@ -1,0 +1,60 @@
+// Internal layout definitions shared by the host API and the HIP kernels.
+//
+// Packed tile layout.  All matrices the hot kernels stream (per-cluster slabs,
+// the whole-W copy, the centroids) are stored as 1 KiB tiles of 16 "items"
+// (candidate tokens, or centroids) x 32 k-values, in the operand order of
+// v_mfma_f32_16x16x32_f16: lane l of a wavefront owns item (l % 16) and the 8
+// consecutive k-values starting at (l / 16) * 8, stored as 16 contiguous bytes
+// at byte l * 16 of the tile.  The tiles of one group of 16 items follow each
+// other along k (KT = d_pad / 32 tiles), so a group is one contiguous run of
+// KT KiB, and consecutive groups are contiguous too: a wavefront that streams
+// a range of items reads one linear range of memory, 1 KiB per load.
+#pragma once
+#include <stdint.h>
+
+#define VP_TILE_ITEMS 16
+#define VP_TILE_K 32
+#define VP_TILE_BYTES 1024
+#define VP_KPAD 256            // d is padded (with zeros) to a multiple of this
+#define VP_WG_THREADS 256      // projection kernel: 4 wavefronts per workgroup
+#define VP_WG_WAVES 4
+#define VP_ROWS_PER_ITEM 16    // rows one work item projects (one MFMA row tile)
+#define VP_GEMV_MAX_ROWS 4
+
+// One unit of projection work: up to 16 rows of one bucket against a range of
+// candidate tiles of that bucket's slab.
+struct VpItem {
+    int32_t cluster;     // slab set entry (cluster id; 0 for the full-vocabulary set)
+    int32_t perm_start;  // first position in perm[] of this item's rows
+    int32_t nrows;       // 1..16
+    int32_t tile0;       // first candidate tile
+    int32_t ntiles;      // candidate tiles of this item (split among the 4 wavefronts)
+    int32_t pad[3];
+};
+
+// Header the planning kernel leaves for the projection and merge kernels.
+struct VpPlanHeader {
+    int32_t total_items;
+    int32_t tiles_per_wave;
+    int32_t overflow;        // set if the item list did not fit (never expected)
+    int32_t total_tiles;
+    int32_t pad[60];
+};
+
+// A set of packed slabs: the K clusters, or the single whole-vocabulary slab.
+struct VpSlabSet {
+    const void *tiles;        // packed fp16 tiles of all entries back to back
+    const float *bias;        // fp32 bias per candidate, padded to 16 per entry
+    const int32_t *ids;       // token id per candidate (-1 in padding); NULL = identity
+    const int32_t *tile_off;  // [entries + 1] cumulative candidate tiles
+    const int32_t *n_cand;    // [entries] candidates per entry
+    int32_t entries;
+    int32_t kt;               // k-tiles per candidate group (d_pad / 32)
+};
+
+// Size in floats of one partial result: running max, sum of exponentials, then
+// k logits and k candidate positions.
+static inline __host__ __device__ int vp_partial_floats(int k) { return 2 + 2 * k; }
+
+#define VP_NEG_BIG (-3.0e38f)
+#define VP_IDX_NONE 0x7fffffff

@@ -1,0 +1,243 @@
+"""Thin Python binding of the C-ABI library (include/vp.h): argument marshalling
+only.  PyTorch supplies device memory and the current stream; every step of
+the projection path runs in the library's HIP kernels.  There is no fallback:
+if libvp.so is missing or fails to load, importing succeeds but the first use
+raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libvp.so")
+
+VP_OK, VP_ERR_INVALID_ARG, VP_ERR_UNSUPPORTED, VP_ERR_WORKSPACE, VP_ERR_HIP = range(5)
+STATUS_NAMES = {0: "VP_OK", 1: "VP_ERR_INVALID_ARG", 2: "VP_ERR_UNSUPPORTED", 3: "VP_ERR_WORKSPACE",
+                4: "VP_ERR_HIP"}
+
+EXPORTS = ("vp_build_bytes", "vp_build", "vp_get_info", "vp_set_option", "vp_workspace_bytes",
+           "vp_project", "vp_project_full", "vp_project_debug_logits", "vp_destroy", "vp_last_error")
+
+
+class VpError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__("%s: %s" % (STATUS_NAMES.get(status, status), message))
+        self.status = status
+
+
+class BuildDesc(ctypes.Structure):
+    _fields_ = [("d", ctypes.c_int32), ("V", ctypes.c_int32), ("K", ctypes.c_int32),
+                ("W", ctypes.c_void_p), ("bias", ctypes.c_void_p), ("centroids", ctypes.c_void_p),
+                ("cand_offsets", ctypes.c_void_p), ("cand_ids", ctypes.c_void_p),
+                ("arena", ctypes.c_void_p), ("arena_bytes", ctypes.c_size_t),
+                ("k_max", ctypes.c_int32), ("flags", ctypes.c_uint32)]
+
+
+class IndexInfo(ctypes.Structure):
+    _fields_ = [("d", ctypes.c_int32), ("V", ctypes.c_int32), ("K", ctypes.c_int32),
+                ("k_max", ctypes.c_int32), ("d_pad", ctypes.c_int32), ("n_min", ctypes.c_int32),
+                ("n_max", ctypes.c_int32), ("n_total", ctypes.c_int64), ("slab_bytes", ctypes.c_int64),
+                ("full_bytes", ctypes.c_int64), ("arena_bytes_used", ctypes.c_int64)]
+
+
+_lib = None
+
+
+def lib():
+    """Loads libvp.so (built in-tree by paper_2208_06874_amd/build.py); fails loudly."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("%s is missing: run `python -m paper_2208_06874_amd.build` "
+                               "(there is no non-HIP fallback)" % LIB_PATH)
+        L = ctypes.CDLL(LIB_PATH)
+        vp = ctypes.c_void_p
+        L.vp_last_error.restype = ctypes.c_char_p
+        L.vp_build_bytes.restype = ctypes.c_size_t
+        L.vp_build_bytes.argtypes = [ctypes.POINTER(BuildDesc)]
+        L.vp_build.restype = ctypes.c_int
+        L.vp_build.argtypes = [ctypes.POINTER(BuildDesc), vp, ctypes.POINTER(vp)]
+        L.vp_get_info.restype = ctypes.c_int
+        L.vp_get_info.argtypes = [vp, ctypes.POINTER(IndexInfo)]
+        L.vp_set_option.restype = ctypes.c_int
+        L.vp_set_option.argtypes = [vp, ctypes.c_char_p, ctypes.c_int64]
+        L.vp_workspace_bytes.restype = ctypes.c_size_t
+        L.vp_workspace_bytes.argtypes = [vp, ctypes.c_int32]
+        L.vp_project.restype = ctypes.c_int
+        L.vp_project.argtypes = [vp, vp, ctypes.c_int32, ctypes.c_int32, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.vp_project_full.restype = ctypes.c_int
+        L.vp_project_full.argtypes = [vp, vp, ctypes.c_int32, ctypes.c_int32, vp, vp, vp, ctypes.c_size_t, vp]
+        L.vp_project_debug_logits.restype = ctypes.c_int
+        L.vp_project_debug_logits.argtypes = [vp, vp, ctypes.c_int32, ctypes.c_int32, vp, vp, vp,
+                                              ctypes.c_size_t, vp, ctypes.c_size_t, vp]
+        L.vp_destroy.restype = None
+        L.vp_destroy.argtypes = [vp]
+        _lib = L
+    return _lib
+
+
+def last_error() -> str:
+    return lib().vp_last_error().decode()
+
+
+def _check(status: int):
+    if status != VP_OK:
+        raise VpError(status, last_error())
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream=None) -> int:
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream
+
+
+def make_desc(d, V, K, W, bias, centroids, cand_off: np.ndarray, cand_ids: np.ndarray, arena, arena_bytes,
+              k_max, flags=0) -> BuildDesc:
+    return BuildDesc(d, V, K, W, bias, centroids, cand_off.ctypes.data, cand_ids.ctypes.data, arena,
+                     arena_bytes, k_max, flags)
+
+
+class Index:
+    """A packed index living in a torch uint8 arena on the GPU."""
+
+    def __init__(self, W, bias, centroids, cand_off, cand_ids, k_max: int = 8, stream=None):
+        import torch
+        assert W.is_cuda and W.dtype == torch.float16 and W.is_contiguous()
+        assert bias.dtype == torch.float16 and centroids.dtype == torch.float16
+        d, V = W.shape
+        K = centroids.shape[0]
+        self._off = np.ascontiguousarray(cand_off, np.int64)
+        self._ids = np.ascontiguousarray(cand_ids, np.int32)
+        desc = make_desc(d, V, K, W.data_ptr(), bias.data_ptr(), centroids.contiguous().data_ptr(), self._off,
+                         self._ids, None, 0, k_max)
+        need = lib().vp_build_bytes(ctypes.byref(desc))
+        if need == 0:
+            # let vp_build report the precise status
+            h = ctypes.c_void_p()
+            _check(lib().vp_build(ctypes.byref(desc), _stream(stream), ctypes.byref(h)))
+            raise VpError(VP_ERR_INVALID_ARG, last_error())
+        self.arena = torch.empty(need, dtype=torch.uint8, device=W.device)
+        desc.arena = self.arena.data_ptr()
+        desc.arena_bytes = need
+        h = ctypes.c_void_p()
+        _check(lib().vp_build(ctypes.byref(desc), _stream(stream), ctypes.byref(h)))
+        self.handle = h
+        self.device = W.device
+        self.d, self.V, self.K, self.k_max = d, V, K, k_max
+        self._ws = None
+
+    def close(self):
+        if getattr(self, "handle", None):
+            lib().vp_destroy(self.handle)
+            self.handle = None
+
+    __del__ = close
+
+    def info(self) -> dict:
+        i = IndexInfo()
+        _check(lib().vp_get_info(self.handle, ctypes.byref(i)))
+        return {f: getattr(i, f) for f, _ in IndexInfo._fields_}
+
+    def set_option(self, name: str, value: int):
+        _check(lib().vp_set_option(self.handle, name.encode(), int(value)))
+        self._ws = None
+
+    def workspace_bytes(self, N: int) -> int:
+        return lib().vp_workspace_bytes(self.handle, N)
+
+    def workspace(self, N: int):
+        import torch
+        need = self.workspace_bytes(N)
+        if self._ws is None or self._ws.numel() < need:
+            self._ws = torch.empty(max(need, 256), dtype=torch.uint8, device=self.device)
+        return self._ws
+
+    def project(self, hidden, k: int, out_ids=None, out_logp=None, out_cluster=None, want_cluster=True,
+                workspace=None, stream=None):
+        """vp_project: hidden[N, d] fp16 -> (ids[N, k] int32, logp[N, k] fp32, cluster[N] int32)."""
+        import torch
+        N = hidden.shape[0]
+        assert hidden.dtype == torch.float16 and hidden.is_contiguous() and hidden.shape[1] == self.d
+        if out_ids is None:
+            out_ids = torch.empty((N, k), dtype=torch.int32, device=self.device)
+        if out_logp is None:
+            out_logp = torch.empty((N, k), dtype=torch.float32, device=self.device)
+        if out_cluster is None and want_cluster:
+            out_cluster = torch.empty((N,), dtype=torch.int32, device=self.device)
+        ws = self.workspace(N) if workspace is None else workspace
+        _check(lib().vp_project(self.handle, hidden.data_ptr(), N, k, out_ids.data_ptr(), out_logp.data_ptr(),
+                                _ptr(out_cluster), ws.data_ptr(), ws.numel(), _stream(stream)))
+        return out_ids, out_logp, out_cluster
+
+    def project_full(self, hidden, k: int, out_ids=None, out_logp=None, workspace=None, stream=None):
+        """vp_project_full: the default projection over all V tokens."""
+        import torch
+        N = hidden.shape[0]
+        assert hidden.dtype == torch.float16 and hidden.is_contiguous() and hidden.shape[1] == self.d
+        if out_ids is None:
+            out_ids = torch.empty((N, k), dtype=torch.int32, device=self.device)
+        if out_logp is None:
+            out_logp = torch.empty((N, k), dtype=torch.float32, device=self.device)
+        ws = self.workspace(N) if workspace is None else workspace
+        _check(lib().vp_project_full(self.handle, hidden.data_ptr(), N, k, out_ids.data_ptr(),
+                                     out_logp.data_ptr(), ws.data_ptr(), ws.numel(), _stream(stream)))
+        return out_ids, out_logp
+
+    def debug_logits(self, hidden, full: bool = False, stream=None):
+        """vp_project_debug_logits -> (cluster[N], row_offsets[N+1] int64, logits fp32)."""
+        import torch
+        N = hidden.shape[0]
+        cap = N * (self.V if full else self.info()["n_max"])
+        cluster = torch.empty((N,), dtype=torch.int32, device=self.device)
+        offs = torch.empty((N + 1,), dtype=torch.int64, device=self.device)
+        logits = torch.full((max(cap, 1),), float("nan"), dtype=torch.float32, device=self.device)
+        ws = self.workspace(N)
+        _check(lib().vp_project_debug_logits(self.handle, hidden.data_ptr(), N, int(full), cluster.data_ptr(),
+                                             offs.data_ptr(), logits.data_ptr(), cap, ws.data_ptr(), ws.numel(),
+                                             _stream(stream)))
+        return cluster, offs, logits
+
+
+# ---- the C-ABI entry points under their own names --------------------------------------------
+def vp_build(W, bias, centroids, cand_off, cand_ids, k_max: int = 8, stream=None) -> Index:
+    return Index(W, bias, centroids, cand_off, cand_ids, k_max=k_max, stream=stream)
+
+
+def vp_project(index: Index, hidden, k: int, **kw):
+    return index.project(hidden, k, **kw)
+
+
+def vp_project_full(index: Index, hidden, k: int, **kw):
+    return index.project_full(hidden, k, **kw)
+
+
+def vp_project_debug_logits(index: Index, hidden, full: bool = False, **kw):
+    return index.debug_logits(hidden, full=full, **kw)
+
+
+def vp_workspace_bytes(index: Index, N_max: int) -> int:
+    return index.workspace_bytes(N_max)
+
+
+def vp_set_option(index: Index, name: str, value: int):
+    index.set_option(name, value)
+
+
+def vp_get_info(index: Index) -> dict:
+    return index.info()
+
+
+def vp_destroy(index: Index):
+    index.close()
+
+
+def vp_last_error() -> str:
+    return last_error()

@@ -1,0 +1,126 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every symbol the
+header declares, and rejects bad arguments on the host before touching a GPU.
+No compute call is made here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2208_06874_amd import vp
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "vp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(vp_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared_functions()
+    assert set(names) == set(vp.EXPORTS)
+    L = vp.lib()
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_python_binding_has_the_same_names():
+    import paper_2208_06874_amd as P
+    for n in ("vp_build", "vp_project", "vp_project_full", "vp_project_debug_logits", "vp_workspace_bytes",
+              "vp_set_option", "vp_get_info", "vp_destroy", "vp_last_error"):
+        assert callable(getattr(P, n))
+
+
+def _desc(d=64, V=100, K=3, lists=None, k_max=4, flags=0):
+    if lists is None:
+        lists = [np.arange(0, 40, 2), np.arange(5, 60), np.array([99])]
+    off = np.zeros(len(lists) + 1, np.int64)
+    np.cumsum([len(x) for x in lists], out=off[1:])
+    ids = (np.concatenate(lists) if len(lists) else np.zeros(0)).astype(np.int32)
+    desc = vp.make_desc(d, V, K, 0x1000, 0x1000, 0x1000, off, ids, None, 0, k_max, flags)
+    return desc, off, ids   # keep the arrays alive
+
+
+def test_build_bytes_valid_and_monotone():
+    L = vp.lib()
+    d1, *_k1 = _desc()
+    n1 = L.vp_build_bytes(ctypes.byref(d1))
+    assert n1 > 0 and n1 % 256 == 0
+    d2, *_k2 = _desc(lists=[np.arange(0, 80), np.arange(5, 60), np.array([99])])
+    assert L.vp_build_bytes(ctypes.byref(d2)) > n1
+    # slab bytes: candidate groups of 16, d padded to 256, 2 bytes each
+    info_groups = sum((len(x) + 15) // 16 for x in [np.arange(0, 40, 2), np.arange(5, 60), np.array([99])])
+    assert n1 >= info_groups * 16 * 256 * 2 + ((100 + 15) // 16) * 16 * 256 * 2
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(d=60), vp.VP_ERR_UNSUPPORTED),          # d % 8 != 0
+    (dict(d=0), vp.VP_ERR_UNSUPPORTED),
+    (dict(d=8192), vp.VP_ERR_UNSUPPORTED),
+    (dict(K=0, lists=[]), vp.VP_ERR_UNSUPPORTED),
+    (dict(k_max=0), vp.VP_ERR_UNSUPPORTED),
+    (dict(k_max=33), vp.VP_ERR_UNSUPPORTED),
+    (dict(flags=1), vp.VP_ERR_INVALID_ARG),
+    (dict(lists=[np.arange(4), np.zeros(0, int), np.arange(3)]), vp.VP_ERR_UNSUPPORTED),   # empty set
+    (dict(lists=[np.array([3, 2]), np.arange(4), np.arange(3)]), vp.VP_ERR_INVALID_ARG),   # unsorted
+    (dict(lists=[np.array([2, 2]), np.arange(4), np.arange(3)]), vp.VP_ERR_INVALID_ARG),   # duplicate
+    (dict(lists=[np.array([2, 100]), np.arange(4), np.arange(3)]), vp.VP_ERR_INVALID_ARG),  # id >= V
+    (dict(lists=[np.array([-1, 4]), np.arange(4), np.arange(3)]), vp.VP_ERR_INVALID_ARG),  # id < 0
+])
+def test_build_rejects_bad_descriptions_on_the_host(kw, status):
+    L = vp.lib()
+    desc, *_keep = _desc(**kw)
+    h = ctypes.c_void_p()
+    st = L.vp_build(ctypes.byref(desc), None, ctypes.byref(h))
+    assert st == status, vp.last_error()
+    assert h.value is None
+    assert vp.last_error() != ""
+
+
+def test_build_rejects_null_and_small_arena_before_any_gpu_work():
+    L = vp.lib()
+    desc, *_keep = _desc()
+    h = ctypes.c_void_p()
+    assert L.vp_build(ctypes.byref(desc), None, ctypes.byref(h)) == vp.VP_ERR_INVALID_ARG   # null arena
+    desc.arena = 0x100000
+    desc.arena_bytes = 1024
+    assert L.vp_build(ctypes.byref(desc), None, ctypes.byref(h)) == vp.VP_ERR_WORKSPACE
+    desc.arena = 0x100010                      # misaligned
+    desc.arena_bytes = 1 << 30
+    assert L.vp_build(ctypes.byref(desc), None, ctypes.byref(h)) == vp.VP_ERR_INVALID_ARG
+    desc.W = None
+    desc.arena = 0x100000
+    assert L.vp_build(ctypes.byref(desc), None, ctypes.byref(h)) == vp.VP_ERR_INVALID_ARG
+    assert L.vp_build(None, None, ctypes.byref(h)) == vp.VP_ERR_INVALID_ARG
+    assert L.vp_build_bytes(None) == 0
+
+
+def test_calls_reject_null_index():
+    L = vp.lib()
+    assert L.vp_project(None, None, 1, 1, None, None, None, None, 0, None) == vp.VP_ERR_INVALID_ARG
+    assert L.vp_project_full(None, None, 1, 1, None, None, None, 0, None) == vp.VP_ERR_INVALID_ARG
+    assert L.vp_project_debug_logits(None, None, 1, 0, None, None, None, 0, None, 0, None) == vp.VP_ERR_INVALID_ARG
+    assert L.vp_workspace_bytes(None, 4) == 0
+    assert L.vp_set_option(None, b"rstar", 1) == vp.VP_ERR_INVALID_ARG
+    assert L.vp_get_info(None, None) == vp.VP_ERR_INVALID_ARG
+    L.vp_destroy(None)   # no-op
+
+
+def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
+    monkeypatch.setattr(vp, "_lib", None)
+    monkeypatch.setattr(vp, "LIB_PATH", str(tmp_path / "libvp.so"))
+    with pytest.raises(RuntimeError, match="missing"):
+        vp.lib()
+
+
+def test_product_path_does_not_reach_the_oracle():
+    """Nothing under the package may import or name the oracle."""
+    pkg = os.path.join(ROOT, "paper_2208_06874_amd")
+    for base, _dirs, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(base, f)).read()
+                assert "vp_oracle" not in text and "import oracle" not in text and "from oracle" not in text, f

@@ -1,0 +1,341 @@
+"""GPU parity: the HIP library, called through the C ABI, against the CPU oracle
+on the same seeded inputs, element by element.  Run with -m gpu on an MI355X."""
+import numpy as np
+import pytest
+
+from paper_2208_06874_amd import workloads as wl
+from tests import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+
+
+def _torch():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    return torch
+
+
+class Built:
+    """A workload with its packed index on the GPU."""
+
+    def __init__(self, W, b, C, cand_off, cand_ids, k_max=8, cfg=None):
+        torch = _torch()
+        from paper_2208_06874_amd import vp
+        self.cfg = cfg
+        self.W, self.b, self.C = W, b, C
+        self.cand_off, self.cand_ids = np.asarray(cand_off, np.int64), np.asarray(cand_ids, np.int32)
+        dev = torch.device("cuda:0")
+        self.dev = dev
+        Wt = torch.from_numpy(W).to(dev)
+        bt = torch.from_numpy(b).to(dev)
+        Ct = torch.from_numpy(C).to(dev)
+        self.index = vp.vp_build(Wt, bt, Ct, self.cand_off, self.cand_ids, k_max=k_max)
+        torch.cuda.synchronize()
+        del Wt, bt, Ct   # the index keeps its own packed copies
+
+    def rows(self, H):
+        import torch
+        return torch.from_numpy(np.ascontiguousarray(H)).to(self.dev)
+
+    def project(self, H, k, **kw):
+        import torch
+        ids, logp, g = self.index.project(self.rows(H), k, **kw)
+        torch.cuda.synchronize()
+        return pu.to_np(ids), pu.to_np(logp), pu.to_np(g)
+
+    def project_full(self, H, k):
+        import torch
+        ids, logp = self.index.project_full(self.rows(H), k)
+        torch.cuda.synchronize()
+        return pu.to_np(ids), pu.to_np(logp)
+
+    def debug(self, H, full=False):
+        import torch
+        g, offs, z = self.index.debug_logits(self.rows(H), full=full)
+        torch.cuda.synchronize()
+        return pu.to_np(g), pu.to_np(offs), pu.to_np(z)
+
+
+def _from_config(name, **scale):
+    _torch()
+    cfg = wl.CONFIGS[name]
+    if scale:
+        cfg = wl.scaled(cfg, **scale)
+    W, b, C = wl.make_model(cfg)
+    off, ids = wl.make_candidates(cfg, W, b, C, device="cuda:0")
+    return Built(W, b, C, off, ids, k_max=8, cfg=cfg)
+
+
+@pytest.fixture(scope="module")
+def tiny():
+    return _from_config("tiny")
+
+
+@pytest.fixture(scope="module")
+def mid():
+    return _from_config("mid")
+
+
+@pytest.fixture(scope="module")
+def large():
+    return _from_config("large")
+
+
+@pytest.fixture(scope="module")
+def skewed():
+    return _from_config("skewed")
+
+
+def _random_lists(r, K, V, lo, hi):
+    lists = [np.sort(r.choice(V, size=int(r.integers(lo, hi + 1)), replace=False)) for _ in range(K)]
+    off = np.zeros(K + 1, np.int64)
+    np.cumsum([len(x) for x in lists], out=off[1:])
+    return off, np.concatenate(lists).astype(np.int32)
+
+
+def _small_model(seed, d, V, K):
+    r = np.random.default_rng(seed)
+    W = (r.standard_normal((d, V)) / np.sqrt(d)).astype(np.float16)
+    b = (r.standard_normal(V) * 0.3).astype(np.float16)
+    C = r.standard_normal((K, d)).astype(np.float16)
+    return r, W, b, C
+
+
+def _rows(r, C, N, noise=0.3, clusters=None):
+    q = r.integers(0, C.shape[0], N) if clusters is None else np.asarray(clusters)
+    return (C[q].astype(np.float32) + noise * r.standard_normal((N, C.shape[1]))).astype(np.float16)
+
+
+def _full_check(oracle, B, H, k, with_logits=True):
+    ids, logp, g = B.project(H, k)
+    if with_logits:
+        g2, offs, z = B.debug(H)
+        assert np.array_equal(g, g2)
+    else:
+        offs = z = None
+    return pu.check_projection(oracle, B.W, B.b, B.C, B.cand_off, B.cand_ids, H, k, ids, logp, g, z, offs)
+
+
+# ------------------------------------------------------------------ the five workloads
+def test_tiny_config(oracle, tiny):
+    cfg = tiny.cfg
+    H, q = wl.make_rows(cfg, tiny.C)
+    st = _full_check(oracle, tiny, H, cfg.k)
+    print("tiny", st)
+    ids, logp = tiny.project_full(H, cfg.k)
+    _, _, zf = tiny.debug(H, full=True)
+    print("tiny full", pu.check_full(oracle, tiny.W, tiny.b, H, cfg.k, ids, logp, zf))
+
+
+def test_mid_config(oracle, mid):
+    cfg = mid.cfg
+    H, q = wl.make_rows(cfg, mid.C)
+    print("mid", _full_check(oracle, mid, H, cfg.k))
+    ids, logp = mid.project_full(H[:8], cfg.k)
+    print("mid full", pu.check_full(oracle, mid.W, mid.b, H[:8], cfg.k, ids, logp))
+
+
+def test_large_config(oracle, large):
+    cfg = large.cfg
+    H, q = wl.make_rows(cfg, large.C)
+    print("large", _full_check(oracle, large, H, cfg.k))
+    # the full projection at this size: a sample of rows the oracle can afford
+    ids, logp = large.project_full(H, cfg.k)
+    sample = np.array([0, 17, 101, 255])
+    print("large full", pu.check_full(oracle, large.W, large.b, H[sample], cfg.k, ids[sample], logp[sample]))
+
+
+@pytest.mark.parametrize("N", [1, 4, 16, 64, 256, 1024])
+def test_decode_size_sweep(oracle, large, N):
+    """Greedy top-1 over the decode-size sweep, rows uniform over clusters."""
+    cfg = wl.CONFIGS["sweep"]
+    H, q = wl.make_rows(cfg, large.C, N=N, stream=10 + N)
+    print("sweep", N, _full_check(oracle, large, H, 1, with_logits=(N <= 64)))
+
+
+def test_skewed_config(oracle, skewed):
+    cfg = skewed.cfg
+    H, q = wl.make_rows(cfg, skewed.C)
+    counts = np.bincount(q, minlength=cfg.K)
+    assert counts.max() > 300          # the Zipf head really is a big bucket
+    print("skewed", _full_check(oracle, skewed, H, cfg.k, with_logits=False))
+
+
+# ------------------------------------------------------------------------- edge cases
+def test_full_lists_equal_full_projection(oracle):
+    r, W, b, C = _small_model(1, 64, 1000, 4)
+    off, ids = wl.full_lists(4, 1000)
+    B = Built(W, b, C, off, ids, k_max=8)
+    H = _rows(r, C, 37)
+    a_ids, a_logp, g = B.project(H, 5)
+    f_ids, f_logp = B.project_full(H, 5)
+    assert np.array_equal(a_ids, f_ids)
+    assert np.allclose(a_logp, f_logp, rtol=0, atol=1e-5)
+    pu.check_full(oracle, W, b, H, 5, f_ids, f_logp, B.debug(H, full=True)[2])
+    pu.check_projection(oracle, W, b, C, off, ids, H, 5, a_ids, a_logp, g)
+
+
+def test_ragged_shapes(oracle):
+    """d not a multiple of the k-tile, list sizes not multiples of 16, N spanning several row groups."""
+    r, W, b, C = _small_model(2, 40, 777, 7)
+    off, ids = _random_lists(r, 7, 777, 1, 130)
+    B = Built(W, b, C, off, ids, k_max=8)
+    for N in (1, 15, 16, 17, 100):
+        H = _rows(r, C, N)
+        print("ragged", N, _full_check(oracle, B, H, 3))
+
+
+def test_fewer_candidates_than_k(oracle):
+    r, W, b, C = _small_model(3, 64, 300, 3)
+    lists = [np.array([5]), np.array([1, 7, 299]), np.sort(r.choice(300, 40, replace=False))]
+    off = np.array([0, 1, 4, 44], np.int64)
+    ids = np.concatenate(lists).astype(np.int32)
+    B = Built(W, b, C, off, ids, k_max=8)
+    H = _rows(r, C, 9, clusters=[0, 1, 2, 0, 1, 2, 0, 0, 1])
+    st = _full_check(oracle, B, H, 8)
+    ids_g, logp_g, g = B.project(H, 8)
+    one = g == 0
+    assert np.all(ids_g[one, 0] == 5) and np.all(logp_g[one, 0] == 0.0) and np.all(ids_g[one, 1:] == -1)
+    print("few", st)
+
+
+def test_all_rows_one_cluster_and_one_row_per_cluster(oracle):
+    r, W, b, C = _small_model(4, 128, 5000, 40)
+    off, ids = _random_lists(r, 40, 5000, 200, 900)
+    B = Built(W, b, C, off, ids, k_max=8)
+    H = _rows(r, C, 300, clusters=np.full(300, 11))
+    ids_g, logp_g, g = B.project(H, 8)
+    assert np.all(g == 11)
+    pu.check_projection(oracle, W, b, C, off, ids, H, 8, ids_g, logp_g, g)
+    H = _rows(r, C, 40, clusters=np.arange(40))
+    ids_g, logp_g, g = B.project(H, 8)
+    assert np.array_equal(g, np.arange(40))
+    pu.check_projection(oracle, W, b, C, off, ids, H, 8, ids_g, logp_g, g)
+
+
+def test_duplicate_centroids_and_single_cluster(oracle):
+    r, W, b, C = _small_model(5, 64, 400, 6)
+    C = np.concatenate([C, C[[2]], C[[0]]], 0)        # clusters 6 and 7 duplicate 2 and 0
+    off, ids = _random_lists(r, 8, 400, 20, 60)
+    B = Built(W, b, C, off, ids, k_max=4)
+    H = _rows(r, C[:6], 24, noise=0.0, clusters=np.arange(24) % 6)    # rows equal to a centroid: exact ties
+    ids_g, logp_g, g = B.project(H, 4)
+    assert np.array_equal(g, np.arange(24) % 6)       # the lower index wins a tie
+    pu.check_projection(oracle, W, b, C, off, ids, H, 4, ids_g, logp_g, g)
+    B1 = Built(W, b, C[:1], off[:2], ids[: off[1]], k_max=4)
+    H = _rows(r, C, 5)
+    ids_g, logp_g, g = B1.project(H, 2)
+    assert np.all(g == 0)
+    pu.check_projection(oracle, W, b, C[:1], off[:2], ids[: off[1]], H, 2, ids_g, logp_g, g)
+
+
+def test_equal_logits_tie_goes_to_smaller_token(oracle):
+    r, W, b, C = _small_model(6, 64, 200, 2)
+    W[:, 150] = W[:, 20] = W[:, 99] = (W[:, 20].astype(np.float32) * 6).astype(np.float16)
+    b[150] = b[20] = b[99] = 1.0
+    off, ids = wl.full_lists(2, 200)
+    B = Built(W, b, C, off, ids, k_max=8)
+    H = _rows(r, C, 12)
+    a_ids, a_logp, g = B.project(H, 8)
+    f_ids, f_logp = B.project_full(H, 8)
+    for got in (a_ids, f_ids):
+        for row in got:
+            row = list(row)
+            if 20 in row and 99 in row and 150 in row:
+                assert row.index(20) < row.index(99) < row.index(150)
+    pu.check_projection(oracle, W, b, C, off, ids, H, 8, a_ids, a_logp, g)
+    pu.check_full(oracle, W, b, H, 8, f_ids, f_logp)
+
+
+def test_empty_batch_and_argument_errors():
+    torch = _torch()
+    from paper_2208_06874_amd import vp
+    r, W, b, C = _small_model(7, 64, 300, 3)
+    off, ids = _random_lists(r, 3, 300, 20, 60)
+    B = Built(W, b, C, off, ids, k_max=4)
+    H0 = torch.empty((0, 64), dtype=torch.float16, device=B.dev)
+    ids_g, logp_g, g = B.index.project(H0, 2)
+    assert ids_g.shape == (0, 2)
+    H = B.rows(_rows(r, C, 4))
+    sentinel = torch.full((4, 2), 77, dtype=torch.int32, device=B.dev)
+    with pytest.raises(vp.VpError) as e:
+        B.index.project(H, 5)                     # k > k_max
+    assert e.value.status == vp.VP_ERR_UNSUPPORTED
+    with pytest.raises(vp.VpError) as e:
+        B.index.project(H, 2, out_ids=sentinel, workspace=torch.empty(256, dtype=torch.uint8, device=B.dev))
+    assert e.value.status == vp.VP_ERR_WORKSPACE
+    torch.cuda.synchronize()
+    assert torch.all(sentinel == 77)              # outputs untouched on error
+    info = B.index.info()
+    assert info["n_total"] == off[-1] and info["K"] == 3 and info["d_pad"] == 256
+
+
+def test_largest_topk_and_wide_d(oracle):
+    r, W, b, C = _small_model(8, 1536, 3000, 5)
+    off, ids = _random_lists(r, 5, 3000, 100, 700)
+    B = Built(W, b, C, off, ids, k_max=32)
+    H = _rows(r, C, 20)
+    ids_g, logp_g, g = B.project(H, 32)
+    print("k32", pu.check_projection(oracle, W, b, C, off, ids, H, 32, ids_g, logp_g, g))
+    f_ids, f_logp = B.project_full(H, 32)
+    pu.check_full(oracle, W, b, H, 32, f_ids, f_logp)
+
+
+def test_gemv_loop_matches_oracle_and_mfma(oracle, tiny):
+    cfg = tiny.cfg
+    r = np.random.default_rng(9)
+    # buckets of 1..4 rows take the GEMV loop when rstar = 4
+    clusters = np.repeat(np.arange(8), [1, 2, 3, 4, 1, 2, 3, 4])
+    H = _rows(r, tiny.C, clusters.size, clusters=clusters)
+    ref = tiny.project(H, cfg.k)
+    tiny.index.set_option("rstar", 4)
+    try:
+        st = _full_check(oracle, tiny, H, cfg.k)
+        got = tiny.project(H, cfg.k)
+    finally:
+        tiny.index.set_option("rstar", 0)
+    print("gemv", st)
+    assert np.array_equal(got[2], ref[2])
+    assert np.allclose(got[1], ref[1], rtol=0, atol=1e-3)
+
+
+def test_split_granularity_does_not_change_results(oracle, tiny):
+    cfg = tiny.cfg
+    H, q = wl.make_rows(cfg, tiny.C, N=40, stream=7)
+    base = tiny.project(H, cfg.k)
+    for target in (1, 16, 300, 100000):
+        tiny.index.set_option("target_items", target)
+        tiny.index.set_option("full_target_items", target)
+        try:
+            got = tiny.project(H, cfg.k)
+            f_ids, f_logp = tiny.project_full(H[:5], cfg.k)
+        finally:
+            tiny.index.set_option("target_items", 8192)
+            tiny.index.set_option("full_target_items", 2048)
+        assert np.array_equal(got[0], base[0]) and np.array_equal(got[2], base[2])
+        assert np.allclose(got[1], base[1], rtol=0, atol=1e-4)
+        pu.check_full(oracle, tiny.W, tiny.b, H[:5], cfg.k, f_ids, f_logp)
+
+
+def test_results_are_deterministic(mid):
+    cfg = mid.cfg
+    H, q = wl.make_rows(cfg, mid.C, N=200, stream=3)
+    a = mid.project(H, cfg.k)
+    for _ in range(3):
+        c = mid.project(H, cfg.k)
+        for x, y in zip(a, c):
+            assert np.array_equal(x, y)
+    fa = mid.project_full(H[:20], cfg.k)
+    fc = mid.project_full(H[:20], cfg.k)
+    assert np.array_equal(fa[0], fc[0]) and np.array_equal(fa[1], fc[1])
+
+
+def test_many_rows_many_clusters(oracle):
+    """Row and cluster counts near the top of what the planner handles in one call."""
+    r, W, b, C = _small_model(10, 64, 4000, 2500)
+    off, ids = _random_lists(r, 2500, 4000, 17, 80)
+    B = Built(W, b, C, off, ids, k_max=2)
+    H = _rows(r, C, 9000)
+    ids_g, logp_g, g = B.project(H, 2)
+    print("many", pu.check_projection(oracle, W, b, C, off, ids, H, 2, ids_g, logp_g, g))
