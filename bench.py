@@ -1,0 +1,169 @@
+#!/usr/bin/env python3
+"""Benchmark of the clustered vocabulary projection on one MI355X.
+
+A step is one vp_project call (centroid selection, bucketing, slab projection
+with fused log-softmax/top-k, merge) over one batch of synthetic hidden rows,
+inputs already resident in HBM.  The workload is the large multilingual shape
+(d = 1024, V = 250,000, K = 1,000 clusters, N = 256 rows, top-8) the metric is
+quoted on.  Distinct batches are cycled so that consecutive steps touch
+different slabs.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, vendor figure
+
+# HBM bytes per launch of the projection kernel from rocprofv3 --pmc runs
+# (FETCH_SIZE / WRITE_SIZE scaled by a copy kernel of known size); filled in from
+# the summaries under profiles/ for the workloads that have been profiled.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="large", help="tiny | mid | large | skewed")
+    ap.add_argument("--rows", type=int, default=None, help="rows per step (default: the workload's N)")
+    ap.add_argument("--topk", type=int, default=None)
+    ap.add_argument("--batches", type=int, default=16, help="distinct hidden batches cycled through")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-full", action="store_true")
+    ap.add_argument("--option", action="append", default=[], help="library option name=value")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); "
+              "--gpus %d is not supported, use --gpus 1" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2208_06874_amd as P
+    from paper_2208_06874_amd import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    cfg = wl.CONFIGS[args.workload]
+    N = args.rows or cfg.N
+    k = args.topk or cfg.k
+    t_gen = time.perf_counter()
+    W, b, C = wl.make_model(cfg)
+    cand_off, cand_ids = wl.make_candidates(cfg, W, b, C, device="cuda:0")
+    index = P.vp_build(torch.from_numpy(W).to(dev), torch.from_numpy(b).to(dev), torch.from_numpy(C).to(dev),
+                       cand_off, cand_ids, k_max=max(8, k))
+    for opt in args.option:
+        name, val = opt.split("=")
+        index.set_option(name, int(val))
+    info = index.info()
+    sizes = cand_off[1:] - cand_off[:-1]
+    batches_np = [wl.make_rows(cfg, C, N=N, stream=1 + i)[0] for i in range(args.batches)]
+    batches = [torch.from_numpy(h).to(dev) for h in batches_np]
+    out_ids = [torch.empty((N, k), dtype=torch.int32, device=dev) for _ in batches]
+    out_logp = [torch.empty((N, k), dtype=torch.float32, device=dev) for _ in batches]
+    out_g = [torch.empty((N,), dtype=torch.int32, device=dev) for _ in batches]
+    ws = index.workspace(N)
+    torch.cuda.synchronize()
+    t_gen = time.perf_counter() - t_gen
+
+    def step(i):
+        j = i % len(batches)
+        index.project(batches[j], k, out_ids=out_ids[j], out_logp=out_logp[j], out_cluster=out_g[j], workspace=ws)
+
+    def step_full(i):
+        j = i % len(batches)
+        index.project_full(batches[j], k, out_ids=full_ids, out_logp=full_logp, workspace=ws)
+
+    def timed(fn, warmup, steps):
+        for i in range(warmup):
+            fn(i)
+        torch.cuda.synchronize()
+        index.get_profile()                      # drop warm-up launches
+        index.set_option("profile", 1)
+        t0 = time.perf_counter()
+        for i in range(steps):
+            fn(i)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        kernel_ms, launches = index.get_profile()
+        index.set_option("profile", 0)
+        return (t1 - t0) * 1e3 / steps, kernel_ms / max(launches, 1), launches
+
+    ms_step, ms_kernel, launches = timed(step, args.warmup, args.steps)
+    rows_per_s = N / (ms_step * 1e-3)
+
+    # algorithmic bytes of one projection-kernel launch: every candidate of every occupied
+    # cluster once (fp16 column + fp32 bias), plus the hidden rows
+    d = cfg.d
+    per_batch = []
+    for g in out_g:
+        occ = np.unique(g.cpu().numpy())
+        per_batch.append(float(sizes[occ].sum()) * (2 * d + 4) + N * 2 * d)
+    used = [per_batch[i % len(batches)] for i in range(args.steps)]
+    alg_bytes = float(np.mean(used))
+    achieved = alg_bytes / (ms_kernel * 1e-3) / 1e9
+    traffic = MEASURED_TRAFFIC_BYTES.get((args.workload, N))
+
+    result = {
+        "metric": "projected rows/sec fp16 at V=250K,d=1024; speedup vs full-vocab projection",
+        "value": rows_per_s, "unit": "rows/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": "%s: d=%d V=%d K=%d N=%d top-%d, %d-%d candidates per cluster" % (
+            cfg.name, cfg.d, cfg.V, cfg.K, N, k, int(sizes.min()), int(sizes.max())),
+            "batches_cycled": len(batches), "slab_bytes": info["slab_bytes"],
+            "occupied_clusters_per_step": float(np.mean([np.unique(g.cpu().numpy()).size for g in out_g])),
+            "setup_seconds": t_gen},
+        "roofline": {"bound": "hbm", "kernel": "project_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": ms_kernel, "launches": launches},
+    }
+
+    if not args.no_full:
+        full_ids = torch.empty((N, k), dtype=torch.int32, device=dev)
+        full_logp = torch.empty((N, k), dtype=torch.float32, device=dev)
+        fsteps = max(5, args.steps // 4)
+        ms_full, ms_full_kernel, _ = timed(step_full, max(2, args.warmup // 4), fsteps)
+        full_bytes = cfg.V * (2.0 * d + 4) + N * 2 * d
+        result["full_vocab"] = {"rows_per_s": N / (ms_full * 1e-3), "ms_per_step": ms_full,
+                                "kernel_ms": ms_full_kernel,
+                                "hbm_frac": full_bytes / (ms_full_kernel * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                "mfma_tflops": 2.0 * N * d * cfg.V / (ms_full_kernel * 1e-3) / 1e12}
+        result["speedup_vs_full"] = ms_full / ms_step
+
+    if not args.no_cpu_baseline:
+        # the CPU oracle, as it stands, on the first batch of the same workload
+        from oracle import vp_oracle
+        vp_oracle.build()
+        threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+        t0 = time.perf_counter()
+        reps = 0
+        while True:
+            ref = vp_oracle.project(W, b, C, cand_off, cand_ids, batches_np[reps % len(batches_np)], k)
+            reps += 1
+            if reps == 1:
+                first = ref
+            if time.perf_counter() - t0 > 10.0 or reps >= 8:
+                break
+        cpu_s = time.perf_counter() - t0
+        result["cpu_baseline"] = {"value": N * reps / cpu_s, "unit": "rows/s", "cores": threads, "kind": "oracle",
+                                  "sample": "%d batch(es) of %d rows of the same workload, %.1f s" % (reps, N, cpu_s)}
+        gi, gl, gg = out_ids[0].cpu().numpy(), out_logp[0].cpu().numpy(), out_g[0].cpu().numpy()
+        same_g = gg == first["g"]
+        same_ids = (gi == first["ids"]).all(1) & same_g
+        err = np.abs(gl[same_ids] - first["logp"][same_ids]).max() if same_ids.any() else float("nan")
+        result["parity"] = {"rows": N, "clusters_equal": int(same_g.sum()), "topk_ids_equal_rows": int(same_ids.sum()),
+                            "max_abs_logp_err": float(err)}
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -99,6 +99,7 @@ vp_status vp_get_info(const vp_index *idx, vp_index_info *info);
  *   "rstar"         buckets with at most this many rows use the dot-product
  *                   GEMV loop, larger ones the MFMA loop (default 0, max 4)
  *   "full_target_items"  same as target_items for vp_project_full
+ *   "profile"       1: time the projection kernel with HIP events (vp_get_profile)
  * Unknown name or out-of-range value: VP_ERR_INVALID_ARG. */
 vp_status vp_set_option(vp_index *idx, const char *name, int64_t value);
 
@@ -140,6 +141,14 @@ vp_status vp_project_debug_logits(const vp_index *idx, const void *hidden, int32
                                   int32_t *out_cluster, int64_t *out_row_offsets,
                                   float *out_logits, size_t out_logits_capacity,
                                   void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Benchmark aid: after vp_set_option(idx, "profile", 1) every vp_project and
+ * vp_project_full brackets its projection kernel (the kernel that streams the
+ * slabs) with a pair of HIP events on the call's stream.  vp_get_profile waits
+ * for the recorded events, returns the summed kernel time in milliseconds and
+ * the number of launches, and forgets them.  At most 16384 launches are kept
+ * between two calls.  Not meant for use under graph capture. */
+vp_status vp_get_profile(vp_index *idx, double *kernel_ms_total, int64_t *launches);
 
 /* Frees the host handle only; the arena stays the caller's. */
 void vp_destroy(vp_index *idx);

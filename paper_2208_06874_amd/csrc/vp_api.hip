@@ -8,6 +8,7 @@
 #include <cstdio>
 #include <cstring>
 #include <new>
+#include <utility>
 #include <vector>
 
 #include "vp.h"
@@ -43,6 +44,13 @@ struct ArenaLayout {
 
 }  // namespace
 
+// Event pairs around the projection kernel (benchmark aid, see vp_get_profile).
+struct VpProfile {
+    bool on = false;
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> pool;   // created on demand, reused
+    size_t used = 0;
+};
+
 struct vp_index {
     int d, V, K, k_max;
     ArenaLayout L;
@@ -52,6 +60,7 @@ struct vp_index {
     const void *cp;
     const float *cnorm;
     int target_items, full_target_items, rstar;
+    VpProfile *prof;
 };
 
 namespace {
@@ -181,6 +190,25 @@ vp_status launch_status(const char *fn)
     return VP_OK;
 }
 
+constexpr size_t PROFILE_MAX = 16384;
+
+// Returns the event pair to bracket the next projection kernel with, or null.
+std::pair<hipEvent_t, hipEvent_t> *profile_slot(const vp_index *I)
+{
+    VpProfile *P = I->prof;
+    if (!P || !P->on || P->used >= PROFILE_MAX) return nullptr;
+    if (P->used == P->pool.size()) {
+        hipEvent_t a, b;
+        if (hipEventCreate(&a) != hipSuccess) return nullptr;
+        if (hipEventCreate(&b) != hipSuccess) {
+            (void)hipEventDestroy(a);
+            return nullptr;
+        }
+        P->pool.emplace_back(a, b);
+    }
+    return &P->pool[P->used++];
+}
+
 // The kernel sequence shared by vp_project and the clustered debug entry.
 vp_status run_clustered(const char *fn, const vp_index *I, const void *hidden, int N, int k, int32_t *out_ids,
                         float *out_logp, int32_t *out_cluster, char *ws, int64_t *dbg_row_off, float *dbg_logits,
@@ -211,8 +239,11 @@ vp_status run_clustered(const char *fn, const vp_index *I, const void *hidden, i
     const long row_groups = (long)row_tiles + std::min(N, I->K);
     const long by_tiles = row_groups * ceil_div(I->L.max_tiles, VP_WG_WAVES);
     const int grid_items = (int)std::min<long>(max_items, by_tiles);
+    auto *ev = profile_slot(I);
+    if (ev) (void)hipEventRecord(ev->first, st);
     vpk_project(I->clusters, hidden, I->d, perm, items, hdr, grid_items, k, I->rstar, partials, dbg_logits,
                 dbg_row_off, st);
+    if (ev) (void)hipEventRecord(ev->second, st);
     if (out_ids)
         vpk_merge(I->clusters, perm, g, row_item0, row_stride, row_nit, items, partials, k, N, out_ids, out_logp, st);
     return launch_status(fn);
@@ -237,8 +268,11 @@ vp_status run_full(const char *fn, const vp_index *I, const void *hidden, int N,
     const long by_tiles = row_groups * ceil_div(I->L.vtiles, VP_WG_WAVES);
     const int grid_items = (int)std::min<long>(max_items, by_tiles);
     // the GEMV loop is reserved for the clustered buckets; the full projection keeps its rows in one bucket
+    auto *ev = profile_slot(I);
+    if (ev) (void)hipEventRecord(ev->first, st);
     vpk_project(I->full, hidden, I->d, perm, items, hdr, grid_items, k, N <= I->rstar ? I->rstar : 0, partials,
                 dbg_logits, dbg_row_off, st);
+    if (ev) (void)hipEventRecord(ev->second, st);
     if (out_ids)
         vpk_merge(I->full, perm, nullptr, row_item0, row_stride, row_nit, items, partials, k, N, out_ids, out_logp,
                   st);
@@ -338,6 +372,7 @@ vp_status vp_build(const vp_build_desc *D, void *hip_stream, vp_index **out)
     I->target_items = 8192;
     I->full_target_items = 2048;
     I->rstar = 0;
+    I->prof = new (std::nothrow) VpProfile();
     *out = I;
     return VP_OK;
 }
@@ -373,6 +408,12 @@ vp_status vp_set_option(vp_index *I, const char *name, int64_t value)
             return fail(VP_ERR_INVALID_ARG, "vp_set_option: rstar = %lld must be in [0, %d]", (long long)value,
                         VP_GEMV_MAX_ROWS);
         I->rstar = (int)value;
+        return VP_OK;
+    }
+    if (!std::strcmp(name, "profile")) {
+        if (value != 0 && value != 1) return fail(VP_ERR_INVALID_ARG, "vp_set_option: profile must be 0 or 1");
+        if (!I->prof) return fail(VP_ERR_INVALID_ARG, "vp_set_option: profiling unavailable");
+        I->prof->on = value == 1;
         return VP_OK;
     }
     return fail(VP_ERR_INVALID_ARG, "vp_set_option: unknown option '%s'", name);
@@ -425,6 +466,39 @@ vp_status vp_project_debug_logits(const vp_index *I, const void *hidden, int32_t
                          out_row_offsets, out_logits, st);
 }
 
-void vp_destroy(vp_index *I) { delete I; }
+vp_status vp_get_profile(vp_index *I, double *kernel_ms_total, int64_t *launches)
+{
+    if (!I || !kernel_ms_total || !launches) return fail(VP_ERR_INVALID_ARG, "vp_get_profile: null argument");
+    *kernel_ms_total = 0.0;
+    *launches = 0;
+    VpProfile *P = I->prof;
+    if (!P) return VP_OK;
+    for (size_t i = 0; i < P->used; ++i) {
+        hipError_t e = hipEventSynchronize(P->pool[i].second);
+        float ms = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, P->pool[i].first, P->pool[i].second);
+        if (e != hipSuccess) {
+            P->used = 0;
+            return fail(VP_ERR_HIP, "vp_get_profile: %s", hipGetErrorString(e));
+        }
+        *kernel_ms_total += ms;
+        *launches += 1;
+    }
+    P->used = 0;
+    return VP_OK;
+}
+
+void vp_destroy(vp_index *I)
+{
+    if (!I) return;
+    if (I->prof) {
+        for (auto &p : I->prof->pool) {
+            (void)hipEventDestroy(p.first);
+            (void)hipEventDestroy(p.second);
+        }
+        delete I->prof;
+    }
+    delete I;
+}
 
 }  // extern "C"

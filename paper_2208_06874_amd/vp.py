@@ -20,7 +20,8 @@ STATUS_NAMES = {0: "VP_OK", 1: "VP_ERR_INVALID_ARG", 2: "VP_ERR_UNSUPPORTED", 3:
                 4: "VP_ERR_HIP"}
 
 EXPORTS = ("vp_build_bytes", "vp_build", "vp_get_info", "vp_set_option", "vp_workspace_bytes",
-           "vp_project", "vp_project_full", "vp_project_debug_logits", "vp_destroy", "vp_last_error")
+           "vp_project", "vp_project_full", "vp_project_debug_logits", "vp_get_profile", "vp_destroy",
+           "vp_last_error")
 
 
 class VpError(RuntimeError):
@@ -74,6 +75,8 @@ def lib():
         L.vp_project_debug_logits.restype = ctypes.c_int
         L.vp_project_debug_logits.argtypes = [vp, vp, ctypes.c_int32, ctypes.c_int32, vp, vp, vp,
                                               ctypes.c_size_t, vp, ctypes.c_size_t, vp]
+        L.vp_get_profile.restype = ctypes.c_int
+        L.vp_get_profile.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
         L.vp_destroy.restype = None
         L.vp_destroy.argtypes = [vp]
         _lib = L
@@ -149,6 +152,12 @@ class Index:
     def set_option(self, name: str, value: int):
         _check(lib().vp_set_option(self.handle, name.encode(), int(value)))
         self._ws = None
+
+    def get_profile(self):
+        """(summed projection-kernel milliseconds, launches) since the last call."""
+        ms, n = ctypes.c_double(), ctypes.c_int64()
+        _check(lib().vp_get_profile(self.handle, ctypes.byref(ms), ctypes.byref(n)))
+        return ms.value, n.value
 
     def workspace_bytes(self, N: int) -> int:
         return lib().vp_workspace_bytes(self.handle, N)
@@ -233,6 +242,10 @@ def vp_set_option(index: Index, name: str, value: int):
 
 def vp_get_info(index: Index) -> dict:
     return index.info()
+
+
+def vp_get_profile(index: Index):
+    return index.get_profile()
 
 
 def vp_destroy(index: Index):
