@@ -164,7 +164,8 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(
         v.nrows = min(VP_ROWS_PER_ITEM, rows - rg * VP_ROWS_PER_ITEM);
         v.tile0 = ch * tpi;
         v.ntiles = min(tpi, tiles - ch * tpi);
-        v.pad[0] = v.pad[1] = v.pad[2] = 0;
+        v.shared = rgs > 1;
+        v.pad[0] = v.pad[1] = 0;
         items[it] = v;
     }
     if (tid == 0) {
@@ -221,7 +222,8 @@ __global__ __launch_bounds__(256) void plan_full_kernel(
         v.nrows = min(VP_ROWS_PER_ITEM, N - rg * VP_ROWS_PER_ITEM);
         v.tile0 = ch * tpi;
         v.ntiles = min(tpi, vtiles - ch * tpi);
-        v.pad[0] = v.pad[1] = v.pad[2] = 0;
+        v.shared = rgs > 1;
+        v.pad[0] = v.pad[1] = 0;
         items[it] = v;
     }
     if (gtid == 0) {

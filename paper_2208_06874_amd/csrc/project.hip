@@ -89,15 +89,28 @@ __device__ inline void fold_logits(const float z[4], int c0, int k, RowState &st
 // (logit descending, position ascending) order used by every merge level.
 __device__ inline bool entry_before(float v, int i, float v2, int i2) { return v > v2 || (v == v2 && i < i2); }
 
-__global__ __launch_bounds__(VP_WG_THREADS) void project_kernel(
-    VpSlabSet set, const uint4 *__restrict__ hidden, int d, const int32_t *__restrict__ perm,
-    const VpItem *__restrict__ items, const VpPlanHeader *__restrict__ hdr, int k, int rstar,
+typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
+
+// One 16-byte piece of a slab tile.  Slabs that only this work item reads are
+// loaded with the non-temporal hint: they stream through once and should not
+// displace anything; slabs shared by several row groups use plain loads so
+// that the later groups find them in the L2.
+template <bool NT>
+__device__ inline uint4 load_piece(const uint4 *p)
+{
+    if (NT) {
+        const uintx4 v = __builtin_nontemporal_load(reinterpret_cast<const uintx4 *>(p));
+        return make_uint4(v.x, v.y, v.z, v.w);
+    }
+    return *p;
+}
+
+template <bool NT>
+__device__ inline void project_item(
+    const VpSlabSet &set, const uint4 *__restrict__ hidden, int d, const int32_t *__restrict__ perm,
+    const VpItem &item, int it, int tpw, int k, int rstar,
     float *__restrict__ partials, float *__restrict__ dbg_logits, const int64_t *__restrict__ dbg_row_off)
 {
-    const int it = blockIdx.x;
-    if (it >= hdr->total_items) return;
-    const VpItem item = items[it];
-    const int tpw = hdr->tiles_per_wave;
     const int KT = set.kt;
     const int X = KT * 4;                       // 16-byte pieces per padded row
     const int tid = threadIdx.x;
@@ -114,6 +127,22 @@ __global__ __launch_bounds__(VP_WG_THREADS) void project_kernel(
     float *hdr_m = reinterpret_cast<float *>(list_idx + VP_WG_WAVES * k * 64);   // [4][16]
     float *hdr_s = hdr_m + VP_WG_WAVES * 16;
     int *rowid = reinterpret_cast<int *>(hdr_s + VP_WG_WAVES * 16);             // [16]
+
+    // this wavefront's run of tiles; its first loads go out before anything else
+    const int ncand = set.n_cand[item.cluster];
+    const int toff = set.tile_off[item.cluster];
+    const uint4 *slab = reinterpret_cast<const uint4 *>(set.tiles) + (size_t)toff * KT * 64;
+    const float *bias = set.bias + (size_t)toff * VP_TILE_ITEMS;
+    const int tb = item.tile0 + wave * tpw;
+    const int te = min(tb + tpw, item.tile0 + item.ntiles);
+    const uint4 *sp = slab + (size_t)tb * KT * 64 + lane;
+    uint4 buf[PF];
+    float4 bcur = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (tb < te) {
+#pragma unroll
+        for (int u = 0; u < PF; ++u) buf[u] = load_piece<NT>(sp + (size_t)u * 64);
+        bcur = *reinterpret_cast<const float4 *>(bias + tb * VP_TILE_ITEMS + q * 4);
+    }
 
     if (tid < VP_ROWS_PER_ITEM) rowid[tid] = tid < item.nrows ? perm[item.perm_start + tid] : -1;
     for (int e = tid; e < VP_WG_WAVES * k * 64; e += VP_WG_THREADS) {
@@ -138,13 +167,6 @@ __global__ __launch_bounds__(VP_WG_THREADS) void project_kernel(
     }
     __syncthreads();
 
-    const int ncand = set.n_cand[item.cluster];
-    const int toff = set.tile_off[item.cluster];
-    const uint4 *slab = reinterpret_cast<const uint4 *>(set.tiles) + (size_t)toff * KT * 64;
-    const float *bias = set.bias + (size_t)toff * VP_TILE_ITEMS;
-
-    const int tb = item.tile0 + wave * tpw;
-    const int te = min(tb + tpw, item.tile0 + item.ntiles);
     const bool row_valid = n < item.nrows;
     RowState st;
     st.m = VP_NEG_BIG;
@@ -156,14 +178,9 @@ __global__ __launch_bounds__(VP_WG_THREADS) void project_kernel(
     const int64_t dbg_base = (dbg_logits && row_valid) ? dbg_row_off[rowid[n]] : 0;
 
     if (tb < te) {
-        const uint4 *sp = slab + (size_t)tb * KT * 64 + lane;
         const int S = (te - tb) * KT;   // 1 KiB steps; KT % 8 == 0
-        uint4 buf[PF];
-#pragma unroll
-        for (int u = 0; u < PF; ++u) buf[u] = sp[(size_t)u * 64];
         int kt = 0;
         int tile = tb;
-        float4 bcur = *reinterpret_cast<const float4 *>(bias + tile * VP_TILE_ITEMS + q * 4);
         floatx4 acc = {0.f, 0.f, 0.f, 0.f};        // MFMA: 4 candidates of row n
         float ga[VP_GEMV_MAX_ROWS] = {0.f, 0.f, 0.f, 0.f};   // GEMV: candidate n, k-slice q, rows 0..3
 
@@ -173,7 +190,7 @@ __global__ __launch_bounds__(VP_WG_THREADS) void project_kernel(
                 Frag a;
                 a.u = buf[u];
                 const int nx = s0 + PF + u;
-                if (nx < S) buf[u] = sp[(size_t)nx * 64];
+                if (nx < S) buf[u] = load_piece<NT>(sp + (size_t)nx * 64);
                 if (!gemv) {
                     Frag b;
                     b.u = ldsA[(kt + u) * 64 + lane];
@@ -301,6 +318,21 @@ __global__ __launch_bounds__(VP_WG_THREADS) void project_kernel(
             pi = bi;
         }
     }
+}
+
+__global__ __launch_bounds__(VP_WG_THREADS) void project_kernel(
+    VpSlabSet set, const uint4 *__restrict__ hidden, int d, const int32_t *__restrict__ perm,
+    const VpItem *__restrict__ items, const VpPlanHeader *__restrict__ hdr, int k, int rstar,
+    float *__restrict__ partials, float *__restrict__ dbg_logits, const int64_t *__restrict__ dbg_row_off)
+{
+    const int it = blockIdx.x;
+    if (it >= hdr->total_items) return;
+    const VpItem item = items[it];
+    const int tpw = hdr->tiles_per_wave;
+    if (item.shared)
+        project_item<false>(set, hidden, d, perm, item, it, tpw, k, rstar, partials, dbg_logits, dbg_row_off);
+    else
+        project_item<true>(set, hidden, d, perm, item, it, tpw, k, rstar, partials, dbg_logits, dbg_row_off);
 }
 
 }  // namespace

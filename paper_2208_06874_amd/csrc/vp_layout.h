@@ -29,7 +29,8 @@ struct VpItem {
     int32_t nrows;       // 1..16
     int32_t tile0;       // first candidate tile
     int32_t ntiles;      // candidate tiles of this item (split among the 4 wavefronts)
-    int32_t pad[3];
+    int32_t shared;      // 1 if other items (further row groups of the bucket) read the same tiles
+    int32_t pad[2];
 };
 
 // Header the planning kernel leaves for the projection and merge kernels.
