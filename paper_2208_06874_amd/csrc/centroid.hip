@@ -2,11 +2,11 @@
 //     g[r] = argmin_j ( ||C_j||^2 - 2 <h_r, C_j> ),  ties to the lowest j,
 // with ||C_j||^2 precomputed at build time.  The inner products of 16 rows
 // with 16 centroids are one v_mfma_f32_16x16x32_f16 per 32 k-values; every
-// lane then holds 4 scores of one row, keeps a running (min, argmin) and the
-// four lane groups of the wavefront are reduced with cross-lane shuffles.
-// The centroids are split into `parts` ranges handled by different
-// wavefronts so that small batches still fill the chip; the planning kernel
-// reduces the per-part minima.
+// lane then holds 4 scores of one row, keeps a running (min, argmin), the
+// four lane groups of the wavefront are reduced with cross-lane shuffles and
+// the four wavefronts of the workgroup through LDS.  The centroids are split
+// into `parts` ranges handled by different workgroups so that small batches
+// still fill the chip; the planning kernel reduces the per-part minima.
 #include <hip/hip_runtime.h>
 #include "vp_kernels.h"
 
@@ -20,6 +20,8 @@ union Frag {
     half8 h;
 };
 
+constexpr int CU = 8;   // k-tiles fetched together (k-tile counts are multiples of 8)
+
 __device__ inline bool score_less(float s, int j, float s2, int j2)
 {
     return s < s2 || (s == s2 && j < j2);
@@ -27,19 +29,18 @@ __device__ inline bool score_less(float s, int j, float s2, int j2)
 
 __global__ __launch_bounds__(256) void centroid_kernel(
     const uint4 *__restrict__ hidden, int N, int d, const uint4 *__restrict__ cp,
-    const float *__restrict__ cnorm, int K, int kt_count, int ctiles, int tiles_per_part, int parts,
+    const float *__restrict__ cnorm, int K, int kt_count, int ctiles, int tiles_per_wave, int parts,
     int2 *__restrict__ cpart)
 {
     const int wave = threadIdx.x >> 6;
     const int lane = threadIdx.x & 63;
     const int n = lane & 15;
     const int q = lane >> 4;
-    const int part = blockIdx.y * 4 + wave;
-    if (part >= parts) return;
+    const int part = blockIdx.y;
     const int row = blockIdx.x * 16 + n;
     const bool valid_row = row < N;
-    const int t0 = part * tiles_per_part;
-    const int t1 = min(t0 + tiles_per_part, ctiles);
+    const int t0 = (part * 4 + wave) * tiles_per_wave;
+    const int t1 = min(t0 + tiles_per_wave, ctiles);
     const int pieces_per_row = d >> 3;   // 16-byte pieces
     const uint4 *hrow = hidden + (size_t)(valid_row ? row : 0) * pieces_per_row;
 
@@ -48,14 +49,17 @@ __global__ __launch_bounds__(256) void centroid_kernel(
     for (int t = t0; t < t1; ++t) {
         floatx4 acc = {0.f, 0.f, 0.f, 0.f};
         const uint4 *ap = cp + (size_t)t * kt_count * 64 + lane;
-#pragma unroll 8
-        for (int kt = 0; kt < kt_count; ++kt) {
-            Frag a, b;
-            a.u = ap[(size_t)kt * 64];
-            const int piece = kt * 4 + q;
-            b.u = make_uint4(0, 0, 0, 0);
-            if (valid_row && piece < pieces_per_row) b.u = hrow[piece];
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a.h, b.h, acc, 0, 0, 0);
+        for (int kt0 = 0; kt0 < kt_count; kt0 += CU) {
+            Frag a[CU], b[CU];
+#pragma unroll
+            for (int u = 0; u < CU; ++u) {
+                a[u].u = ap[(size_t)(kt0 + u) * 64];
+                const int piece = (kt0 + u) * 4 + q;
+                b[u].u = make_uint4(0, 0, 0, 0);
+                if (valid_row && piece < pieces_per_row) b[u].u = hrow[piece];
+            }
+#pragma unroll
+            for (int u = 0; u < CU; ++u) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[u].h, b[u].h, acc, 0, 0, 0);
         }
         const float4 cn = *reinterpret_cast<const float4 *>(cnorm + t * 16 + q * 4);
         const float cnv[4] = {cn.x, cn.y, cn.z, cn.w};
@@ -78,15 +82,32 @@ __global__ __launch_bounds__(256) void centroid_kernel(
             best_j = j2;
         }
     }
-    if (q == 0 && valid_row) cpart[(size_t)row * parts + part] = make_int2(__float_as_int(best_s), best_j);
+    __shared__ float ws[4][16];
+    __shared__ int wj[4][16];
+    if (q == 0) {
+        ws[wave][n] = best_s;
+        wj[wave][n] = best_j;
+    }
+    __syncthreads();
+    if (wave == 0 && q == 0 && valid_row) {
+#pragma unroll
+        for (int w = 1; w < 4; ++w) {
+            if (score_less(ws[w][n], wj[w][n], best_s, best_j)) {
+                best_s = ws[w][n];
+                best_j = wj[w][n];
+            }
+        }
+        cpart[(size_t)row * parts + part] = make_int2(__float_as_int(best_s), best_j);
+    }
 }
 
 }  // namespace
 
+// parts: workgroups along the centroid axis; each of their 4 wavefronts takes tiles_per_wave tiles.
 void vpk_centroid(const void *hidden, int N, int d, const void *cp, const float *cnorm, int K, int kt,
-                  int ctiles, int tiles_per_part, int parts, void *cpart, hipStream_t st)
+                  int ctiles, int tiles_per_wave, int parts, void *cpart, hipStream_t st)
 {
-    dim3 grid((N + 15) / 16, (parts + 3) / 4);
+    dim3 grid((N + 15) / 16, parts);
     hipLaunchKernelGGL(centroid_kernel, grid, dim3(256), 0, st, (const uint4 *)hidden, N, d, (const uint4 *)cp,
-                       cnorm, K, kt, ctiles, tiles_per_part, parts, (int2 *)cpart);
+                       cnorm, K, kt, ctiles, tiles_per_wave, parts, (int2 *)cpart);
 }

@@ -14,39 +14,44 @@ constexpr int MERGE_THREADS = 256;
 __device__ inline float fast_exp(float x) { return __builtin_amdgcn_exp2f(x * LOG2E); }
 __device__ inline bool entry_before(float v, int i, float v2, int i2) { return v > v2 || (v == v2 && i < i2); }
 
+// One workgroup per row.  Thread t owns the parts t, t + 256, ...  The entries
+// of its first part are copied to LDS in one batch of loads; every part lists
+// its entries in (logit descending, position ascending) order, so a part only
+// ever offers its first entry not yet taken, and a round is one workgroup-wide
+// arg-max over those offers.
 __global__ __launch_bounds__(MERGE_THREADS) void merge_kernel(
-    VpSlabSet set, const int32_t *__restrict__ perm, const int32_t *__restrict__ g,
-    const int32_t *__restrict__ row_item0, const int32_t *__restrict__ row_stride,
-    const int32_t *__restrict__ row_nit, const VpItem *__restrict__ items,
-    const float *__restrict__ partials, int k, int32_t *__restrict__ out_ids, float *__restrict__ out_logp)
+    VpSlabSet set, const VpRowPlan *__restrict__ rowplan, const float *__restrict__ partials, int k,
+    int32_t *__restrict__ out_ids, float *__restrict__ out_logp)
 {
-    const int p = blockIdx.x;
+    const VpRowPlan rp = rowplan[blockIdx.x];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-    const int row = perm[p];
-    const int cluster = g ? g[row] : 0;
-    const int item0 = row_item0[p];
-    const int stride = row_stride[p];
-    const int nit = row_nit[p];
-    const int nloc = p - items[item0].perm_start;
+    const int nit = rp.nit;
     const int PFL = vp_partial_floats(k);
-    const float *base = partials + ((size_t)item0 * VP_ROWS_PER_ITEM + nloc) * PFL;
-    const size_t part_stride = (size_t)stride * VP_ROWS_PER_ITEM * PFL;
+    const float *base = partials + ((size_t)rp.item0 * VP_ROWS_PER_ITEM + rp.local) * PFL;
+    const size_t part_stride = (size_t)rp.stride * VP_ROWS_PER_ITEM * PFL;
 
+    extern __shared__ float staged[];            // [2k][256]: entries of each thread's first part
     __shared__ float red_v[MERGE_THREADS / 64];
     __shared__ float red_s[MERGE_THREADS / 64];
     __shared__ int red_i[MERGE_THREADS / 64];
 
-    // log-sum-exp over all parts
     float m = VP_NEG_BIG, s = 0.f;
-    for (int c = tid; c < nit; c += MERGE_THREADS) {
+    if (tid < nit) {
+        const float *pp = base + tid * part_stride;
+        m = pp[0];
+        s = pp[1];
+        for (int e = 0; e < 2 * k; ++e) staged[e * MERGE_THREADS + tid] = pp[2 + e];
+    }
+    for (int c = tid + MERGE_THREADS; c < nit; c += MERGE_THREADS) {
         const float *pp = base + c * part_stride;
         const float m2 = pp[0], s2 = pp[1];
         const float mn = fmaxf(m, m2);
         s = s * fast_exp(m - mn) + s2 * fast_exp(m2 - mn);
         m = mn;
     }
+    // log-sum-exp over all parts
 #pragma unroll
     for (int off = 1; off < 64; off <<= 1) {
         const float m2 = __shfl_xor(m, off), s2 = __shfl_xor(s, off);
@@ -68,16 +73,22 @@ __global__ __launch_bounds__(MERGE_THREADS) void merge_kernel(
     const float lse = M + __builtin_amdgcn_logf(S) * LN2;
     __syncthreads();
 
-    const int32_t *ids = set.ids ? set.ids + (size_t)set.tile_off[cluster] * VP_TILE_ITEMS : nullptr;
+    const int32_t *ids = set.ids ? set.ids + rp.ids_off : nullptr;
 
-    // k rounds: the best entry that comes after the previous winner.  Every part
-    // lists its entries in that order already, so its first such entry is its best.
+    int pos = 0;                                  // entries of the first part already taken
+    float cv = -__builtin_inff();
+    int ci = VP_IDX_NONE;
+    if (tid < nit) {
+        cv = staged[tid];
+        ci = __float_as_int(staged[k * MERGE_THREADS + tid]);
+    }
     float pv = __builtin_inff();
     int pi = -1;
     for (int t = 0; t < k; ++t) {
-        float bv = -__builtin_inff();
-        int bi = VP_IDX_NONE;
-        for (int c = tid; c < nit; c += MERGE_THREADS) {
+        float bv = cv;
+        int bi = ci;
+        // parts beyond the first of this thread (only when a row has more than 256 parts)
+        for (int c = tid + MERGE_THREADS; c < nit; c += MERGE_THREADS) {
             const float *pp = base + c * part_stride;
             for (int e = 0; e < k; ++e) {
                 const float v = pp[2 + e];
@@ -117,8 +128,13 @@ __global__ __launch_bounds__(MERGE_THREADS) void merge_kernel(
         __syncthreads();
         if (tid == 0) {
             const bool real = bi != VP_IDX_NONE;
-            out_ids[(size_t)row * k + t] = real ? (ids ? ids[bi] : bi) : -1;
-            out_logp[(size_t)row * k + t] = real ? bv - lse : -__builtin_inff();
+            out_ids[(size_t)rp.row * k + t] = real ? (ids ? ids[bi] : bi) : -1;
+            out_logp[(size_t)rp.row * k + t] = real ? bv - lse : -__builtin_inff();
+        }
+        if (bi != VP_IDX_NONE && ci == bi) {      // my first part won: offer its next entry
+            ++pos;
+            cv = pos < k ? staged[pos * MERGE_THREADS + tid] : -__builtin_inff();
+            ci = pos < k ? __float_as_int(staged[(k + pos) * MERGE_THREADS + tid]) : VP_IDX_NONE;
         }
         pv = bv;
         pi = bi;
@@ -127,10 +143,17 @@ __global__ __launch_bounds__(MERGE_THREADS) void merge_kernel(
 
 }  // namespace
 
-void vpk_merge(const VpSlabSet &set, const int32_t *perm, const int32_t *g, const int32_t *row_item0,
-               const int32_t *row_stride, const int32_t *row_nit, const VpItem *items, const float *partials,
-               int k, int N, int32_t *out_ids, float *out_logp, hipStream_t st)
+size_t vpk_merge_lds_bytes(int k) { return (size_t)2 * k * MERGE_THREADS * sizeof(float); }
+
+hipError_t vpk_merge_prepare()
 {
-    hipLaunchKernelGGL(merge_kernel, dim3(N), dim3(MERGE_THREADS), 0, st, set, perm, g, row_item0, row_stride,
-                       row_nit, items, partials, k, out_ids, out_logp);
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(merge_kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, 72 * 1024);
+}
+
+void vpk_merge(const VpSlabSet &set, const VpRowPlan *rowplan, const float *partials, int k, int N,
+               int32_t *out_ids, float *out_logp, hipStream_t st)
+{
+    hipLaunchKernelGGL(merge_kernel, dim3(N), dim3(MERGE_THREADS), vpk_merge_lds_bytes(k), st, set, rowplan,
+                       partials, k, out_ids, out_logp);
 }

@@ -52,40 +52,57 @@ __device__ T block_exscan(T v, T *total, T *wsum)
 
 __device__ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
+constexpr int RPT = 4;   // rows per thread whose cluster id stays in registers between phases
+
 __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(
     const int2 *__restrict__ cpart, int parts, int N, int K, const int32_t *__restrict__ n_cand,
     const int32_t *__restrict__ tile_off, int target_items, int max_items, int32_t *__restrict__ g,
-    int32_t *__restrict__ out_cluster, int32_t *__restrict__ perm, int32_t *__restrict__ row_item0,
-    int32_t *__restrict__ row_stride, int32_t *__restrict__ row_nit, VpItem *__restrict__ items,
-    VpPlanHeader *__restrict__ hdr, int64_t *__restrict__ dbg_row_off)
+    int32_t *__restrict__ out_cluster, int32_t *__restrict__ perm, VpRowPlan *__restrict__ rowplan,
+    VpItem *__restrict__ items, VpPlanHeader *__restrict__ hdr, int64_t *__restrict__ dbg_row_off)
 {
     extern __shared__ int lds[];
     int *cnt = lds;             // [K]   rows per cluster, later the scatter cursor
     int *off = cnt + K;         // [K+1] first perm position of each bucket
     int *ioff = off + K + 1;    // [K+1] first item of each bucket
+    int *tl = ioff + K + 1;     // [K]   candidate tiles of each cluster
     __shared__ int wsum[PLAN_THREADS / 64 + 1];
     __shared__ long long wsum64[PLAN_THREADS / 64 + 1];
     const int tid = threadIdx.x;
 
-    for (int j = tid; j < K; j += PLAN_THREADS) cnt[j] = 0;
+    for (int j = tid; j < K; j += PLAN_THREADS) {
+        cnt[j] = 0;
+        tl[j] = tile_off[j + 1] - tile_off[j];
+    }
     __syncthreads();
 
     // finish Eq. 2: minimum over the centroid parts, ties to the lowest index
-    for (int r = tid; r < N; r += PLAN_THREADS) {
+    int myj[RPT];
+#pragma unroll
+    for (int u = 0; u < RPT; ++u) myj[u] = 0;
+    for (int r = tid, u = 0; r < N; r += PLAN_THREADS, ++u) {
         float bs = __builtin_inff();
         int bj = VP_IDX_NONE;
-        for (int p = 0; p < parts; ++p) {
-            const int2 e = cpart[(size_t)r * parts + p];
-            const float s = __int_as_float(e.x);
-            if (s < bs || (s == bs && e.y < bj)) {
-                bs = s;
-                bj = e.y;
+        const int2 *cp = cpart + (size_t)r * parts;
+        for (int p0 = 0; p0 < parts; p0 += 8) {
+            int2 e[8];
+#pragma unroll
+            for (int v = 0; v < 8; ++v) e[v] = p0 + v < parts ? cp[p0 + v] : make_int2(0x7f800000, VP_IDX_NONE);
+#pragma unroll
+            for (int v = 0; v < 8; ++v) {
+                const float s = __int_as_float(e[v].x);
+                if (s < bs || (s == bs && e[v].y < bj)) {
+                    bs = s;
+                    bj = e[v].y;
+                }
             }
         }
         if (bj < 0 || bj >= K) bj = 0;   // non-finite scores: keep every index in range
         g[r] = bj;
         if (out_cluster) out_cluster[r] = bj;
         atomicAdd(&cnt[bj], 1);
+#pragma unroll
+        for (int v = 0; v < RPT; ++v)
+            if (v == u) myj[v] = bj;
     }
     __syncthreads();
 
@@ -99,7 +116,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(
         const int ex = block_exscan<int>(c, &tot, wsum);
         if (j < K) {
             off[j] = carry + ex;
-            my_tiles += ceil_div(c, VP_ROWS_PER_ITEM) * (tile_off[j + 1] - tile_off[j]);
+            my_tiles += ceil_div(c, VP_ROWS_PER_ITEM) * tl[j];
         }
         carry += tot;
     }
@@ -114,7 +131,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(
     for (int base = 0; base < K; base += PLAN_THREADS) {
         const int j = base + tid;
         int c = 0;
-        if (j < K) c = ceil_div(cnt[j], VP_ROWS_PER_ITEM) * ceil_div(tile_off[j + 1] - tile_off[j], tpi);
+        if (j < K) c = ceil_div(cnt[j], VP_ROWS_PER_ITEM) * ceil_div(tl[j], tpi);
         int tot;
         const int ex = block_exscan<int>(c, &tot, wsum);
         if (j < K) ioff[j] = carry + ex;
@@ -124,23 +141,32 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(
     __syncthreads();
     const int total_items = min(ioff[K], max_items);
 
-    // scatter rows into bucket order (cnt becomes the per-bucket cursor)
+    // scatter rows into bucket order (cnt becomes the per-bucket cursor) and tell the
+    // merge kernel where the partial results of each row will be
     for (int j = tid; j < K; j += PLAN_THREADS) cnt[j] = 0;
     __syncthreads();
-    for (int r = tid; r < N; r += PLAN_THREADS) {
-        const int j = g[r];
-        const int pos = atomicAdd(&cnt[j], 1);
-        perm[off[j] + pos] = r;
-    }
-    __syncthreads();
-
-    // where the merge kernel finds the partial results of each row
-    for (int p = tid; p < N; p += PLAN_THREADS) {
-        const int j = g[perm[p]];
-        const int rgs = ceil_div(off[j + 1] - off[j], VP_ROWS_PER_ITEM);
-        row_item0[p] = ioff[j] + (p - off[j]) / VP_ROWS_PER_ITEM;
-        row_stride[p] = rgs;
-        row_nit[p] = ceil_div(tile_off[j + 1] - tile_off[j], tpi);
+    for (int r = tid, u = 0; r < N; r += PLAN_THREADS, ++u) {
+        int j = 0;
+        if (u < RPT) {
+#pragma unroll
+            for (int v = 0; v < RPT; ++v)
+                if (v == u) j = myj[v];
+        } else {
+            j = g[r];
+        }
+        const int local = atomicAdd(&cnt[j], 1);
+        const int p = off[j] + local;
+        perm[p] = r;
+        VpRowPlan rp;
+        rp.row = r;
+        rp.cluster = j;
+        rp.item0 = ioff[j] + local / VP_ROWS_PER_ITEM;
+        rp.stride = ceil_div(off[j + 1] - off[j], VP_ROWS_PER_ITEM);
+        rp.nit = ceil_div(tl[j], tpi);
+        rp.local = local % VP_ROWS_PER_ITEM;
+        rp.ids_off = tile_off[j] * VP_TILE_ITEMS;
+        rp.pad = 0;
+        rowplan[p] = rp;
     }
 
     // the items: for each bucket, candidate ranges outermost and row groups
@@ -157,13 +183,12 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(
         const int local = it - ioff[j];
         const int ch = local / rgs;
         const int rg = local - ch * rgs;
-        const int tiles = tile_off[j + 1] - tile_off[j];
         VpItem v;
         v.cluster = j;
         v.perm_start = off[j] + rg * VP_ROWS_PER_ITEM;
         v.nrows = min(VP_ROWS_PER_ITEM, rows - rg * VP_ROWS_PER_ITEM);
         v.tile0 = ch * tpi;
-        v.ntiles = min(tpi, tiles - ch * tpi);
+        v.ntiles = min(tpi, tl[j] - ch * tpi);
         v.shared = rgs > 1;
         v.pad[0] = v.pad[1] = 0;
         items[it] = v;
@@ -177,6 +202,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(
 
     // debug entry only: where each row's candidate logits start
     if (dbg_row_off) {
+        __syncthreads();
         long long carry64 = 0;
         for (int base = 0; base < N; base += PLAN_THREADS) {
             const int r = base + tid;
@@ -194,8 +220,8 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(
 // order, one slab holding every token.  Nothing depends on device data.
 __global__ __launch_bounds__(256) void plan_full_kernel(
     int N, int V, int vtiles, int target_items, int max_items, int32_t *__restrict__ perm,
-    int32_t *__restrict__ row_item0, int32_t *__restrict__ row_stride, int32_t *__restrict__ row_nit,
-    VpItem *__restrict__ items, VpPlanHeader *__restrict__ hdr, int64_t *__restrict__ dbg_row_off)
+    VpRowPlan *__restrict__ rowplan, VpItem *__restrict__ items, VpPlanHeader *__restrict__ hdr,
+    int64_t *__restrict__ dbg_row_off)
 {
     const int rgs = ceil_div(N, VP_ROWS_PER_ITEM);
     const long long total_tiles = (long long)rgs * vtiles;
@@ -208,9 +234,16 @@ __global__ __launch_bounds__(256) void plan_full_kernel(
     const int gsize = gridDim.x * blockDim.x;
     for (int p = gtid; p < N; p += gsize) {
         perm[p] = p;
-        row_item0[p] = p / VP_ROWS_PER_ITEM;
-        row_stride[p] = rgs;
-        row_nit[p] = chunks;
+        VpRowPlan rp;
+        rp.row = p;
+        rp.cluster = 0;
+        rp.item0 = p / VP_ROWS_PER_ITEM;
+        rp.stride = rgs;
+        rp.nit = chunks;
+        rp.local = p % VP_ROWS_PER_ITEM;
+        rp.ids_off = 0;
+        rp.pad = 0;
+        rowplan[p] = rp;
         if (dbg_row_off) dbg_row_off[p] = (int64_t)p * V;
     }
     for (int it = gtid; it < total_items; it += gsize) {
@@ -237,31 +270,29 @@ __global__ __launch_bounds__(256) void plan_full_kernel(
 
 }  // namespace
 
-size_t vpk_plan_lds_bytes(int K) { return (size_t)(3 * K + 2) * sizeof(int); }
+size_t vpk_plan_lds_bytes(int K) { return (size_t)(4 * K + 2) * sizeof(int); }
 
 hipError_t vpk_plan_prepare()
 {
-    // clusters up to VP_MAX_CLUSTERS need 48 KiB of dynamic LDS; allow it explicitly
+    // clusters up to VP_MAX_CLUSTERS need a little over 64 KiB of dynamic LDS; allow it explicitly
     return hipFuncSetAttribute(reinterpret_cast<const void *>(plan_kernel),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024);
+                               hipFuncAttributeMaxDynamicSharedMemorySize, 72 * 1024);
 }
 
 void vpk_plan(const void *cpart, int parts, int N, int K, const int32_t *n_cand, const int32_t *tile_off,
               int target_items, int max_items, int32_t *g, int32_t *out_cluster, int32_t *perm,
-              int32_t *row_item0, int32_t *row_stride, int32_t *row_nit, VpItem *items, VpPlanHeader *hdr,
-              int64_t *dbg_row_off, hipStream_t st)
+              VpRowPlan *rowplan, VpItem *items, VpPlanHeader *hdr, int64_t *dbg_row_off, hipStream_t st)
 {
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(PLAN_THREADS), vpk_plan_lds_bytes(K), st, (const int2 *)cpart,
-                       parts, N, K, n_cand, tile_off, target_items, max_items, g, out_cluster, perm, row_item0,
-                       row_stride, row_nit, items, hdr, dbg_row_off);
+                       parts, N, K, n_cand, tile_off, target_items, max_items, g, out_cluster, perm, rowplan, items,
+                       hdr, dbg_row_off);
 }
 
-void vpk_plan_full(int N, int V, int vtiles, int target_items, int max_items, int32_t *perm, int32_t *row_item0,
-                   int32_t *row_stride, int32_t *row_nit, VpItem *items, VpPlanHeader *hdr,
-                   int64_t *dbg_row_off, hipStream_t st)
+void vpk_plan_full(int N, int V, int vtiles, int target_items, int max_items, int32_t *perm, VpRowPlan *rowplan,
+                   VpItem *items, VpPlanHeader *hdr, int64_t *dbg_row_off, hipStream_t st)
 {
     const int work = max(N, max_items);
     const int blocks = min(64, (work + 255) / 256);
     hipLaunchKernelGGL(plan_full_kernel, dim3(blocks), dim3(256), 0, st, N, V, vtiles, target_items, max_items,
-                       perm, row_item0, row_stride, row_nit, items, hdr, dbg_row_off);
+                       perm, rowplan, items, hdr, dbg_row_off);
 }

@@ -110,7 +110,7 @@ vp_status plan_arena(const vp_build_desc *D, bool check_ids, ArenaLayout *L)
         n_min = std::min<int64_t>(n_min, n);
         n_max = std::max<int64_t>(n_max, n);
     }
-    if (groups > 2147483647L / 2) return fail(VP_ERR_UNSUPPORTED, "vp_build: active sets too large in total");
+    if (groups > (1L << 27)) return fail(VP_ERR_UNSUPPORTED, "vp_build: active sets too large in total");
     L->total_groups = groups;
     L->n_total = total;
     L->n_min = n_min;
@@ -137,7 +137,7 @@ vp_status plan_arena(const vp_build_desc *D, bool check_ids, ArenaLayout *L)
 // Byte offsets of the per-call scratch inside the workspace.
 struct WsLayout {
     int max_items;
-    size_t hdr, cpart, g, perm, row_item0, row_stride, row_nit, items, partials, total;
+    size_t hdr, cpart, g, perm, rowplan, items, partials, total;
 };
 
 int max_items_clustered(const vp_index *I, int N)
@@ -157,9 +157,7 @@ WsLayout plan_workspace(const vp_index *I, int N)
     W.cpart = take(n * I->L.ctiles * 8);
     W.g = take(n * 4);
     W.perm = take(n * 4);
-    W.row_item0 = take(n * 4);
-    W.row_stride = take(n * 4);
-    W.row_nit = take(n * 4);
+    W.rowplan = take(n * sizeof(VpRowPlan));
     W.items = take((size_t)W.max_items * sizeof(VpItem));
     W.partials = take((size_t)W.max_items * VP_ROWS_PER_ITEM * vp_partial_floats(I->k_max) * sizeof(float));
     W.total = o;
@@ -219,22 +217,20 @@ vp_status run_clustered(const char *fn, const vp_index *I, const void *hidden, i
     void *cpart = ws + W.cpart;
     int32_t *g = reinterpret_cast<int32_t *>(ws + W.g);
     int32_t *perm = reinterpret_cast<int32_t *>(ws + W.perm);
-    int32_t *row_item0 = reinterpret_cast<int32_t *>(ws + W.row_item0);
-    int32_t *row_stride = reinterpret_cast<int32_t *>(ws + W.row_stride);
-    int32_t *row_nit = reinterpret_cast<int32_t *>(ws + W.row_nit);
+    VpRowPlan *rowplan = reinterpret_cast<VpRowPlan *>(ws + W.rowplan);
     VpItem *items = reinterpret_cast<VpItem *>(ws + W.items);
     float *partials = reinterpret_cast<float *>(ws + W.partials);
 
     // Eq. 2 in parts so that a handful of rows still occupies many wavefronts
     const int row_tiles = ceil_div(N, 16);
-    int parts = std::max(1, std::min(I->L.ctiles, ceil_div(1024, row_tiles)));
-    const int tpp = ceil_div(I->L.ctiles, parts);
-    parts = ceil_div(I->L.ctiles, tpp);
-    vpk_centroid(hidden, N, I->d, I->cp, I->cnorm, I->K, I->L.kt, I->L.ctiles, tpp, parts, cpart, st);
+    int parts = std::min(ceil_div(I->L.ctiles, 4), std::max(1, 2048 / (4 * row_tiles)));
+    const int tpw_c = ceil_div(I->L.ctiles, parts * 4);
+    parts = ceil_div(I->L.ctiles, tpw_c * 4);
+    vpk_centroid(hidden, N, I->d, I->cp, I->cnorm, I->K, I->L.kt, I->L.ctiles, tpw_c, parts, cpart, st);
 
     const int max_items = max_items_clustered(I, N);
     vpk_plan(cpart, parts, N, I->K, I->clusters.n_cand, I->clusters.tile_off, I->target_items, max_items, g,
-             out_cluster, perm, row_item0, row_stride, row_nit, items, hdr, dbg_row_off, st);
+             out_cluster, perm, rowplan, items, hdr, dbg_row_off, st);
 
     const long row_groups = (long)row_tiles + std::min(N, I->K);
     const long by_tiles = row_groups * ceil_div(I->L.max_tiles, VP_WG_WAVES);
@@ -245,7 +241,7 @@ vp_status run_clustered(const char *fn, const vp_index *I, const void *hidden, i
                 dbg_row_off, st);
     if (ev) (void)hipEventRecord(ev->second, st);
     if (out_ids)
-        vpk_merge(I->clusters, perm, g, row_item0, row_stride, row_nit, items, partials, k, N, out_ids, out_logp, st);
+        vpk_merge(I->clusters, rowplan, partials, k, N, out_ids, out_logp, st);
     return launch_status(fn);
 }
 
@@ -255,15 +251,13 @@ vp_status run_full(const char *fn, const vp_index *I, const void *hidden, int N,
     const WsLayout W = plan_workspace(I, N);
     VpPlanHeader *hdr = reinterpret_cast<VpPlanHeader *>(ws + W.hdr);
     int32_t *perm = reinterpret_cast<int32_t *>(ws + W.perm);
-    int32_t *row_item0 = reinterpret_cast<int32_t *>(ws + W.row_item0);
-    int32_t *row_stride = reinterpret_cast<int32_t *>(ws + W.row_stride);
-    int32_t *row_nit = reinterpret_cast<int32_t *>(ws + W.row_nit);
+    VpRowPlan *rowplan = reinterpret_cast<VpRowPlan *>(ws + W.rowplan);
     VpItem *items = reinterpret_cast<VpItem *>(ws + W.items);
     float *partials = reinterpret_cast<float *>(ws + W.partials);
 
     const int max_items = max_items_full(I, N);
-    vpk_plan_full(N, I->V, I->L.vtiles, I->full_target_items, max_items, perm, row_item0, row_stride, row_nit,
-                  items, hdr, dbg_row_off, st);
+    vpk_plan_full(N, I->V, I->L.vtiles, I->full_target_items, max_items, perm, rowplan, items, hdr, dbg_row_off,
+                  st);
     const long row_groups = ceil_div(N, VP_ROWS_PER_ITEM);
     const long by_tiles = row_groups * ceil_div(I->L.vtiles, VP_WG_WAVES);
     const int grid_items = (int)std::min<long>(max_items, by_tiles);
@@ -274,8 +268,7 @@ vp_status run_full(const char *fn, const vp_index *I, const void *hidden, int N,
                 dbg_logits, dbg_row_off, st);
     if (ev) (void)hipEventRecord(ev->second, st);
     if (out_ids)
-        vpk_merge(I->full, perm, nullptr, row_item0, row_stride, row_nit, items, partials, k, N, out_ids, out_logp,
-                  st);
+        vpk_merge(I->full, rowplan, partials, k, N, out_ids, out_logp, st);
     return launch_status(fn);
 }
 
@@ -309,6 +302,7 @@ vp_status vp_build(const vp_build_desc *D, void *hip_stream, vp_index **out)
     hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
     hipError_t e = vpk_plan_prepare();
     if (e == hipSuccess) e = vpk_project_prepare();
+    if (e == hipSuccess) e = vpk_merge_prepare();
     if (e != hipSuccess) return fail(VP_ERR_HIP, "vp_build: cannot configure kernels: %s", hipGetErrorString(e));
 
     // host-side metadata: candidate groups per cluster, ids padded to whole groups

@@ -22,11 +22,9 @@ size_t vpk_plan_lds_bytes(int K);
 hipError_t vpk_plan_prepare();
 void vpk_plan(const void *cpart, int parts, int N, int K, const int32_t *n_cand, const int32_t *tile_off,
               int target_items, int max_items, int32_t *g, int32_t *out_cluster, int32_t *perm,
-              int32_t *row_item0, int32_t *row_stride, int32_t *row_nit, VpItem *items, VpPlanHeader *hdr,
-              int64_t *dbg_row_off, hipStream_t st);
-void vpk_plan_full(int N, int V, int vtiles, int target_items, int max_items, int32_t *perm, int32_t *row_item0,
-                   int32_t *row_stride, int32_t *row_nit, VpItem *items, VpPlanHeader *hdr,
-                   int64_t *dbg_row_off, hipStream_t st);
+              VpRowPlan *rowplan, VpItem *items, VpPlanHeader *hdr, int64_t *dbg_row_off, hipStream_t st);
+void vpk_plan_full(int N, int V, int vtiles, int target_items, int max_items, int32_t *perm, VpRowPlan *rowplan,
+                   VpItem *items, VpPlanHeader *hdr, int64_t *dbg_row_off, hipStream_t st);
 
 // projection + fused log-softmax / top-k partials
 size_t vpk_project_lds_bytes(int kt, int k);
@@ -36,6 +34,7 @@ void vpk_project(const VpSlabSet &set, const void *hidden, int d, const int32_t 
                  const int64_t *dbg_row_off, hipStream_t st);
 
 // per-row merge
-void vpk_merge(const VpSlabSet &set, const int32_t *perm, const int32_t *g, const int32_t *row_item0,
-               const int32_t *row_stride, const int32_t *row_nit, const VpItem *items, const float *partials,
-               int k, int N, int32_t *out_ids, float *out_logp, hipStream_t st);
+size_t vpk_merge_lds_bytes(int k);
+hipError_t vpk_merge_prepare();
+void vpk_merge(const VpSlabSet &set, const VpRowPlan *rowplan, const float *partials, int k, int N,
+               int32_t *out_ids, float *out_logp, hipStream_t st);

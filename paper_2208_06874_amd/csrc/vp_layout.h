@@ -33,6 +33,20 @@ struct VpItem {
     int32_t pad[2];
 };
 
+// Where the merge kernel finds everything about the row at one position of
+// the bucket order: partial results sit at items item0, item0 + stride, ...
+// (nit of them), in row slot `local` of each.
+struct VpRowPlan {
+    int32_t row;        // row number in the caller's batch
+    int32_t cluster;
+    int32_t item0;
+    int32_t stride;
+    int32_t nit;
+    int32_t local;
+    int32_t ids_off;    // first entry of the cluster's token-id list
+    int32_t pad;
+};
+
 // Header the planning kernel leaves for the projection and merge kernels.
 struct VpPlanHeader {
     int32_t total_items;
