@@ -38,6 +38,11 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-full", action="store_true")
     ap.add_argument("--option", action="append", default=[], help="library option name=value")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay each step from a captured HIP graph (one graph per batch) instead of launching it")
+    ap.add_argument("--single-cluster", action="store_true",
+                    help="microbenchmark, not a configured workload: all rows of a batch sit in one cluster "
+                         "(a different one per batch), to expose the GEMV/MFMA crossover over the bucket size")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
@@ -67,7 +72,12 @@ def main():
         index.set_option(name, int(val))
     info = index.info()
     sizes = cand_off[1:] - cand_off[:-1]
-    batches_np = [wl.make_rows(cfg, C, N=N, stream=1 + i)[0] for i in range(args.batches)]
+    if args.single_cluster:
+        pick = np.random.default_rng(7).permutation(cfg.K)
+        batches_np = [wl.make_rows(cfg, C, N=N, stream=1 + i, clusters=np.full(N, pick[i % cfg.K]))[0]
+                      for i in range(args.batches)]
+    else:
+        batches_np = [wl.make_rows(cfg, C, N=N, stream=1 + i)[0] for i in range(args.batches)]
     batches = [torch.from_numpy(h).to(dev) for h in batches_np]
     out_ids = [torch.empty((N, k), dtype=torch.int32, device=dev) for _ in batches]
     out_logp = [torch.empty((N, k), dtype=torch.float32, device=dev) for _ in batches]
@@ -91,12 +101,28 @@ def main():
         j = i % len(batches)
         index.project_full(batches[j], k, out_ids=full_ids, out_logp=full_logp, workspace=ws)
 
-    def timed(fn, warmup, steps):
+    graphs = {}
+
+    def graphed(fn):
+        # one captured graph per batch; event recording is not captured, so the kernel
+        # time of the roofline comes from an un-graphed pass
+        def run(i):
+            j = i % len(batches)
+            key = (fn.__name__, j)
+            if key not in graphs:
+                gr = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(gr):
+                    fn(j)
+                graphs[key] = gr
+            graphs[key].replay()
+        return run
+
+    def timed(fn, warmup, steps, profile=True):
         for i in range(warmup):
             fn(i)
         torch.cuda.synchronize()
         index.get_profile()                      # drop warm-up launches
-        index.set_option("profile", 1)
+        index.set_option("profile", 1 if profile else 0)
         t0 = time.perf_counter()
         for i in range(steps):
             fn(i)
@@ -107,6 +133,12 @@ def main():
         return (t1 - t0) * 1e3 / steps, kernel_ms / max(launches, 1), launches
 
     ms_step, ms_kernel, launches = timed(step, args.warmup, args.steps)
+    if args.graph:
+        for i in range(len(batches)):
+            step(i)                               # results of every batch before capture
+        torch.cuda.synchronize()
+        gstep = graphed(step)
+        ms_step, _, _ = timed(gstep, max(args.warmup, len(batches)), args.steps, profile=False)
     rows_per_s = N / (ms_step * 1e-3)
 
     # algorithmic bytes of one projection-kernel launch: every candidate of every occupied
@@ -129,6 +161,7 @@ def main():
         "config": {"workload": "%s: d=%d V=%d K=%d N=%d top-%d, %d-%d candidates per cluster" % (
             cfg.name, cfg.d, cfg.V, cfg.K, N, k, int(sizes.min()), int(sizes.max())),
             "batches_cycled": len(batches), "slab_bytes": info["slab_bytes"],
+            "single_cluster_microbenchmark": bool(args.single_cluster), "hip_graph_replay": bool(args.graph),
             "occupied_clusters_per_step": float(np.mean([np.unique(g.cpu().numpy()).size for g in out_g])),
             "setup_seconds": t_gen},
         "roofline": {"bound": "hbm", "kernel": "project_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,

@@ -56,7 +56,7 @@ constexpr int RPT = 4;   // rows per thread whose cluster id stays in registers 
 
 __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(
     const int2 *__restrict__ cpart, int parts, int N, int K, const int32_t *__restrict__ n_cand,
-    const int32_t *__restrict__ tile_off, int target_items, int max_items, int32_t *__restrict__ g,
+    const int32_t *__restrict__ tile_off, int target_items, int min_items, int max_items, int32_t *__restrict__ g,
     int32_t *__restrict__ out_cluster, int32_t *__restrict__ perm, VpRowPlan *__restrict__ rowplan,
     VpItem *__restrict__ items, VpPlanHeader *__restrict__ hdr, int64_t *__restrict__ dbg_row_off)
 {
@@ -123,7 +123,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(
     if (tid == 0) off[K] = carry;
     int total_tiles;
     block_exscan<int>(my_tiles, &total_tiles, wsum);
-    const int tpw = max(1, ceil_div(total_tiles, VP_WG_WAVES * max(1, target_items)));
+    const int tpw = vp_tiles_per_wave(total_tiles, target_items, min_items);
     const int tpi = tpw * VP_WG_WAVES;
 
     // items per bucket -> item offsets
@@ -198,6 +198,8 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(
         hdr->tiles_per_wave = tpw;
         hdr->overflow = ioff[K] > max_items;
         hdr->total_tiles = total_tiles;
+        hdr->swz_rgs = 0;
+        hdr->swz_chunks = 0;
     }
 
     // debug entry only: where each row's candidate logits start
@@ -219,14 +221,13 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(
 // Plan of the full-vocabulary projection: one bucket holding every row in
 // order, one slab holding every token.  Nothing depends on device data.
 __global__ __launch_bounds__(256) void plan_full_kernel(
-    int N, int V, int vtiles, int target_items, int max_items, int32_t *__restrict__ perm,
+    int N, int V, int vtiles, int target_items, int min_items, int max_items, int32_t *__restrict__ perm,
     VpRowPlan *__restrict__ rowplan, VpItem *__restrict__ items, VpPlanHeader *__restrict__ hdr,
     int64_t *__restrict__ dbg_row_off)
 {
     const int rgs = ceil_div(N, VP_ROWS_PER_ITEM);
     const long long total_tiles = (long long)rgs * vtiles;
-    const int tpw = (int)max(1LL, (total_tiles + (long long)VP_WG_WAVES * target_items - 1) /
-                                      ((long long)VP_WG_WAVES * target_items));
+    const int tpw = vp_tiles_per_wave(total_tiles, target_items, min_items);
     const int tpi = tpw * VP_WG_WAVES;
     const int chunks = ceil_div(vtiles, tpi);
     const int total_items = min(chunks * rgs, max_items);
@@ -264,6 +265,8 @@ __global__ __launch_bounds__(256) void plan_full_kernel(
         hdr->tiles_per_wave = tpw;
         hdr->overflow = chunks * rgs > max_items;
         hdr->total_tiles = (int)min(total_tiles, 2147483647LL);
+        hdr->swz_rgs = rgs > 1 ? rgs : 0;
+        hdr->swz_chunks = chunks;
         if (dbg_row_off) dbg_row_off[N] = (int64_t)N * V;
     }
 }
@@ -280,19 +283,20 @@ hipError_t vpk_plan_prepare()
 }
 
 void vpk_plan(const void *cpart, int parts, int N, int K, const int32_t *n_cand, const int32_t *tile_off,
-              int target_items, int max_items, int32_t *g, int32_t *out_cluster, int32_t *perm,
+              int target_items, int min_items, int max_items, int32_t *g, int32_t *out_cluster, int32_t *perm,
               VpRowPlan *rowplan, VpItem *items, VpPlanHeader *hdr, int64_t *dbg_row_off, hipStream_t st)
 {
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(PLAN_THREADS), vpk_plan_lds_bytes(K), st, (const int2 *)cpart,
-                       parts, N, K, n_cand, tile_off, target_items, max_items, g, out_cluster, perm, rowplan, items,
+                       parts, N, K, n_cand, tile_off, target_items, min_items, max_items, g, out_cluster, perm, rowplan, items,
                        hdr, dbg_row_off);
 }
 
-void vpk_plan_full(int N, int V, int vtiles, int target_items, int max_items, int32_t *perm, VpRowPlan *rowplan,
+void vpk_plan_full(int N, int V, int vtiles, int target_items, int min_items, int max_items, int32_t *perm,
+                   VpRowPlan *rowplan,
                    VpItem *items, VpPlanHeader *hdr, int64_t *dbg_row_off, hipStream_t st)
 {
     const int work = max(N, max_items);
     const int blocks = min(64, (work + 255) / 256);
-    hipLaunchKernelGGL(plan_full_kernel, dim3(blocks), dim3(256), 0, st, N, V, vtiles, target_items, max_items,
+    hipLaunchKernelGGL(plan_full_kernel, dim3(blocks), dim3(256), 0, st, N, V, vtiles, target_items, min_items, max_items,
                        perm, rowplan, items, hdr, dbg_row_off);
 }

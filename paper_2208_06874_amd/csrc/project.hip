@@ -325,7 +325,19 @@ __global__ __launch_bounds__(VP_WG_THREADS) void project_kernel(
     const VpItem *__restrict__ items, const VpPlanHeader *__restrict__ hdr, int k, int rstar,
     float *__restrict__ partials, float *__restrict__ dbg_logits, const int64_t *__restrict__ dbg_row_off)
 {
-    const int it = blockIdx.x;
+    int it = blockIdx.x;
+    const int swz_rgs = hdr->swz_rgs;
+    if (swz_rgs > 1) {
+        // Workgroups are handed to the 8 XCDs in turn.  Give each XCD its own candidate
+        // ranges and let all row groups of a range follow each other on that XCD, so
+        // the range is fetched from HBM once and then served by that XCD's L2.
+        const int xcd = it & 7;
+        const int t = it >> 3;
+        const int chl = t / swz_rgs;
+        const int ch = chl * 8 + xcd;
+        if (ch >= hdr->swz_chunks) return;
+        it = ch * swz_rgs + (t - chl * swz_rgs);
+    }
     if (it >= hdr->total_items) return;
     const VpItem item = items[it];
     const int tpw = hdr->tiles_per_wave;

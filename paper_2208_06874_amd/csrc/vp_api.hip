@@ -60,6 +60,7 @@ struct vp_index {
     const void *cp;
     const float *cnorm;
     int target_items, full_target_items, rstar;
+    int min_items;   // resident workgroup slots of the projection kernel on this GPU
     VpProfile *prof;
 };
 
@@ -229,7 +230,7 @@ vp_status run_clustered(const char *fn, const vp_index *I, const void *hidden, i
     vpk_centroid(hidden, N, I->d, I->cp, I->cnorm, I->K, I->L.kt, I->L.ctiles, tpw_c, parts, cpart, st);
 
     const int max_items = max_items_clustered(I, N);
-    vpk_plan(cpart, parts, N, I->K, I->clusters.n_cand, I->clusters.tile_off, I->target_items, max_items, g,
+    vpk_plan(cpart, parts, N, I->K, I->clusters.n_cand, I->clusters.tile_off, I->target_items, I->min_items, max_items, g,
              out_cluster, perm, rowplan, items, hdr, dbg_row_off, st);
 
     const long row_groups = (long)row_tiles + std::min(N, I->K);
@@ -256,11 +257,14 @@ vp_status run_full(const char *fn, const vp_index *I, const void *hidden, int N,
     float *partials = reinterpret_cast<float *>(ws + W.partials);
 
     const int max_items = max_items_full(I, N);
-    vpk_plan_full(N, I->V, I->L.vtiles, I->full_target_items, max_items, perm, rowplan, items, hdr, dbg_row_off,
+    vpk_plan_full(N, I->V, I->L.vtiles, I->full_target_items, I->min_items, max_items, perm, rowplan, items, hdr, dbg_row_off,
                   st);
-    const long row_groups = ceil_div(N, VP_ROWS_PER_ITEM);
-    const long by_tiles = row_groups * ceil_div(I->L.vtiles, VP_WG_WAVES);
-    const int grid_items = (int)std::min<long>(max_items, by_tiles);
+    // the same split the planning kernel makes; with several row groups the projection kernel
+    // deals candidate ranges to the XCDs, which needs the grid padded to 8 ranges at a time
+    const int rgs = ceil_div(N, VP_ROWS_PER_ITEM);
+    const int tpw = vp_tiles_per_wave((long long)rgs * I->L.vtiles, I->full_target_items, I->min_items);
+    const int chunks = ceil_div(I->L.vtiles, (long)tpw * VP_WG_WAVES);
+    const int grid_items = rgs > 1 ? ceil_div(chunks, 8) * 8 * rgs : chunks;
     // the GEMV loop is reserved for the clustered buckets; the full projection keeps its rows in one bucket
     auto *ev = profile_slot(I);
     if (ev) (void)hipEventRecord(ev->first, st);
@@ -366,6 +370,14 @@ vp_status vp_build(const vp_build_desc *D, void *hip_stream, vp_index **out)
     I->target_items = 8192;
     I->full_target_items = 2048;
     I->rstar = 0;
+    {
+        // workgroups of the projection kernel that fit on the chip at once (LDS-limited)
+        int dev = 0, cus = 256;
+        if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        const size_t lds = vpk_project_lds_bytes(L.kt, D->k_max);
+        const int per_cu = (int)std::max<size_t>(1, std::min<size_t>(8, LDS_LIMIT / lds));
+        I->min_items = std::max(1, cus) * per_cu;
+    }
     I->prof = new (std::nothrow) VpProfile();
     *out = I;
     return VP_OK;

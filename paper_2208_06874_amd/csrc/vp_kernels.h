@@ -21,9 +21,10 @@ void vpk_centroid(const void *hidden, int N, int d, const void *cp, const float 
 size_t vpk_plan_lds_bytes(int K);
 hipError_t vpk_plan_prepare();
 void vpk_plan(const void *cpart, int parts, int N, int K, const int32_t *n_cand, const int32_t *tile_off,
-              int target_items, int max_items, int32_t *g, int32_t *out_cluster, int32_t *perm,
+              int target_items, int min_items, int max_items, int32_t *g, int32_t *out_cluster, int32_t *perm,
               VpRowPlan *rowplan, VpItem *items, VpPlanHeader *hdr, int64_t *dbg_row_off, hipStream_t st);
-void vpk_plan_full(int N, int V, int vtiles, int target_items, int max_items, int32_t *perm, VpRowPlan *rowplan,
+void vpk_plan_full(int N, int V, int vtiles, int target_items, int min_items, int max_items, int32_t *perm,
+                   VpRowPlan *rowplan,
                    VpItem *items, VpPlanHeader *hdr, int64_t *dbg_row_off, hipStream_t st);
 
 // projection + fused log-softmax / top-k partials

@@ -53,7 +53,11 @@ struct VpPlanHeader {
     int32_t tiles_per_wave;
     int32_t overflow;        // set if the item list did not fit (never expected)
     int32_t total_tiles;
-    int32_t pad[60];
+    // Workgroup -> item swizzle for a single bucket whose row groups share tiles (the
+    // full-vocabulary projection): 0, or the number of row groups / candidate ranges.
+    int32_t swz_rgs;
+    int32_t swz_chunks;
+    int32_t pad[58];
 };
 
 // A set of packed slabs: the K clusters, or the single whole-vocabulary slab.
@@ -66,6 +70,22 @@ struct VpSlabSet {
     int32_t entries;
     int32_t kt;               // k-tiles per candidate group (d_pad / 32)
 };
+
+// Tiles per wavefront for a projection of total_tiles candidate tiles (counted once
+// per row group): about target_items items when there is plenty of work; with little
+// work, fewer and longer items (at least ~4 tiles per wavefront while that still
+// leaves min_items items, one per resident workgroup slot), because a short item
+// spends most of its life staging rows and waiting for its first loads.
+static inline __host__ __device__ int vp_tiles_per_wave(long long total_tiles, int target_items, int min_items)
+{
+    long long eff = total_tiles / (4 * VP_WG_WAVES);
+    if (eff < min_items) eff = min_items;
+    if (eff > target_items) eff = target_items;
+    if (eff < 1) eff = 1;
+    const long long per = (long long)VP_WG_WAVES * eff;
+    const long long tpw = (total_tiles + per - 1) / per;
+    return (int)(tpw > 1 ? tpw : 1);
+}
 
 // Size in floats of one partial result: running max, sum of exponentials, then
 // k logits and k candidate positions.
