@@ -58,7 +58,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(
     const int2 *__restrict__ cpart, int parts, int N, int K, const int32_t *__restrict__ n_cand,
     const int32_t *__restrict__ tile_off, int target_items, int min_items, int max_items, int32_t *__restrict__ g,
     int32_t *__restrict__ out_cluster, int32_t *__restrict__ perm, VpRowPlan *__restrict__ rowplan,
-    VpItem *__restrict__ items, VpPlanHeader *__restrict__ hdr, int64_t *__restrict__ dbg_row_off)
+    unsigned int *__restrict__ floors, VpItem *__restrict__ items, VpPlanHeader *__restrict__ hdr, int64_t *__restrict__ dbg_row_off)
 {
     extern __shared__ int lds[];
     int *cnt = lds;             // [K]   rows per cluster, later the scatter cursor
@@ -157,6 +157,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(
         const int local = atomicAdd(&cnt[j], 1);
         const int p = off[j] + local;
         perm[p] = r;
+        floors[r] = VP_FLOOR_NONE;   // no lower bound of the row's k-th best logit known yet
         VpRowPlan rp;
         rp.row = r;
         rp.cluster = j;
@@ -222,8 +223,8 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(
 // order, one slab holding every token.  Nothing depends on device data.
 __global__ __launch_bounds__(256) void plan_full_kernel(
     int N, int V, int vtiles, int target_items, int min_items, int max_items, int32_t *__restrict__ perm,
-    VpRowPlan *__restrict__ rowplan, VpItem *__restrict__ items, VpPlanHeader *__restrict__ hdr,
-    int64_t *__restrict__ dbg_row_off)
+    VpRowPlan *__restrict__ rowplan, unsigned int *__restrict__ floors, VpItem *__restrict__ items,
+    VpPlanHeader *__restrict__ hdr, int64_t *__restrict__ dbg_row_off)
 {
     const int rgs = ceil_div(N, VP_ROWS_PER_ITEM);
     const long long total_tiles = (long long)rgs * vtiles;
@@ -235,6 +236,7 @@ __global__ __launch_bounds__(256) void plan_full_kernel(
     const int gsize = gridDim.x * blockDim.x;
     for (int p = gtid; p < N; p += gsize) {
         perm[p] = p;
+        floors[p] = VP_FLOOR_NONE;
         VpRowPlan rp;
         rp.row = p;
         rp.cluster = 0;
@@ -284,19 +286,20 @@ hipError_t vpk_plan_prepare()
 
 void vpk_plan(const void *cpart, int parts, int N, int K, const int32_t *n_cand, const int32_t *tile_off,
               int target_items, int min_items, int max_items, int32_t *g, int32_t *out_cluster, int32_t *perm,
-              VpRowPlan *rowplan, VpItem *items, VpPlanHeader *hdr, int64_t *dbg_row_off, hipStream_t st)
+              VpRowPlan *rowplan, unsigned int *floors, VpItem *items, VpPlanHeader *hdr, int64_t *dbg_row_off,
+              hipStream_t st)
 {
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(PLAN_THREADS), vpk_plan_lds_bytes(K), st, (const int2 *)cpart,
-                       parts, N, K, n_cand, tile_off, target_items, min_items, max_items, g, out_cluster, perm, rowplan, items,
-                       hdr, dbg_row_off);
+                       parts, N, K, n_cand, tile_off, target_items, min_items, max_items, g, out_cluster, perm, rowplan, floors,
+                       items, hdr, dbg_row_off);
 }
 
 void vpk_plan_full(int N, int V, int vtiles, int target_items, int min_items, int max_items, int32_t *perm,
-                   VpRowPlan *rowplan,
-                   VpItem *items, VpPlanHeader *hdr, int64_t *dbg_row_off, hipStream_t st)
+                   VpRowPlan *rowplan, unsigned int *floors, VpItem *items, VpPlanHeader *hdr,
+                   int64_t *dbg_row_off, hipStream_t st)
 {
     const int work = max(N, max_items);
     const int blocks = min(64, (work + 255) / 256);
     hipLaunchKernelGGL(plan_full_kernel, dim3(blocks), dim3(256), 0, st, N, V, vtiles, target_items, min_items, max_items,
-                       perm, rowplan, items, hdr, dbg_row_off);
+                       perm, rowplan, floors, items, hdr, dbg_row_off);
 }

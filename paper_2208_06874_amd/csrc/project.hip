@@ -44,45 +44,88 @@ __device__ inline float fast_exp(float x) { return __builtin_amdgcn_exp2f(x * LO
 struct RowState {
     float m;     // running maximum of the logits
     float s;     // sum of exp(z - m)
-    float thr;   // logit of the lane's current k-th best (+inf: lane inactive)
+    float thr;   // logit of the row's current k-th best in this wavefront (+inf: lane inactive)
 };
 
-// Lane-private sorted list of the k best (logit, position) pairs, kept in LDS
-// as [slot][lane] so that the 64 lanes of a wavefront hit 64 different banks.
-struct LaneList {
+// Sorted list of the k best (logit, position) pairs of one row, one list per
+// wavefront and row, kept in LDS as [slot][row] (16 rows = 16 different banks).
+// The four lanes that own a row share it and take turns (see fold_logits).
+struct RowList {
     float *val;
     int *idx;
-    __device__ inline float &v(int slot) { return val[slot * 64]; }
-    __device__ inline int &i(int slot) { return idx[slot * 64]; }
+    __device__ inline float &v(int slot) { return val[slot * 16]; }
+    __device__ inline int &i(int slot) { return idx[slot * 16]; }
 };
 
+// Orders LDS traffic between lanes of one wavefront: the hardware serves a
+// wavefront's LDS instructions in order, this only stops the compiler from
+// moving or merging the accesses across it.
+__device__ inline void wave_lds_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Order-preserving map of a float onto unsigned integers (for atomicMax).
+__device__ inline unsigned int float_key(float v)
+{
+    const unsigned int b = __float_as_uint(v);
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+__device__ inline float key_float(unsigned int key)
+{
+    return __uint_as_float((key & 0x80000000u) ? (key & 0x7fffffffu) : ~key);
+}
+
 // Folds the four logits a lane holds for its row into the running state.
-// z[i] belongs to candidate position c0 + i; positions ascend call after call,
-// so on equal logits the entry already listed (smaller position = smaller
-// token id) stays ahead.
-__device__ inline void fold_logits(const float z[4], int c0, int k, RowState &st, LaneList list)
+// z[i] belongs to candidate position c0 + i with c0 = 16 * tile + 4 * q + i.
+// The four lanes of a row (q = 0..3) insert into the row's list one after the
+// other, in ascending q: positions therefore reach the list in ascending
+// order, tile after tile, and on equal logits the entry already listed
+// (smaller position = smaller token id) stays ahead.
+//
+// *floor_key is a lower bound of the row's final k-th best logit shared by the
+// workgroup's wavefronts (a list that holds k entries >= x proves the k-th
+// best is >= x).  A logit strictly below it cannot be among the k best and
+// skips the list.  When bounds get published only changes how much list work
+// is saved, never which entries survive the merges.
+__device__ inline void fold_logits(const float z[4], int c0, int q, int k, RowState &st, RowList list,
+                                   unsigned int *floor_key)
 {
     const float tmax = fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3]));
     const float mn = fmaxf(st.m, tmax);
     st.s = st.s * fast_exp(st.m - mn) + fast_exp(z[0] - mn) + fast_exp(z[1] - mn) + fast_exp(z[2] - mn) +
            fast_exp(z[3] - mn);
     st.m = mn;
-    if (tmax > st.thr) {
+    const float floor = key_float(__hip_atomic_load(floor_key, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
+    if (__ballot(tmax > st.thr && tmax >= floor) != 0) {   // same decision for the whole wavefront
+        const float thr_before = st.thr;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const float v = z[i];
-            if (v > st.thr) {
-                int p = k - 1;
-                while (p > 0 && list.v(p - 1) < v) {
-                    list.v(p) = list.v(p - 1);
-                    list.i(p) = list.i(p - 1);
-                    --p;
+        for (int turn = 0; turn < 4; ++turn) {
+            if (q == turn && tmax > st.thr && tmax >= floor) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float v = z[i];
+                    if (v > st.thr && v >= floor) {
+                        int p = k - 1;
+                        while (p > 0 && list.v(p - 1) < v) {
+                            list.v(p) = list.v(p - 1);
+                            list.i(p) = list.i(p - 1);
+                            --p;
+                        }
+                        list.v(p) = v;
+                        list.i(p) = c0 + i;
+                        st.thr = list.v(k - 1);
+                    }
                 }
-                list.v(p) = v;
-                list.i(p) = c0 + i;
-                st.thr = list.v(k - 1);
             }
+            wave_lds_fence();
+            if (st.thr != __builtin_inff()) st.thr = list.v(k - 1);   // the row's other lanes may have raised it
+            wave_lds_fence();
         }
+        if (q == 0 && st.thr != __builtin_inff() && st.thr > thr_before && st.thr > floor)
+            atomicMax(floor_key, float_key(st.thr));
     }
 }
 
@@ -109,7 +152,8 @@ template <bool NT>
 __device__ inline void project_item(
     const VpSlabSet &set, const uint4 *__restrict__ hidden, int d, const int32_t *__restrict__ perm,
     const VpItem &item, int it, int tpw, int k, int rstar,
-    float *__restrict__ partials, float *__restrict__ dbg_logits, const int64_t *__restrict__ dbg_row_off)
+    float *__restrict__ partials, unsigned int *__restrict__ floors, float *__restrict__ dbg_logits,
+    const int64_t *__restrict__ dbg_row_off)
 {
     const int KT = set.kt;
     const int X = KT * 4;                       // 16-byte pieces per padded row
@@ -122,11 +166,12 @@ __device__ inline void project_item(
 
     extern __shared__ uint4 lds[];
     uint4 *ldsA = lds;                                                  // KT KiB: the hidden rows
-    float *list_val = reinterpret_cast<float *>(lds + (size_t)KT * 64);  // [4 waves][k][64]
-    int *list_idx = reinterpret_cast<int *>(list_val + VP_WG_WAVES * k * 64);
-    float *hdr_m = reinterpret_cast<float *>(list_idx + VP_WG_WAVES * k * 64);   // [4][16]
+    float *list_val = reinterpret_cast<float *>(lds + (size_t)KT * 64);  // [4 waves][k][16 rows]
+    int *list_idx = reinterpret_cast<int *>(list_val + VP_WG_WAVES * k * 16);
+    float *hdr_m = reinterpret_cast<float *>(list_idx + VP_WG_WAVES * k * 16);   // [4][16]
     float *hdr_s = hdr_m + VP_WG_WAVES * 16;
     int *rowid = reinterpret_cast<int *>(hdr_s + VP_WG_WAVES * 16);             // [16]
+    unsigned int *wg_floor = reinterpret_cast<unsigned int *>(rowid + 16);      // [16]
 
     // this wavefront's run of tiles; its first loads go out before anything else
     const int ncand = set.n_cand[item.cluster];
@@ -144,8 +189,13 @@ __device__ inline void project_item(
         bcur = *reinterpret_cast<const float4 *>(bias + tb * VP_TILE_ITEMS + q * 4);
     }
 
-    if (tid < VP_ROWS_PER_ITEM) rowid[tid] = tid < item.nrows ? perm[item.perm_start + tid] : -1;
-    for (int e = tid; e < VP_WG_WAVES * k * 64; e += VP_WG_THREADS) {
+    if (tid < VP_ROWS_PER_ITEM) {
+        const int row = tid < item.nrows ? perm[item.perm_start + tid] : -1;
+        rowid[tid] = row;
+        // buckets walked by several row groups hand their bound from workgroup to workgroup
+        wg_floor[tid] = (item.shared && row >= 0) ? floors[row] : VP_FLOOR_NONE;
+    }
+    for (int e = tid; e < VP_WG_WAVES * k * 16; e += VP_WG_THREADS) {
         list_val[e] = -__builtin_inff();
         list_idx[e] = VP_IDX_NONE;
     }
@@ -172,11 +222,14 @@ __device__ inline void project_item(
     st.m = VP_NEG_BIG;
     st.s = 0.f;
     st.thr = row_valid ? -__builtin_inff() : __builtin_inff();
-    LaneList list;
-    list.val = list_val + wave * k * 64 + lane;
-    list.idx = list_idx + wave * k * 64 + lane;
+    RowList list;
+    list.val = list_val + wave * k * 16 + n;
+    list.idx = list_idx + wave * k * 16 + n;
     const int64_t dbg_base = (dbg_logits && row_valid) ? dbg_row_off[rowid[n]] : 0;
 
+    const bool exchange = item.shared && wave == 0 && q == 0 && row_valid;
+    unsigned int pending = 0;
+    bool has_pending = false;
     if (tb < te) {
         const int S = (te - tb) * KT;   // 1 KiB steps; KT % 8 == 0
         int kt = 0;
@@ -244,7 +297,21 @@ __device__ inline void project_item(
                     for (int i = 0; i < 4; ++i)
                         if (c0 + i < ncand) dbg_logits[dbg_base + c0 + i] = z[i];
                 }
-                fold_logits(z, c0, k, st, list);
+                fold_logits(z, c0, q, k, st, list, wg_floor + n);
+                if (exchange) {
+                    // Every fourth tile the first wavefront trades bounds with the other workgroups
+                    // that walk this bucket: one atomicMax per row publishes ours and returns
+                    // theirs, which is folded into the LDS copy a tile later (no wait here).
+                    if (has_pending) {
+                        atomicMax(wg_floor + n, pending);
+                        has_pending = false;
+                    }
+                    if (((tile - tb) & 3) == 3) {
+                        pending = atomicMax(floors + rowid[n], __hip_atomic_load(wg_floor + n, __ATOMIC_RELAXED,
+                                                                                 __HIP_MEMORY_SCOPE_WORKGROUP));
+                        has_pending = true;
+                    }
+                }
                 kt = 0;
                 ++tile;
                 if (tile < te) bcur = *reinterpret_cast<const float4 *>(bias + tile * VP_TILE_ITEMS + q * 4);
@@ -267,8 +334,8 @@ __device__ inline void project_item(
     }
     __syncthreads();
 
-    // Combine the workgroup's 16 lane lists per row (4 wavefronts x 4 lanes) into one
-    // partial result per (item, row): k rounds of "best entry after the previous winner".
+    // Combine the workgroup's four lists per row (one per wavefront) into one partial
+    // result per (item, row): k rounds of "best entry after the previous winner".
     const int PFL = vp_partial_floats(k);
     for (int r = wave; r < item.nrows; r += VP_WG_WAVES) {
         float M = hdr_m[r];
@@ -282,19 +349,17 @@ __device__ inline void project_item(
             out[0] = M;
             out[1] = Ssum;
         }
-        // lane -> one of the 16 source lists and a residue class of its slots
-        const int src = lane & 15;
-        const int sw = src >> 2, sq = src & 3;
-        const float *sv = list_val + sw * k * 64 + (sq * 16 + r);
-        const int *si = list_idx + sw * k * 64 + (sq * 16 + r);
+        // lane -> one of the 4 source lists and a residue class (mod 16) of its slots
+        const float *sv = list_val + (lane & 3) * k * 16 + r;
+        const int *si = list_idx + (lane & 3) * k * 16 + r;
         float pv = __builtin_inff();
         int pi = -1;
         for (int t = 0; t < k; ++t) {
             float bv = -__builtin_inff();
             int bi = VP_IDX_NONE;
-            for (int p = lane >> 4; p < k; p += 4) {
-                const float v = sv[p * 64];
-                const int i = si[p * 64];
+            for (int p = lane >> 2; p < k; p += 16) {
+                const float v = sv[p * 16];
+                const int i = si[p * 16];
                 const bool after_prev = v < pv || (v == pv && i > pi);
                 if (after_prev && entry_before(v, i, bv, bi)) {
                     bv = v;
@@ -318,12 +383,14 @@ __device__ inline void project_item(
             pi = bi;
         }
     }
+    if (item.shared && tid < item.nrows) atomicMax(floors + rowid[tid], wg_floor[tid]);
 }
 
 __global__ __launch_bounds__(VP_WG_THREADS) void project_kernel(
     VpSlabSet set, const uint4 *__restrict__ hidden, int d, const int32_t *__restrict__ perm,
     const VpItem *__restrict__ items, const VpPlanHeader *__restrict__ hdr, int k, int rstar,
-    float *__restrict__ partials, float *__restrict__ dbg_logits, const int64_t *__restrict__ dbg_row_off)
+    float *__restrict__ partials, unsigned int *__restrict__ floors, float *__restrict__ dbg_logits,
+    const int64_t *__restrict__ dbg_row_off)
 {
     int it = blockIdx.x;
     const int swz_rgs = hdr->swz_rgs;
@@ -342,16 +409,16 @@ __global__ __launch_bounds__(VP_WG_THREADS) void project_kernel(
     const VpItem item = items[it];
     const int tpw = hdr->tiles_per_wave;
     if (item.shared)
-        project_item<false>(set, hidden, d, perm, item, it, tpw, k, rstar, partials, dbg_logits, dbg_row_off);
+        project_item<false>(set, hidden, d, perm, item, it, tpw, k, rstar, partials, floors, dbg_logits, dbg_row_off);
     else
-        project_item<true>(set, hidden, d, perm, item, it, tpw, k, rstar, partials, dbg_logits, dbg_row_off);
+        project_item<true>(set, hidden, d, perm, item, it, tpw, k, rstar, partials, floors, dbg_logits, dbg_row_off);
 }
 
 }  // namespace
 
 size_t vpk_project_lds_bytes(int kt, int k)
 {
-    return (size_t)kt * VP_TILE_BYTES + (size_t)VP_WG_WAVES * k * 64 * 8 + VP_WG_WAVES * 16 * 8 + 64;
+    return (size_t)kt * VP_TILE_BYTES + (size_t)VP_WG_WAVES * k * 16 * 8 + VP_WG_WAVES * 16 * 8 + 128;
 }
 
 hipError_t vpk_project_prepare()
@@ -361,10 +428,10 @@ hipError_t vpk_project_prepare()
 }
 
 void vpk_project(const VpSlabSet &set, const void *hidden, int d, const int32_t *perm, const VpItem *items,
-                 const VpPlanHeader *hdr, int grid_items, int k, int rstar, float *partials, float *dbg_logits,
-                 const int64_t *dbg_row_off, hipStream_t st)
+                 const VpPlanHeader *hdr, int grid_items, int k, int rstar, float *partials, unsigned int *floors,
+                 float *dbg_logits, const int64_t *dbg_row_off, hipStream_t st)
 {
     hipLaunchKernelGGL(project_kernel, dim3(grid_items), dim3(VP_WG_THREADS), vpk_project_lds_bytes(set.kt, k), st,
-                       set, (const uint4 *)hidden, d, perm, items, hdr, k, rstar, partials, dbg_logits,
+                       set, (const uint4 *)hidden, d, perm, items, hdr, k, rstar, partials, floors, dbg_logits,
                        dbg_row_off);
 }

@@ -138,7 +138,7 @@ vp_status plan_arena(const vp_build_desc *D, bool check_ids, ArenaLayout *L)
 // Byte offsets of the per-call scratch inside the workspace.
 struct WsLayout {
     int max_items;
-    size_t hdr, cpart, g, perm, rowplan, items, partials, total;
+    size_t hdr, cpart, g, perm, rowplan, floors, items, partials, total;
 };
 
 int max_items_clustered(const vp_index *I, int N)
@@ -159,6 +159,7 @@ WsLayout plan_workspace(const vp_index *I, int N)
     W.g = take(n * 4);
     W.perm = take(n * 4);
     W.rowplan = take(n * sizeof(VpRowPlan));
+    W.floors = take(n * 4);
     W.items = take((size_t)W.max_items * sizeof(VpItem));
     W.partials = take((size_t)W.max_items * VP_ROWS_PER_ITEM * vp_partial_floats(I->k_max) * sizeof(float));
     W.total = o;
@@ -219,6 +220,7 @@ vp_status run_clustered(const char *fn, const vp_index *I, const void *hidden, i
     int32_t *g = reinterpret_cast<int32_t *>(ws + W.g);
     int32_t *perm = reinterpret_cast<int32_t *>(ws + W.perm);
     VpRowPlan *rowplan = reinterpret_cast<VpRowPlan *>(ws + W.rowplan);
+    unsigned int *floors = reinterpret_cast<unsigned int *>(ws + W.floors);
     VpItem *items = reinterpret_cast<VpItem *>(ws + W.items);
     float *partials = reinterpret_cast<float *>(ws + W.partials);
 
@@ -231,14 +233,14 @@ vp_status run_clustered(const char *fn, const vp_index *I, const void *hidden, i
 
     const int max_items = max_items_clustered(I, N);
     vpk_plan(cpart, parts, N, I->K, I->clusters.n_cand, I->clusters.tile_off, I->target_items, I->min_items, max_items, g,
-             out_cluster, perm, rowplan, items, hdr, dbg_row_off, st);
+             out_cluster, perm, rowplan, floors, items, hdr, dbg_row_off, st);
 
     const long row_groups = (long)row_tiles + std::min(N, I->K);
     const long by_tiles = row_groups * ceil_div(I->L.max_tiles, VP_WG_WAVES);
     const int grid_items = (int)std::min<long>(max_items, by_tiles);
     auto *ev = profile_slot(I);
     if (ev) (void)hipEventRecord(ev->first, st);
-    vpk_project(I->clusters, hidden, I->d, perm, items, hdr, grid_items, k, I->rstar, partials, dbg_logits,
+    vpk_project(I->clusters, hidden, I->d, perm, items, hdr, grid_items, k, I->rstar, partials, floors, dbg_logits,
                 dbg_row_off, st);
     if (ev) (void)hipEventRecord(ev->second, st);
     if (out_ids)
@@ -253,12 +255,13 @@ vp_status run_full(const char *fn, const vp_index *I, const void *hidden, int N,
     VpPlanHeader *hdr = reinterpret_cast<VpPlanHeader *>(ws + W.hdr);
     int32_t *perm = reinterpret_cast<int32_t *>(ws + W.perm);
     VpRowPlan *rowplan = reinterpret_cast<VpRowPlan *>(ws + W.rowplan);
+    unsigned int *floors = reinterpret_cast<unsigned int *>(ws + W.floors);
     VpItem *items = reinterpret_cast<VpItem *>(ws + W.items);
     float *partials = reinterpret_cast<float *>(ws + W.partials);
 
     const int max_items = max_items_full(I, N);
-    vpk_plan_full(N, I->V, I->L.vtiles, I->full_target_items, I->min_items, max_items, perm, rowplan, items, hdr, dbg_row_off,
-                  st);
+    vpk_plan_full(N, I->V, I->L.vtiles, I->full_target_items, I->min_items, max_items, perm, rowplan, floors, items, hdr,
+                  dbg_row_off, st);
     // the same split the planning kernel makes; with several row groups the projection kernel
     // deals candidate ranges to the XCDs, which needs the grid padded to 8 ranges at a time
     const int rgs = ceil_div(N, VP_ROWS_PER_ITEM);
@@ -269,7 +272,7 @@ vp_status run_full(const char *fn, const vp_index *I, const void *hidden, int N,
     auto *ev = profile_slot(I);
     if (ev) (void)hipEventRecord(ev->first, st);
     vpk_project(I->full, hidden, I->d, perm, items, hdr, grid_items, k, N <= I->rstar ? I->rstar : 0, partials,
-                dbg_logits, dbg_row_off, st);
+                floors, dbg_logits, dbg_row_off, st);
     if (ev) (void)hipEventRecord(ev->second, st);
     if (out_ids)
         vpk_merge(I->full, rowplan, partials, k, N, out_ids, out_logp, st);

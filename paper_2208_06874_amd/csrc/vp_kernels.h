@@ -22,17 +22,18 @@ size_t vpk_plan_lds_bytes(int K);
 hipError_t vpk_plan_prepare();
 void vpk_plan(const void *cpart, int parts, int N, int K, const int32_t *n_cand, const int32_t *tile_off,
               int target_items, int min_items, int max_items, int32_t *g, int32_t *out_cluster, int32_t *perm,
-              VpRowPlan *rowplan, VpItem *items, VpPlanHeader *hdr, int64_t *dbg_row_off, hipStream_t st);
+              VpRowPlan *rowplan, unsigned int *floors, VpItem *items, VpPlanHeader *hdr, int64_t *dbg_row_off,
+              hipStream_t st);
 void vpk_plan_full(int N, int V, int vtiles, int target_items, int min_items, int max_items, int32_t *perm,
-                   VpRowPlan *rowplan,
-                   VpItem *items, VpPlanHeader *hdr, int64_t *dbg_row_off, hipStream_t st);
+                   VpRowPlan *rowplan, unsigned int *floors, VpItem *items, VpPlanHeader *hdr,
+                   int64_t *dbg_row_off, hipStream_t st);
 
 // projection + fused log-softmax / top-k partials
 size_t vpk_project_lds_bytes(int kt, int k);
 hipError_t vpk_project_prepare();
 void vpk_project(const VpSlabSet &set, const void *hidden, int d, const int32_t *perm, const VpItem *items,
-                 const VpPlanHeader *hdr, int grid_items, int k, int rstar, float *partials, float *dbg_logits,
-                 const int64_t *dbg_row_off, hipStream_t st);
+                 const VpPlanHeader *hdr, int grid_items, int k, int rstar, float *partials, unsigned int *floors,
+                 float *dbg_logits, const int64_t *dbg_row_off, hipStream_t st);
 
 // per-row merge
 size_t vpk_merge_lds_bytes(int k);

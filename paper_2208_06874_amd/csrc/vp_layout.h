@@ -93,3 +93,4 @@ static inline __host__ __device__ int vp_partial_floats(int k) { return 2 + 2 * 
 
 #define VP_NEG_BIG (-3.0e38f)
 #define VP_IDX_NONE 0x7fffffff
+#define VP_FLOOR_NONE 0x007fffffu   // order-preserving key of -infinity (float_key in project.hip)
