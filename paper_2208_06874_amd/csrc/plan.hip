@@ -191,7 +191,8 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(
         v.tile0 = ch * tpi;
         v.ntiles = min(tpi, tl[j] - ch * tpi);
         v.shared = rgs > 1;
-        v.pad[0] = v.pad[1] = 0;
+        v.tile_off = tile_off[j];
+        v.ncand = n_cand[j];
         items[it] = v;
     }
     if (tid == 0) {
@@ -259,7 +260,8 @@ __global__ __launch_bounds__(256) void plan_full_kernel(
         v.tile0 = ch * tpi;
         v.ntiles = min(tpi, vtiles - ch * tpi);
         v.shared = rgs > 1;
-        v.pad[0] = v.pad[1] = 0;
+        v.tile_off = 0;
+        v.ncand = V;
         items[it] = v;
     }
     if (gtid == 0) {

@@ -99,11 +99,13 @@ __device__ inline void fold_logits(const float z[4], int c0, int q, int k, RowSt
            fast_exp(z[3] - mn);
     st.m = mn;
     const float floor = key_float(__hip_atomic_load(floor_key, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
-    if (__ballot(tmax > st.thr && tmax >= floor) != 0) {   // same decision for the whole wavefront
+    const unsigned long long mask = __ballot(tmax > st.thr && tmax >= floor);   // lanes with something to insert
+    if (mask != 0) {
         const float thr_before = st.thr;
 #pragma unroll
         for (int turn = 0; turn < 4; ++turn) {
-            if (q == turn && tmax > st.thr && tmax >= floor) {
+            if (((mask >> (turn * 16)) & 0xffffull) == 0) continue;   // nobody in this quarter (wavefront-uniform)
+            if (q == turn && tmax > st.thr) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const float v = z[i];
@@ -174,8 +176,8 @@ __device__ inline void project_item(
     unsigned int *wg_floor = reinterpret_cast<unsigned int *>(rowid + 16);      // [16]
 
     // this wavefront's run of tiles; its first loads go out before anything else
-    const int ncand = set.n_cand[item.cluster];
-    const int toff = set.tile_off[item.cluster];
+    const int ncand = item.ncand;
+    const int toff = item.tile_off;
     const uint4 *slab = reinterpret_cast<const uint4 *>(set.tiles) + (size_t)toff * KT * 64;
     const float *bias = set.bias + (size_t)toff * VP_TILE_ITEMS;
     const int tb = item.tile0 + wave * tpw;
@@ -386,28 +388,39 @@ __device__ inline void project_item(
     if (item.shared && tid < item.nrows) atomicMax(floors + rowid[tid], wg_floor[tid]);
 }
 
+// Which item a workgroup takes.  Workgroups are handed to the 8 XCDs in turn; for a
+// single bucket whose row groups share tiles (the full projection) each XCD gets its
+// own candidate ranges and all row groups of a range follow each other on that XCD,
+// so the range is fetched from HBM once and then served by that XCD's L2.
+__device__ inline int item_of_workgroup(const VpPlanHeader *hdr)
+{
+    int it = blockIdx.x;
+    const int swz_rgs = hdr->swz_rgs;
+    if (swz_rgs > 1) {
+        const int xcd = it & 7;
+        const int t = it >> 3;
+        const int chl = t / swz_rgs;
+        const int ch = chl * 8 + xcd;
+        if (ch >= hdr->swz_chunks) return -1;
+        it = ch * swz_rgs + (t - chl * swz_rgs);
+    }
+    return it;
+}
+
 __global__ __launch_bounds__(VP_WG_THREADS) void project_kernel(
     VpSlabSet set, const uint4 *__restrict__ hidden, int d, const int32_t *__restrict__ perm,
     const VpItem *__restrict__ items, const VpPlanHeader *__restrict__ hdr, int k, int rstar,
     float *__restrict__ partials, unsigned int *__restrict__ floors, float *__restrict__ dbg_logits,
     const int64_t *__restrict__ dbg_row_off)
 {
-    int it = blockIdx.x;
-    const int swz_rgs = hdr->swz_rgs;
-    if (swz_rgs > 1) {
-        // Workgroups are handed to the 8 XCDs in turn.  Give each XCD its own candidate
-        // ranges and let all row groups of a range follow each other on that XCD, so
-        // the range is fetched from HBM once and then served by that XCD's L2.
-        const int xcd = it & 7;
-        const int t = it >> 3;
-        const int chl = t / swz_rgs;
-        const int ch = chl * 8 + xcd;
-        if (ch >= hdr->swz_chunks) return;
-        it = ch * swz_rgs + (t - chl * swz_rgs);
-    }
-    if (it >= hdr->total_items) return;
-    const VpItem item = items[it];
+    // without the swizzle the item record does not depend on the header: both loads go out
+    // together (the grid never exceeds the item array; records past total_items are unused)
+    const VpItem probe = items[blockIdx.x];
+    const int total_items = hdr->total_items;
     const int tpw = hdr->tiles_per_wave;
+    const int it = item_of_workgroup(hdr);
+    if (it < 0 || it >= total_items) return;
+    const VpItem item = it == (int)blockIdx.x ? probe : items[it];
     if (item.shared)
         project_item<false>(set, hidden, d, perm, item, it, tpw, k, rstar, partials, floors, dbg_logits, dbg_row_off);
     else

@@ -145,7 +145,8 @@ int max_items_clustered(const vp_index *I, int N)
 {
     return I->target_items + ceil_div(N, VP_ROWS_PER_ITEM) + std::min(N, I->K) + 2;
 }
-int max_items_full(const vp_index *I, int N) { return I->full_target_items + ceil_div(N, VP_ROWS_PER_ITEM) + 2; }
+// (the grid of the full projection is padded to 8 candidate ranges at a time, one per XCD)
+int max_items_full(const vp_index *I, int N) { return I->full_target_items + 8 * ceil_div(N, VP_ROWS_PER_ITEM) + 2; }
 
 WsLayout plan_workspace(const vp_index *I, int N)
 {

@@ -27,10 +27,11 @@ struct VpItem {
     int32_t cluster;     // slab set entry (cluster id; 0 for the full-vocabulary set)
     int32_t perm_start;  // first position in perm[] of this item's rows
     int32_t nrows;       // 1..16
-    int32_t tile0;       // first candidate tile
+    int32_t tile0;       // first candidate tile, counted within the entry's slab
     int32_t ntiles;      // candidate tiles of this item (split among the 4 wavefronts)
     int32_t shared;      // 1 if other items (further row groups of the bucket) read the same tiles
-    int32_t pad[2];
+    int32_t tile_off;    // first tile of the entry's slab within the slab set (copy of tile_off[cluster])
+    int32_t ncand;       // candidates of the entry (copy of n_cand[cluster])
 };
 
 // Where the merge kernel finds everything about the row at one position of
