@@ -203,16 +203,16 @@ __device__ inline void project_item(
     }
     __syncthreads();
 
-    // stage the hidden rows: MFMA operand order, or row-major for the GEMV loop
+    // Stage the item's hidden rows: MFMA operand order, or row-major for the GEMV loop.
+    // Row slots beyond nrows are left as they are: an MFMA output column depends on its
+    // own operand column only, and those columns are never looked at.
     {
         const int pieces_per_row = d >> 3;
-        const int rows_to_stage = gemv ? item.nrows : VP_ROWS_PER_ITEM;
-        for (int e = tid; e < rows_to_stage * X; e += VP_WG_THREADS) {
+        for (int e = tid; e < item.nrows * X; e += VP_WG_THREADS) {
             const int r = e / X;
             const int x = e - r * X;
             uint4 v = make_uint4(0, 0, 0, 0);
-            const int row = rowid[r];
-            if (row >= 0 && x < pieces_per_row) v = hidden[(size_t)row * pieces_per_row + x];
+            if (x < pieces_per_row) v = hidden[(size_t)rowid[r] * pieces_per_row + x];
             if (gemv) ldsA[r * X + x] = v;
             else ldsA[(x >> 2) * 64 + (x & 3) * 16 + r] = v;
         }
