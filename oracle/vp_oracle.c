@@ -18,7 +18,9 @@
  * Pins (see tests): nearest centroid vs brute-force Euclidean distance,
  * full-list candidate sets reproduce the full projection, full projection vs
  * a library log_softmax(h W + b), sum of exp(logp) over the candidates = 1,
- * hand-computed integer case, tie-break cases.  The paper prints no logits,
+ * hand-computed integer case, tie-break cases; the batch-union form against the
+ * paper's worked example of the boolean list and against the per-cluster form
+ * when all rows share a cluster.  The paper prints no logits,
  * probabilities or cluster ids, so no value here is pinned to a number
  * printed in the paper.
  */
@@ -209,6 +211,63 @@ void vpo_project_full(const uint16_t *W, const uint16_t *b, int d, int V,
         }
         if (out_lse) out_lse[r] = lse;
         if (all_z) memcpy(all_z + (size_t)r * V, z, sizeof(double) * (size_t)V);
+        free(pos);
+        free(z);
+    }
+}
+
+/*
+ * The paper's own batched form of the inference list (section 2.3): the active
+ * sets of the predicted clusters of ALL rows of the batch are united (a
+ * boolean list over the vocabulary, switched on for every active token of
+ * every predicted cluster; the reduced column set U is where it is 1, in
+ * ascending order), every row is projected onto U (step 3), tokens outside U
+ * are at -infinity (step 4) and the softmax (step 5) therefore normalises over
+ * U for every row.
+ *   flags[V] (optional) receives the boolean list, U[V] the reduced column
+ *   set (first *nU entries).  all_z (optional) is N * (*nU) logits, row-major.
+ */
+void vpo_project_union(const uint16_t *W, const uint16_t *b, int d, int V,
+                       const uint16_t *C, int K,
+                       const int64_t *cand_off, const int32_t *cand_ids,
+                       const uint16_t *H, int N, int k, const int32_t *forced_g,
+                       int32_t *out_g, uint8_t *flags, int32_t *U, int32_t *nU,
+                       int32_t *out_ids, double *out_logp, double *out_z,
+                       double *out_lse, double *all_z)
+{
+    double *cnorm = (double *)malloc(sizeof(double) * (size_t)K);
+    vpo_cnorm(C, K, d, cnorm);
+    vpo_assign(H, N, d, C, K, cnorm, out_g, NULL);
+    free(cnorm);
+    if (forced_g)
+        for (int r = 0; r < N; ++r) if (forced_g[r] >= 0) out_g[r] = forced_g[r];
+
+    uint8_t *fl = flags ? flags : (uint8_t *)malloc((size_t)V);
+    memset(fl, 0, (size_t)V);
+    for (int r = 0; r < N; ++r) {
+        int j = out_g[r];
+        for (int64_t c = cand_off[j]; c < cand_off[j + 1]; ++c) fl[cand_ids[c]] = 1;
+    }
+    int n = 0;
+    for (int v = 0; v < V; ++v) if (fl[v]) U[n++] = v;
+    *nU = n;
+    if (!flags) free(fl);
+
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int r = 0; r < N; ++r) {
+        double *z = (double *)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1));
+        int32_t *pos = (int32_t *)malloc(sizeof(int32_t) * (size_t)k);
+        vpo_logits_row(W, b, d, V, H + (size_t)r * d, U, n, z);
+        double lse = n > 0 ? vpo_log_softmax(z, n, NULL) : -INFINITY;
+        vpo_topk(z, n, k, pos);
+        for (int t = 0; t < k; ++t) {
+            int p = pos[t];
+            if (out_ids)  out_ids[(size_t)r * k + t]  = p >= 0 ? U[p] : -1;
+            if (out_logp) out_logp[(size_t)r * k + t] = p >= 0 ? z[p] - lse : -INFINITY;
+            if (out_z)    out_z[(size_t)r * k + t]    = p >= 0 ? z[p] : -INFINITY;
+        }
+        if (out_lse) out_lse[r] = lse;
+        if (all_z) memcpy(all_z + (size_t)r * n, z, sizeof(double) * (size_t)n);
         free(pos);
         free(z);
     }

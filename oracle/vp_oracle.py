@@ -149,6 +149,37 @@ def project(W, b, C, cand_off, cand_ids, H, k: int, forced_g=None, want_all: boo
     return out
 
 
+def project_union(W, b, C, cand_off, cand_ids, H, k: int, forced_g=None, want_all: bool = False):
+    """The paper's batched form: every row is projected onto the union U of the
+    active sets of all predicted clusters and normalised over U.  Returns g, flags
+    (the boolean list over V), U, ids, logp, z, lse and, if want_all, all_z[N, |U|]."""
+    W, b, C, H = _bits(W), _bits(b), _bits(C), _bits(H)
+    d, V = W.shape
+    K = C.shape[0]
+    N = H.shape[0]
+    cand_off = np.ascontiguousarray(cand_off, np.int64)
+    cand_ids = np.ascontiguousarray(cand_ids, np.int32)
+    fg = None if forced_g is None else np.ascontiguousarray(forced_g, np.int32)
+    g = np.empty(N, np.int32)
+    flags = np.zeros(V, np.uint8)
+    U = np.empty(V, np.int32)
+    nU = ctypes.c_int32(0)
+    ids = np.empty((N, k), np.int32)
+    logp = np.empty((N, k), np.float64)
+    z = np.empty((N, k), np.float64)
+    lse = np.empty(N, np.float64)
+    all_z = np.empty((N, V), np.float64) if want_all else None   # upper bound; trimmed below
+    _load().vpo_project_union(_p(W), _p(b), ctypes.c_int(d), ctypes.c_int(V), _p(C), ctypes.c_int(K),
+                              _p(cand_off), _p(cand_ids), _p(H), ctypes.c_int(N), ctypes.c_int(k), _p(fg),
+                              _p(g), _p(flags), _p(U), ctypes.byref(nU), _p(ids), _p(logp), _p(z), _p(lse),
+                              _p(all_z))
+    n = nU.value
+    out = dict(g=g, flags=flags, U=U[:n].copy(), ids=ids, logp=logp, z=z, lse=lse)
+    if want_all:
+        out["all_z"] = all_z.reshape(-1)[: N * n].reshape(N, n).copy()
+    return out
+
+
 def project_full(W, b, H, k: int, want_all: bool = False):
     """Full-vocabulary projection, log-softmax over V and top-k."""
     W, b, H = _bits(W), _bits(b), _bits(H)

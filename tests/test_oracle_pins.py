@@ -273,6 +273,71 @@ def test_logit_points(oracle):
     assert np.array_equal(oracle.logit_points(W, b, H, rows, toks), f["all_z"][rows, toks])
 
 
+# ------------------------------------------------ the paper's batch-union form
+def test_union_worked_example_of_the_boolean_list(oracle):
+    """Section 2.3: predicted centroids {0,1,2} with active sets {2,4,6}, {2,8,9},
+    {1,3} give the boolean list [0,1,1,1,1,0,1,0,1,1] and the columns {1,2,3,4,6,8,9}."""
+    members, rows = _read_golden("batch_union.txt")
+    V, d = len(rows["flags"]), 8
+    r = np.random.default_rng(0)
+    W = (r.standard_normal((d, V)) / 3).astype(np.float16)
+    b = np.zeros(V, np.float16)
+    C = np.eye(3, d).astype(np.float16) * 4
+    H = C.copy()                                   # row i sits on centroid i
+    off = np.zeros(4, np.int64)
+    np.cumsum([len(m) for m in members], out=off[1:])
+    ids = np.concatenate(members).astype(np.int32)
+    u = oracle.project_union(W, b, C, off, ids, H, k=3, want_all=True)
+    assert list(u["g"]) == [0, 1, 2]
+    assert list(u["flags"]) == rows["flags"]
+    assert list(u["U"]) == rows["union"]
+    f = oracle.project_full(W, b, H, k=1, want_all=True)
+    assert np.array_equal(u["all_z"], f["all_z"][:, rows["union"]])
+    assert np.allclose(np.exp(u["all_z"] - u["lse"][:, None]).sum(1), 1.0, atol=1e-12)
+
+
+def test_union_equals_per_cluster_form_when_rows_share_a_cluster(oracle):
+    W, b, C, H = _small(101, d=24, V=70, K=4, N=9)
+    r = np.random.default_rng(101)
+    cand_off, cand_ids = _random_lists(r, 4, 70, 5, 30)
+    forced = np.full(9, 2, np.int32)
+    a = oracle.project(W, b, C, cand_off, cand_ids, H, k=4, forced_g=forced)
+    u = oracle.project_union(W, b, C, cand_off, cand_ids, H, k=4, forced_g=forced)
+    assert np.array_equal(u["U"], cand_ids[cand_off[2]:cand_off[3]])
+    for key in ("g", "ids", "logp", "z", "lse"):
+        assert np.array_equal(a[key], u[key])
+
+
+def test_union_normalises_over_the_union_and_relates_to_the_other_forms(oracle):
+    W, b, C, H = _small(111, d=24, V=90, K=5, N=12)
+    r = np.random.default_rng(111)
+    cand_off, cand_ids = _random_lists(r, 5, 90, 5, 25)
+    kk = 90
+    u = oracle.project_union(W, b, C, cand_off, cand_ids, H, k=kk, want_all=True)
+    a = oracle.project(W, b, C, cand_off, cand_ids, H, k=kk)
+    f = oracle.project_full(W, b, H, k=1, want_all=True)
+    U = u["U"]
+    want_U = np.unique(np.concatenate([cand_ids[cand_off[j]:cand_off[j + 1]] for j in set(u["g"])]))
+    assert np.array_equal(U, want_U) and np.array_equal(np.nonzero(u["flags"])[0], U)
+    n = len(U)
+    for row in range(12):
+        lp = u["logp"][row, :n]
+        assert abs(np.exp(lp).sum() - 1.0) < 1e-12
+        assert np.all(u["ids"][row, n:] == -1)
+        assert np.array_equal(np.sort(u["ids"][row, :n]), U)
+        # the union is a superset of the row's own active set: its normaliser is larger
+        assert u["lse"][row] >= a["lse"][row] - 1e-12
+        # and renormalising the full softmax over U gives the same numbers
+        logp_full = f["all_z"][row] - f["lse"][row]
+        mass = np.log(np.exp(logp_full[U]).sum())
+        assert np.allclose(lp, logp_full[u["ids"][row, :n]] - mass, atol=1e-12)
+    cand_off_f, cand_ids_f = wl.full_lists(5, 90)
+    uf = oracle.project_union(W, b, C, cand_off_f, cand_ids_f, H, k=6)
+    ff = oracle.project_full(W, b, H, k=6)
+    for key in ("ids", "logp", "z", "lse"):
+        assert np.array_equal(uf[key], ff[key])
+
+
 # ------------------------------------------------- workload generator (inputs)
 def _read_golden(name):
     members, rows = [], {}
