@@ -128,6 +128,21 @@ vp_status vp_project_full(const vp_index *idx, const void *hidden, int32_t N, in
                           int32_t *out_ids, float *out_logp,
                           void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* The paper's own batched form of the inference list (section 2.3): the active
+ * sets of the predicted clusters of all N rows are united (boolean list over
+ * the vocabulary -> reduced column set U, ascending), every row is projected
+ * onto U and its log-softmax is normalised over U (tokens outside U are at
+ * -infinity).  Same output contract as vp_project, with logp relative to U;
+ * the two agree when all rows of the batch fall into one cluster.
+ *   out_union_size  device, int32 [1] or NULL: receives |U|
+ *   workspace       device, 256-byte aligned, >= vp_union_workspace_bytes(idx, N)
+ *                   (it also holds the columns of U gathered for this call) */
+size_t vp_union_workspace_bytes(const vp_index *idx, int32_t N_max);
+vp_status vp_project_union(const vp_index *idx, const void *hidden, int32_t N, int32_t k,
+                           int32_t *out_ids, float *out_logp, int32_t *out_cluster,
+                           int32_t *out_union_size, void *workspace, size_t workspace_bytes,
+                           void *hip_stream);
+
 /* Parity/debug entry, not part of the timed path: every candidate logit.
  *   full == 0: row r's logits over its cluster's active set, in list order, at
  *              out_logits[out_row_offsets[r] .. out_row_offsets[r+1]);

@@ -1,0 +1,61 @@
+// Device code shared by the planning kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include "vp_layout.h"
+
+__device__ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// Plan for one bucket that holds all N rows in their own order against one slab
+// of ncand candidates in vtiles tiles (the full vocabulary, or the union of the
+// batch's active sets).  Called by every thread gtid of gsize cooperating threads.
+__device__ inline void vp_plan_single_bucket(int N, int ncand, int vtiles, int target_items, int min_items,
+                                             int max_items, int32_t *__restrict__ perm,
+                                             VpRowPlan *__restrict__ rowplan, unsigned int *__restrict__ floors,
+                                             VpItem *__restrict__ items, VpPlanHeader *__restrict__ hdr,
+                                             int64_t *__restrict__ dbg_row_off, int gtid, int gsize)
+{
+    const int rgs = ceil_div(N, VP_ROWS_PER_ITEM);
+    const long long total_tiles = (long long)rgs * vtiles;
+    const int tpw = vp_tiles_per_wave(total_tiles, target_items, min_items);
+    const int tpi = tpw * VP_WG_WAVES;
+    const int chunks = ceil_div(vtiles, tpi);
+    const int total_items = min(chunks * rgs, max_items);
+    for (int p = gtid; p < N; p += gsize) {
+        perm[p] = p;
+        floors[p] = VP_FLOOR_NONE;
+        VpRowPlan rp;
+        rp.row = p;
+        rp.cluster = 0;
+        rp.item0 = p / VP_ROWS_PER_ITEM;
+        rp.stride = rgs;
+        rp.nit = chunks;
+        rp.local = p % VP_ROWS_PER_ITEM;
+        rp.ids_off = 0;
+        rp.pad = 0;
+        rowplan[p] = rp;
+        if (dbg_row_off) dbg_row_off[p] = (int64_t)p * ncand;
+    }
+    for (int it = gtid; it < total_items; it += gsize) {
+        const int ch = it / rgs;
+        const int rg = it - ch * rgs;
+        VpItem v;
+        v.cluster = 0;
+        v.perm_start = rg * VP_ROWS_PER_ITEM;
+        v.nrows = min(VP_ROWS_PER_ITEM, N - rg * VP_ROWS_PER_ITEM);
+        v.tile0 = ch * tpi;
+        v.ntiles = min(tpi, vtiles - ch * tpi);
+        v.shared = rgs > 1;
+        v.tile_off = 0;
+        v.ncand = ncand;
+        items[it] = v;
+    }
+    if (gtid == 0) {
+        hdr->total_items = total_items;
+        hdr->tiles_per_wave = tpw;
+        hdr->overflow = chunks * rgs > max_items;
+        hdr->total_tiles = (int)min(total_tiles, 2147483647LL);
+        hdr->swz_rgs = rgs > 1 ? rgs : 0;
+        hdr->swz_chunks = chunks;
+        if (dbg_row_off) dbg_row_off[N] = (int64_t)N * ncand;
+    }
+}

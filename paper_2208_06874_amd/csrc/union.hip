@@ -1,0 +1,190 @@
+// The paper's own batched form of the inference list (section 2.3): the active
+// sets of the predicted clusters of all rows of the batch are united and every
+// row is projected onto the union.
+//
+// As in the paper, the union is formed with a boolean list over the vocabulary
+// (bit-packed here): it starts all zero, threads switch on the bits of every
+// active token of every predicted cluster, and a prefix scan over the list
+// yields the reduced column set U in ascending order.  The columns of U are
+// then gathered from the packed copy of W into a slab in the workspace, and
+// the projection / log-softmax / top-k kernels run on that slab with all rows
+// in one bucket, so every row is normalised over U (tokens outside U are at
+// -infinity, steps 4-5).
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include "vp_kernels.h"
+#include "plan_common.h"
+
+namespace {
+
+constexpr int UNION_THREADS = 1024;
+
+// Finishes Eq. 2 (minimum over the centroid parts), lists the occupied clusters
+// and clears the boolean list.
+__global__ __launch_bounds__(UNION_THREADS) void union_prepare_kernel(
+    const int2 *__restrict__ cpart, int parts, int N, int K, int mask_words, int32_t *__restrict__ g,
+    int32_t *__restrict__ out_cluster, int32_t *__restrict__ occ, VpUnionHeader *__restrict__ uh,
+    unsigned int *__restrict__ mask)
+{
+    extern __shared__ int seen[];   // [K]
+    __shared__ int n_occ;
+    const int tid = threadIdx.x;
+    for (int j = tid; j < K; j += UNION_THREADS) seen[j] = 0;
+    for (int w = tid; w < mask_words; w += UNION_THREADS) mask[w] = 0;
+    if (tid == 0) n_occ = 0;
+    __syncthreads();
+    for (int r = tid; r < N; r += UNION_THREADS) {
+        float bs = __builtin_inff();
+        int bj = VP_IDX_NONE;
+        for (int p = 0; p < parts; ++p) {
+            const int2 e = cpart[(size_t)r * parts + p];
+            const float s = __int_as_float(e.x);
+            if (s < bs || (s == bs && e.y < bj)) {
+                bs = s;
+                bj = e.y;
+            }
+        }
+        if (bj < 0 || bj >= K) bj = 0;
+        g[r] = bj;
+        if (out_cluster) out_cluster[r] = bj;
+        seen[bj] = 1;
+    }
+    __syncthreads();
+    for (int j = tid; j < K; j += UNION_THREADS)
+        if (seen[j]) occ[atomicAdd(&n_occ, 1)] = j;   // any order: the boolean list does not care
+    __syncthreads();
+    if (tid == 0) uh->n_occ = n_occ;
+}
+
+// Switches on the bits of the active tokens of every occupied cluster.
+__global__ __launch_bounds__(256) void union_flag_kernel(
+    const int32_t *__restrict__ occ, const VpUnionHeader *__restrict__ uh, const int32_t *__restrict__ tile_off,
+    const int32_t *__restrict__ n_cand, const int32_t *__restrict__ ids, int chunk, unsigned int *__restrict__ mask)
+{
+    if ((int)blockIdx.x >= uh->n_occ) return;
+    const int j = occ[blockIdx.x];
+    const int n = n_cand[j];
+    const int32_t *list = ids + (size_t)tile_off[j] * VP_TILE_ITEMS;
+    const int c1 = min(n, (int)(blockIdx.y + 1) * chunk);
+    for (int c = blockIdx.y * chunk + threadIdx.x; c < c1; c += blockDim.x) {
+        const int v = list[c];
+        const unsigned int bit = 1u << (v & 31);
+        if (!(mask[v >> 5] & bit)) atomicOr(&mask[v >> 5], bit);
+    }
+}
+
+// Prefix scan over the boolean list -> U (ascending, padded with -1 to whole
+// groups of 16), its size, and the plan of the projection over U.
+__global__ __launch_bounds__(UNION_THREADS) void union_compact_kernel(
+    const unsigned int *__restrict__ mask, int mask_words, int V, int N, int target_items, int min_items,
+    int max_items, int32_t *__restrict__ uids, VpUnionHeader *__restrict__ uh, int32_t *__restrict__ out_union_size,
+    int32_t *__restrict__ perm, VpRowPlan *__restrict__ rowplan, unsigned int *__restrict__ floors,
+    VpItem *__restrict__ items, VpPlanHeader *__restrict__ hdr)
+{
+    __shared__ int wsum[UNION_THREADS / 64 + 1];
+    __shared__ int total_s;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int per = (mask_words + UNION_THREADS - 1) / UNION_THREADS;
+    const int w0 = min(tid * per, mask_words), w1 = min(w0 + per, mask_words);
+    int cnt = 0;
+    for (int w = w0; w < w1; ++w) cnt += __popc(mask[w]);
+    // exclusive scan of the per-thread counts
+    int inc = cnt;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int up = __shfl_up(inc, off);
+        if (lane >= off) inc += up;
+    }
+    if (lane == 63) wsum[wave] = inc;
+    __syncthreads();
+    if (tid == 0) {
+        int run = 0;
+        for (int w = 0; w < UNION_THREADS / 64; ++w) {
+            const int t = wsum[w];
+            wsum[w] = run;
+            run += t;
+        }
+        total_s = run;
+    }
+    __syncthreads();
+    int pos = wsum[wave] + inc - cnt;
+    const int nU = total_s;
+    for (int w = w0; w < w1; ++w) {
+        unsigned int bits = mask[w];
+        while (bits) {
+            const int b = __ffs(bits) - 1;
+            bits &= bits - 1;
+            uids[pos++] = w * 32 + b;
+        }
+    }
+    const int tiles = (nU + VP_TILE_ITEMS - 1) / VP_TILE_ITEMS;
+    for (int c = nU + tid; c < tiles * VP_TILE_ITEMS; c += UNION_THREADS) uids[c] = -1;
+    if (tid == 0) {
+        uh->n_union = nU;
+        uh->tiles = tiles;
+        if (out_union_size) *out_union_size = nU;
+    }
+    vp_plan_single_bucket(N, nU, tiles, target_items, min_items, max_items, perm, rowplan, floors, items, hdr,
+                          nullptr, tid, UNION_THREADS);
+}
+
+// Gathers the columns of U from the packed copy of W into the union slab (same
+// tile layout), with their bias.  One workgroup per group of 16 union tokens.
+__global__ __launch_bounds__(256) void union_gather_kernel(
+    const uint4 *__restrict__ wp, const float *__restrict__ bias_full, int kt_count,
+    const int32_t *__restrict__ uids, const VpUnionHeader *__restrict__ uh, uint4 *__restrict__ slab,
+    float *__restrict__ ubias)
+{
+    const int group = blockIdx.x;
+    if (group >= uh->tiles) return;
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int v = uids[group * VP_TILE_ITEMS + (lane & 15)];
+    if (threadIdx.x < 16) ubias[group * VP_TILE_ITEMS + lane] = v >= 0 ? bias_full[v] : 0.f;
+    const int q = lane >> 4;
+    for (int kt = wave; kt < kt_count; kt += VP_WG_WAVES) {
+        uint4 o = make_uint4(0, 0, 0, 0);
+        if (v >= 0) o = wp[((size_t)(v >> 4) * kt_count + kt) * 64 + q * 16 + (v & 15)];
+        slab[((size_t)group * kt_count + kt) * 64 + lane] = o;
+    }
+}
+
+}  // namespace
+
+hipError_t vpk_union_prepare()
+{
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(union_prepare_kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, 32 * 1024);
+}
+
+void vpk_union_mark(const void *cpart, int parts, int N, int K, int mask_words, int32_t *g, int32_t *out_cluster,
+                    int32_t *occ, VpUnionHeader *uh, unsigned int *mask, hipStream_t st)
+{
+    hipLaunchKernelGGL(union_prepare_kernel, dim3(1), dim3(UNION_THREADS), (size_t)K * sizeof(int), st,
+                       (const int2 *)cpart, parts, N, K, mask_words, g, out_cluster, occ, uh, mask);
+}
+
+void vpk_union_flags(const int32_t *occ, const VpUnionHeader *uh, const VpSlabSet &clusters, int max_occ,
+                     int n_max, unsigned int *mask, hipStream_t st)
+{
+    const int chunk = 4096;
+    dim3 grid(max_occ, (n_max + chunk - 1) / chunk);
+    hipLaunchKernelGGL(union_flag_kernel, grid, dim3(256), 0, st, occ, uh, clusters.tile_off, clusters.n_cand,
+                       clusters.ids, chunk, mask);
+}
+
+void vpk_union_compact(const unsigned int *mask, int mask_words, int V, int N, int target_items, int min_items,
+                       int max_items, int32_t *uids, VpUnionHeader *uh, int32_t *out_union_size, int32_t *perm,
+                       VpRowPlan *rowplan, unsigned int *floors, VpItem *items, VpPlanHeader *hdr, hipStream_t st)
+{
+    hipLaunchKernelGGL(union_compact_kernel, dim3(1), dim3(UNION_THREADS), 0, st, mask, mask_words, V, N,
+                       target_items, min_items, max_items, uids, uh, out_union_size, perm, rowplan, floors, items, hdr);
+}
+
+void vpk_union_gather(const void *wp, const float *bias_full, int kt, const int32_t *uids, const VpUnionHeader *uh,
+                      int max_groups, void *slab, float *ubias, hipStream_t st)
+{
+    hipLaunchKernelGGL(union_gather_kernel, dim3(max_groups), dim3(256), 0, st, (const uint4 *)wp, bias_full, kt, uids,
+                       uh, (uint4 *)slab, ubias);
+}

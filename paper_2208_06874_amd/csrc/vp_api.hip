@@ -280,6 +280,30 @@ vp_status run_full(const char *fn, const vp_index *I, const void *hidden, int N,
     return launch_status(fn);
 }
 
+// Extra workspace of the batch-union form, placed after the common part.
+struct UnionLayout {
+    size_t base, uh, occ, mask, uids, ubias, uslab, total;
+    int mask_words;
+};
+
+UnionLayout plan_union_workspace(const vp_index *I, int N)
+{
+    UnionLayout U;
+    U.base = plan_workspace(I, N).total;
+    size_t o = U.base;
+    auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
+    U.mask_words = ceil_div(I->V, 32);
+    const size_t vpad = (size_t)I->L.vtiles * VP_TILE_ITEMS;
+    U.uh = take(sizeof(VpUnionHeader));
+    U.occ = take((size_t)I->K * 4);
+    U.mask = take((size_t)U.mask_words * 4);
+    U.uids = take(vpad * 4);
+    U.ubias = take(vpad * 4);
+    U.uslab = take((size_t)I->L.vtiles * I->L.kt * VP_TILE_BYTES);
+    U.total = o;
+    return U;
+}
+
 }  // namespace
 
 extern "C" {
@@ -311,6 +335,7 @@ vp_status vp_build(const vp_build_desc *D, void *hip_stream, vp_index **out)
     hipError_t e = vpk_plan_prepare();
     if (e == hipSuccess) e = vpk_project_prepare();
     if (e == hipSuccess) e = vpk_merge_prepare();
+    if (e == hipSuccess) e = vpk_union_prepare();
     if (e != hipSuccess) return fail(VP_ERR_HIP, "vp_build: cannot configure kernels: %s", hipGetErrorString(e));
 
     // host-side metadata: candidate groups per cluster, ids padded to whole groups
@@ -496,6 +521,70 @@ vp_status vp_get_profile(vp_index *I, double *kernel_ms_total, int64_t *launches
     }
     P->used = 0;
     return VP_OK;
+}
+
+size_t vp_union_workspace_bytes(const vp_index *I, int32_t N_max)
+{
+    if (!I || N_max < 0 || N_max > VP_MAX_ROWS) {
+        fail(VP_ERR_INVALID_ARG, "vp_union_workspace_bytes: bad index or N_max");
+        return 0;
+    }
+    return plan_union_workspace(I, N_max).total;
+}
+
+vp_status vp_project_union(const vp_index *I, const void *hidden, int32_t N, int32_t k, int32_t *out_ids,
+                           float *out_logp, int32_t *out_cluster, int32_t *out_union_size, void *workspace,
+                           size_t workspace_bytes, void *hip_stream)
+{
+    const char *fn = "vp_project_union";
+    vp_status s = check_call(fn, I, hidden, N, k, out_ids, out_logp, workspace, workspace_bytes, true);
+    if (s != VP_OK || N == 0) return s;
+    const UnionLayout U = plan_union_workspace(I, N);
+    if (workspace_bytes < U.total)
+        return fail(VP_ERR_WORKSPACE, "%s: workspace of %zu bytes, %zu needed for N = %d", fn, workspace_bytes,
+                    U.total, N);
+    hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+    char *ws = static_cast<char *>(workspace);
+    const WsLayout W = plan_workspace(I, N);
+    VpPlanHeader *hdr = reinterpret_cast<VpPlanHeader *>(ws + W.hdr);
+    void *cpart = ws + W.cpart;
+    int32_t *g = reinterpret_cast<int32_t *>(ws + W.g);
+    int32_t *perm = reinterpret_cast<int32_t *>(ws + W.perm);
+    VpRowPlan *rowplan = reinterpret_cast<VpRowPlan *>(ws + W.rowplan);
+    unsigned int *floors = reinterpret_cast<unsigned int *>(ws + W.floors);
+    VpItem *items = reinterpret_cast<VpItem *>(ws + W.items);
+    float *partials = reinterpret_cast<float *>(ws + W.partials);
+    VpUnionHeader *uh = reinterpret_cast<VpUnionHeader *>(ws + U.uh);
+    int32_t *occ = reinterpret_cast<int32_t *>(ws + U.occ);
+    unsigned int *mask = reinterpret_cast<unsigned int *>(ws + U.mask);
+    int32_t *uids = reinterpret_cast<int32_t *>(ws + U.uids);
+    float *ubias = reinterpret_cast<float *>(ws + U.ubias);
+    void *uslab = ws + U.uslab;
+
+    // step 1: predicted centroids (Eq. 2)
+    const int row_tiles = ceil_div(N, 16);
+    int parts = std::min(ceil_div(I->L.ctiles, 4), std::max(1, 2048 / (4 * row_tiles)));
+    const int tpw_c = ceil_div(I->L.ctiles, parts * 4);
+    parts = ceil_div(I->L.ctiles, tpw_c * 4);
+    vpk_centroid(hidden, N, I->d, I->cp, I->cnorm, I->K, I->L.kt, I->L.ctiles, tpw_c, parts, cpart, st);
+    // step 2: boolean list over the vocabulary -> reduced column set U
+    vpk_union_mark(cpart, parts, N, I->K, U.mask_words, g, out_cluster, occ, uh, mask, st);
+    vpk_union_flags(occ, uh, I->clusters, std::min(N, I->K), I->L.n_max, mask, st);
+    const int max_items = max_items_full(I, N);
+    vpk_union_compact(mask, U.mask_words, I->V, N, I->full_target_items, I->min_items, max_items, uids, uh,
+                      out_union_size, perm, rowplan, floors, items, hdr, st);
+    // step 3: the reduced weight matrix and Eq. 1 over it; steps 4-5 fused (no [N, V] array)
+    vpk_union_gather(I->full.tiles, I->full.bias, I->L.kt, uids, uh, I->L.vtiles, uslab, ubias, st);
+    VpSlabSet uset = I->full;
+    uset.tiles = uslab;
+    uset.bias = ubias;
+    uset.ids = uids;
+    // grid: the largest split the planner can choose for |U| <= V
+    const int rgs = ceil_div(N, VP_ROWS_PER_ITEM);
+    const int grid_items = std::min(max_items, ceil_div(rgs * (long)ceil_div(I->L.vtiles, VP_WG_WAVES), 8) * 8 + 8 * rgs);
+    vpk_project(uset, hidden, I->d, perm, items, hdr, grid_items, k, 0, partials, floors, nullptr, nullptr, st);
+    vpk_merge(uset, rowplan, partials, k, N, out_ids, out_logp, st);
+    return launch_status(fn);
 }
 
 void vp_destroy(vp_index *I)

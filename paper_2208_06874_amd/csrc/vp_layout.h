@@ -61,6 +61,14 @@ struct VpPlanHeader {
     int32_t pad[58];
 };
 
+// State of one batch-union projection (see union.hip).
+struct VpUnionHeader {
+    int32_t n_occ;     // occupied clusters
+    int32_t n_union;   // |U|
+    int32_t tiles;     // candidate groups of 16 in the union slab
+    int32_t pad[61];
+};
+
 // A set of packed slabs: the K clusters, or the single whole-vocabulary slab.
 struct VpSlabSet {
     const void *tiles;        // packed fp16 tiles of all entries back to back

@@ -20,8 +20,8 @@ STATUS_NAMES = {0: "VP_OK", 1: "VP_ERR_INVALID_ARG", 2: "VP_ERR_UNSUPPORTED", 3:
                 4: "VP_ERR_HIP"}
 
 EXPORTS = ("vp_build_bytes", "vp_build", "vp_get_info", "vp_set_option", "vp_workspace_bytes",
-           "vp_project", "vp_project_full", "vp_project_debug_logits", "vp_get_profile", "vp_destroy",
-           "vp_last_error")
+           "vp_project", "vp_project_full", "vp_union_workspace_bytes", "vp_project_union",
+           "vp_project_debug_logits", "vp_get_profile", "vp_destroy", "vp_last_error")
 
 
 class VpError(RuntimeError):
@@ -72,6 +72,10 @@ def lib():
         L.vp_project.argtypes = [vp, vp, ctypes.c_int32, ctypes.c_int32, vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.vp_project_full.restype = ctypes.c_int
         L.vp_project_full.argtypes = [vp, vp, ctypes.c_int32, ctypes.c_int32, vp, vp, vp, ctypes.c_size_t, vp]
+        L.vp_union_workspace_bytes.restype = ctypes.c_size_t
+        L.vp_union_workspace_bytes.argtypes = [vp, ctypes.c_int32]
+        L.vp_project_union.restype = ctypes.c_int
+        L.vp_project_union.argtypes = [vp, vp, ctypes.c_int32, ctypes.c_int32, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.vp_project_debug_logits.restype = ctypes.c_int
         L.vp_project_debug_logits.argtypes = [vp, vp, ctypes.c_int32, ctypes.c_int32, vp, vp, vp,
                                               ctypes.c_size_t, vp, ctypes.c_size_t, vp]
@@ -200,6 +204,33 @@ class Index:
                                      out_logp.data_ptr(), ws.data_ptr(), ws.numel(), _stream(stream)))
         return out_ids, out_logp
 
+    def union_workspace_bytes(self, N: int) -> int:
+        return lib().vp_union_workspace_bytes(self.handle, N)
+
+    def project_union(self, hidden, k: int, out_ids=None, out_logp=None, out_cluster=None, out_union_size=None,
+                      workspace=None, stream=None):
+        """vp_project_union: the paper's batched form -> (ids, logp, cluster, union_size[1])."""
+        import torch
+        N = hidden.shape[0]
+        assert hidden.dtype == torch.float16 and hidden.is_contiguous() and hidden.shape[1] == self.d
+        if out_ids is None:
+            out_ids = torch.empty((N, k), dtype=torch.int32, device=self.device)
+        if out_logp is None:
+            out_logp = torch.empty((N, k), dtype=torch.float32, device=self.device)
+        if out_cluster is None:
+            out_cluster = torch.empty((N,), dtype=torch.int32, device=self.device)
+        if out_union_size is None:
+            out_union_size = torch.zeros((1,), dtype=torch.int32, device=self.device)
+        if workspace is None:
+            need = self.union_workspace_bytes(N)
+            if getattr(self, "_uws", None) is None or self._uws.numel() < need:
+                self._uws = torch.empty(max(need, 256), dtype=torch.uint8, device=self.device)
+            workspace = self._uws
+        _check(lib().vp_project_union(self.handle, hidden.data_ptr(), N, k, out_ids.data_ptr(), out_logp.data_ptr(),
+                                      out_cluster.data_ptr(), out_union_size.data_ptr(), workspace.data_ptr(),
+                                      workspace.numel(), _stream(stream)))
+        return out_ids, out_logp, out_cluster, out_union_size
+
     def debug_logits(self, hidden, full: bool = False, stream=None):
         """vp_project_debug_logits -> (cluster[N], row_offsets[N+1] int64, logits fp32)."""
         import torch
@@ -226,6 +257,14 @@ def vp_project(index: Index, hidden, k: int, **kw):
 
 def vp_project_full(index: Index, hidden, k: int, **kw):
     return index.project_full(hidden, k, **kw)
+
+
+def vp_project_union(index: Index, hidden, k: int, **kw):
+    return index.project_union(hidden, k, **kw)
+
+
+def vp_union_workspace_bytes(index: Index, N_max: int) -> int:
+    return index.union_workspace_bytes(N_max)
 
 
 def vp_project_debug_logits(index: Index, hidden, full: bool = False, **kw):

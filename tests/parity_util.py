@@ -100,6 +100,24 @@ def _compare_topk(ref, cand_off, cand_ids, g, k, ids_gpu, logp_gpu):
     return dict(max_logp_err=max_err, excused_ids=excused)
 
 
+def check_union(oracle, W, b, C, cand_off, cand_ids, H, k, ids_gpu, logp_gpu, g_gpu, union_size_gpu):
+    """The batch-union form: every row against the union of the predicted clusters' active sets."""
+    _, excused_c = check_clusters(oracle, H, C, g_gpu)
+    ref = oracle.project_union(W, b, C, cand_off, cand_ids, H, k, forced_g=np.asarray(g_gpu, np.int32),
+                               want_all=True)
+    U = ref["U"]
+    assert int(union_size_gpu) == len(U), "union size %d vs %d" % (int(union_size_gpu), len(U))
+    N = H.shape[0]
+    view = dict(ref)
+    view["all_off"] = np.arange(N + 1, dtype=np.int64) * len(U)
+    view["all_z"] = ref["all_z"].reshape(-1)
+    one_off = np.array([0, len(U)], np.int64)
+    stats = _compare_topk(view, one_off, U, np.zeros(N, np.int64), k, ids_gpu, logp_gpu)
+    stats["excused_clusters"] = excused_c
+    stats["union_size"] = len(U)
+    return stats
+
+
 def check_full(oracle, W, b, H, k, ids_gpu, logp_gpu, logits_gpu=None):
     ref = oracle.project_full(W, b, H, k, want_all=True)
     ref["V"] = W.shape[1]

@@ -30,7 +30,8 @@ def test_library_exports_every_declared_symbol():
 def test_python_binding_has_the_same_names():
     import paper_2208_06874_amd as P
     for n in ("vp_build", "vp_project", "vp_project_full", "vp_project_debug_logits", "vp_workspace_bytes",
-              "vp_set_option", "vp_get_info", "vp_get_profile", "vp_destroy", "vp_last_error"):
+              "vp_set_option", "vp_get_info", "vp_get_profile", "vp_destroy", "vp_last_error", "vp_project_union",
+              "vp_union_workspace_bytes"):
         assert callable(getattr(P, n))
 
 
@@ -103,6 +104,8 @@ def test_calls_reject_null_index():
     assert L.vp_project(None, None, 1, 1, None, None, None, None, 0, None) == vp.VP_ERR_INVALID_ARG
     assert L.vp_project_full(None, None, 1, 1, None, None, None, 0, None) == vp.VP_ERR_INVALID_ARG
     assert L.vp_project_debug_logits(None, None, 1, 0, None, None, None, 0, None, 0, None) == vp.VP_ERR_INVALID_ARG
+    assert L.vp_project_union(None, None, 1, 1, None, None, None, None, None, 0, None) == vp.VP_ERR_INVALID_ARG
+    assert L.vp_union_workspace_bytes(None, 4) == 0
     assert L.vp_workspace_bytes(None, 4) == 0
     assert L.vp_set_option(None, b"rstar", 1) == vp.VP_ERR_INVALID_ARG
     assert L.vp_get_info(None, None) == vp.VP_ERR_INVALID_ARG

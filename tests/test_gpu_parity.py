@@ -50,6 +50,12 @@ class Built:
         torch.cuda.synchronize()
         return pu.to_np(ids), pu.to_np(logp)
 
+    def project_union(self, H, k):
+        import torch
+        ids, logp, g, nu = self.index.project_union(self.rows(H), k)
+        torch.cuda.synchronize()
+        return pu.to_np(ids), pu.to_np(logp), pu.to_np(g), int(nu.item())
+
     def debug(self, H, full=False):
         import torch
         g, offs, z = self.index.debug_logits(self.rows(H), full=full)
@@ -160,6 +166,61 @@ def test_skewed_config(oracle, skewed):
     counts = np.bincount(q, minlength=cfg.K)
     assert counts.max() > 300          # the Zipf head really is a big bucket
     print("skewed", _full_check(oracle, skewed, H, cfg.k, with_logits=False))
+
+
+# ------------------------------------------------------- the paper's batch-union form
+def _union_check(oracle, B, H, k):
+    ids, logp, g, nu = B.project_union(H, k)
+    return pu.check_union(oracle, B.W, B.b, B.C, B.cand_off, B.cand_ids, H, k, ids, logp, g, nu)
+
+
+def test_union_worked_example(oracle):
+    """Section 2.3: clusters {2,4,6}, {2,8,9}, {1,3} predicted together give the columns {1,2,3,4,6,8,9}."""
+    r = np.random.default_rng(0)
+    V, d = 10, 64
+    W = (r.standard_normal((d, V)) / 3).astype(np.float16)
+    b = (r.standard_normal(V) * 0.3).astype(np.float16)
+    C = (np.eye(3, d) * 4).astype(np.float16)
+    off = np.array([0, 3, 6, 8], np.int64)
+    ids = np.array([2, 4, 6, 2, 8, 9, 1, 3], np.int32)
+    B = Built(W, b, C, off, ids, k_max=8)
+    H = C.copy()
+    got_ids, got_logp, g, nu = B.project_union(H, 7)
+    assert list(g) == [0, 1, 2] and nu == 7
+    for row in got_ids:
+        assert sorted(row.tolist()) == [1, 2, 3, 4, 6, 8, 9]
+    pu.check_union(oracle, W, b, C, off, ids, H, 7, got_ids, got_logp, g, nu)
+
+
+def test_union_on_the_workloads(oracle, tiny, mid):
+    H, q = wl.make_rows(tiny.cfg, tiny.C)
+    print("union tiny", _union_check(oracle, tiny, H, tiny.cfg.k))
+    H, q = wl.make_rows(mid.cfg, mid.C, N=8, stream=21)
+    print("union mid N=8", _union_check(oracle, mid, H, mid.cfg.k))
+    H, q = wl.make_rows(mid.cfg, mid.C, N=40, stream=22)        # the paper's beam 2 x batch 20
+    print("union mid N=40", _union_check(oracle, mid, H, mid.cfg.k))
+
+
+def test_union_equals_per_cluster_form_for_one_cluster(oracle, tiny):
+    r = np.random.default_rng(31)
+    H = _rows(r, tiny.C, 21, clusters=np.full(21, 5))
+    a_ids, a_logp, a_g = tiny.project(H, tiny.cfg.k)
+    u_ids, u_logp, u_g, nu = tiny.project_union(H, tiny.cfg.k)
+    assert nu == tiny.cand_off[6] - tiny.cand_off[5]
+    assert np.array_equal(a_ids, u_ids) and np.array_equal(a_g, u_g)
+    assert np.allclose(a_logp, u_logp, rtol=0, atol=1e-5)
+    pu.check_union(oracle, tiny.W, tiny.b, tiny.C, tiny.cand_off, tiny.cand_ids, H, tiny.cfg.k, u_ids, u_logp, u_g, nu)
+
+
+def test_union_ragged_and_large(oracle, large):
+    r, W, b, C = _small_model(12, 40, 777, 7)
+    off, ids = _random_lists(r, 7, 777, 1, 130)
+    B = Built(W, b, C, off, ids, k_max=8)
+    for N in (1, 17, 100):
+        print("union ragged", N, _union_check(oracle, B, _rows(r, C, N), 3))
+    cfg = wl.CONFIGS["sweep"]
+    H, q = wl.make_rows(cfg, large.C, N=4, stream=77)
+    print("union large N=4", _union_check(oracle, large, H, 8))
 
 
 # ------------------------------------------------------------------------- edge cases
