@@ -23,7 +23,10 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, vendor figure
 # HBM bytes per launch of the projection kernel from rocprofv3 --pmc runs
 # (FETCH_SIZE / WRITE_SIZE scaled by a copy kernel of known size); filled in from
 # the summaries under profiles/ for the workloads that have been profiled.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    # profiles/project_kernel_large_N256.md: 3,421,600 KiB x 1.99989 read + 800 KiB written per launch
+    ("large", 256): 7.008e9,
+}
 
 
 def main():
@@ -37,6 +40,7 @@ def main():
     ap.add_argument("--batches", type=int, default=16, help="distinct hidden batches cycled through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-full", action="store_true")
+    ap.add_argument("--no-union", action="store_true")
     ap.add_argument("--option", action="append", default=[], help="library option name=value")
     ap.add_argument("--graph", action="store_true",
                     help="replay each step from a captured HIP graph (one graph per batch) instead of launching it")
@@ -181,6 +185,27 @@ def main():
                                 "hbm_frac": full_bytes / (ms_full_kernel * 1e-3) / 1e9 / HBM_PEAK_GBS,
                                 "mfma_tflops": 2.0 * N * d * cfg.V / (ms_full_kernel * 1e-3) / 1e12}
         result["speedup_vs_full"] = ms_full / ms_step
+
+    if not args.no_union:
+        # the paper's own batched form (union of the active sets of the batch), whole call timed
+        u_ids = torch.empty((N, k), dtype=torch.int32, device=dev)
+        u_logp = torch.empty((N, k), dtype=torch.float32, device=dev)
+        u_g = torch.empty((N,), dtype=torch.int32, device=dev)
+        u_n = torch.zeros((1,), dtype=torch.int32, device=dev)
+        uws = torch.empty(index.union_workspace_bytes(N), dtype=torch.uint8, device=dev)
+
+        def step_union(i):
+            j = i % len(batches)
+            index.project_union(batches[j], k, out_ids=u_ids, out_logp=u_logp, out_cluster=u_g, out_union_size=u_n,
+                                workspace=uws)
+
+        usteps = max(5, args.steps // 4)
+        ms_union, _, _ = timed(step_union, max(2, args.warmup // 4), usteps, profile=False)
+        result["union_form"] = {"rows_per_s": N / (ms_union * 1e-3), "ms_per_step": ms_union,
+                                "union_size_last_step": int(u_n.item()),
+                                "speedup_vs_full": (result["full_vocab"]["ms_per_step"] / ms_union)
+                                if "full_vocab" in result else None}
+        del uws
 
     if not args.no_cpu_baseline:
         # the CPU oracle, as it stands, on the first batch of the same workload
