@@ -392,6 +392,56 @@ def test_results_are_deterministic(mid):
     assert np.array_equal(fa[0], fc[0]) and np.array_equal(fa[1], fc[1])
 
 
+def test_replay_from_a_captured_graph(mid):
+    """vp_project only enqueues kernels (no allocation, no synchronisation, no memset), so a call can be
+    captured into a HIP graph; every replay, with eager work in between, must equal the eager result."""
+    import torch
+    cfg = mid.cfg
+    H, q = wl.make_rows(cfg, mid.C, N=48, stream=5)
+    H2, _ = wl.make_rows(cfg, mid.C, N=48, stream=6)
+    eager = mid.project(H, cfg.k)
+    eager2 = mid.project(H2, cfg.k)
+    dev = mid.dev
+    hbuf = mid.rows(H)
+    ids = torch.empty((48, cfg.k), dtype=torch.int32, device=dev)
+    logp = torch.empty((48, cfg.k), dtype=torch.float32, device=dev)
+    g = torch.empty((48,), dtype=torch.int32, device=dev)
+    ws = torch.empty(mid.index.workspace_bytes(48), dtype=torch.uint8, device=dev)
+    mid.index.project(hbuf, cfg.k, out_ids=ids, out_logp=logp, out_cluster=g, workspace=ws)   # warm-up
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        mid.index.project(hbuf, cfg.k, out_ids=ids, out_logp=logp, out_cluster=g, workspace=ws)
+    for rep in range(4):
+        src, want = (H, eager) if rep % 2 == 0 else (H2, eager2)
+        hbuf.copy_(mid.rows(src))
+        ids.fill_(-7)
+        logp.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(pu.to_np(ids), want[0]) and np.array_equal(pu.to_np(g), want[2])
+        assert np.array_equal(pu.to_np(logp), want[1])
+        mid.project(H2 if rep % 2 == 0 else H, cfg.k)     # eager work between replays
+
+
+def test_union_argument_errors():
+    torch = _torch()
+    from paper_2208_06874_amd import vp
+    r, W, b, C = _small_model(13, 64, 300, 3)
+    off, ids = _random_lists(r, 3, 300, 20, 60)
+    B = Built(W, b, C, off, ids, k_max=4)
+    H = B.rows(_rows(r, C, 4))
+    assert B.index.union_workspace_bytes(4) > B.index.workspace_bytes(4)
+    with pytest.raises(vp.VpError) as e:
+        B.index.project_union(H, 2, workspace=torch.empty(B.index.workspace_bytes(4), dtype=torch.uint8, device=B.dev))
+    assert e.value.status == vp.VP_ERR_WORKSPACE
+    with pytest.raises(vp.VpError) as e:
+        B.index.project_union(H, 9)
+    assert e.value.status == vp.VP_ERR_UNSUPPORTED
+    out = B.index.project_union(torch.empty((0, 64), dtype=torch.float16, device=B.dev), 2)
+    assert out[0].shape == (0, 2)
+
+
 def test_many_rows_many_clusters(oracle):
     """Row and cluster counts near the top of what the planner handles in one call."""
     r, W, b, C = _small_model(10, 64, 4000, 2500)
