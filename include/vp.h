@@ -99,6 +99,8 @@ vp_status vp_get_info(const vp_index *idx, vp_index_info *info);
  *   "rstar"         buckets with at most this many rows use the dot-product
  *                   GEMV loop, larger ones the MFMA loop (default 0, max 4)
  *   "full_target_items"  same as target_items for vp_project_full
+ *   "wide_items"    1 (default): vp_project_full / vp_project_union of more than 16
+ *                   rows with k <= 2 put 32 rows in an item; 0: always 16
  *   "profile"       1: time the projection kernel with HIP events (vp_get_profile)
  * Unknown name or out-of-range value: VP_ERR_INVALID_ARG. */
 vp_status vp_set_option(vp_index *idx, const char *name, int64_t value);

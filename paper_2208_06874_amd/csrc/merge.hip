@@ -20,17 +20,19 @@ __device__ inline bool entry_before(float v, int i, float v2, int i2) { return v
 // ever offers its first entry not yet taken, and a round is one workgroup-wide
 // arg-max over those offers.
 __global__ __launch_bounds__(MERGE_THREADS) void merge_kernel(
-    VpSlabSet set, const VpRowPlan *__restrict__ rowplan, const float *__restrict__ partials, int k,
+    VpSlabSet set, const VpRowPlan *__restrict__ rowplan, const VpPlanHeader *__restrict__ hdr,
+    const float *__restrict__ partials, int k,
     int32_t *__restrict__ out_ids, float *__restrict__ out_logp)
 {
     const VpRowPlan rp = rowplan[blockIdx.x];
+    const int rpi = hdr->rows_per_item;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const int nit = rp.nit;
     const int PFL = vp_partial_floats(k);
-    const float *base = partials + ((size_t)rp.item0 * VP_ROWS_PER_ITEM + rp.local) * PFL;
-    const size_t part_stride = (size_t)rp.stride * VP_ROWS_PER_ITEM * PFL;
+    const float *base = partials + ((size_t)rp.item0 * rpi + rp.local) * PFL;
+    const size_t part_stride = (size_t)rp.stride * rpi * PFL;
 
     extern __shared__ float staged[];            // [2k][256]: entries of each thread's first part
     __shared__ float red_v[MERGE_THREADS / 64];
@@ -151,9 +153,10 @@ hipError_t vpk_merge_prepare()
                                hipFuncAttributeMaxDynamicSharedMemorySize, 72 * 1024);
 }
 
-void vpk_merge(const VpSlabSet &set, const VpRowPlan *rowplan, const float *partials, int k, int N,
+void vpk_merge(const VpSlabSet &set, const VpRowPlan *rowplan, const VpPlanHeader *hdr, const float *partials, int k,
+               int N,
                int32_t *out_ids, float *out_logp, hipStream_t st)
 {
     hipLaunchKernelGGL(merge_kernel, dim3(N), dim3(MERGE_THREADS), vpk_merge_lds_bytes(k), st, set, rowplan,
-                       partials, k, out_ids, out_logp);
+                       hdr, partials, k, out_ids, out_logp);
 }

@@ -202,6 +202,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(
         hdr->total_tiles = total_tiles;
         hdr->swz_rgs = 0;
         hdr->swz_chunks = 0;
+        hdr->rows_per_item = VP_ROWS_PER_ITEM;
     }
 
     // debug entry only: where each row's candidate logits start
@@ -223,11 +224,11 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(
 // Plan of the full-vocabulary projection: one bucket holding every row in
 // order, one slab holding every token.  Nothing depends on device data.
 __global__ __launch_bounds__(256) void plan_full_kernel(
-    int N, int V, int vtiles, int target_items, int min_items, int max_items, int32_t *__restrict__ perm,
+    int N, int V, int vtiles, int rpi, int target_items, int min_items, int max_items, int32_t *__restrict__ perm,
     VpRowPlan *__restrict__ rowplan, unsigned int *__restrict__ floors, VpItem *__restrict__ items,
     VpPlanHeader *__restrict__ hdr, int64_t *__restrict__ dbg_row_off)
 {
-    vp_plan_single_bucket(N, V, vtiles, target_items, min_items, max_items, perm, rowplan, floors, items, hdr,
+    vp_plan_single_bucket(N, V, vtiles, rpi, target_items, min_items, max_items, perm, rowplan, floors, items, hdr,
                           dbg_row_off, blockIdx.x * blockDim.x + threadIdx.x, gridDim.x * blockDim.x);
 }
 
@@ -252,12 +253,12 @@ void vpk_plan(const void *cpart, int parts, int N, int K, const int32_t *n_cand,
                        items, hdr, dbg_row_off);
 }
 
-void vpk_plan_full(int N, int V, int vtiles, int target_items, int min_items, int max_items, int32_t *perm,
+void vpk_plan_full(int N, int V, int vtiles, int rpi, int target_items, int min_items, int max_items, int32_t *perm,
                    VpRowPlan *rowplan, unsigned int *floors, VpItem *items, VpPlanHeader *hdr,
                    int64_t *dbg_row_off, hipStream_t st)
 {
     const int work = max(N, max_items);
     const int blocks = min(64, (work + 255) / 256);
-    hipLaunchKernelGGL(plan_full_kernel, dim3(blocks), dim3(256), 0, st, N, V, vtiles, target_items, min_items, max_items,
+    hipLaunchKernelGGL(plan_full_kernel, dim3(blocks), dim3(256), 0, st, N, V, vtiles, rpi, target_items, min_items, max_items,
                        perm, rowplan, floors, items, hdr, dbg_row_off);
 }

@@ -7,14 +7,15 @@ __device__ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 // Plan for one bucket that holds all N rows in their own order against one slab
 // of ncand candidates in vtiles tiles (the full vocabulary, or the union of the
-// batch's active sets).  Called by every thread gtid of gsize cooperating threads.
-__device__ inline void vp_plan_single_bucket(int N, int ncand, int vtiles, int target_items, int min_items,
+// batch's active sets), rpi (16 or 32) rows per item.  Called by every thread gtid of
+// gsize cooperating threads.
+__device__ inline void vp_plan_single_bucket(int N, int ncand, int vtiles, int rpi, int target_items, int min_items,
                                              int max_items, int32_t *__restrict__ perm,
                                              VpRowPlan *__restrict__ rowplan, unsigned int *__restrict__ floors,
                                              VpItem *__restrict__ items, VpPlanHeader *__restrict__ hdr,
                                              int64_t *__restrict__ dbg_row_off, int gtid, int gsize)
 {
-    const int rgs = ceil_div(N, VP_ROWS_PER_ITEM);
+    const int rgs = ceil_div(N, rpi);
     const long long total_tiles = (long long)rgs * vtiles;
     const int tpw = vp_tiles_per_wave(total_tiles, target_items, min_items);
     const int tpi = tpw * VP_WG_WAVES;
@@ -26,10 +27,10 @@ __device__ inline void vp_plan_single_bucket(int N, int ncand, int vtiles, int t
         VpRowPlan rp;
         rp.row = p;
         rp.cluster = 0;
-        rp.item0 = p / VP_ROWS_PER_ITEM;
+        rp.item0 = p / rpi;
         rp.stride = rgs;
         rp.nit = chunks;
-        rp.local = p % VP_ROWS_PER_ITEM;
+        rp.local = p % rpi;
         rp.ids_off = 0;
         rp.pad = 0;
         rowplan[p] = rp;
@@ -40,8 +41,8 @@ __device__ inline void vp_plan_single_bucket(int N, int ncand, int vtiles, int t
         const int rg = it - ch * rgs;
         VpItem v;
         v.cluster = 0;
-        v.perm_start = rg * VP_ROWS_PER_ITEM;
-        v.nrows = min(VP_ROWS_PER_ITEM, N - rg * VP_ROWS_PER_ITEM);
+        v.perm_start = rg * rpi;
+        v.nrows = min(rpi, N - rg * rpi);
         v.tile0 = ch * tpi;
         v.ntiles = min(tpi, vtiles - ch * tpi);
         v.shared = rgs > 1;
@@ -56,6 +57,7 @@ __device__ inline void vp_plan_single_bucket(int N, int ncand, int vtiles, int t
         hdr->total_tiles = (int)min(total_tiles, 2147483647LL);
         hdr->swz_rgs = rgs > 1 ? rgs : 0;
         hdr->swz_chunks = chunks;
+        hdr->rows_per_item = rpi;
         if (dbg_row_off) dbg_row_off[N] = (int64_t)N * ncand;
     }
 }

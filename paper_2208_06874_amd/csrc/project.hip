@@ -36,7 +36,6 @@ union Frag {
 };
 
 constexpr float LOG2E = 1.4426950408889634f;
-constexpr int PF = 8;   // tile loads in flight per wavefront
 
 __device__ inline float fast_exp(float x) { return __builtin_amdgcn_exp2f(x * LOG2E); }
 
@@ -53,8 +52,9 @@ struct RowState {
 struct RowList {
     float *val;
     int *idx;
-    __device__ inline float &v(int slot) { return val[slot * 16]; }
-    __device__ inline int &i(int slot) { return idx[slot * 16]; }
+    int stride;   // row slots of the item (16 or 32)
+    __device__ inline float &v(int slot) { return val[slot * stride]; }
+    __device__ inline int &i(int slot) { return idx[slot * stride]; }
 };
 
 // Orders LDS traffic between lanes of one wavefront: the hardware serves a
@@ -150,30 +150,36 @@ __device__ inline uint4 load_piece(const uint4 *p)
     return *p;
 }
 
-template <bool NT>
+// PF = 1 KiB tile loads a wavefront keeps in flight.  RT = row tiles of 16 rows per
+// item: 1 everywhere except in single-bucket projections (full, union) of more than
+// 16 rows, where RT = 2 feeds every loaded slab tile to two MFMAs (half the L2-to-CU
+// traffic per row) and, with half as many wavefronts per CU, keeps twice the loads in
+// flight per wavefront.
+template <bool NT, int RT, int PF>
 __device__ inline void project_item(
     const VpSlabSet &set, const uint4 *__restrict__ hidden, int d, const int32_t *__restrict__ perm,
     const VpItem &item, int it, int tpw, int k, int rstar,
     float *__restrict__ partials, unsigned int *__restrict__ floors, float *__restrict__ dbg_logits,
     const int64_t *__restrict__ dbg_row_off)
 {
+    constexpr int ROWS = 16 * RT;               // row slots of an item
     const int KT = set.kt;
     const int X = KT * 4;                       // 16-byte pieces per padded row
     const int tid = threadIdx.x;
     const int wave = tid >> 6;
     const int lane = tid & 63;
-    const int n = lane & 15;                    // row slot this lane owns in the epilogue
+    const int n = lane & 15;                    // this lane owns row slots n, 16 + n, ... in the epilogue
     const int q = lane >> 4;
-    const bool gemv = item.nrows <= rstar;
+    const bool gemv = RT == 1 && item.nrows <= rstar;
 
     extern __shared__ uint4 lds[];
-    uint4 *ldsA = lds;                                                  // KT KiB: the hidden rows
-    float *list_val = reinterpret_cast<float *>(lds + (size_t)KT * 64);  // [4 waves][k][16 rows]
-    int *list_idx = reinterpret_cast<int *>(list_val + VP_WG_WAVES * k * 16);
-    float *hdr_m = reinterpret_cast<float *>(list_idx + VP_WG_WAVES * k * 16);   // [4][16]
-    float *hdr_s = hdr_m + VP_WG_WAVES * 16;
-    int *rowid = reinterpret_cast<int *>(hdr_s + VP_WG_WAVES * 16);             // [16]
-    unsigned int *wg_floor = reinterpret_cast<unsigned int *>(rowid + 16);      // [16]
+    uint4 *ldsA = lds;                                                       // RT * KT KiB: the hidden rows
+    float *list_val = reinterpret_cast<float *>(lds + (size_t)RT * KT * 64);  // [4 waves][k][ROWS]
+    int *list_idx = reinterpret_cast<int *>(list_val + VP_WG_WAVES * k * ROWS);
+    float *hdr_m = reinterpret_cast<float *>(list_idx + VP_WG_WAVES * k * ROWS);   // [4][16]
+    float *hdr_s = hdr_m + VP_WG_WAVES * ROWS;
+    int *rowid = reinterpret_cast<int *>(hdr_s + VP_WG_WAVES * ROWS);             // [ROWS]
+    unsigned int *wg_floor = reinterpret_cast<unsigned int *>(rowid + ROWS);      // [ROWS]
 
     // this wavefront's run of tiles; its first loads go out before anything else
     const int ncand = item.ncand;
@@ -191,13 +197,13 @@ __device__ inline void project_item(
         bcur = *reinterpret_cast<const float4 *>(bias + tb * VP_TILE_ITEMS + q * 4);
     }
 
-    if (tid < VP_ROWS_PER_ITEM) {
+    if (tid < ROWS) {
         const int row = tid < item.nrows ? perm[item.perm_start + tid] : -1;
         rowid[tid] = row;
         // buckets walked by several row groups hand their bound from workgroup to workgroup
         wg_floor[tid] = (item.shared && row >= 0) ? floors[row] : VP_FLOOR_NONE;
     }
-    for (int e = tid; e < VP_WG_WAVES * k * 16; e += VP_WG_THREADS) {
+    for (int e = tid; e < VP_WG_WAVES * k * ROWS; e += VP_WG_THREADS) {
         list_val[e] = -__builtin_inff();
         list_idx[e] = VP_IDX_NONE;
     }
@@ -214,29 +220,38 @@ __device__ inline void project_item(
             uint4 v = make_uint4(0, 0, 0, 0);
             if (x < pieces_per_row) v = hidden[(size_t)rowid[r] * pieces_per_row + x];
             if (gemv) ldsA[r * X + x] = v;
-            else ldsA[(x >> 2) * 64 + (x & 3) * 16 + r] = v;
+            else ldsA[((r >> 4) * KT + (x >> 2)) * 64 + (x & 3) * 16 + (r & 15)] = v;
         }
     }
     __syncthreads();
 
-    const bool row_valid = n < item.nrows;
-    RowState st;
-    st.m = VP_NEG_BIG;
-    st.s = 0.f;
-    st.thr = row_valid ? -__builtin_inff() : __builtin_inff();
-    RowList list;
-    list.val = list_val + wave * k * 16 + n;
-    list.idx = list_idx + wave * k * 16 + n;
-    const int64_t dbg_base = (dbg_logits && row_valid) ? dbg_row_off[rowid[n]] : 0;
+    RowState st[RT];
+    RowList list[RT];
+    bool row_valid[RT];
+    int64_t dbg_base[RT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+        const int slot = rt * 16 + n;
+        row_valid[rt] = slot < item.nrows;
+        st[rt].m = VP_NEG_BIG;
+        st[rt].s = 0.f;
+        st[rt].thr = row_valid[rt] ? -__builtin_inff() : __builtin_inff();
+        list[rt].val = list_val + wave * k * ROWS + slot;
+        list[rt].idx = list_idx + wave * k * ROWS + slot;
+        list[rt].stride = ROWS;
+        dbg_base[rt] = (dbg_logits && row_valid[rt]) ? dbg_row_off[rowid[slot]] : 0;
+    }
 
-    const bool exchange = item.shared && wave == 0 && q == 0 && row_valid;
-    unsigned int pending = 0;
+    const bool exchange = item.shared && wave == 0 && q == 0;
+    unsigned int pending[RT];
     bool has_pending = false;
     if (tb < te) {
         const int S = (te - tb) * KT;   // 1 KiB steps; KT % 8 == 0
         int kt = 0;
         int tile = tb;
-        floatx4 acc = {0.f, 0.f, 0.f, 0.f};        // MFMA: 4 candidates of row n
+        floatx4 acc[RT];                              // MFMA: 4 candidates of row slot rt * 16 + n
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) acc[rt] = floatx4{0.f, 0.f, 0.f, 0.f};
         float ga[VP_GEMV_MAX_ROWS] = {0.f, 0.f, 0.f, 0.f};   // GEMV: candidate n, k-slice q, rows 0..3
 
         for (int s0 = 0; s0 < S; s0 += PF) {
@@ -247,9 +262,12 @@ __device__ inline void project_item(
                 const int nx = s0 + PF + u;
                 if (nx < S) buf[u] = load_piece<NT>(sp + (size_t)nx * 64);
                 if (!gemv) {
-                    Frag b;
-                    b.u = ldsA[(kt + u) * 64 + lane];
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a.h, b.h, acc, 0, 0, 0);
+#pragma unroll
+                    for (int rt = 0; rt < RT; ++rt) {
+                        Frag b;
+                        b.u = ldsA[(rt * KT + kt + u) * 64 + lane];
+                        acc[rt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a.h, b.h, acc[rt], 0, 0, 0);
+                    }
                 } else {
 #pragma unroll
                     for (int r = 0; r < VP_GEMV_MAX_ROWS; ++r) {
@@ -265,52 +283,61 @@ __device__ inline void project_item(
             kt += PF;
             if (kt == KT) {
                 // a group of 16 candidates is complete for all rows
-                float z[4];
-                if (!gemv) {
-                    z[0] = acc[0]; z[1] = acc[1]; z[2] = acc[2]; z[3] = acc[3];
-                    acc = floatx4{0.f, 0.f, 0.f, 0.f};
-                } else {
-                    float full[VP_GEMV_MAX_ROWS];
-#pragma unroll
-                    for (int r = 0; r < VP_GEMV_MAX_ROWS; ++r) {
-                        float t = ga[r];
-                        t += __shfl_xor(t, 16);
-                        t += __shfl_xor(t, 32);
-                        full[r] = t;     // every lane with the same (lane & 15) holds candidate (lane & 15) of row r
-                        ga[r] = 0.f;
-                    }
-                    // hand lane (n, q) the logits of row n for candidates 4q .. 4q+3
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const int src = q * 4 + i;
-                        const float t0 = __shfl(full[0], src);
-                        const float t1 = __shfl(full[1], src);
-                        const float t2 = __shfl(full[2], src);
-                        const float t3 = __shfl(full[3], src);
-                        z[i] = n == 0 ? t0 : n == 1 ? t1 : n == 2 ? t2 : t3;
-                    }
-                }
                 const int c0 = tile * VP_TILE_ITEMS + q * 4;
                 const float bz[4] = {bcur.x, bcur.y, bcur.z, bcur.w};
 #pragma unroll
-                for (int i = 0; i < 4; ++i) z[i] = (c0 + i < ncand) ? z[i] + bz[i] : -__builtin_inff();
-                if (dbg_logits && row_valid) {
+                for (int rt = 0; rt < RT; ++rt) {
+                    float z[4];
+                    if (!gemv) {
+                        z[0] = acc[rt][0]; z[1] = acc[rt][1]; z[2] = acc[rt][2]; z[3] = acc[rt][3];
+                        acc[rt] = floatx4{0.f, 0.f, 0.f, 0.f};
+                    } else {
+                        float full[VP_GEMV_MAX_ROWS];
 #pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        if (c0 + i < ncand) dbg_logits[dbg_base + c0 + i] = z[i];
+                        for (int r = 0; r < VP_GEMV_MAX_ROWS; ++r) {
+                            float t = ga[r];
+                            t += __shfl_xor(t, 16);
+                            t += __shfl_xor(t, 32);
+                            full[r] = t;     // every lane with the same (lane & 15) holds candidate (lane & 15) of row r
+                            ga[r] = 0.f;
+                        }
+                        // hand lane (n, q) the logits of row n for candidates 4q .. 4q+3
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const int src = q * 4 + i;
+                            const float t0 = __shfl(full[0], src);
+                            const float t1 = __shfl(full[1], src);
+                            const float t2 = __shfl(full[2], src);
+                            const float t3 = __shfl(full[3], src);
+                            z[i] = n == 0 ? t0 : n == 1 ? t1 : n == 2 ? t2 : t3;
+                        }
+                    }
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) z[i] = (c0 + i < ncand) ? z[i] + bz[i] : -__builtin_inff();
+                    if (dbg_logits && row_valid[rt]) {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            if (c0 + i < ncand) dbg_logits[dbg_base[rt] + c0 + i] = z[i];
+                    }
+                    fold_logits(z, c0, q, k, st[rt], list[rt], wg_floor + rt * 16 + n);
                 }
-                fold_logits(z, c0, q, k, st, list, wg_floor + n);
                 if (exchange) {
                     // Every fourth tile the first wavefront trades bounds with the other workgroups
                     // that walk this bucket: one atomicMax per row publishes ours and returns
                     // theirs, which is folded into the LDS copy a tile later (no wait here).
                     if (has_pending) {
-                        atomicMax(wg_floor + n, pending);
+#pragma unroll
+                        for (int rt = 0; rt < RT; ++rt)
+                            if (row_valid[rt]) atomicMax(wg_floor + rt * 16 + n, pending[rt]);
                         has_pending = false;
                     }
                     if (((tile - tb) & 3) == 3) {
-                        pending = atomicMax(floors + rowid[n], __hip_atomic_load(wg_floor + n, __ATOMIC_RELAXED,
-                                                                                 __HIP_MEMORY_SCOPE_WORKGROUP));
+#pragma unroll
+                        for (int rt = 0; rt < RT; ++rt)
+                            if (row_valid[rt])
+                                pending[rt] = atomicMax(floors + rowid[rt * 16 + n],
+                                                        __hip_atomic_load(wg_floor + rt * 16 + n, __ATOMIC_RELAXED,
+                                                                          __HIP_MEMORY_SCOPE_WORKGROUP));
                         has_pending = true;
                     }
                 }
@@ -323,16 +350,19 @@ __device__ inline void project_item(
 
     // the four lanes that own a row (one per candidate quarter) -> one (m, s)
 #pragma unroll
-    for (int off = 16; off <= 32; off <<= 1) {
-        const float m2 = __shfl_xor(st.m, off);
-        const float s2 = __shfl_xor(st.s, off);
-        const float mn = fmaxf(st.m, m2);
-        st.s = st.s * fast_exp(st.m - mn) + s2 * fast_exp(m2 - mn);
-        st.m = mn;
-    }
-    if (q == 0) {
-        hdr_m[wave * 16 + n] = st.m;
-        hdr_s[wave * 16 + n] = st.s;
+    for (int rt = 0; rt < RT; ++rt) {
+#pragma unroll
+        for (int off = 16; off <= 32; off <<= 1) {
+            const float m2 = __shfl_xor(st[rt].m, off);
+            const float s2 = __shfl_xor(st[rt].s, off);
+            const float mn = fmaxf(st[rt].m, m2);
+            st[rt].s = st[rt].s * fast_exp(st[rt].m - mn) + s2 * fast_exp(m2 - mn);
+            st[rt].m = mn;
+        }
+        if (q == 0) {
+            hdr_m[wave * ROWS + rt * 16 + n] = st[rt].m;
+            hdr_s[wave * ROWS + rt * 16 + n] = st[rt].s;
+        }
     }
     __syncthreads();
 
@@ -342,26 +372,26 @@ __device__ inline void project_item(
     for (int r = wave; r < item.nrows; r += VP_WG_WAVES) {
         float M = hdr_m[r];
 #pragma unroll
-        for (int w = 1; w < VP_WG_WAVES; ++w) M = fmaxf(M, hdr_m[w * 16 + r]);
+        for (int w = 1; w < VP_WG_WAVES; ++w) M = fmaxf(M, hdr_m[w * ROWS + r]);
         float Ssum = 0.f;
 #pragma unroll
-        for (int w = 0; w < VP_WG_WAVES; ++w) Ssum += hdr_s[w * 16 + r] * fast_exp(hdr_m[w * 16 + r] - M);
-        float *out = partials + ((size_t)it * VP_ROWS_PER_ITEM + r) * PFL;
+        for (int w = 0; w < VP_WG_WAVES; ++w) Ssum += hdr_s[w * ROWS + r] * fast_exp(hdr_m[w * ROWS + r] - M);
+        float *out = partials + ((size_t)it * ROWS + r) * PFL;
         if (lane == 0) {
             out[0] = M;
             out[1] = Ssum;
         }
         // lane -> one of the 4 source lists and a residue class (mod 16) of its slots
-        const float *sv = list_val + (lane & 3) * k * 16 + r;
-        const int *si = list_idx + (lane & 3) * k * 16 + r;
+        const float *sv = list_val + (lane & 3) * k * ROWS + r;
+        const int *si = list_idx + (lane & 3) * k * ROWS + r;
         float pv = __builtin_inff();
         int pi = -1;
         for (int t = 0; t < k; ++t) {
             float bv = -__builtin_inff();
             int bi = VP_IDX_NONE;
             for (int p = lane >> 2; p < k; p += 16) {
-                const float v = sv[p * 16];
-                const int i = si[p * 16];
+                const float v = sv[p * ROWS];
+                const int i = si[p * ROWS];
                 const bool after_prev = v < pv || (v == pv && i > pi);
                 if (after_prev && entry_before(v, i, bv, bi)) {
                     bv = v;
@@ -422,29 +452,59 @@ __global__ __launch_bounds__(VP_WG_THREADS) void project_kernel(
     if (it < 0 || it >= total_items) return;
     const VpItem item = it == (int)blockIdx.x ? probe : items[it];
     if (item.shared)
-        project_item<false>(set, hidden, d, perm, item, it, tpw, k, rstar, partials, floors, dbg_logits, dbg_row_off);
+        project_item<false, 1, 8>(set, hidden, d, perm, item, it, tpw, k, rstar, partials, floors, dbg_logits,
+                                  dbg_row_off);
     else
-        project_item<true>(set, hidden, d, perm, item, it, tpw, k, rstar, partials, floors, dbg_logits, dbg_row_off);
+        project_item<true, 1, 8>(set, hidden, d, perm, item, it, tpw, k, rstar, partials, floors, dbg_logits,
+                                 dbg_row_off);
+}
+
+// Items of up to 32 rows, all sharing their tiles with other row groups: single-bucket
+// projections (full, union) of more than 16 rows.
+__global__ __launch_bounds__(VP_WG_THREADS) void project2_kernel(
+    VpSlabSet set, const uint4 *__restrict__ hidden, int d, const int32_t *__restrict__ perm,
+    const VpItem *__restrict__ items, const VpPlanHeader *__restrict__ hdr, int k,
+    float *__restrict__ partials, unsigned int *__restrict__ floors, float *__restrict__ dbg_logits,
+    const int64_t *__restrict__ dbg_row_off)
+{
+    const int total_items = hdr->total_items;
+    const int tpw = hdr->tiles_per_wave;
+    const int it = item_of_workgroup(hdr);
+    if (it < 0 || it >= total_items) return;
+    const VpItem item = items[it];
+    project_item<false, 2, 16>(set, hidden, d, perm, item, it, tpw, k, 0, partials, floors, dbg_logits, dbg_row_off);
 }
 
 }  // namespace
 
-size_t vpk_project_lds_bytes(int kt, int k)
+size_t vpk_project_lds_bytes(int kt, int k, int row_tiles)
 {
-    return (size_t)kt * VP_TILE_BYTES + (size_t)VP_WG_WAVES * k * 16 * 8 + VP_WG_WAVES * 16 * 8 + 128;
+    const size_t rows = 16 * (size_t)row_tiles;
+    return (size_t)row_tiles * kt * VP_TILE_BYTES + (size_t)VP_WG_WAVES * k * rows * 8 + VP_WG_WAVES * rows * 8 +
+           rows * 8;
 }
 
 hipError_t vpk_project_prepare()
 {
-    return hipFuncSetAttribute(reinterpret_cast<const void *>(project_kernel),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(project_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(project2_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    return e;
 }
 
 void vpk_project(const VpSlabSet &set, const void *hidden, int d, const int32_t *perm, const VpItem *items,
-                 const VpPlanHeader *hdr, int grid_items, int k, int rstar, float *partials, unsigned int *floors,
-                 float *dbg_logits, const int64_t *dbg_row_off, hipStream_t st)
+                 const VpPlanHeader *hdr, int grid_items, int row_tiles, int k, int rstar, float *partials,
+                 unsigned int *floors, float *dbg_logits, const int64_t *dbg_row_off, hipStream_t st)
 {
-    hipLaunchKernelGGL(project_kernel, dim3(grid_items), dim3(VP_WG_THREADS), vpk_project_lds_bytes(set.kt, k), st,
+    if (row_tiles == 2) {
+        hipLaunchKernelGGL(project2_kernel, dim3(grid_items), dim3(VP_WG_THREADS),
+                           vpk_project_lds_bytes(set.kt, k, 2), st, set, (const uint4 *)hidden, d, perm, items, hdr, k,
+                           partials, floors, dbg_logits, dbg_row_off);
+        return;
+    }
+    hipLaunchKernelGGL(project_kernel, dim3(grid_items), dim3(VP_WG_THREADS), vpk_project_lds_bytes(set.kt, k, 1), st,
                        set, (const uint4 *)hidden, d, perm, items, hdr, k, rstar, partials, floors, dbg_logits,
                        dbg_row_off);
 }

@@ -76,7 +76,7 @@ __global__ __launch_bounds__(256) void union_flag_kernel(
 // Prefix scan over the boolean list -> U (ascending, padded with -1 to whole
 // groups of 16), its size, and the plan of the projection over U.
 __global__ __launch_bounds__(UNION_THREADS) void union_compact_kernel(
-    const unsigned int *__restrict__ mask, int mask_words, int V, int N, int target_items, int min_items,
+    const unsigned int *__restrict__ mask, int mask_words, int V, int N, int rpi, int target_items, int min_items,
     int max_items, int32_t *__restrict__ uids, VpUnionHeader *__restrict__ uh, int32_t *__restrict__ out_union_size,
     int32_t *__restrict__ perm, VpRowPlan *__restrict__ rowplan, unsigned int *__restrict__ floors,
     VpItem *__restrict__ items, VpPlanHeader *__restrict__ hdr)
@@ -125,7 +125,7 @@ __global__ __launch_bounds__(UNION_THREADS) void union_compact_kernel(
         uh->tiles = tiles;
         if (out_union_size) *out_union_size = nU;
     }
-    vp_plan_single_bucket(N, nU, tiles, target_items, min_items, max_items, perm, rowplan, floors, items, hdr,
+    vp_plan_single_bucket(N, nU, tiles, rpi, target_items, min_items, max_items, perm, rowplan, floors, items, hdr,
                           nullptr, tid, UNION_THREADS);
 }
 
@@ -174,11 +174,11 @@ void vpk_union_flags(const int32_t *occ, const VpUnionHeader *uh, const VpSlabSe
                        clusters.ids, chunk, mask);
 }
 
-void vpk_union_compact(const unsigned int *mask, int mask_words, int V, int N, int target_items, int min_items,
+void vpk_union_compact(const unsigned int *mask, int mask_words, int V, int N, int rpi, int target_items, int min_items,
                        int max_items, int32_t *uids, VpUnionHeader *uh, int32_t *out_union_size, int32_t *perm,
                        VpRowPlan *rowplan, unsigned int *floors, VpItem *items, VpPlanHeader *hdr, hipStream_t st)
 {
-    hipLaunchKernelGGL(union_compact_kernel, dim3(1), dim3(UNION_THREADS), 0, st, mask, mask_words, V, N,
+    hipLaunchKernelGGL(union_compact_kernel, dim3(1), dim3(UNION_THREADS), 0, st, mask, mask_words, V, N, rpi,
                        target_items, min_items, max_items, uids, uh, out_union_size, perm, rowplan, floors, items, hdr);
 }
 

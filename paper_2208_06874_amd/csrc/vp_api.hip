@@ -61,6 +61,7 @@ struct vp_index {
     const float *cnorm;
     int target_items, full_target_items, rstar;
     int min_items;   // resident workgroup slots of the projection kernel on this GPU
+    int wide_items;  // 1: single-bucket projections of more than 16 rows use items of 32 rows
     VpProfile *prof;
 };
 
@@ -83,7 +84,7 @@ vp_status plan_arena(const vp_build_desc *D, bool check_ids, ArenaLayout *L)
 
     L->d_pad = (D->d + VP_KPAD - 1) / VP_KPAD * VP_KPAD;
     L->kt = L->d_pad / VP_TILE_K;
-    if (vpk_project_lds_bytes(L->kt, D->k_max) > LDS_LIMIT)
+    if (vpk_project_lds_bytes(L->kt, D->k_max, 1) > LDS_LIMIT)
         return fail(VP_ERR_UNSUPPORTED, "vp_build: d = %d with k_max = %d needs more than %zu bytes of LDS", D->d,
                     D->k_max, LDS_LIMIT);
     L->vtiles = ceil_div(D->V, VP_TILE_ITEMS);
@@ -162,7 +163,7 @@ WsLayout plan_workspace(const vp_index *I, int N)
     W.rowplan = take(n * sizeof(VpRowPlan));
     W.floors = take(n * 4);
     W.items = take((size_t)W.max_items * sizeof(VpItem));
-    W.partials = take((size_t)W.max_items * VP_ROWS_PER_ITEM * vp_partial_floats(I->k_max) * sizeof(float));
+    W.partials = take((size_t)W.max_items * VP_MAX_ROWS_PER_ITEM * vp_partial_floats(I->k_max) * sizeof(float));
     W.total = o;
     return W;
 }
@@ -210,6 +211,16 @@ std::pair<hipEvent_t, hipEvent_t> *profile_slot(const vp_index *I)
     return &P->pool[P->used++];
 }
 
+// Row tiles per item for projections that keep all rows in one bucket (full, union).
+// Two row tiles per loaded slab tile pay off (measured: -10 % at top-1, N = 256) only
+// while the top-k lists are short; with longer lists the epilogue of two row tiles in
+// half as many wavefronts costs more than the saved L2 traffic (+40 % at top-8).
+int single_bucket_row_tiles(const vp_index *I, int N, int k)
+{
+    if (!I->wide_items || k > 2 || N <= VP_ROWS_PER_ITEM || I->L.kt % 16 != 0) return 1;
+    return vpk_project_lds_bytes(I->L.kt, k, 2) <= LDS_LIMIT / 2 ? 2 : 1;
+}
+
 // The kernel sequence shared by vp_project and the clustered debug entry.
 vp_status run_clustered(const char *fn, const vp_index *I, const void *hidden, int N, int k, int32_t *out_ids,
                         float *out_logp, int32_t *out_cluster, char *ws, int64_t *dbg_row_off, float *dbg_logits,
@@ -241,11 +252,11 @@ vp_status run_clustered(const char *fn, const vp_index *I, const void *hidden, i
     const int grid_items = (int)std::min<long>(max_items, by_tiles);
     auto *ev = profile_slot(I);
     if (ev) (void)hipEventRecord(ev->first, st);
-    vpk_project(I->clusters, hidden, I->d, perm, items, hdr, grid_items, k, I->rstar, partials, floors, dbg_logits,
+    vpk_project(I->clusters, hidden, I->d, perm, items, hdr, grid_items, 1, k, I->rstar, partials, floors, dbg_logits,
                 dbg_row_off, st);
     if (ev) (void)hipEventRecord(ev->second, st);
     if (out_ids)
-        vpk_merge(I->clusters, rowplan, partials, k, N, out_ids, out_logp, st);
+        vpk_merge(I->clusters, rowplan, hdr, partials, k, N, out_ids, out_logp, st);
     return launch_status(fn);
 }
 
@@ -260,23 +271,25 @@ vp_status run_full(const char *fn, const vp_index *I, const void *hidden, int N,
     VpItem *items = reinterpret_cast<VpItem *>(ws + W.items);
     float *partials = reinterpret_cast<float *>(ws + W.partials);
 
+    // more than 16 rows: two row tiles per item when two such workgroups fit in a CU's LDS
+    const int row_tiles = single_bucket_row_tiles(I, N, k);
+    const int rpi = VP_ROWS_PER_ITEM * row_tiles;
     const int max_items = max_items_full(I, N);
-    vpk_plan_full(N, I->V, I->L.vtiles, I->full_target_items, I->min_items, max_items, perm, rowplan, floors, items, hdr,
-                  dbg_row_off, st);
+    vpk_plan_full(N, I->V, I->L.vtiles, rpi, I->full_target_items, I->min_items, max_items, perm, rowplan, floors,
+                  items, hdr, dbg_row_off, st);
     // the same split the planning kernel makes; with several row groups the projection kernel
     // deals candidate ranges to the XCDs, which needs the grid padded to 8 ranges at a time
-    const int rgs = ceil_div(N, VP_ROWS_PER_ITEM);
+    const int rgs = ceil_div(N, rpi);
     const int tpw = vp_tiles_per_wave((long long)rgs * I->L.vtiles, I->full_target_items, I->min_items);
     const int chunks = ceil_div(I->L.vtiles, (long)tpw * VP_WG_WAVES);
     const int grid_items = rgs > 1 ? ceil_div(chunks, 8) * 8 * rgs : chunks;
-    // the GEMV loop is reserved for the clustered buckets; the full projection keeps its rows in one bucket
     auto *ev = profile_slot(I);
     if (ev) (void)hipEventRecord(ev->first, st);
-    vpk_project(I->full, hidden, I->d, perm, items, hdr, grid_items, k, N <= I->rstar ? I->rstar : 0, partials,
-                floors, dbg_logits, dbg_row_off, st);
+    vpk_project(I->full, hidden, I->d, perm, items, hdr, grid_items, row_tiles, k, N <= I->rstar ? I->rstar : 0,
+                partials, floors, dbg_logits, dbg_row_off, st);
     if (ev) (void)hipEventRecord(ev->second, st);
     if (out_ids)
-        vpk_merge(I->full, rowplan, partials, k, N, out_ids, out_logp, st);
+        vpk_merge(I->full, rowplan, hdr, partials, k, N, out_ids, out_logp, st);
     return launch_status(fn);
 }
 
@@ -399,11 +412,12 @@ vp_status vp_build(const vp_build_desc *D, void *hip_stream, vp_index **out)
     I->target_items = 8192;
     I->full_target_items = 2048;
     I->rstar = 0;
+    I->wide_items = 1;
     {
         // workgroups of the projection kernel that fit on the chip at once (LDS-limited)
         int dev = 0, cus = 256;
         if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-        const size_t lds = vpk_project_lds_bytes(L.kt, D->k_max);
+        const size_t lds = vpk_project_lds_bytes(L.kt, D->k_max, 1);
         const int per_cu = (int)std::max<size_t>(1, std::min<size_t>(8, LDS_LIMIT / lds));
         I->min_items = std::max(1, cus) * per_cu;
     }
@@ -443,6 +457,11 @@ vp_status vp_set_option(vp_index *I, const char *name, int64_t value)
             return fail(VP_ERR_INVALID_ARG, "vp_set_option: rstar = %lld must be in [0, %d]", (long long)value,
                         VP_GEMV_MAX_ROWS);
         I->rstar = (int)value;
+        return VP_OK;
+    }
+    if (!std::strcmp(name, "wide_items")) {
+        if (value != 0 && value != 1) return fail(VP_ERR_INVALID_ARG, "vp_set_option: wide_items must be 0 or 1");
+        I->wide_items = (int)value;
         return VP_OK;
     }
     if (!std::strcmp(name, "profile")) {
@@ -571,7 +590,8 @@ vp_status vp_project_union(const vp_index *I, const void *hidden, int32_t N, int
     vpk_union_mark(cpart, parts, N, I->K, U.mask_words, g, out_cluster, occ, uh, mask, st);
     vpk_union_flags(occ, uh, I->clusters, std::min(N, I->K), I->L.n_max, mask, st);
     const int max_items = max_items_full(I, N);
-    vpk_union_compact(mask, U.mask_words, I->V, N, I->full_target_items, I->min_items, max_items, uids, uh,
+    const int row_tiles_u = single_bucket_row_tiles(I, N, k);
+    vpk_union_compact(mask, U.mask_words, I->V, N, VP_ROWS_PER_ITEM * row_tiles_u, I->full_target_items, I->min_items, max_items, uids, uh,
                       out_union_size, perm, rowplan, floors, items, hdr, st);
     // step 3: the reduced weight matrix and Eq. 1 over it; steps 4-5 fused (no [N, V] array)
     vpk_union_gather(I->full.tiles, I->full.bias, I->L.kt, uids, uh, I->L.vtiles, uslab, ubias, st);
@@ -580,10 +600,11 @@ vp_status vp_project_union(const vp_index *I, const void *hidden, int32_t N, int
     uset.bias = ubias;
     uset.ids = uids;
     // grid: the largest split the planner can choose for |U| <= V
-    const int rgs = ceil_div(N, VP_ROWS_PER_ITEM);
+    const int rgs = ceil_div(N, VP_ROWS_PER_ITEM * row_tiles_u);
     const int grid_items = std::min(max_items, ceil_div(rgs * (long)ceil_div(I->L.vtiles, VP_WG_WAVES), 8) * 8 + 8 * rgs);
-    vpk_project(uset, hidden, I->d, perm, items, hdr, grid_items, k, 0, partials, floors, nullptr, nullptr, st);
-    vpk_merge(uset, rowplan, partials, k, N, out_ids, out_logp, st);
+    vpk_project(uset, hidden, I->d, perm, items, hdr, grid_items, row_tiles_u, k, 0, partials, floors, nullptr,
+                nullptr, st);
+    vpk_merge(uset, rowplan, hdr, partials, k, N, out_ids, out_logp, st);
     return launch_status(fn);
 }
 

@@ -24,21 +24,21 @@ void vpk_plan(const void *cpart, int parts, int N, int K, const int32_t *n_cand,
               int target_items, int min_items, int max_items, int32_t *g, int32_t *out_cluster, int32_t *perm,
               VpRowPlan *rowplan, unsigned int *floors, VpItem *items, VpPlanHeader *hdr, int64_t *dbg_row_off,
               hipStream_t st);
-void vpk_plan_full(int N, int V, int vtiles, int target_items, int min_items, int max_items, int32_t *perm,
+void vpk_plan_full(int N, int V, int vtiles, int rpi, int target_items, int min_items, int max_items, int32_t *perm,
                    VpRowPlan *rowplan, unsigned int *floors, VpItem *items, VpPlanHeader *hdr,
                    int64_t *dbg_row_off, hipStream_t st);
 
 // projection + fused log-softmax / top-k partials
-size_t vpk_project_lds_bytes(int kt, int k);
+size_t vpk_project_lds_bytes(int kt, int k, int row_tiles);
 hipError_t vpk_project_prepare();
 void vpk_project(const VpSlabSet &set, const void *hidden, int d, const int32_t *perm, const VpItem *items,
-                 const VpPlanHeader *hdr, int grid_items, int k, int rstar, float *partials, unsigned int *floors,
-                 float *dbg_logits, const int64_t *dbg_row_off, hipStream_t st);
+                 const VpPlanHeader *hdr, int grid_items, int row_tiles, int k, int rstar, float *partials,
+                 unsigned int *floors, float *dbg_logits, const int64_t *dbg_row_off, hipStream_t st);
 
 // per-row merge
 size_t vpk_merge_lds_bytes(int k);
 hipError_t vpk_merge_prepare();
-void vpk_merge(const VpSlabSet &set, const VpRowPlan *rowplan, const float *partials, int k, int N,
+void vpk_merge(const VpSlabSet &set, const VpRowPlan *rowplan, const VpPlanHeader *hdr, const float *partials, int k, int N,
                int32_t *out_ids, float *out_logp, hipStream_t st);
 
 // the paper's batch-union form
@@ -47,7 +47,7 @@ void vpk_union_mark(const void *cpart, int parts, int N, int K, int mask_words, 
                     int32_t *occ, VpUnionHeader *uh, unsigned int *mask, hipStream_t st);
 void vpk_union_flags(const int32_t *occ, const VpUnionHeader *uh, const VpSlabSet &clusters, int max_occ,
                      int n_max, unsigned int *mask, hipStream_t st);
-void vpk_union_compact(const unsigned int *mask, int mask_words, int V, int N, int target_items, int min_items,
+void vpk_union_compact(const unsigned int *mask, int mask_words, int V, int N, int rpi, int target_items, int min_items,
                        int max_items, int32_t *uids, VpUnionHeader *uh, int32_t *out_union_size, int32_t *perm,
                        VpRowPlan *rowplan, unsigned int *floors, VpItem *items, VpPlanHeader *hdr, hipStream_t st);
 void vpk_union_gather(const void *wp, const float *bias_full, int kt, const int32_t *uids, const VpUnionHeader *uh,

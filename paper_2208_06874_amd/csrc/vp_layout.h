@@ -19,6 +19,7 @@
 #define VP_WG_THREADS 256      // projection kernel: 4 wavefronts per workgroup
 #define VP_WG_WAVES 4
 #define VP_ROWS_PER_ITEM 16    // rows one work item projects (one MFMA row tile)
+#define VP_MAX_ROWS_PER_ITEM 32  // with two row tiles (single-bucket projections of more than 16 rows)
 #define VP_GEMV_MAX_ROWS 4
 
 // One unit of projection work: up to 16 rows of one bucket against a range of
@@ -58,7 +59,8 @@ struct VpPlanHeader {
     // full-vocabulary projection): 0, or the number of row groups / candidate ranges.
     int32_t swz_rgs;
     int32_t swz_chunks;
-    int32_t pad[58];
+    int32_t rows_per_item;   // row slots per item in the partial results (16, or 32 with two row tiles)
+    int32_t pad[57];
 };
 
 // State of one batch-union projection (see union.hip).

@@ -392,6 +392,27 @@ def test_results_are_deterministic(mid):
     assert np.array_equal(fa[0], fc[0]) and np.array_equal(fa[1], fc[1])
 
 
+def test_wide_items_of_the_full_projection(oracle, tiny):
+    """Items of 32 rows (two row tiles per slab tile) are used for k <= 2 and more than 16 rows."""
+    cfg = tiny.cfg
+    H, q = wl.make_rows(cfg, tiny.C, N=75, stream=9)
+    for k in (1, 2):
+        wide = tiny.project_full(H, k)
+        print("wide full", k, pu.check_full(oracle, tiny.W, tiny.b, H, k, wide[0], wide[1]))
+        tiny.index.set_option("wide_items", 0)
+        try:
+            narrow = tiny.project_full(H, k)
+        finally:
+            tiny.index.set_option("wide_items", 1)
+        assert np.array_equal(wide[0], narrow[0])
+        assert np.allclose(wide[1], narrow[1], rtol=0, atol=1e-4)
+    ids, logp, g, nu = tiny.project_union(H, 2)
+    pu.check_union(oracle, tiny.W, tiny.b, tiny.C, tiny.cand_off, tiny.cand_ids, H, 2, ids, logp, g, nu)
+    _, _, zf = tiny.debug(H[:40], full=True)
+    f = oracle.project_full(tiny.W, tiny.b, H[:40], 1, want_all=True)
+    assert np.abs(zf.reshape(40, -1) - f["all_z"]).max() < pu.SANITY
+
+
 def test_replay_from_a_captured_graph(mid):
     """vp_project only enqueues kernels (no allocation, no synchronisation, no memset), so a call can be
     captured into a HIP graph; every replay, with eager work in between, must equal the eager result."""
