@@ -41,6 +41,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-full", action="store_true")
     ap.add_argument("--no-union", action="store_true")
+    ap.add_argument("--no-dispatch", action="store_true")
     ap.add_argument("--option", action="append", default=[], help="library option name=value")
     ap.add_argument("--graph", action="store_true",
                     help="replay each step from a captured HIP graph (one graph per batch) instead of launching it")
@@ -185,6 +186,16 @@ def main():
                                 "hbm_frac": full_bytes / (ms_full_kernel * 1e-3) / 1e9 / HBM_PEAK_GBS,
                                 "mfma_tflops": 2.0 * N * d * cfg.V / (ms_full_kernel * 1e-3) / 1e12}
         result["speedup_vs_full"] = ms_full / ms_step
+
+    if not args.no_dispatch:
+        # vp_project with the planner allowed to pick the masked full projection (same results)
+        index.set_option("dispatch", 1)
+        dsteps = max(5, args.steps // 4)
+        ms_disp, _, _ = timed(step, max(2, args.warmup // 4), dsteps, profile=False)
+        mode = int(ws[:64].view(torch.int32)[7].item())
+        index.set_option("dispatch", 0)
+        result["with_dispatch"] = {"rows_per_s": N / (ms_disp * 1e-3), "ms_per_step": ms_disp,
+                                   "planner_chose": "masked full projection" if mode == 1 else "per-cluster slabs"}
 
     if not args.no_union:
         # the paper's own batched form (union of the active sets of the batch), whole call timed

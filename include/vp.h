@@ -99,6 +99,11 @@ vp_status vp_get_info(const vp_index *idx, vp_index_info *info);
  *   "rstar"         buckets with at most this many rows use the dot-product
  *                   GEMV loop, larger ones the MFMA loop (default 0, max 4)
  *   "full_target_items"  same as target_items for vp_project_full
+ *   "dispatch"      1: vp_project may run the full projection with every row masked to
+ *                   its own cluster's active set instead of streaming the occupied
+ *                   slabs, when the planner's cost model says that is cheaper (many
+ *                   occupied clusters); same results.  Default 0.
+ *   "cost_bw_slab_gbs", "cost_bw_full_gbs", "cost_bw_l2_gbs"  GB/s of the cost model
  *   "wide_items"    1 (default): vp_project_full / vp_project_union of more than 16
  *                   rows with k <= 2 put 32 rows in an item; 0: always 16
  *   "profile"       1: time the projection kernel with HIP events (vp_get_profile)

@@ -100,7 +100,32 @@ __global__ __launch_bounds__(256) void gather_slab_kernel(
     }
 }
 
+// Membership bit lists: bit v of cluster j's list is set iff token v is in A_j (the
+// list must be zero beforehand).  One workgroup of 16 threads' worth of work per group
+// of 16 candidates; the cluster of a group is found by bisection of the tile offsets.
+__global__ __launch_bounds__(64) void bitmap_kernel(const int32_t *__restrict__ ids_pad,
+                                                    const int32_t *__restrict__ tile_off, int K, long total_groups,
+                                                    int words, uint32_t *__restrict__ bitmaps)
+{
+    const long group = (long)blockIdx.x * 4 + (threadIdx.x >> 4);
+    if (group >= total_groups) return;
+    int lo = 0, hi = K;   // largest j with tile_off[j] <= group
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (tile_off[mid] <= group) lo = mid; else hi = mid;
+    }
+    const int v = ids_pad[group * VP_TILE_ITEMS + (threadIdx.x & 15)];
+    if (v >= 0) atomicOr(&bitmaps[(size_t)lo * words + (v >> 5)], 1u << (v & 31));
+}
+
 }  // namespace
+
+void vpk_bitmaps(const int32_t *ids_pad, const int32_t *tile_off, int K, long total_groups, int words,
+                 uint32_t *bitmaps, hipStream_t st)
+{
+    hipLaunchKernelGGL(bitmap_kernel, dim3((unsigned)((total_groups + 3) / 4)), dim3(64), 0, st, ids_pad, tile_off, K,
+                       total_groups, words, bitmaps);
+}
 
 void vpk_pack_w(const void *W, int d, int V, int kt, void *out, hipStream_t st)
 {

@@ -75,7 +75,8 @@ __global__ __launch_bounds__(MERGE_THREADS) void merge_kernel(
     const float lse = M + __builtin_amdgcn_logf(S) * LN2;
     __syncthreads();
 
-    const int32_t *ids = set.ids ? set.ids + rp.ids_off : nullptr;
+    // (in the masked full projection candidate positions are token ids already)
+    const int32_t *ids = (set.ids && hdr->mode == 0) ? set.ids + rp.ids_off : nullptr;
 
     int pos = 0;                                  // entries of the first part already taken
     float cv = -__builtin_inff();

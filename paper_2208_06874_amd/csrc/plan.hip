@@ -58,7 +58,9 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(
     const int2 *__restrict__ cpart, int parts, int N, int K, const int32_t *__restrict__ n_cand,
     const int32_t *__restrict__ tile_off, int target_items, int min_items, int max_items, int32_t *__restrict__ g,
     int32_t *__restrict__ out_cluster, int32_t *__restrict__ perm, VpRowPlan *__restrict__ rowplan,
-    unsigned int *__restrict__ floors, VpItem *__restrict__ items, VpPlanHeader *__restrict__ hdr, int64_t *__restrict__ dbg_row_off)
+    unsigned int *__restrict__ floors, VpItem *__restrict__ items, VpPlanHeader *__restrict__ hdr,
+    int64_t *__restrict__ dbg_row_off, int dispatch, VpCostModel cost, int k, int V, int vtiles,
+    int full_target_items, int max_items_full)
 {
     extern __shared__ int lds[];
     int *cnt = lds;             // [K]   rows per cluster, later the scatter cursor
@@ -108,7 +110,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(
 
     // exclusive scan of the histogram -> bucket offsets; total candidate tiles of all row groups
     int carry = 0;
-    int my_tiles = 0;
+    int my_tiles = 0, my_occ_tiles = 0;
     for (int base = 0; base < K; base += PLAN_THREADS) {
         const int j = base + tid;
         const int c = j < K ? cnt[j] : 0;
@@ -117,12 +119,34 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(
         if (j < K) {
             off[j] = carry + ex;
             my_tiles += ceil_div(c, VP_ROWS_PER_ITEM) * tl[j];
+            if (c > 0) my_occ_tiles += tl[j];
         }
         carry += tot;
     }
     if (tid == 0) off[K] = carry;
     int total_tiles;
     block_exscan<int>(my_tiles, &total_tiles, wsum);
+
+    // Cost model: the occupied slabs are streamed once from HBM, further row groups of a
+    // bucket re-read them through the L2; the masked full projection streams W once and
+    // re-reads it through the L2 for every further group of 16 rows.  Both give the same
+    // results, so the cheaper one is taken.
+    if (dispatch) {
+        int occ_tiles;
+        block_exscan<int>(my_occ_tiles, &occ_tiles, wsum);
+        const int rgs_full = ceil_div(N, VP_ROWS_PER_ITEM);
+        const float t_slab = occ_tiles / cost.bw_slab + (total_tiles - occ_tiles) / cost.bw_l2;
+        // the top-k lists cost the full projection more than the slabs (every lane of every
+        // wavefront is busy there): a margin that grows with k keeps the choice on the safe side
+        const float t_full = fmaxf(vtiles / cost.bw_full, (float)rgs_full * vtiles / cost.bw_l2) * (1.f + k * 0.125f);
+        if (t_full < t_slab) {
+            __syncthreads();
+            vp_plan_single_bucket(N, V, vtiles, VP_ROWS_PER_ITEM, full_target_items, min_items, max_items_full, perm,
+                                  rowplan, floors, items, hdr, nullptr, tid, PLAN_THREADS);
+            if (tid == 0) hdr->mode = 1;
+            return;
+        }
+    }
     const int tpw = vp_tiles_per_wave(total_tiles, target_items, min_items);
     const int tpi = tpw * VP_WG_WAVES;
 
@@ -203,6 +227,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(
         hdr->swz_rgs = 0;
         hdr->swz_chunks = 0;
         hdr->rows_per_item = VP_ROWS_PER_ITEM;
+        hdr->mode = 0;
     }
 
     // debug entry only: where each row's candidate logits start
@@ -246,11 +271,12 @@ hipError_t vpk_plan_prepare()
 void vpk_plan(const void *cpart, int parts, int N, int K, const int32_t *n_cand, const int32_t *tile_off,
               int target_items, int min_items, int max_items, int32_t *g, int32_t *out_cluster, int32_t *perm,
               VpRowPlan *rowplan, unsigned int *floors, VpItem *items, VpPlanHeader *hdr, int64_t *dbg_row_off,
-              hipStream_t st)
+              int dispatch, const VpCostModel &cost, int k, int V, int vtiles, int full_target_items,
+              int max_items_full, hipStream_t st)
 {
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(PLAN_THREADS), vpk_plan_lds_bytes(K), st, (const int2 *)cpart,
                        parts, N, K, n_cand, tile_off, target_items, min_items, max_items, g, out_cluster, perm, rowplan, floors,
-                       items, hdr, dbg_row_off);
+                       items, hdr, dbg_row_off, dispatch, cost, k, V, vtiles, full_target_items, max_items_full);
 }
 
 void vpk_plan_full(int N, int V, int vtiles, int rpi, int target_items, int min_items, int max_items, int32_t *perm,

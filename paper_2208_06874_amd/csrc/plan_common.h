@@ -58,6 +58,7 @@ __device__ inline void vp_plan_single_bucket(int N, int ncand, int vtiles, int r
         hdr->swz_rgs = rgs > 1 ? rgs : 0;
         hdr->swz_chunks = chunks;
         hdr->rows_per_item = rpi;
+        hdr->mode = 0;
         if (dbg_row_off) dbg_row_off[N] = (int64_t)N * ncand;
     }
 }

@@ -155,12 +155,12 @@ __device__ inline uint4 load_piece(const uint4 *p)
 // 16 rows, where RT = 2 feeds every loaded slab tile to two MFMAs (half the L2-to-CU
 // traffic per row) and, with half as many wavefronts per CU, keeps twice the loads in
 // flight per wavefront.
-template <bool NT, int RT, int PF>
+template <bool NT, int RT, int PF, bool MASKED>
 __device__ inline void project_item(
     const VpSlabSet &set, const uint4 *__restrict__ hidden, int d, const int32_t *__restrict__ perm,
     const VpItem &item, int it, int tpw, int k, int rstar,
     float *__restrict__ partials, unsigned int *__restrict__ floors, float *__restrict__ dbg_logits,
-    const int64_t *__restrict__ dbg_row_off)
+    const int64_t *__restrict__ dbg_row_off, const VpMaskInfo &mask)
 {
     constexpr int ROWS = 16 * RT;               // row slots of an item
     const int KT = set.kt;
@@ -180,6 +180,7 @@ __device__ inline void project_item(
     float *hdr_s = hdr_m + VP_WG_WAVES * ROWS;
     int *rowid = reinterpret_cast<int *>(hdr_s + VP_WG_WAVES * ROWS);             // [ROWS]
     unsigned int *wg_floor = reinterpret_cast<unsigned int *>(rowid + ROWS);      // [ROWS]
+    int *rowcl = reinterpret_cast<int *>(wg_floor + ROWS);                        // [ROWS] (masked projection)
 
     // this wavefront's run of tiles; its first loads go out before anything else
     const int ncand = item.ncand;
@@ -202,6 +203,7 @@ __device__ inline void project_item(
         rowid[tid] = row;
         // buckets walked by several row groups hand their bound from workgroup to workgroup
         wg_floor[tid] = (item.shared && row >= 0) ? floors[row] : VP_FLOOR_NONE;
+        if (MASKED) rowcl[tid] = row >= 0 ? mask.g[row] : 0;
     }
     for (int e = tid; e < VP_WG_WAVES * k * ROWS; e += VP_WG_THREADS) {
         list_val[e] = -__builtin_inff();
@@ -240,6 +242,17 @@ __device__ inline void project_item(
         list[rt].idx = list_idx + wave * k * ROWS + slot;
         list[rt].stride = ROWS;
         dbg_base[rt] = (dbg_logits && row_valid[rt]) ? dbg_row_off[rowid[slot]] : 0;
+    }
+
+    // masked full projection: the 4 membership bits of this lane's candidates, per row tile,
+    // fetched a tile ahead like the bias (4 consecutive tokens never straddle a 32-bit word)
+    const uint32_t *mrow[RT];
+    uint32_t mcur[RT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+        mrow[rt] = MASKED ? mask.bitmaps + (size_t)rowcl[rt * 16 + n] * mask.words : nullptr;
+        mcur[rt] = 0xffffffffu;
+        if (MASKED && tb < te) mcur[rt] = mrow[rt][(tb * VP_TILE_ITEMS + q * 4) >> 5];
     }
 
     const bool exchange = item.shared && wave == 0 && q == 0;
@@ -313,7 +326,10 @@ __device__ inline void project_item(
                         }
                     }
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) z[i] = (c0 + i < ncand) ? z[i] + bz[i] : -__builtin_inff();
+                    for (int i = 0; i < 4; ++i) {
+                        const bool member = !MASKED || ((mcur[rt] >> ((c0 & 31) + i)) & 1u);
+                        z[i] = (c0 + i < ncand && member) ? z[i] + bz[i] : -__builtin_inff();
+                    }
                     if (dbg_logits && row_valid[rt]) {
 #pragma unroll
                         for (int i = 0; i < 4; ++i)
@@ -343,7 +359,13 @@ __device__ inline void project_item(
                 }
                 kt = 0;
                 ++tile;
-                if (tile < te) bcur = *reinterpret_cast<const float4 *>(bias + tile * VP_TILE_ITEMS + q * 4);
+                if (tile < te) {
+                    bcur = *reinterpret_cast<const float4 *>(bias + tile * VP_TILE_ITEMS + q * 4);
+                    if (MASKED) {
+#pragma unroll
+                        for (int rt = 0; rt < RT; ++rt) mcur[rt] = mrow[rt][(tile * VP_TILE_ITEMS + q * 4) >> 5];
+                    }
+                }
             }
         }
     }
@@ -448,15 +470,17 @@ __global__ __launch_bounds__(VP_WG_THREADS) void project_kernel(
     const VpItem probe = items[blockIdx.x];
     const int total_items = hdr->total_items;
     const int tpw = hdr->tiles_per_wave;
+    if (hdr->mode != 0) return;   // the planner chose the masked full projection for this batch
     const int it = item_of_workgroup(hdr);
     if (it < 0 || it >= total_items) return;
     const VpItem item = it == (int)blockIdx.x ? probe : items[it];
+    const VpMaskInfo none = {nullptr, nullptr, 0};
     if (item.shared)
-        project_item<false, 1, 8>(set, hidden, d, perm, item, it, tpw, k, rstar, partials, floors, dbg_logits,
-                                  dbg_row_off);
+        project_item<false, 1, 8, false>(set, hidden, d, perm, item, it, tpw, k, rstar, partials, floors, dbg_logits,
+                                         dbg_row_off, none);
     else
-        project_item<true, 1, 8>(set, hidden, d, perm, item, it, tpw, k, rstar, partials, floors, dbg_logits,
-                                 dbg_row_off);
+        project_item<true, 1, 8, false>(set, hidden, d, perm, item, it, tpw, k, rstar, partials, floors, dbg_logits,
+                                        dbg_row_off, none);
 }
 
 // Items of up to 32 rows, all sharing their tiles with other row groups: single-bucket
@@ -472,7 +496,31 @@ __global__ __launch_bounds__(VP_WG_THREADS) void project2_kernel(
     const int it = item_of_workgroup(hdr);
     if (it < 0 || it >= total_items) return;
     const VpItem item = items[it];
-    project_item<false, 2, 16>(set, hidden, d, perm, item, it, tpw, k, 0, partials, floors, dbg_logits, dbg_row_off);
+    const VpMaskInfo none = {nullptr, nullptr, 0};
+    project_item<false, 2, 16, false>(set, hidden, d, perm, item, it, tpw, k, 0, partials, floors, dbg_logits,
+                                      dbg_row_off, none);
+}
+
+// The full projection with every row masked to its own cluster's active set: the same
+// results as the per-cluster slabs (token ids as candidate positions), for batches whose
+// occupied slabs outweigh one pass over W.  Runs only when the planner chose it.
+__global__ __launch_bounds__(VP_WG_THREADS) void project_masked_kernel(
+    VpSlabSet set, const uint4 *__restrict__ hidden, int d, const int32_t *__restrict__ perm,
+    const VpItem *__restrict__ items, const VpPlanHeader *__restrict__ hdr, int k,
+    float *__restrict__ partials, unsigned int *__restrict__ floors, VpMaskInfo mask)
+{
+    if (hdr->mode != 1) return;
+    const int total_items = hdr->total_items;
+    const int tpw = hdr->tiles_per_wave;
+    const int it = item_of_workgroup(hdr);
+    if (it < 0 || it >= total_items) return;
+    const VpItem item = items[it];
+    if (item.shared)
+        project_item<false, 1, 8, true>(set, hidden, d, perm, item, it, tpw, k, 0, partials, floors, nullptr, nullptr,
+                                        mask);
+    else
+        project_item<true, 1, 8, true>(set, hidden, d, perm, item, it, tpw, k, 0, partials, floors, nullptr, nullptr,
+                                       mask);
 }
 
 }  // namespace
@@ -481,7 +529,7 @@ size_t vpk_project_lds_bytes(int kt, int k, int row_tiles)
 {
     const size_t rows = 16 * (size_t)row_tiles;
     return (size_t)row_tiles * kt * VP_TILE_BYTES + (size_t)VP_WG_WAVES * k * rows * 8 + VP_WG_WAVES * rows * 8 +
-           rows * 8;
+           rows * 12;
 }
 
 hipError_t vpk_project_prepare()
@@ -490,6 +538,9 @@ hipError_t vpk_project_prepare()
                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e == hipSuccess)
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(project2_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(project_masked_kernel),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     return e;
 }
@@ -507,4 +558,13 @@ void vpk_project(const VpSlabSet &set, const void *hidden, int d, const int32_t 
     hipLaunchKernelGGL(project_kernel, dim3(grid_items), dim3(VP_WG_THREADS), vpk_project_lds_bytes(set.kt, k, 1), st,
                        set, (const uint4 *)hidden, d, perm, items, hdr, k, rstar, partials, floors, dbg_logits,
                        dbg_row_off);
+}
+
+void vpk_project_masked(const VpSlabSet &full, const void *hidden, int d, const int32_t *perm, const VpItem *items,
+                        const VpPlanHeader *hdr, int grid_items, int k, float *partials, unsigned int *floors,
+                        const VpMaskInfo &mask, hipStream_t st)
+{
+    hipLaunchKernelGGL(project_masked_kernel, dim3(grid_items), dim3(VP_WG_THREADS),
+                       vpk_project_lds_bytes(full.kt, k, 1), st, full, (const uint4 *)hidden, d, perm, items, hdr, k,
+                       partials, floors, mask);
 }

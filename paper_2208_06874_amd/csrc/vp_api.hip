@@ -39,7 +39,8 @@ struct ArenaLayout {
     long total_groups;     // candidate groups (of 16) over all clusters
     long n_total;
     int n_min, n_max, max_tiles;
-    size_t wp, biasf, cp, cnorm, full_meta, tile_off, n_cand, ids_pad, sbias, slabs, total;
+    size_t wp, biasf, cp, cnorm, full_meta, tile_off, n_cand, ids_pad, sbias, bitmaps, slabs, total;
+    int bm_words;
 };
 
 }  // namespace
@@ -62,6 +63,9 @@ struct vp_index {
     int target_items, full_target_items, rstar;
     int min_items;   // resident workgroup slots of the projection kernel on this GPU
     int wide_items;  // 1: single-bucket projections of more than 16 rows use items of 32 rows
+    int dispatch;    // 1: the planner may choose the masked full projection (same results)
+    VpCostModel cost;
+    const uint32_t *bitmaps;
     VpProfile *prof;
 };
 
@@ -131,6 +135,8 @@ vp_status plan_arena(const vp_build_desc *D, bool check_ids, ArenaLayout *L)
     L->n_cand = take((size_t)D->K * sizeof(int32_t));
     L->ids_pad = take((size_t)groups * VP_TILE_ITEMS * sizeof(int32_t));
     L->sbias = take((size_t)groups * VP_TILE_ITEMS * sizeof(float));
+    L->bm_words = ceil_div((long)L->vtiles * VP_TILE_ITEMS, 32);
+    L->bitmaps = take((size_t)D->K * L->bm_words * sizeof(uint32_t));
     L->slabs = take((size_t)groups * group_bytes);
     L->total = o;
     return VP_OK;
@@ -244,8 +250,18 @@ vp_status run_clustered(const char *fn, const vp_index *I, const void *hidden, i
     vpk_centroid(hidden, N, I->d, I->cp, I->cnorm, I->K, I->L.kt, I->L.ctiles, tpw_c, parts, cpart, st);
 
     const int max_items = max_items_clustered(I, N);
+    // the debug entry lays its logits out per cluster list, so it always takes the slabs
+    const int dispatch = (I->dispatch && !dbg_logits) ? 1 : 0;
+    const int max_full = max_items_full(I, N);
+    // the tile counts of the cost model are in tiles of kt KiB: fold that into the constants
+    VpCostModel cost = I->cost;
+    const float tile_bytes = (float)I->L.kt * VP_TILE_BYTES;
+    cost.bw_slab /= tile_bytes;
+    cost.bw_full /= tile_bytes;
+    cost.bw_l2 /= tile_bytes;
     vpk_plan(cpart, parts, N, I->K, I->clusters.n_cand, I->clusters.tile_off, I->target_items, I->min_items, max_items, g,
-             out_cluster, perm, rowplan, floors, items, hdr, dbg_row_off, st);
+             out_cluster, perm, rowplan, floors, items, hdr, dbg_row_off, dispatch, cost, k, I->V, I->L.vtiles,
+             I->full_target_items, max_full, st);
 
     const long row_groups = (long)row_tiles + std::min(N, I->K);
     const long by_tiles = row_groups * ceil_div(I->L.max_tiles, VP_WG_WAVES);
@@ -254,6 +270,15 @@ vp_status run_clustered(const char *fn, const vp_index *I, const void *hidden, i
     if (ev) (void)hipEventRecord(ev->first, st);
     vpk_project(I->clusters, hidden, I->d, perm, items, hdr, grid_items, 1, k, I->rstar, partials, floors, dbg_logits,
                 dbg_row_off, st);
+    if (dispatch) {
+        // launched as well; exactly one of the two does the work, as the planner decided
+        const int rgs = ceil_div(N, VP_ROWS_PER_ITEM);
+        const int tpw = vp_tiles_per_wave((long long)rgs * I->L.vtiles, I->full_target_items, I->min_items);
+        const int chunks = ceil_div(I->L.vtiles, (long)tpw * VP_WG_WAVES);
+        const int grid_full = rgs > 1 ? ceil_div(chunks, 8) * 8 * rgs : chunks;
+        const VpMaskInfo mask = {g, I->bitmaps, I->L.bm_words};
+        vpk_project_masked(I->full, hidden, I->d, perm, items, hdr, grid_full, k, partials, floors, mask, st);
+    }
     if (ev) (void)hipEventRecord(ev->second, st);
     if (out_ids)
         vpk_merge(I->clusters, rowplan, hdr, partials, k, N, out_ids, out_logp, st);
@@ -380,6 +405,10 @@ vp_status vp_build(const vp_build_desc *D, void *hip_stream, vp_index **out)
     vpk_cnorm(D->centroids, D->K, D->d, L.ctiles * VP_TILE_ITEMS, reinterpret_cast<float *>(A + L.cnorm), st);
     vpk_gather_slabs(A + L.wp, D->bias, L.kt, reinterpret_cast<const int32_t *>(A + L.ids_pad), L.total_groups,
                      A + L.slabs, reinterpret_cast<float *>(A + L.sbias), st);
+    e = hipMemsetAsync(A + L.bitmaps, 0, (size_t)D->K * L.bm_words * sizeof(uint32_t), st);
+    if (e != hipSuccess) return fail(VP_ERR_HIP, "vp_build: %s", hipGetErrorString(e));
+    vpk_bitmaps(reinterpret_cast<const int32_t *>(A + L.ids_pad), reinterpret_cast<const int32_t *>(A + L.tile_off),
+                D->K, L.total_groups, L.bm_words, reinterpret_cast<uint32_t *>(A + L.bitmaps), st);
     s = launch_status("vp_build");
     if (s != VP_OK) return s;
     e = hipStreamSynchronize(st);
@@ -413,6 +442,12 @@ vp_status vp_build(const vp_build_desc *D, void *hip_stream, vp_index **out)
     I->full_target_items = 2048;
     I->rstar = 0;
     I->wide_items = 1;
+    I->dispatch = 0;
+    // measured on MI355X at d = 1024: bytes per second of the three regimes of the cost model
+    I->cost.bw_slab = 6.8e12f;
+    I->cost.bw_full = 5.4e12f;
+    I->cost.bw_l2 = 17.0e12f;
+    I->bitmaps = reinterpret_cast<const uint32_t *>(A + L.bitmaps);
     {
         // workgroups of the projection kernel that fit on the chip at once (LDS-limited)
         int dev = 0, cus = 256;
@@ -457,6 +492,18 @@ vp_status vp_set_option(vp_index *I, const char *name, int64_t value)
             return fail(VP_ERR_INVALID_ARG, "vp_set_option: rstar = %lld must be in [0, %d]", (long long)value,
                         VP_GEMV_MAX_ROWS);
         I->rstar = (int)value;
+        return VP_OK;
+    }
+    if (!std::strcmp(name, "dispatch")) {
+        if (value != 0 && value != 1) return fail(VP_ERR_INVALID_ARG, "vp_set_option: dispatch must be 0 or 1");
+        I->dispatch = (int)value;
+        return VP_OK;
+    }
+    if (!std::strcmp(name, "cost_bw_slab_gbs") || !std::strcmp(name, "cost_bw_full_gbs") ||
+        !std::strcmp(name, "cost_bw_l2_gbs")) {
+        if (value < 1 || value > 1000000) return fail(VP_ERR_INVALID_ARG, "vp_set_option: %s out of range", name);
+        float &f = name[8] == 's' ? I->cost.bw_slab : name[8] == 'f' ? I->cost.bw_full : I->cost.bw_l2;
+        f = (float)value * 1e9f;
         return VP_OK;
     }
     if (!std::strcmp(name, "wide_items")) {

@@ -13,6 +13,9 @@ void vpk_bias_full(const void *b, int V, int V_pad, float *out, hipStream_t st);
 void vpk_gather_slabs(const void *wp, const void *b, int kt, const int32_t *ids_pad, long total_groups,
                       void *slabs, float *sbias, hipStream_t st);
 
+void vpk_bitmaps(const int32_t *ids_pad, const int32_t *tile_off, int K, long total_groups, int words,
+                 uint32_t *bitmaps, hipStream_t st);
+
 // centroid selection (Eq. 2)
 void vpk_centroid(const void *hidden, int N, int d, const void *cp, const float *cnorm, int K, int kt,
                   int ctiles, int tiles_per_part, int parts, void *cpart, hipStream_t st);
@@ -23,7 +26,8 @@ hipError_t vpk_plan_prepare();
 void vpk_plan(const void *cpart, int parts, int N, int K, const int32_t *n_cand, const int32_t *tile_off,
               int target_items, int min_items, int max_items, int32_t *g, int32_t *out_cluster, int32_t *perm,
               VpRowPlan *rowplan, unsigned int *floors, VpItem *items, VpPlanHeader *hdr, int64_t *dbg_row_off,
-              hipStream_t st);
+              int dispatch, const VpCostModel &cost, int k, int V, int vtiles, int full_target_items,
+              int max_items_full, hipStream_t st);
 void vpk_plan_full(int N, int V, int vtiles, int rpi, int target_items, int min_items, int max_items, int32_t *perm,
                    VpRowPlan *rowplan, unsigned int *floors, VpItem *items, VpPlanHeader *hdr,
                    int64_t *dbg_row_off, hipStream_t st);
@@ -34,6 +38,10 @@ hipError_t vpk_project_prepare();
 void vpk_project(const VpSlabSet &set, const void *hidden, int d, const int32_t *perm, const VpItem *items,
                  const VpPlanHeader *hdr, int grid_items, int row_tiles, int k, int rstar, float *partials,
                  unsigned int *floors, float *dbg_logits, const int64_t *dbg_row_off, hipStream_t st);
+
+void vpk_project_masked(const VpSlabSet &full, const void *hidden, int d, const int32_t *perm, const VpItem *items,
+                        const VpPlanHeader *hdr, int grid_items, int k, float *partials, unsigned int *floors,
+                        const VpMaskInfo &mask, hipStream_t st);
 
 // per-row merge
 size_t vpk_merge_lds_bytes(int k);

@@ -60,7 +60,8 @@ struct VpPlanHeader {
     int32_t swz_rgs;
     int32_t swz_chunks;
     int32_t rows_per_item;   // row slots per item in the partial results (16, or 32 with two row tiles)
-    int32_t pad[57];
+    int32_t mode;            // 0: per-cluster slabs; 1: masked full projection chosen by the planner
+    int32_t pad[56];
 };
 
 // State of one batch-union projection (see union.hip).
@@ -97,6 +98,21 @@ static inline __host__ __device__ int vp_tiles_per_wave(long long total_tiles, i
     const long long tpw = (total_tiles + per - 1) / per;
     return (int)(tpw > 1 ? tpw : 1);
 }
+
+// What the masked full projection needs besides the slab set: each row's cluster
+// and the per-cluster membership bit lists over the vocabulary.
+struct VpMaskInfo {
+    const int32_t *g;          // [N] cluster of each row (NULL: no masking)
+    const uint32_t *bitmaps;   // [K][words]
+    int32_t words;             // 32-bit words per cluster
+};
+
+// Machine constants of the planner's cost model (bytes per second).
+struct VpCostModel {
+    float bw_slab;   // slabs streamed once from HBM
+    float bw_full;   // one pass over the packed W from HBM
+    float bw_l2;     // further passes over tiles already in the L2
+};
 
 // Size in floats of one partial result: running max, sum of exponentials, then
 // k logits and k candidate positions.

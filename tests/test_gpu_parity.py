@@ -413,6 +413,54 @@ def test_wide_items_of_the_full_projection(oracle, tiny):
     assert np.abs(zf.reshape(40, -1) - f["all_z"]).max() < pu.SANITY
 
 
+def _planner_mode(index, N):
+    """White-box: the planner's decision sits in the header at the start of the workspace."""
+    import torch
+    ws = index.workspace(N)
+    torch.cuda.synchronize()
+    return int(ws[:64].view(torch.int32)[7].item())
+
+
+def test_dispatch_to_the_masked_full_projection(oracle, tiny, mid):
+    """With dispatch on, batches that occupy many clusters run the full projection with every row masked
+    to its own active set; the results must be those of the per-cluster projection."""
+    for B, N, k, want_mode in ((mid, 64, 1, 1), (mid, 200, 1, 1), (mid, 64, 8, 0), (mid, 2, 8, 0), (tiny, 16, 4, 0),
+                               (tiny, 1, 4, 0)):
+        cfg = wl.scaled(B.cfg, k=k)
+        H, q = wl.make_rows(cfg, B.C, N=N, stream=40 + N)
+        base = B.project(H, cfg.k)
+        B.index.set_option("dispatch", 1)
+        try:
+            got = B.project(H, cfg.k)
+            mode = _planner_mode(B.index, N)
+            st = pu.check_projection(oracle, B.W, B.b, B.C, B.cand_off, B.cand_ids, H, cfg.k, got[0], got[1], got[2])
+            # the debug entry keeps the per-cluster layout whatever the option says
+            g2, offs, z = B.debug(H)
+        finally:
+            B.index.set_option("dispatch", 0)
+        print("dispatch", cfg.name, N, "mode", mode, st)
+        assert mode == want_mode
+        assert np.array_equal(got[0], base[0]) and np.array_equal(got[2], base[2])
+        assert np.allclose(got[1], base[1], rtol=0, atol=1e-4)
+        assert np.array_equal(g2, base[2])
+    assert _planner_mode(mid.index, 8) in (0, 1)
+
+
+def test_dispatch_cost_model_constants(mid):
+    cfg = wl.scaled(mid.cfg, k=1)
+    H, q = wl.make_rows(cfg, mid.C, N=64, stream=50)
+    mid.index.set_option("dispatch", 1)
+    mid.index.set_option("cost_bw_l2_gbs", 10)       # make re-reading through the L2 look hopeless
+    try:
+        got = mid.project(H, cfg.k)
+        assert _planner_mode(mid.index, 64) == 0
+    finally:
+        mid.index.set_option("cost_bw_l2_gbs", 17000)
+        mid.index.set_option("dispatch", 0)
+    base = mid.project(H, cfg.k)
+    assert np.array_equal(got[0], base[0])
+
+
 def test_replay_from_a_captured_graph(mid):
     """vp_project only enqueues kernels (no allocation, no synchronisation, no memset), so a call can be
     captured into a HIP graph; every replay, with eager work in between, must equal the eager result."""
