@@ -15,18 +15,18 @@ import subprocess
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRC = os.path.join(_HERE, "vp_oracle.c")
+_SRCS = [os.path.join(_HERE, "vp_oracle.c"), os.path.join(_HERE, "vp_train_oracle.c")]
 _SO = os.path.join(_HERE, "libvp_oracle.so")
 _lib = None
 
 
 def build(force: bool = False) -> str:
-    """Compile vp_oracle.c with gcc (plain -O2 loops, OpenMP over rows only)."""
-    stale = (not os.path.exists(_SO)) or os.path.getmtime(_SO) < os.path.getmtime(_SRC)
+    """Compile the oracle's C files with gcc (plain -O2 loops, OpenMP over rows only)."""
+    stale = (not os.path.exists(_SO)) or os.path.getmtime(_SO) < max(os.path.getmtime(f) for f in _SRCS)
     if force or stale:
         tmp = _SO + ".tmp.%d" % os.getpid()
         subprocess.check_call(
-            ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-o", tmp, _SRC, "-lm"]
+            ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-o", tmp] + _SRCS + ["-lm"]
         )
         os.replace(tmp, _SO)
     return _SO
@@ -40,6 +40,9 @@ def _load():
         lib.vpo_half_to_double.restype = ctypes.c_double
         lib.vpo_half_to_double.argtypes = [ctypes.c_uint16]
         lib.vpo_log_softmax.restype = ctypes.c_double
+        lib.vpo_double_to_half.restype = ctypes.c_uint16
+        lib.vpo_double_to_half.argtypes = [ctypes.c_double]
+        lib.vpo_active_sets.restype = ctypes.c_int64
         _lib = lib
     return _lib
 
@@ -209,3 +212,58 @@ def logit_points(W, b, H, rows, toks) -> np.ndarray:
     _load().vpo_logit_points(_p(W), _p(b), ctypes.c_int(d), ctypes.c_int(V), _p(H), _p(rows),
                              _p(toks), ctypes.c_int(rows.shape[0]), _p(z))
     return z
+
+
+# ------------------------------------------------------------------ offline training of the clusters
+def double_to_half(v: float) -> int:
+    """binary16 bit pattern of v, round to nearest even."""
+    return int(_load().vpo_double_to_half(ctypes.c_double(float(v))))
+
+
+def kmeans_step(X, C, forced=None):
+    """One Lloyd iteration from the centroids C (float64 [K, d]).  Returns assign, counts, the new
+    centroids (float64, not rounded) and the objective of the assignment."""
+    X = _bits(X)
+    n, d = X.shape
+    C = np.ascontiguousarray(C, np.float64)
+    K = C.shape[0]
+    assert C.shape[1] == d
+    fg = None if forced is None else np.ascontiguousarray(forced, np.int32)
+    assign = np.empty(n, np.int32)
+    counts = np.empty(K, np.int32)
+    Cn = np.empty((K, d), np.float64)
+    obj = ctypes.c_double(0.0)
+    _load().vpo_kmeans_step(_p(X), ctypes.c_int(n), ctypes.c_int(d), _p(C), ctypes.c_int(K), _p(fg), _p(assign),
+                            _p(counts), _p(Cn), ctypes.byref(obj))
+    return dict(assign=assign, counts=counts, C=Cn, objective=obj.value)
+
+
+def kmeans(X, C0, iters: int, round_half: bool = True):
+    """iters Lloyd iterations from the binary16 centroids C0, then the membership against the final
+    centroids.  Returns C (float64), C_bits (uint16), assign, counts, objective[iters + 1]."""
+    X, C0 = _bits(X), _bits(C0)
+    n, d = X.shape
+    K = C0.shape[0]
+    assert C0.shape[1] == d
+    C = np.empty((K, d), np.float64)
+    Cb = np.empty((K, d), np.uint16)
+    assign = np.empty(n, np.int32)
+    counts = np.empty(K, np.int32)
+    obj = np.empty(iters + 1, np.float64)
+    _load().vpo_kmeans(_p(X), ctypes.c_int(n), ctypes.c_int(d), _p(C0), ctypes.c_int(K), ctypes.c_int(iters),
+                       ctypes.c_int(1 if round_half else 0), _p(C), _p(Cb), _p(assign), _p(counts), _p(obj))
+    return dict(C=C, C_bits=Cb, assign=assign, counts=counts, objective=obj)
+
+
+def active_sets(top, assign, K: int, V: int):
+    """Section 2.2: per cluster, the ascending union of the recorded tokens of its members.
+    top is int32 [n, T] (entries < 0 mean none).  Returns cand_off (int64 [K+1]) and cand_ids."""
+    top = np.ascontiguousarray(top, np.int32)
+    n, T = top.shape
+    assign = np.ascontiguousarray(assign, np.int32)
+    off = np.empty(K + 1, np.int64)
+    args = (_p(top), ctypes.c_int(n), ctypes.c_int(T), _p(assign), ctypes.c_int(K), ctypes.c_int(V), _p(off))
+    total = _load().vpo_active_sets(*args, None)
+    ids = np.empty(int(total), np.int32)
+    _load().vpo_active_sets(*args, _p(ids))
+    return off, ids
