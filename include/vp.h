@@ -172,6 +172,53 @@ vp_status vp_project_debug_logits(const vp_index *idx, const void *hidden, int32
  * between two calls.  Not meant for use under graph capture. */
 vp_status vp_get_profile(vp_index *idx, double *kernel_ms_total, int64_t *launches);
 
+/* ---- Offline training of the clusters (section 2.2 "Offline Training of Clusters";
+ * training settings of section 3.1: k-means, 20 iterations) ----
+ *
+ * vp_kmeans: `iters` Lloyd iterations over n recorded hidden vectors, then the
+ * membership of every vector against the final centroids.  An iteration assigns
+ * every vector to its nearest centroid (Eq. 2 as at decode time: fp16 inputs, fp32
+ * accumulation, ties to the lowest index) and replaces every centroid by the mean
+ * of its members; a cluster without members keeps its centroid.  The sums are
+ * exact (64-bit integers in units of 2^-24) and each mean is rounded once to fp16
+ * (nearest, ties to even), so equal inputs give bit-identical centroids and, given
+ * the memberships, the centroids equal the correctly rounded means.
+ *   x          device, fp16 [n, d] row-major, 16-byte aligned, finite values;
+ *              per cluster and coordinate the sum of |x| must stay below 2^29
+ *   centroids  device, fp16 [K, d]: starting centroids in, trained centroids out
+ *   assign     device, int32 [n]: cluster of every vector under the final centroids
+ *   counts     device, int32 [K]: members per cluster under the final centroids
+ *   workspace  device, 256-byte aligned, >= vp_kmeans_workspace_bytes(n, d, K)
+ * Only enqueues kernels.  Limits: d % 8 == 0, 8 <= d <= 4096, 1 <= K <= 4096,
+ * 1 <= n < 2^31, 0 <= iters <= 1000. */
+size_t vp_kmeans_workspace_bytes(int64_t n, int32_t d, int32_t K);
+vp_status vp_kmeans(const void *x, int64_t n, int32_t d, int32_t K, int32_t iters, void *centroids,
+                    int32_t *assign, int32_t *counts, void *workspace, size_t workspace_bytes,
+                    void *hip_stream);
+
+/* vp_active_sets: the active set of cluster j is the ascending union of the T
+ * recorded likely tokens of all of its members (section 2.2; the worked example
+ * there: members with tokens {2,4,6} and {2,8,9} give {2,4,6,8,9}).
+ *   top_ids       device, int32 [n, T]: recorded tokens (for instance out_ids of
+ *                 vp_project_full with k = T); entries outside [0, V) are skipped
+ *   assign        device, int32 [n]: cluster of every vector (vp_kmeans); vectors
+ *                 with a cluster outside [0, K) are skipped
+ *   cand_offsets  device, int64 [K + 1]: receives the offsets (always written)
+ *   cand_ids      device, int32 [capacity]: receives the sets back to back, the
+ *                 layout vp_build_desc takes (after a copy to the host)
+ *   total         host, receives the number of entries; when it exceeds capacity
+ *                 nothing is written to cand_ids and VP_ERR_WORKSPACE is returned
+ *   workspace     device, 256-byte aligned, >= vp_active_sets_workspace_bytes(K, V)
+ * Synchronises the stream once (to learn the total).  A cluster without members
+ * gets an empty set. */
+size_t vp_active_sets_workspace_bytes(int32_t K, int32_t V);
+vp_status vp_active_sets(const int32_t *top_ids, const int32_t *assign, int64_t n, int32_t T, int32_t K,
+                         int32_t V, int64_t *cand_offsets, int32_t *cand_ids, int64_t capacity,
+                         int64_t *total, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Host utility: v rounded to fp16 bits exactly as vp_kmeans rounds a mean. */
+uint16_t vp_round_to_half(double v);
+
 /* Frees the host handle only; the arena stays the caller's. */
 void vp_destroy(vp_index *idx);
 

@@ -12,7 +12,8 @@ CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(ROOT, "_build")
 LIB = os.path.join(HERE, "libvp.so")
 
-SOURCES = ["vp_api.hip", "build_kernels.hip", "centroid.hip", "plan.hip", "project.hip", "merge.hip", "union.hip"]
+SOURCES = ["vp_api.hip", "build_kernels.hip", "centroid.hip", "plan.hip", "project.hip", "merge.hip", "union.hip",
+           "train.hip", "train_api.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

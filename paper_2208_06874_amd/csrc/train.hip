@@ -1,0 +1,339 @@
+// Offline training of the clusters on the GPU (section 2.2 and the training
+// settings of section 3.1): Lloyd k-means over recorded hidden vectors and the
+// active set of each cluster as the union of its members' recorded tokens.
+//
+// Assignment reuses the Eq. 2 kernel of the decode path (nearest centroid,
+// ties to the lowest index).  The update is exact: every binary16 value is an
+// integer multiple of 2^-24, so the members of a cluster are summed as 64-bit
+// integers in that unit.  Integer sums do not depend on the order of the
+// additions, which makes the result independent of how the atomics below are
+// served, and the mean sum / count is rounded once, in double precision, to
+// binary16 (nearest, ties to even).  A cluster without members keeps its
+// centroid.
+#include <hip/hip_runtime.h>
+#include "vp_kernels.h"
+
+namespace {
+
+__device__ inline bool part_less(float s, int j, float s2, int j2) { return s < s2 || (s == s2 && j < j2); }
+
+// Finishes Eq. 2 for a chunk of rows (minimum over the centroid ranges) and counts the members.
+__global__ __launch_bounds__(256) void kmeans_assign_kernel(const int2 *__restrict__ cpart, int parts, int rows,
+                                                            int K, int32_t *__restrict__ assign,
+                                                            int32_t *__restrict__ counts)
+{
+    const int r = blockIdx.x * 256 + threadIdx.x;
+    if (r >= rows) return;
+    float bs = __builtin_inff();
+    int bj = VP_IDX_NONE;
+    for (int p = 0; p < parts; ++p) {
+        const int2 e = cpart[(size_t)r * parts + p];
+        const float s = __int_as_float(e.x);
+        if (part_less(s, e.y, bs, bj)) {
+            bs = s;
+            bj = e.y;
+        }
+    }
+    if ((unsigned)bj >= (unsigned)K) bj = 0;   // only when every score is NaN: keep the index in range
+    assign[r] = bj;
+    atomicAdd(&counts[bj], 1);
+}
+
+// start[j] = number of members of clusters below j; cursor[j] = start[j].  One workgroup.
+__global__ __launch_bounds__(1024) void kmeans_scan_kernel(const int32_t *__restrict__ counts, int K,
+                                                           int32_t *__restrict__ start, int32_t *__restrict__ cursor)
+{
+    __shared__ int wsum[17];
+    __shared__ int carry;
+    if (threadIdx.x == 0) carry = 0;
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int base = 0; base < K; base += 1024) {
+        const int j = base + threadIdx.x;
+        const int v = j < K ? counts[j] : 0;
+        int inc = v;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int up = __shfl_up(inc, off);
+            if (lane >= off) inc += up;
+        }
+        if (lane == 63) wsum[wave] = inc;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            int run = carry;
+            for (int w = 0; w < 16; ++w) {
+                const int t = wsum[w];
+                wsum[w] = run;
+                run += t;
+            }
+            wsum[16] = run;
+        }
+        __syncthreads();
+        if (j < K) {
+            const int ex = wsum[wave] + inc - v;
+            start[j] = ex;
+            cursor[j] = ex;
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) carry = wsum[16];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) start[K] = carry;
+}
+
+// Row numbers in cluster order (the order inside a cluster is arbitrary: the sums are exact).
+__global__ __launch_bounds__(256) void kmeans_scatter_kernel(const int32_t *__restrict__ assign, long n,
+                                                             int32_t *__restrict__ cursor, int32_t *__restrict__ perm)
+{
+    const long r = (long)blockIdx.x * 256 + threadIdx.x;
+    if (r >= n) return;
+    const int pos = atomicAdd(&cursor[assign[r]], 1);
+    perm[pos] = (int32_t)r;
+}
+
+// A binary16 bit pattern as an integer count of 2^-24 (finite inputs only).
+__device__ inline long long half_units(uint32_t h)
+{
+    const int expo = (h >> 10) & 0x1f;
+    const long long frac = h & 0x3ff;
+    const long long mag = expo ? ((frac | 0x400) << (expo - 1)) : frac;
+    return (h & 0x8000) ? -mag : mag;
+}
+
+__device__ inline void add_units(long long (&s)[8], const uint4 v)
+{
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        s[2 * e] += half_units(w[e] & 0xffff);
+        s[2 * e + 1] += half_units(w[e] >> 16);
+    }
+}
+
+// Sum of the members of cluster blockIdx.x, every `splits`-th one starting at blockIdx.y,
+// over 8 coordinates per thread.
+__global__ __launch_bounds__(256) void kmeans_sum_kernel(const uint4 *__restrict__ X, int pieces,
+                                                         const int32_t *__restrict__ perm,
+                                                         const int32_t *__restrict__ start, int splits,
+                                                         unsigned long long *__restrict__ acc)
+{
+    const int j = blockIdx.x;
+    const int m0 = start[j], m1 = start[j + 1];
+    for (int piece = threadIdx.x; piece < pieces; piece += 256) {
+        long long s[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        int m = m0 + blockIdx.y;
+        for (; m + 3 * splits < m1; m += 4 * splits) {   // four rows in flight
+            uint4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) v[u] = X[(size_t)perm[m + u * splits] * pieces + piece];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) add_units(s, v[u]);
+        }
+        for (; m < m1; m += splits) add_units(s, X[(size_t)perm[m] * pieces + piece]);
+        if (m0 + (int)blockIdx.y < m1) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                atomicAdd(&acc[((size_t)j * pieces + piece) * 8 + e], (unsigned long long)s[e]);
+        }
+    }
+}
+
+// double -> binary16 bits, round to nearest, ties to even (integer arithmetic on the bits).
+__host__ __device__ inline uint16_t double_to_half_bits(double v)
+{
+    unsigned long long b;
+    __builtin_memcpy(&b, &v, sizeof(b));
+    const uint16_t sign = (uint16_t)((b >> 48) & 0x8000);
+    const int ex = (int)((b >> 52) & 0x7ff);
+    const unsigned long long man = b & ((1ull << 52) - 1);
+    if (ex == 0x7ff) return (uint16_t)(sign | (man ? 0x7e00 : 0x7c00));
+    if (ex == 0) return sign;                                   // zero (and double subnormals)
+    const int e = ex - 1023;
+    if (e > 15) return (uint16_t)(sign | 0x7c00);
+    unsigned long long q, rem, half;
+    uint32_t base;
+    if (e >= -14) {                                             // normal binary16 range
+        q = man >> 42;
+        rem = man & ((1ull << 42) - 1);
+        half = 1ull << 41;
+        base = (uint32_t)(e + 15) << 10;
+    } else {                                                    // multiples of 2^-24
+        const int shift = 28 - e;                               // >= 43
+        if (shift > 63) return sign;
+        const unsigned long long full = man | (1ull << 52);
+        q = full >> shift;
+        rem = full & ((1ull << shift) - 1);
+        half = 1ull << (shift - 1);
+        base = 0;
+    }
+    uint32_t h = base + (uint32_t)q;
+    if (rem > half || (rem == half && (q & 1))) h += 1;        // a carry moves into the exponent field
+    if (h >= 0x7c00) h = 0x7c00;
+    return (uint16_t)(sign | h);
+}
+
+// New centroids from the sums; the sums are cleared for the next iteration.
+__global__ __launch_bounds__(256) void kmeans_update_kernel(unsigned long long *__restrict__ acc,
+                                                            const int32_t *__restrict__ counts, int K, int d,
+                                                            uint16_t *__restrict__ C)
+{
+    const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= (size_t)K * d) return;
+    const int j = (int)(e / d);
+    const int c = counts[j];
+    if (c > 0) {
+        const double sum = (double)(long long)acc[e];
+        C[e] = double_to_half_bits(sum * 0x1p-24 / (double)c);
+    }
+    acc[e] = 0ull;
+}
+
+__global__ void fill_u32_kernel(uint32_t *__restrict__ p, size_t n, uint32_t v)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+// ---------------------------------------------------------------- active sets
+// bit v of cluster assign[r]'s list is set for every recorded token v of vector r
+__global__ __launch_bounds__(256) void aset_flag_kernel(const int32_t *__restrict__ top,
+                                                        const int32_t *__restrict__ assign, long n, int T, int K,
+                                                        int V, int words, uint32_t *__restrict__ bitmaps)
+{
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n * T) return;
+    const int v = top[i];
+    const int j = assign[i / T];
+    if (v < 0 || v >= V || j < 0 || j >= K) return;
+    atomicOr(&bitmaps[(size_t)j * words + (v >> 5)], 1u << (v & 31));
+}
+
+__device__ inline int block_sum_256(int v, int *lds)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return lds[0] + lds[1] + lds[2] + lds[3];
+}
+
+__global__ __launch_bounds__(256) void aset_count_kernel(const uint32_t *__restrict__ bitmaps, int words,
+                                                         int32_t *__restrict__ sizes)
+{
+    __shared__ int lds[4];
+    const uint32_t *bm = bitmaps + (size_t)blockIdx.x * words;
+    int c = 0;
+    for (int w = threadIdx.x; w < words; w += 256) c += __popc(bm[w]);
+    c = block_sum_256(c, lds);
+    if (threadIdx.x == 0) sizes[blockIdx.x] = c;
+}
+
+// cand_off[j] = sum of the sizes below j (64-bit); one wavefront
+__global__ __launch_bounds__(64) void aset_scan_kernel(const int32_t *__restrict__ sizes, int K,
+                                                       int64_t *__restrict__ cand_off)
+{
+    long long carry = 0;
+    const int lane = threadIdx.x;
+    for (int base = 0; base < K; base += 64) {
+        const int j = base + lane;
+        const long long v = j < K ? sizes[j] : 0;
+        long long inc = v;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const long long up = __shfl_up(inc, off);
+            if (lane >= off) inc += up;
+        }
+        if (j < K) cand_off[j] = carry + inc - v;
+        carry += __shfl(inc, 63);
+    }
+    if (lane == 0) cand_off[K] = carry;
+}
+
+// the set bits of cluster blockIdx.x's list as ascending token ids
+__global__ __launch_bounds__(256) void aset_emit_kernel(const uint32_t *__restrict__ bitmaps, int words,
+                                                        const int64_t *__restrict__ cand_off,
+                                                        int32_t *__restrict__ cand_ids)
+{
+    __shared__ int wsum[4];
+    const uint32_t *bm = bitmaps + (size_t)blockIdx.x * words;
+    int64_t out = cand_off[blockIdx.x];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int base = 0; base < words; base += 256) {
+        const int w = base + threadIdx.x;
+        uint32_t bits = w < words ? bm[w] : 0u;
+        const int c = __popc(bits);
+        int inc = c;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int up = __shfl_up(inc, off);
+            if (lane >= off) inc += up;
+        }
+        __syncthreads();   // wsum of the previous round has been read
+        if (lane == 63) wsum[wave] = inc;
+        __syncthreads();
+        int before = inc - c;
+        for (int x = 0; x < wave; ++x) before += wsum[x];
+        const int round_total = wsum[0] + wsum[1] + wsum[2] + wsum[3];
+        int64_t pos = out + before;
+        while (bits) {
+            const int bit = __ffs(bits) - 1;
+            bits &= bits - 1;
+            cand_ids[pos++] = w * 32 + bit;
+        }
+        out += round_total;
+    }
+}
+
+}  // namespace
+
+uint16_t vpk_round_to_half(double v) { return double_to_half_bits(v); }
+
+void vpk_fill_u32(void *p, size_t n, uint32_t v, hipStream_t st)
+{
+    if (n == 0) return;
+    hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, (uint32_t *)p, n, v);
+}
+
+void vpk_kmeans_assign(const void *cpart, int parts, int rows, int K, int32_t *assign, int32_t *counts,
+                       hipStream_t st)
+{
+    hipLaunchKernelGGL(kmeans_assign_kernel, dim3((rows + 255) / 256), dim3(256), 0, st, (const int2 *)cpart, parts,
+                       rows, K, assign, counts);
+}
+
+void vpk_kmeans_bucket(const int32_t *assign, long n, const int32_t *counts, int K, int32_t *start, int32_t *cursor,
+                       int32_t *perm, hipStream_t st)
+{
+    hipLaunchKernelGGL(kmeans_scan_kernel, dim3(1), dim3(1024), 0, st, counts, K, start, cursor);
+    hipLaunchKernelGGL(kmeans_scatter_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, assign, n, cursor,
+                       perm);
+}
+
+void vpk_kmeans_update(const void *X, int d, const int32_t *perm, const int32_t *start, const int32_t *counts, int K,
+                       int splits, void *acc, void *C, hipStream_t st)
+{
+    hipLaunchKernelGGL(kmeans_sum_kernel, dim3(K, splits), dim3(256), 0, st, (const uint4 *)X, d / 8, perm, start,
+                       splits, (unsigned long long *)acc);
+    const size_t e = (size_t)K * d;
+    hipLaunchKernelGGL(kmeans_update_kernel, dim3((unsigned)((e + 255) / 256)), dim3(256), 0, st,
+                       (unsigned long long *)acc, counts, K, d, (uint16_t *)C);
+}
+
+void vpk_aset_flags(const int32_t *top, const int32_t *assign, long n, int T, int K, int V, int words,
+                    uint32_t *bitmaps, int32_t *sizes, int64_t *cand_off, hipStream_t st)
+{
+    vpk_fill_u32(bitmaps, (size_t)K * words, 0u, st);
+    const long total = n * T;
+    if (total > 0)
+        hipLaunchKernelGGL(aset_flag_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, top, assign, n,
+                           T, K, V, words, bitmaps);
+    hipLaunchKernelGGL(aset_count_kernel, dim3(K), dim3(256), 0, st, bitmaps, words, sizes);
+    hipLaunchKernelGGL(aset_scan_kernel, dim3(1), dim3(64), 0, st, sizes, K, cand_off);
+}
+
+void vpk_aset_emit(const uint32_t *bitmaps, int words, int K, const int64_t *cand_off, int32_t *cand_ids,
+                   hipStream_t st)
+{
+    hipLaunchKernelGGL(aset_emit_kernel, dim3(K), dim3(256), 0, st, bitmaps, words, cand_off, cand_ids);
+}

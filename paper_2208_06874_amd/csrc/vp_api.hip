@@ -45,6 +45,15 @@ struct ArenaLayout {
 
 }  // namespace
 
+int vpi_fail(int status, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return status;
+}
+
 // Event pairs around the projection kernel (benchmark aid, see vp_get_profile).
 struct VpProfile {
     bool on = false;

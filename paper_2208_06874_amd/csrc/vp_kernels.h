@@ -60,3 +60,20 @@ void vpk_union_compact(const unsigned int *mask, int mask_words, int V, int N, i
                        VpRowPlan *rowplan, unsigned int *floors, VpItem *items, VpPlanHeader *hdr, hipStream_t st);
 void vpk_union_gather(const void *wp, const float *bias_full, int kt, const int32_t *uids, const VpUnionHeader *uh,
                       int max_groups, void *slab, float *ubias, hipStream_t st);
+
+// offline training of the clusters (section 2.2)
+void vpk_fill_u32(void *p, size_t n, uint32_t v, hipStream_t st);
+void vpk_kmeans_assign(const void *cpart, int parts, int rows, int K, int32_t *assign, int32_t *counts,
+                       hipStream_t st);
+void vpk_kmeans_bucket(const int32_t *assign, long n, const int32_t *counts, int K, int32_t *start, int32_t *cursor,
+                       int32_t *perm, hipStream_t st);
+void vpk_kmeans_update(const void *X, int d, const int32_t *perm, const int32_t *start, const int32_t *counts, int K,
+                       int splits, void *acc, void *C, hipStream_t st);
+void vpk_aset_flags(const int32_t *top, const int32_t *assign, long n, int T, int K, int V, int words,
+                    uint32_t *bitmaps, int32_t *sizes, int64_t *cand_off, hipStream_t st);
+void vpk_aset_emit(const uint32_t *bitmaps, int words, int K, const int64_t *cand_off, int32_t *cand_ids,
+                   hipStream_t st);
+
+// error message of the calling thread (shared by the translation units of the host API)
+int vpi_fail(int status, const char *fmt, ...);
+uint16_t vpk_round_to_half(double v);

@@ -21,7 +21,9 @@ STATUS_NAMES = {0: "VP_OK", 1: "VP_ERR_INVALID_ARG", 2: "VP_ERR_UNSUPPORTED", 3:
 
 EXPORTS = ("vp_build_bytes", "vp_build", "vp_get_info", "vp_set_option", "vp_workspace_bytes",
            "vp_project", "vp_project_full", "vp_union_workspace_bytes", "vp_project_union",
-           "vp_project_debug_logits", "vp_get_profile", "vp_destroy", "vp_last_error")
+           "vp_project_debug_logits", "vp_get_profile", "vp_destroy", "vp_last_error",
+           "vp_kmeans_workspace_bytes", "vp_kmeans", "vp_active_sets_workspace_bytes", "vp_active_sets",
+           "vp_round_to_half")
 
 
 class VpError(RuntimeError):
@@ -83,6 +85,18 @@ def lib():
         L.vp_get_profile.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
         L.vp_destroy.restype = None
         L.vp_destroy.argtypes = [vp]
+        L.vp_kmeans_workspace_bytes.restype = ctypes.c_size_t
+        L.vp_kmeans_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32]
+        L.vp_kmeans.restype = ctypes.c_int
+        L.vp_kmeans.argtypes = [vp, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp, vp, vp, vp,
+                                ctypes.c_size_t, vp]
+        L.vp_active_sets_workspace_bytes.restype = ctypes.c_size_t
+        L.vp_active_sets_workspace_bytes.argtypes = [ctypes.c_int32, ctypes.c_int32]
+        L.vp_active_sets.restype = ctypes.c_int
+        L.vp_active_sets.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp, vp,
+                                     ctypes.c_int64, ctypes.POINTER(ctypes.c_int64), vp, ctypes.c_size_t, vp]
+        L.vp_round_to_half.restype = ctypes.c_uint16
+        L.vp_round_to_half.argtypes = [ctypes.c_double]
         _lib = L
     return _lib
 
@@ -293,3 +307,58 @@ def vp_destroy(index: Index):
 
 def vp_last_error() -> str:
     return last_error()
+
+
+# ---------------------------------------------------------------- offline training of the clusters
+def vp_round_to_half(v: float) -> int:
+    return int(lib().vp_round_to_half(float(v)))
+
+
+def vp_kmeans(X, centroids, iters: int = 20, workspace=None, stream=None):
+    """vp_kmeans: trains `centroids` (fp16 [K, d], updated in place) on X (fp16 [n, d]).
+    Returns (assign int32 [n], counts int32 [K]) under the final centroids."""
+    import torch
+    assert X.is_cuda and X.dtype == torch.float16 and X.is_contiguous() and X.dim() == 2
+    assert centroids.is_cuda and centroids.dtype == torch.float16 and centroids.is_contiguous()
+    n, d = X.shape
+    K = centroids.shape[0]
+    assert centroids.shape[1] == d
+    need = lib().vp_kmeans_workspace_bytes(n, d, K)
+    if need == 0:
+        raise VpError(VP_ERR_UNSUPPORTED, last_error())
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
+    assign = torch.empty(n, dtype=torch.int32, device=X.device)
+    counts = torch.empty(K, dtype=torch.int32, device=X.device)
+    _check(lib().vp_kmeans(X.data_ptr(), n, d, K, iters, centroids.data_ptr(), assign.data_ptr(), counts.data_ptr(),
+                           workspace.data_ptr(), workspace.numel(), _stream(stream)))
+    return assign, counts
+
+
+def vp_active_sets(top_ids, assign, K: int, V: int, capacity: Optional[int] = None, stream=None):
+    """vp_active_sets: returns (cand_offsets int64 [K+1], cand_ids int32 [total]) on the device."""
+    import torch
+    assert top_ids.is_cuda and top_ids.dtype == torch.int32 and top_ids.is_contiguous() and top_ids.dim() == 2
+    assert assign.is_cuda and assign.dtype == torch.int32 and assign.is_contiguous()
+    n, T = top_ids.shape
+    assert assign.shape[0] == n
+    need = lib().vp_active_sets_workspace_bytes(K, V)
+    if need == 0:
+        raise VpError(VP_ERR_UNSUPPORTED, last_error())
+    ws = torch.empty(need, dtype=torch.uint8, device=top_ids.device)
+    if capacity is None:
+        capacity = n * T   # a union cannot hold more entries than were recorded
+    off = torch.empty(K + 1, dtype=torch.int64, device=top_ids.device)
+    ids = torch.empty(max(capacity, 1), dtype=torch.int32, device=top_ids.device)
+    total = ctypes.c_int64(0)
+    _check(lib().vp_active_sets(top_ids.data_ptr(), assign.data_ptr(), n, T, K, V, off.data_ptr(), ids.data_ptr(),
+                                capacity, ctypes.byref(total), ws.data_ptr(), ws.numel(), _stream(stream)))
+    return off, ids[: total.value]
+
+
+def vp_kmeans_workspace_bytes(n: int, d: int, K: int) -> int:
+    return lib().vp_kmeans_workspace_bytes(n, d, K)
+
+
+def vp_active_sets_workspace_bytes(K: int, V: int) -> int:
+    return lib().vp_active_sets_workspace_bytes(K, V)

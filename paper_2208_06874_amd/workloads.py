@@ -106,6 +106,15 @@ def make_rows(cfg: Config, C: np.ndarray, N: Optional[int] = None, stream: int =
     return H, q
 
 
+def training_set(cfg: Config, C: np.ndarray, n: int, stream: int = 7):
+    """Recorded hidden vectors for the offline training of the clusters: n draws from the same
+    mixture as the decode rows (a centroid of C plus noise), and K of them, picked without
+    replacement, as starting centroids.  Returns (X fp16 [n, d], q int32 [n], C0 fp16 [K, d])."""
+    X, q = make_rows(cfg, C, N=n, stream=stream, clusters=_rng(cfg, 300 + stream).integers(0, C.shape[0], n))
+    pick = _rng(cfg, 400 + stream).choice(n, size=C.shape[0], replace=False)
+    return X, q.astype(np.int32), X[np.sort(pick)].copy()
+
+
 def union_sorted(token_lists: Iterable[Iterable[int]]) -> np.ndarray:
     """Active set of a cluster: the union of its members' recorded tokens
     (section 2.2), as an ascending list without duplicates."""

@@ -31,7 +31,8 @@ def test_python_binding_has_the_same_names():
     import paper_2208_06874_amd as P
     for n in ("vp_build", "vp_project", "vp_project_full", "vp_project_debug_logits", "vp_workspace_bytes",
               "vp_set_option", "vp_get_info", "vp_get_profile", "vp_destroy", "vp_last_error", "vp_project_union",
-              "vp_union_workspace_bytes"):
+              "vp_union_workspace_bytes", "vp_kmeans", "vp_kmeans_workspace_bytes", "vp_active_sets",
+              "vp_active_sets_workspace_bytes", "vp_round_to_half"):
         assert callable(getattr(P, n))
 
 
@@ -111,6 +112,47 @@ def test_calls_reject_null_index():
     assert L.vp_get_info(None, None) == vp.VP_ERR_INVALID_ARG
     assert L.vp_get_profile(None, None, None) == vp.VP_ERR_INVALID_ARG
     L.vp_destroy(None)   # no-op
+
+
+def test_training_calls_reject_bad_arguments_on_the_host():
+    L = vp.lib()
+    assert L.vp_kmeans_workspace_bytes(1000, 64, 10) > 0
+    assert L.vp_kmeans_workspace_bytes(1000, 60, 10) == 0        # d % 8
+    assert L.vp_kmeans_workspace_bytes(0, 64, 10) == 0
+    assert L.vp_kmeans_workspace_bytes(1000, 64, 5000) == 0
+    assert L.vp_kmeans_workspace_bytes(2000, 64, 10) >= L.vp_kmeans_workspace_bytes(1000, 64, 10)
+    assert L.vp_kmeans(None, 10, 64, 4, 1, None, None, None, None, 0, None) == vp.VP_ERR_INVALID_ARG
+    assert L.vp_kmeans(0x1000, 10, 64, 4, -1, 0x1000, 0x1000, 0x1000, 0x1000, 1 << 30, None) == vp.VP_ERR_INVALID_ARG
+    assert L.vp_kmeans(0x1000, 10, 64, 4, 1, 0x1000, 0x1000, 0x1000, 0x1000, 16, None) == vp.VP_ERR_WORKSPACE
+    assert "needed" in vp.last_error()
+    assert L.vp_kmeans(0x1008, 10, 64, 4, 1, 0x1000, 0x1000, 0x1000, 0x1000, 1 << 30, None) == vp.VP_ERR_INVALID_ARG
+    assert L.vp_active_sets_workspace_bytes(4, 100) > 0
+    assert L.vp_active_sets_workspace_bytes(0, 100) == 0
+    tot = ctypes.c_int64(0)
+    assert L.vp_active_sets(None, None, 5, 3, 4, 100, None, None, 0, ctypes.byref(tot), None, 0, None) == \
+        vp.VP_ERR_INVALID_ARG
+    assert L.vp_active_sets(0x1000, 0x1000, 5, 0, 4, 100, 0x1000, 0x1000, 8, ctypes.byref(tot), 0x1000, 1 << 20,
+                            None) == vp.VP_ERR_INVALID_ARG
+    assert L.vp_active_sets(0x1000, 0x1000, 5, 3, 4, 100, 0x1000, 0x1000, 8, ctypes.byref(tot), 0x1000, 16,
+                            None) == vp.VP_ERR_WORKSPACE
+
+
+def test_round_to_half_is_the_library_cast():
+    """The host copy of the rounding vp_kmeans applies to a mean: every fp16 value, midpoints, random doubles."""
+    pos = np.arange(0, 0x7c00, dtype=np.uint16)
+    vals = pos.view(np.float16).astype(np.float64)
+    for i in range(len(pos)):
+        assert vp.vp_round_to_half(vals[i]) == int(pos[i])
+        assert vp.vp_round_to_half(-vals[i]) == int(pos[i]) | 0x8000
+    mids = 0.5 * (vals[:-1] + vals[1:])
+    r = np.random.default_rng(0)
+    v = np.concatenate([mids, -mids, np.nextafter(mids, np.inf), np.nextafter(mids, -np.inf),
+                        r.standard_normal(20000), r.standard_normal(5000) * 1e-6, r.standard_normal(5000) * 3e4,
+                        r.standard_normal(1000) * 1e-9, r.standard_normal(1000) * 1e6, [65519.9, 65520.0, 1e300, 0.0]])
+    with np.errstate(over="ignore"):
+        want = v.astype(np.float16).view(np.uint16)
+    got = np.array([vp.vp_round_to_half(x) for x in v], np.uint16)
+    assert np.array_equal(got, want)
 
 
 def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):

@@ -1,0 +1,229 @@
+"""GPU parity of the offline cluster training (paper, section 2.2): vp_kmeans and
+vp_active_sets, called through the C ABI, against the CPU oracle on the same seeded
+inputs.  Centroids and active sets are compared bit for bit; memberships are equal
+except where the oracle's own distances of the two competing centroids differ by less
+than the tolerance of the fp32 scores."""
+import ctypes
+
+import numpy as np
+import pytest
+
+from paper_2208_06874_amd import workloads as wl
+from tests import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+
+
+def _torch():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    return torch
+
+
+def _dev(a):
+    torch = _torch()
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def _gpu_kmeans(X, C0, iters):
+    """Returns (centroid bits uint16 [K, d], assign, counts) of vp_kmeans."""
+    torch = _torch()
+    from paper_2208_06874_amd import vp
+    Xt, Ct = _dev(X), _dev(C0.copy())
+    assign, counts = vp.vp_kmeans(Xt, Ct, iters)
+    torch.cuda.synchronize()
+    return pu.to_np(Ct).view(np.uint16), pu.to_np(assign), pu.to_np(counts)
+
+
+def _check_membership(oracle, X, Cbits, assign_gpu):
+    """GPU membership against the oracle's nearest centroid; returns the number of excused rows."""
+    C = Cbits.view(np.float16)
+    _, excused = pu.check_clusters(oracle, X, C, assign_gpu)
+    return excused
+
+
+def _mixture(cfg_name, n, **scale):
+    cfg = wl.scaled(wl.CONFIGS[cfg_name], **scale) if scale else wl.CONFIGS[cfg_name]
+    _W, _b, C = wl.make_model(cfg)
+    X, q, C0 = wl.training_set(cfg, C, n)
+    return cfg, X, q, C0
+
+
+@pytest.mark.parametrize("name,n,scale", [("tiny", 4096, {}), ("tiny", 1000, dict(d=72, K=5)),
+                                          ("mid", 3000, dict(d=264, K=77))])
+def test_lloyd_steps_match_the_oracle(oracle, name, n, scale):
+    cfg, X, _q, C0 = _mixture(name, n, **scale)
+    Cb = C0.view(np.uint16).copy()
+    excused = 0
+    for step in range(3):
+        # membership under the current centroids (no update) ...
+        same, assign, counts = _gpu_kmeans(X, Cb.view(np.float16), 0)
+        assert np.array_equal(same, Cb), "iters = 0 must leave the centroids alone"
+        excused += _check_membership(oracle, X, Cb, assign)
+        assert np.array_equal(counts, np.bincount(assign, minlength=Cb.shape[0]))
+        # ... and one iteration from them: the means of exactly those members, rounded once
+        new, _a2, _c2 = _gpu_kmeans(X, Cb.view(np.float16), 1)
+        st = oracle.kmeans_step(X, Cb.view(np.float16).astype(np.float64), forced=assign)
+        want = st["C"].astype(np.float16).view(np.uint16)
+        assert np.array_equal(new, want), "step %d: %d centroid coordinates differ" % (step, (new != want).sum())
+        Cb = new
+    print("lloyd steps", name, n, scale, "excused memberships", excused)
+
+
+def test_twenty_iterations_and_determinism(oracle):
+    cfg, X, q, C0 = _mixture("tiny", 8192)
+    Cb, assign, counts = _gpu_kmeans(X, C0, 20)
+    Cb2, assign2, counts2 = _gpu_kmeans(X, C0, 20)
+    assert np.array_equal(Cb, Cb2) and np.array_equal(assign, assign2) and np.array_equal(counts, counts2)
+    ref = oracle.kmeans(X, C0, 20, round_half=True)
+    excused = _check_membership(oracle, X, Cb, assign)
+    assert counts.sum() == X.shape[0] and np.array_equal(counts, np.bincount(assign, minlength=cfg.K))
+    if np.array_equal(Cb, ref["C_bits"]):
+        assert excused > 0 or np.array_equal(assign, ref["assign"])
+        verdict = "bit-identical centroids"
+    else:
+        # a membership decided differently inside the fp32 tolerance sends the two runs down
+        # different paths; both must end at the same quality
+        mine = oracle.kmeans_step(X, Cb.view(np.float16).astype(np.float64))["objective"]
+        assert abs(mine - ref["objective"][-1]) <= 1e-3 * ref["objective"][-1]
+        verdict = "objective %.6g vs %.6g" % (mine, ref["objective"][-1])
+    # the training must have improved on the start
+    assert ref["objective"][-1] < ref["objective"][0]
+    print("twenty iterations:", verdict, "excused", excused)
+
+
+def test_ties_round_to_even_for_every_pair_of_neighbours(oracle):
+    """One cluster of two members whose coordinates are neighbouring fp16 values: every mean is a tie."""
+    pos = np.arange(0, 0x7bff, dtype=np.uint16)   # neighbour pairs (p, p + 1), all finite
+    d = 4096
+    for lo in range(0, len(pos), d):
+        a = pos[lo:lo + d]
+        if len(a) < d:
+            a = np.concatenate([a, np.zeros(d - len(a), np.uint16)])
+        sign = np.uint16(0x8000) if (lo // d) % 2 else np.uint16(0)
+        X = np.stack([a | sign, (a + 1) | sign]).view(np.float16)
+        C0 = X[:1].copy()
+        got, assign, counts = _gpu_kmeans(X, C0, 1)
+        assert counts.tolist() == [2] and assign.tolist() == [0, 0]
+        mean = 0.5 * (X[0].astype(np.float64) + X[1].astype(np.float64))
+        want = mean.astype(np.float16).view(np.uint16)
+        assert np.array_equal(got[0], want)
+        assert np.array_equal(got[0], np.array([oracle.double_to_half(v) for v in mean], np.uint16))
+
+
+def test_edge_cases(oracle):
+    torch = _torch()
+    from paper_2208_06874_amd import vp
+    # a centroid nobody is near keeps its value; K = 1; a single vector; more vectors than one launch takes
+    cfg, X, _q, C0 = _mixture("tiny", 777, d=64, K=6)
+    C0 = np.concatenate([C0, np.full((1, 64), 90.0, np.float16)])
+    Cb, assign, counts = _gpu_kmeans(X, C0, 2)
+    assert counts[-1] == 0 and np.all(Cb[-1].view(np.float16) == 90.0)
+    ref = oracle.kmeans(X, C0, 2, round_half=True)
+    if _check_membership(oracle, X, Cb, assign) == 0:
+        assert np.array_equal(Cb, ref["C_bits"]) and np.array_equal(assign, ref["assign"])
+
+    Cb, assign, counts = _gpu_kmeans(X, X[:1].copy(), 1)
+    assert counts.tolist() == [777] and not assign.any()
+    assert np.array_equal(Cb[0], X.astype(np.float64).mean(0).astype(np.float16).view(np.uint16))
+
+    Cb, assign, counts = _gpu_kmeans(X[:1], C0[:3], 1)
+    assert counts.sum() == 1 and np.array_equal(Cb[assign[0]], X[0].view(np.uint16))
+
+    cfg, X, _q, C0 = _mixture("tiny", 70001, d=32, K=9)
+    Cb, assign, counts = _gpu_kmeans(X, C0, 1)
+    _s, a0, _c = _gpu_kmeans(X, C0, 0)
+    st = oracle.kmeans_step(X, C0.astype(np.float64), forced=a0)
+    assert np.array_equal(Cb, st["C"].astype(np.float16).view(np.uint16))
+    assert _check_membership(oracle, X, Cb, assign) >= 0 and counts.sum() == 70001
+
+    # argument errors leave the outputs alone
+    Xt, Ct = _dev(X[:100]), _dev(C0)
+    ws = torch.empty(16, dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(vp.VpError) as e:
+        vp.vp_kmeans(Xt, Ct, 1, workspace=ws)
+    assert e.value.status == vp.VP_ERR_WORKSPACE
+    torch.cuda.synchronize()
+    assert np.array_equal(pu.to_np(Ct).view(np.uint16), C0.view(np.uint16))
+
+
+def test_active_sets_match_the_oracle(oracle):
+    torch = _torch()
+    from paper_2208_06874_amd import vp
+    r = np.random.default_rng(21)
+    for n, T, K, V in ((5000, 5, 37, 1000), (300, 1, 4, 33), (20000, 3, 200, 128000), (0, 3, 5, 100)):
+        top = r.integers(0, V, (n, T)).astype(np.int32)
+        top[r.random((n, T)) < 0.05] = -1
+        assign = r.integers(0, max(K - 1, 1), n).astype(np.int32)   # the last cluster stays empty
+        if n:
+            off, ids = vp.vp_active_sets(_dev(top), _dev(assign), K, V)
+        else:
+            off, ids = vp.vp_active_sets(torch.empty((0, T), dtype=torch.int32, device="cuda:0"),
+                                         torch.empty(0, dtype=torch.int32, device="cuda:0"), K, V)
+        torch.cuda.synchronize()
+        want_off, want_ids = oracle.active_sets(top, assign, K, V)
+        assert np.array_equal(pu.to_np(off), want_off)
+        assert np.array_equal(pu.to_np(ids), want_ids)
+    # too small an output: the total is reported, nothing is written
+    top = r.integers(0, 50, (64, 2)).astype(np.int32)
+    assign = np.zeros(64, np.int32)
+    with pytest.raises(vp.VpError) as e:
+        vp.vp_active_sets(_dev(top), _dev(assign), 2, 50, capacity=3)
+    assert e.value.status == vp.VP_ERR_WORKSPACE and "needed" in str(e.value)
+
+
+def test_worked_example_of_the_active_set(oracle):
+    """Section 2.2: members with recorded tokens {2,4,6} and {2,8,9} give {2,4,6,8,9}."""
+    torch = _torch()
+    from paper_2208_06874_amd import vp
+    top = np.array([[2, 4, 6], [2, 8, 9]], np.int32)
+    off, ids = vp.vp_active_sets(_dev(top), _dev(np.zeros(2, np.int32)), 1, 10)
+    torch.cuda.synchronize()
+    assert pu.to_np(off).tolist() == [0, 5] and pu.to_np(ids).tolist() == [2, 4, 6, 8, 9]
+
+
+def test_trained_index_end_to_end(oracle):
+    """Record top-T tokens with the full projection, train the clusters, build the active sets, build
+    the index from them and check a decode batch against the oracle with the same lists."""
+    torch = _torch()
+    from paper_2208_06874_amd import vp
+    cfg = wl.CONFIGS["tiny"]
+    W, b, C_true = wl.make_model(cfg)
+    X, _q, C0 = wl.training_set(cfg, C_true, 6000)
+    T = 3
+    Wt, bt = _dev(W), _dev(b)
+    boot = vp.vp_build(Wt, bt, _dev(C0[:1]), np.array([0, 1], np.int64), np.array([0], np.int32), k_max=T)
+    Xt = _dev(X)
+    top, _lp = boot.project_full(Xt, T)
+    Ct = _dev(C0.copy())
+    assign, counts = vp.vp_kmeans(Xt, Ct, 20)
+    off, ids = vp.vp_active_sets(top, assign, cfg.K, cfg.V)
+    torch.cuda.synchronize()
+    counts = pu.to_np(counts)
+    off_h, ids_h = pu.to_np(off), pu.to_np(ids)
+    # the sets are the oracle's union of what was recorded, for the GPU's memberships
+    want_off, want_ids = oracle.active_sets(pu.to_np(top), pu.to_np(assign), cfg.K, cfg.V)
+    assert np.array_equal(off_h, want_off) and np.array_equal(ids_h, want_ids)
+    # the recorded tokens are the oracle's top-T of the full projection
+    sf = pu.check_full(oracle, W, b, X[:64], T, pu.to_np(top)[:64], pu.to_np(_lp)[:64])
+    # a cluster that lost all its members has no active set: it is left out of the index
+    keep = np.nonzero(counts > 0)[0]
+    sizes = np.diff(off_h)
+    assert np.all(sizes[keep] > 0) and np.all(sizes[counts == 0] == 0)
+    C_new = np.ascontiguousarray(pu.to_np(Ct)[keep])
+    ids_h = np.concatenate([ids_h[off_h[j]:off_h[j + 1]] for j in keep])
+    off_h = np.concatenate([[0], np.cumsum(sizes[keep])]).astype(np.int64)
+    index = vp.vp_build(Wt, bt, _dev(C_new), off_h, ids_h, k_max=8)
+    H, _ = wl.make_rows(cfg, C_true, N=64, stream=9)
+    out_ids, out_logp, g = index.project(_dev(H), 4)
+    torch.cuda.synchronize()
+    st = pu.check_projection(oracle, W, b, C_new, off_h, ids_h, H, 4, pu.to_np(out_ids), pu.to_np(out_logp),
+                             pu.to_np(g))
+    # the trained clusters do their job: the full projection's best token is in the row's active set
+    f_ids, _ = boot.project_full(_dev(H), 1)
+    torch.cuda.synchronize()
+    hit = np.mean(pu.to_np(f_ids)[:, 0] == pu.to_np(out_ids)[:, 0])
+    print("trained index:", st, sf, "top-1 agreement with the full projection %.3f" % hit,
+          "clusters kept %d of %d," % (len(keep), cfg.K), "mean active set %.0f of %d" % (len(ids_h) / len(keep), cfg.V))
+    assert hit >= 0.6
