@@ -42,6 +42,8 @@ def main():
     ap.add_argument("--no-full", action="store_true")
     ap.add_argument("--no-union", action="store_true")
     ap.add_argument("--no-dispatch", action="store_true")
+    ap.add_argument("--no-training", action="store_true")
+    ap.add_argument("--train-vectors", type=int, default=131072, help="recorded vectors of the cluster-training leg")
     ap.add_argument("--option", action="append", default=[], help="library option name=value")
     ap.add_argument("--graph", action="store_true",
                     help="replay each step from a captured HIP graph (one graph per batch) instead of launching it")
@@ -217,6 +219,55 @@ def main():
                                 "speedup_vs_full": (result["full_vocab"]["ms_per_step"] / ms_union)
                                 if "full_vocab" in result else None}
         del uws
+
+    if not args.no_training:
+        # offline training of the clusters (section 2.2) on synthetic recorded vectors of the same mixture:
+        # Lloyd iterations (vp_kmeans) and the active sets from recorded top-3 tokens (vp_active_sets)
+        n_tr, T = args.train_vectors, 3
+        Xn, _q, C0 = wl.training_set(cfg, C, n_tr)
+        Xt = torch.from_numpy(Xn).to(dev)
+        C0t = torch.from_numpy(C0).to(dev)
+        kws = torch.empty(P.vp_kmeans_workspace_bytes(n_tr, cfg.d, cfg.K), dtype=torch.uint8, device=dev)
+
+        def kmeans_ms(iters):
+            Ct = C0t.clone()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            out = P.vp_kmeans(Xt, Ct, iters, workspace=kws)
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) * 1e3, Ct, out
+
+        kmeans_ms(1)                                  # warm-up
+        ms0, _, _ = kmeans_ms(0)                      # one membership pass
+        iters_tr = 5
+        ms5, Ct, (assign, counts) = kmeans_ms(iters_tr)
+        ms_iter = (ms5 - ms0) / iters_tr
+        top = torch.empty((n_tr, T), dtype=torch.int32, device=dev)
+        lp = torch.empty((min(n_tr, 32768), T), dtype=torch.float32, device=dev)
+        wst = index.workspace(min(n_tr, 32768))
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for r0 in range(0, n_tr, 32768):              # recording: top-T of the full projection
+            r1 = min(n_tr, r0 + 32768)
+            index.project_full(Xt[r0:r1], T, out_ids=top[r0:r1], out_logp=lp[: r1 - r0], workspace=wst)
+        torch.cuda.synchronize()
+        ms_rec = (time.perf_counter() - t0) * 1e3
+        P.vp_active_sets(top, assign, cfg.K, cfg.V)   # warm-up
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        a_off, a_ids = P.vp_active_sets(top, assign, cfg.K, cfg.V)
+        torch.cuda.synchronize()
+        ms_sets = (time.perf_counter() - t0) * 1e3
+        flops = 2.0 * n_tr * cfg.K * cfg.d
+        result["cluster_training"] = {
+            "vectors": n_tr, "K": cfg.K, "d": cfg.d, "ms_per_lloyd_iteration": ms_iter,
+            "vectors_per_s": n_tr / (ms_iter * 1e-3),
+            "roofline": {"bound": "mfma", "achieved": flops / (ms_iter * 1e-3) / 1e12, "peak": 2500.0,
+                         "unit": "TFLOP/s", "frac": flops / (ms_iter * 1e-3) / 2.5e15,
+                         "note": "2 n K d flop of the membership pass over the whole iteration"},
+            "membership_pass_ms": ms0, "record_top%d_ms" % T: ms_rec, "active_sets_ms": ms_sets,
+            "active_set_entries": int(a_ids.numel()), "empty_clusters": int((counts == 0).sum().item())}
+        del Xt, kws, top, wst
 
     if not args.no_cpu_baseline:
         # the CPU oracle, as it stands, on the first batch of the same workload

@@ -60,7 +60,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(
     int32_t *__restrict__ out_cluster, int32_t *__restrict__ perm, VpRowPlan *__restrict__ rowplan,
     unsigned int *__restrict__ floors, VpItem *__restrict__ items, VpPlanHeader *__restrict__ hdr,
     int64_t *__restrict__ dbg_row_off, int dispatch, VpCostModel cost, int k, int V, int vtiles,
-    int full_target_items, int max_items_full)
+    int full_target_items, int full_min_items, int max_items_full)
 {
     extern __shared__ int lds[];
     int *cnt = lds;             // [K]   rows per cluster, later the scatter cursor
@@ -134,14 +134,19 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(
     if (dispatch) {
         int occ_tiles;
         block_exscan<int>(my_occ_tiles, &occ_tiles, wsum);
-        const int rgs_full = ceil_div(N, VP_ROWS_PER_ITEM);
+        const int rpi_full = dispatch;   // rows per item of the masked projection (16 or 64)
+        const int rgs_full = ceil_div(N, rpi_full);
         const float t_slab = occ_tiles / cost.bw_slab + (total_tiles - occ_tiles) / cost.bw_l2;
-        // the top-k lists cost the full projection more than the slabs (every lane of every
-        // wavefront is busy there): a margin that grows with k keeps the choice on the safe side
-        const float t_full = fmaxf(vtiles / cost.bw_full, (float)rgs_full * vtiles / cost.bw_l2) * (1.f + k * 0.125f);
+        // The top-k lists cost the full projection more than the slabs (every lane of every
+        // wavefront is busy there): a margin that grows with k keeps the choice on the safe side.
+        // 64-row items: one pass from HBM, each further row group at the measured rate of the
+        // GEMM-shaped kernel.  16-row items: every row group re-reads W through the L2.
+        const float t_full = rpi_full == 64
+            ? (vtiles / cost.bw_full + (rgs_full - 1) * (vtiles / cost.bw_gemm)) * (1.f + k * 0.0625f)
+            : fmaxf(vtiles / cost.bw_full, (float)rgs_full * vtiles / cost.bw_l2) * (1.f + k * 0.125f);
         if (t_full < t_slab) {
             __syncthreads();
-            vp_plan_single_bucket(N, V, vtiles, VP_ROWS_PER_ITEM, full_target_items, min_items, max_items_full, perm,
+            vp_plan_single_bucket(N, V, vtiles, rpi_full, full_target_items, full_min_items, max_items_full, perm,
                                   rowplan, floors, items, hdr, nullptr, tid, PLAN_THREADS);
             if (tid == 0) hdr->mode = 1;
             return;
@@ -272,11 +277,11 @@ void vpk_plan(const void *cpart, int parts, int N, int K, const int32_t *n_cand,
               int target_items, int min_items, int max_items, int32_t *g, int32_t *out_cluster, int32_t *perm,
               VpRowPlan *rowplan, unsigned int *floors, VpItem *items, VpPlanHeader *hdr, int64_t *dbg_row_off,
               int dispatch, const VpCostModel &cost, int k, int V, int vtiles, int full_target_items,
-              int max_items_full, hipStream_t st)
+              int full_min_items, int max_items_full, hipStream_t st)
 {
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(PLAN_THREADS), vpk_plan_lds_bytes(K), st, (const int2 *)cpart,
                        parts, N, K, n_cand, tile_off, target_items, min_items, max_items, g, out_cluster, perm, rowplan, floors,
-                       items, hdr, dbg_row_off, dispatch, cost, k, V, vtiles, full_target_items, max_items_full);
+                       items, hdr, dbg_row_off, dispatch, cost, k, V, vtiles, full_target_items, full_min_items, max_items_full);
 }
 
 void vpk_plan_full(int N, int V, int vtiles, int rpi, int target_items, int min_items, int max_items, int32_t *perm,

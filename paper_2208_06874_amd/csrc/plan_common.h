@@ -7,7 +7,7 @@ __device__ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 // Plan for one bucket that holds all N rows in their own order against one slab
 // of ncand candidates in vtiles tiles (the full vocabulary, or the union of the
-// batch's active sets), rpi (16 or 32) rows per item.  Called by every thread gtid of
+// batch's active sets), rpi (16, 32 or 64) rows per item.  Called by every thread gtid of
 // gsize cooperating threads.
 __device__ inline void vp_plan_single_bucket(int N, int ncand, int vtiles, int rpi, int target_items, int min_items,
                                              int max_items, int32_t *__restrict__ perm,
@@ -24,6 +24,7 @@ __device__ inline void vp_plan_single_bucket(int N, int ncand, int vtiles, int r
     for (int p = gtid; p < N; p += gsize) {
         perm[p] = p;
         floors[p] = VP_FLOOR_NONE;
+        for (int j = 0; j < VP_BOUND_SETS; ++j) floors[N + p * VP_BOUND_SETS + j] = VP_FLOOR_NONE;
         VpRowPlan rp;
         rp.row = p;
         rp.cluster = 0;

@@ -72,6 +72,8 @@ struct vp_index {
     int target_items, full_target_items, rstar;
     int min_items;   // resident workgroup slots of the projection kernel on this GPU
     int wide_items;  // 1: single-bucket projections of more than 16 rows use items of 32 rows
+    int gemm_target_items;   // work items of the GEMM-shaped kernel: its resident workgroup slots
+    int gemm_min_rows;   // single-bucket projections of at least this many rows use the GEMM-shaped kernel (0: never)
     int dispatch;    // 1: the planner may choose the masked full projection (same results)
     VpCostModel cost;
     const uint32_t *bitmaps;
@@ -162,7 +164,10 @@ int max_items_clustered(const vp_index *I, int N)
     return I->target_items + ceil_div(N, VP_ROWS_PER_ITEM) + std::min(N, I->K) + 2;
 }
 // (the grid of the full projection is padded to 8 candidate ranges at a time, one per XCD)
-int max_items_full(const vp_index *I, int N) { return I->full_target_items + 8 * ceil_div(N, VP_ROWS_PER_ITEM) + 2; }
+int max_items_full(const vp_index *I, int N)
+{
+    return std::max(I->full_target_items, I->gemm_target_items) + 8 * ceil_div(N, VP_ROWS_PER_ITEM) + 2;
+}
 
 WsLayout plan_workspace(const vp_index *I, int N)
 {
@@ -176,7 +181,7 @@ WsLayout plan_workspace(const vp_index *I, int N)
     W.g = take(n * 4);
     W.perm = take(n * 4);
     W.rowplan = take(n * sizeof(VpRowPlan));
-    W.floors = take(n * 4);
+    W.floors = take(n * 4 * (1 + VP_BOUND_SETS));   // [N] bounds of the 16-row kernels, then [N][sets] of the GEMM kernel
     W.items = take((size_t)W.max_items * sizeof(VpItem));
     W.partials = take((size_t)W.max_items * VP_MAX_ROWS_PER_ITEM * vp_partial_floats(I->k_max) * sizeof(float));
     W.total = o;
@@ -226,14 +231,32 @@ std::pair<hipEvent_t, hipEvent_t> *profile_slot(const vp_index *I)
     return &P->pool[P->used++];
 }
 
-// Row tiles per item for projections that keep all rows in one bucket (full, union).
-// Two row tiles per loaded slab tile pay off (measured: -10 % at top-1, N = 256) only
-// while the top-k lists are short; with longer lists the epilogue of two row tiles in
-// half as many wavefronts costs more than the saved L2 traffic (+40 % at top-8).
+// Row tiles per item for projections that keep all rows in one bucket (full, masked, union).
+// From gemm_min_rows rows on: 4, the GEMM-shaped kernel (64 rows per item, every loaded slab
+// tile feeds four MFMAs).  Below that, two row tiles per loaded slab tile pay off (measured:
+// -10 % at top-1, N = 256) only while the top-k lists are short.
 int single_bucket_row_tiles(const vp_index *I, int N, int k)
 {
+    if (I->gemm_min_rows > 0 && N >= I->gemm_min_rows && vpk_project_gemm_supported(I->L.kt)) return 4;
     if (!I->wide_items || k > 2 || N <= VP_ROWS_PER_ITEM || I->L.kt % 16 != 0) return 1;
     return vpk_project_lds_bytes(I->L.kt, k, 2) <= LDS_LIMIT / 2 ? 2 : 1;
+}
+
+// Item count bounds (target, minimum) of a single-bucket plan with this many row tiles.
+inline int sb_target(const vp_index *I, int row_tiles) { return row_tiles == 4 ? I->gemm_target_items : I->full_target_items; }
+inline int sb_min(const vp_index *I, int row_tiles) { return row_tiles == 4 ? I->gemm_target_items : I->min_items; }
+
+// Launches the projection kernel that goes with the plan's rows per item.
+void launch_single_bucket(const VpSlabSet &set, const vp_index *I, const void *hidden, const int32_t *perm,
+                          const VpItem *items, const VpPlanHeader *hdr, int N, int grid_items, int row_tiles, int k, int rstar,
+                          float *partials, unsigned int *floors, float *dbg_logits, const int64_t *dbg_row_off,
+                          hipStream_t st)
+{
+    if (row_tiles == 4)
+        vpk_project_gemm(set, hidden, I->d, perm, items, hdr, grid_items, k, partials, floors + N, nullptr, st);
+    else
+        vpk_project(set, hidden, I->d, perm, items, hdr, grid_items, row_tiles, k, rstar, partials, floors, dbg_logits,
+                    dbg_row_off, st);
 }
 
 // The kernel sequence shared by vp_project and the clustered debug entry.
@@ -260,7 +283,9 @@ vp_status run_clustered(const char *fn, const vp_index *I, const void *hidden, i
 
     const int max_items = max_items_clustered(I, N);
     // the debug entry lays its logits out per cluster list, so it always takes the slabs
-    const int dispatch = (I->dispatch && !dbg_logits) ? 1 : 0;
+    // with dispatch: rows per item of the masked full projection the planner may choose
+    const int rt_masked = single_bucket_row_tiles(I, N, VP_MAX_TOPK) == 4 ? 4 : 1;
+    const int dispatch = (I->dispatch && !dbg_logits) ? VP_ROWS_PER_ITEM * rt_masked : 0;
     const int max_full = max_items_full(I, N);
     // the tile counts of the cost model are in tiles of kt KiB: fold that into the constants
     VpCostModel cost = I->cost;
@@ -268,9 +293,10 @@ vp_status run_clustered(const char *fn, const vp_index *I, const void *hidden, i
     cost.bw_slab /= tile_bytes;
     cost.bw_full /= tile_bytes;
     cost.bw_l2 /= tile_bytes;
+    cost.bw_gemm /= tile_bytes;
     vpk_plan(cpart, parts, N, I->K, I->clusters.n_cand, I->clusters.tile_off, I->target_items, I->min_items, max_items, g,
              out_cluster, perm, rowplan, floors, items, hdr, dbg_row_off, dispatch, cost, k, I->V, I->L.vtiles,
-             I->full_target_items, max_full, st);
+             sb_target(I, rt_masked), sb_min(I, rt_masked), max_full, st);
 
     const long row_groups = (long)row_tiles + std::min(N, I->K);
     const long by_tiles = row_groups * ceil_div(I->L.max_tiles, VP_WG_WAVES);
@@ -281,12 +307,15 @@ vp_status run_clustered(const char *fn, const vp_index *I, const void *hidden, i
                 dbg_row_off, st);
     if (dispatch) {
         // launched as well; exactly one of the two does the work, as the planner decided
-        const int rgs = ceil_div(N, VP_ROWS_PER_ITEM);
-        const int tpw = vp_tiles_per_wave((long long)rgs * I->L.vtiles, I->full_target_items, I->min_items);
+        const int rgs = ceil_div(N, dispatch);
+        const int tpw = vp_tiles_per_wave((long long)rgs * I->L.vtiles, sb_target(I, rt_masked), sb_min(I, rt_masked));
         const int chunks = ceil_div(I->L.vtiles, (long)tpw * VP_WG_WAVES);
         const int grid_full = rgs > 1 ? ceil_div(chunks, 8) * 8 * rgs : chunks;
         const VpMaskInfo mask = {g, I->bitmaps, I->L.bm_words};
-        vpk_project_masked(I->full, hidden, I->d, perm, items, hdr, grid_full, k, partials, floors, mask, st);
+        if (rt_masked == 4)
+            vpk_project_gemm(I->full, hidden, I->d, perm, items, hdr, grid_full, k, partials, floors + N, &mask, st);
+        else
+            vpk_project_masked(I->full, hidden, I->d, perm, items, hdr, grid_full, k, partials, floors, mask, st);
     }
     if (ev) (void)hipEventRecord(ev->second, st);
     if (out_ids)
@@ -305,22 +334,22 @@ vp_status run_full(const char *fn, const vp_index *I, const void *hidden, int N,
     VpItem *items = reinterpret_cast<VpItem *>(ws + W.items);
     float *partials = reinterpret_cast<float *>(ws + W.partials);
 
-    // more than 16 rows: two row tiles per item when two such workgroups fit in a CU's LDS
-    const int row_tiles = single_bucket_row_tiles(I, N, k);
+    // rows per item: 16, 32 or (GEMM-shaped kernel) 64; the debug entry always takes 16
+    const int row_tiles = dbg_logits ? 1 : single_bucket_row_tiles(I, N, k);
     const int rpi = VP_ROWS_PER_ITEM * row_tiles;
     const int max_items = max_items_full(I, N);
-    vpk_plan_full(N, I->V, I->L.vtiles, rpi, I->full_target_items, I->min_items, max_items, perm, rowplan, floors,
+    vpk_plan_full(N, I->V, I->L.vtiles, rpi, sb_target(I, row_tiles), sb_min(I, row_tiles), max_items, perm, rowplan, floors,
                   items, hdr, dbg_row_off, st);
     // the same split the planning kernel makes; with several row groups the projection kernel
     // deals candidate ranges to the XCDs, which needs the grid padded to 8 ranges at a time
     const int rgs = ceil_div(N, rpi);
-    const int tpw = vp_tiles_per_wave((long long)rgs * I->L.vtiles, I->full_target_items, I->min_items);
+    const int tpw = vp_tiles_per_wave((long long)rgs * I->L.vtiles, sb_target(I, row_tiles), sb_min(I, row_tiles));
     const int chunks = ceil_div(I->L.vtiles, (long)tpw * VP_WG_WAVES);
     const int grid_items = rgs > 1 ? ceil_div(chunks, 8) * 8 * rgs : chunks;
     auto *ev = profile_slot(I);
     if (ev) (void)hipEventRecord(ev->first, st);
-    vpk_project(I->full, hidden, I->d, perm, items, hdr, grid_items, row_tiles, k, N <= I->rstar ? I->rstar : 0,
-                partials, floors, dbg_logits, dbg_row_off, st);
+    launch_single_bucket(I->full, I, hidden, perm, items, hdr, N, grid_items, row_tiles, k, N <= I->rstar ? I->rstar : 0,
+                         partials, floors, dbg_logits, dbg_row_off, st);
     if (ev) (void)hipEventRecord(ev->second, st);
     if (out_ids)
         vpk_merge(I->full, rowplan, hdr, partials, k, N, out_ids, out_logp, st);
@@ -451,11 +480,14 @@ vp_status vp_build(const vp_build_desc *D, void *hip_stream, vp_index **out)
     I->full_target_items = 2048;
     I->rstar = 0;
     I->wide_items = 1;
+    I->gemm_min_rows = 33;
+    I->gemm_target_items = 512;
     I->dispatch = 0;
     // measured on MI355X at d = 1024: bytes per second of the three regimes of the cost model
     I->cost.bw_slab = 6.8e12f;
     I->cost.bw_full = 5.4e12f;
     I->cost.bw_l2 = 17.0e12f;
+    I->cost.bw_gemm = 12.0e12f;
     I->bitmaps = reinterpret_cast<const uint32_t *>(A + L.bitmaps);
     {
         // workgroups of the projection kernel that fit on the chip at once (LDS-limited)
@@ -509,10 +541,20 @@ vp_status vp_set_option(vp_index *I, const char *name, int64_t value)
         return VP_OK;
     }
     if (!std::strcmp(name, "cost_bw_slab_gbs") || !std::strcmp(name, "cost_bw_full_gbs") ||
-        !std::strcmp(name, "cost_bw_l2_gbs")) {
+        !std::strcmp(name, "cost_bw_l2_gbs") || !std::strcmp(name, "cost_bw_gemm_gbs")) {
         if (value < 1 || value > 1000000) return fail(VP_ERR_INVALID_ARG, "vp_set_option: %s out of range", name);
-        float &f = name[8] == 's' ? I->cost.bw_slab : name[8] == 'f' ? I->cost.bw_full : I->cost.bw_l2;
+        float &f = name[8] == 's' ? I->cost.bw_slab : name[8] == 'f' ? I->cost.bw_full : name[8] == 'g' ? I->cost.bw_gemm : I->cost.bw_l2;
         f = (float)value * 1e9f;
+        return VP_OK;
+    }
+    if (!std::strcmp(name, "gemm_target_items")) {
+        if (value < 1 || value > (1 << 20)) return fail(VP_ERR_INVALID_ARG, "vp_set_option: gemm_target_items out of range");
+        I->gemm_target_items = (int)value;
+        return VP_OK;
+    }
+    if (!std::strcmp(name, "gemm_min_rows")) {
+        if (value < 0 || value > VP_MAX_ROWS) return fail(VP_ERR_INVALID_ARG, "vp_set_option: gemm_min_rows out of range");
+        I->gemm_min_rows = (int)value;
         return VP_OK;
     }
     if (!std::strcmp(name, "wide_items")) {
@@ -647,7 +689,7 @@ vp_status vp_project_union(const vp_index *I, const void *hidden, int32_t N, int
     vpk_union_flags(occ, uh, I->clusters, std::min(N, I->K), I->L.n_max, mask, st);
     const int max_items = max_items_full(I, N);
     const int row_tiles_u = single_bucket_row_tiles(I, N, k);
-    vpk_union_compact(mask, U.mask_words, I->V, N, VP_ROWS_PER_ITEM * row_tiles_u, I->full_target_items, I->min_items, max_items, uids, uh,
+    vpk_union_compact(mask, U.mask_words, I->V, N, VP_ROWS_PER_ITEM * row_tiles_u, sb_target(I, row_tiles_u), sb_min(I, row_tiles_u), max_items, uids, uh,
                       out_union_size, perm, rowplan, floors, items, hdr, st);
     // step 3: the reduced weight matrix and Eq. 1 over it; steps 4-5 fused (no [N, V] array)
     vpk_union_gather(I->full.tiles, I->full.bias, I->L.kt, uids, uh, I->L.vtiles, uslab, ubias, st);
@@ -658,8 +700,8 @@ vp_status vp_project_union(const vp_index *I, const void *hidden, int32_t N, int
     // grid: the largest split the planner can choose for |U| <= V
     const int rgs = ceil_div(N, VP_ROWS_PER_ITEM * row_tiles_u);
     const int grid_items = std::min(max_items, ceil_div(rgs * (long)ceil_div(I->L.vtiles, VP_WG_WAVES), 8) * 8 + 8 * rgs);
-    vpk_project(uset, hidden, I->d, perm, items, hdr, grid_items, row_tiles_u, k, 0, partials, floors, nullptr,
-                nullptr, st);
+    launch_single_bucket(uset, I, hidden, perm, items, hdr, N, grid_items, row_tiles_u, k, 0, partials, floors, nullptr,
+                         nullptr, st);
     vpk_merge(uset, rowplan, hdr, partials, k, N, out_ids, out_logp, st);
     return launch_status(fn);
 }

@@ -27,7 +27,7 @@ void vpk_plan(const void *cpart, int parts, int N, int K, const int32_t *n_cand,
               int target_items, int min_items, int max_items, int32_t *g, int32_t *out_cluster, int32_t *perm,
               VpRowPlan *rowplan, unsigned int *floors, VpItem *items, VpPlanHeader *hdr, int64_t *dbg_row_off,
               int dispatch, const VpCostModel &cost, int k, int V, int vtiles, int full_target_items,
-              int max_items_full, hipStream_t st);
+              int full_min_items, int max_items_full, hipStream_t st);
 void vpk_plan_full(int N, int V, int vtiles, int rpi, int target_items, int min_items, int max_items, int32_t *perm,
                    VpRowPlan *rowplan, unsigned int *floors, VpItem *items, VpPlanHeader *hdr,
                    int64_t *dbg_row_off, hipStream_t st);
@@ -42,6 +42,14 @@ void vpk_project(const VpSlabSet &set, const void *hidden, int d, const int32_t 
 void vpk_project_masked(const VpSlabSet &full, const void *hidden, int d, const int32_t *perm, const VpItem *items,
                         const VpPlanHeader *hdr, int grid_items, int k, float *partials, unsigned int *floors,
                         const VpMaskInfo &mask, hipStream_t st);
+
+// GEMM-shaped projection of single-bucket plans with 64 rows per item (mask: nullptr, or the
+// membership lists of the masked full projection)
+size_t vpk_project_gemm_lds_bytes(int k);
+bool vpk_project_gemm_supported(int kt);
+void vpk_project_gemm(const VpSlabSet &set, const void *hidden, int d, const int32_t *perm, const VpItem *items,
+                      const VpPlanHeader *hdr, int grid_items, int k, float *partials, unsigned int *bounds,
+                      const VpMaskInfo *mask, hipStream_t st);
 
 // per-row merge
 size_t vpk_merge_lds_bytes(int k);

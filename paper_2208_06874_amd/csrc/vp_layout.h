@@ -19,7 +19,8 @@
 #define VP_WG_THREADS 256      // projection kernel: 4 wavefronts per workgroup
 #define VP_WG_WAVES 4
 #define VP_ROWS_PER_ITEM 16    // rows one work item projects (one MFMA row tile)
-#define VP_MAX_ROWS_PER_ITEM 32  // with two row tiles (single-bucket projections of more than 16 rows)
+#define VP_BOUND_SETS 8          // per row: candidate-range sets whose best logits bound the k-th best (GEMM kernel)
+#define VP_MAX_ROWS_PER_ITEM 64  // four row tiles: the GEMM-shaped kernel of single-bucket projections
 #define VP_GEMV_MAX_ROWS 4
 
 // One unit of projection work: up to 16 rows of one bucket against a range of
@@ -111,7 +112,8 @@ struct VpMaskInfo {
 struct VpCostModel {
     float bw_slab;   // slabs streamed once from HBM
     float bw_full;   // one pass over the packed W from HBM
-    float bw_l2;     // further passes over tiles already in the L2
+    float bw_l2;     // further passes over tiles already in the L2 (16-row items)
+    float bw_gemm;   // further passes over W by 64-row items of the GEMM-shaped kernel
 };
 
 // Size in floats of one partial result: running max, sum of exponentials, then

@@ -424,8 +424,8 @@ def _planner_mode(index, N):
 def test_dispatch_to_the_masked_full_projection(oracle, tiny, mid):
     """With dispatch on, batches that occupy many clusters run the full projection with every row masked
     to its own active set; the results must be those of the per-cluster projection."""
-    for B, N, k, want_mode in ((mid, 64, 1, 1), (mid, 200, 1, 1), (mid, 64, 8, 0), (mid, 2, 8, 0), (tiny, 16, 4, 0),
-                               (tiny, 1, 4, 0)):
+    for B, N, k, want_mode in ((mid, 64, 1, 1), (mid, 200, 1, 1), (mid, 64, 8, 1), (mid, 20, 8, 0), (mid, 2, 8, 0),
+                               (tiny, 16, 4, 0), (tiny, 1, 4, 0)):
         cfg = wl.scaled(B.cfg, k=k)
         H, q = wl.make_rows(cfg, B.C, N=N, stream=40 + N)
         base = B.project(H, cfg.k)
@@ -450,12 +450,12 @@ def test_dispatch_cost_model_constants(mid):
     cfg = wl.scaled(mid.cfg, k=1)
     H, q = wl.make_rows(cfg, mid.C, N=64, stream=50)
     mid.index.set_option("dispatch", 1)
-    mid.index.set_option("cost_bw_l2_gbs", 10)       # make re-reading through the L2 look hopeless
+    mid.index.set_option("cost_bw_full_gbs", 10)       # make a pass over the whole W look hopeless
     try:
         got = mid.project(H, cfg.k)
         assert _planner_mode(mid.index, 64) == 0
     finally:
-        mid.index.set_option("cost_bw_l2_gbs", 17000)
+        mid.index.set_option("cost_bw_full_gbs", 5400)
         mid.index.set_option("dispatch", 0)
     base = mid.project(H, cfg.k)
     assert np.array_equal(got[0], base[0])
