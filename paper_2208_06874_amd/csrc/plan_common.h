@@ -56,7 +56,8 @@ __device__ inline void vp_plan_single_bucket(int N, int ncand, int vtiles, int r
         hdr->tiles_per_wave = tpw;
         hdr->overflow = chunks * rgs > max_items;
         hdr->total_tiles = (int)min(total_tiles, 2147483647LL);
-        hdr->swz_rgs = rgs > 1 ? rgs : 0;
+        // candidate ranges are dealt to the 8 XCDs only when there are enough of them to go round
+        hdr->swz_rgs = (rgs > 1 && chunks >= 8) ? rgs : 0;
         hdr->swz_chunks = chunks;
         hdr->rows_per_item = rpi;
         hdr->mode = 0;

@@ -12,6 +12,7 @@
 // centroid.
 #include <hip/hip_runtime.h>
 #include "vp_kernels.h"
+#include "project_common.h"
 
 namespace {
 
@@ -37,6 +38,114 @@ __global__ __launch_bounds__(256) void kmeans_assign_kernel(const int2 *__restri
     if ((unsigned)bj >= (unsigned)K) bj = 0;   // only when every score is NaN: keep the index in range
     assign[r] = bj;
     atomicAdd(&counts[bj], 1);
+}
+
+// Membership of many vectors at once: Eq. 2 as a GEMM.  One workgroup takes 64 vectors and
+// all centroids.  As in the GEMM-shaped projection kernel the k-extent is split over the four
+// wavefronts, each keeping its slice of the 64 vectors in registers in MFMA operand order and
+// streaming its slice of every packed centroid tile (the centroids stay in the caches), so
+// each 1 KiB load feeds four MFMAs; the partial inner products of a group of 16 centroids meet
+// in LDS and wavefront w keeps the running (min, argmin) of vector tile w.
+template <int KW>
+__global__ __launch_bounds__(256, (KW <= 8 ? 2 : 1)) void kmeans_assign_gemm_kernel(
+    const uint4 *__restrict__ X, long n, int d, const uint4 *__restrict__ cp, const float *__restrict__ cnorm, int K,
+    int ctiles, int32_t *__restrict__ assign, int32_t *__restrict__ counts)
+{
+    constexpr int KT = KW * 4;
+    constexpr int RT = 4;
+    const int wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int nn = lane & 15;
+    const int q = lane >> 4;
+    __shared__ floatx4 xbuf[2 * RT * 4 * 64];
+
+    const uint4 *tiles = cp + (size_t)wave * KW * 64 + lane;
+    Frag Xb[KW], Yb[KW];
+    auto issue = [&](Frag(&buf)[KW], int g) {
+        const uint4 *p = tiles + (size_t)g * KT * 64;
+#pragma unroll
+        for (int i = 0; i < KW; ++i) buf[i].u = p[i * 64];
+    };
+    issue(Xb, 0);
+    if (1 < ctiles) issue(Yb, 1);
+
+    const long r0 = (long)blockIdx.x * (16 * RT);
+    const int pieces_per_row = d >> 3;
+    Frag B[RT][KW];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+        const long row = r0 + rt * 16 + nn;
+#pragma unroll
+        for (int i = 0; i < KW; ++i) {
+            const int piece = (wave * KW + i) * 4 + q;
+            B[rt][i].u = make_uint4(0, 0, 0, 0);
+            if (row < n && piece < pieces_per_row) B[rt][i].u = X[(size_t)row * pieces_per_row + piece];
+        }
+    }
+
+    float best_s = __builtin_inff();
+    int best_j = VP_IDX_NONE;
+    floatx4 acc[RT];
+    auto compute = [&](Frag(&buf)[KW], int gnext) {
+        const bool more = gnext < ctiles;
+        const uint4 *p = tiles + (size_t)gnext * KT * 64;
+#pragma unroll
+        for (int i = 0; i < KW; ++i) {
+            Frag a;
+            a.u = buf[i].u;
+            if (more) buf[i].u = p[i * 64];
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt)
+                acc[rt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a.h, B[rt][i].h,
+                                                                 i == 0 ? floatx4{0.f, 0.f, 0.f, 0.f} : acc[rt], 0, 0, 0);
+        }
+    };
+    auto finish = [&](int g, int par) {
+        floatx4 *xw = xbuf + (size_t)par * RT * 4 * 64;
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) xw[(rt * 4 + wave) * 64 + lane] = acc[rt];
+        const float4 cn = *reinterpret_cast<const float4 *>(cnorm + g * 16 + q * 4);
+        __syncthreads();
+        const floatx4 dot = (xw[(wave * 4 + 0) * 64 + lane] + xw[(wave * 4 + 1) * 64 + lane]) +
+                            (xw[(wave * 4 + 2) * 64 + lane] + xw[(wave * 4 + 3) * 64 + lane]);
+        const float cnv[4] = {cn.x, cn.y, cn.z, cn.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int j = g * 16 + q * 4 + i;
+            const float s = cnv[i] - 2.0f * dot[i];
+            if (j < K && s < best_s) {   // j ascends within a lane: strict < keeps the lowest
+                best_s = s;
+                best_j = j;
+            }
+        }
+    };
+    int g = 0, par = 0;
+    while (g < ctiles) {
+        compute(Xb, g + 2);
+        finish(g, par);
+        par ^= 1;
+        ++g;
+        if (g >= ctiles) break;
+        compute(Yb, g + 2);
+        finish(g, par);
+        par ^= 1;
+        ++g;
+    }
+#pragma unroll
+    for (int off = 16; off <= 32; off <<= 1) {
+        const float s2 = __shfl_xor(best_s, off);
+        const int j2 = __shfl_xor(best_j, off);
+        if (part_less(s2, j2, best_s, best_j)) {
+            best_s = s2;
+            best_j = j2;
+        }
+    }
+    const long row = r0 + wave * 16 + nn;
+    if (q == 0 && row < n) {
+        if ((unsigned)best_j >= (unsigned)K) best_j = 0;   // only when every score is NaN
+        assign[row] = best_j;
+        atomicAdd(&counts[best_j], 1);
+    }
 }
 
 // start[j] = number of members of clusters below j; cursor[j] = start[j].  One workgroup.
@@ -300,6 +409,25 @@ void vpk_kmeans_assign(const void *cpart, int parts, int rows, int K, int32_t *a
 {
     hipLaunchKernelGGL(kmeans_assign_kernel, dim3((rows + 255) / 256), dim3(256), 0, st, (const int2 *)cpart, parts,
                        rows, K, assign, counts);
+}
+
+bool vpk_kmeans_assign_gemm(const void *X, long n, int d, const void *cp, const float *cnorm, int K, int kt, int ctiles,
+                            int32_t *assign, int32_t *counts, hipStream_t st)
+{
+    const dim3 grid((unsigned)((n + 63) / 64)), block(256);
+#define VP_KM_CASE(KW)                                                                                                \
+    case KW * 4:                                                                                                      \
+        hipLaunchKernelGGL((kmeans_assign_gemm_kernel<KW>), grid, block, 0, st, (const uint4 *)X, n, d,               \
+                           (const uint4 *)cp, cnorm, K, ctiles, assign, counts);                                      \
+        return true;
+    switch (kt) {
+        VP_KM_CASE(2)
+        VP_KM_CASE(4)
+        VP_KM_CASE(8)
+        VP_KM_CASE(12)
+        default: return false;   // other k-extents: the caller falls back to the decode-time kernel
+    }
+#undef VP_KM_CASE
 }
 
 void vpk_kmeans_bucket(const int32_t *assign, long n, const int32_t *counts, int K, int32_t *start, int32_t *cursor,

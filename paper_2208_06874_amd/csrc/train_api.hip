@@ -89,7 +89,10 @@ vp_status vp_kmeans(const void *x, int64_t n, int32_t d, int32_t K, int32_t iter
         vpk_pack_rows(centroids, K, d, L.kt, cp, st);
         vpk_cnorm(centroids, K, d, L.K_pad, cnorm, st);
         vpk_fill_u32(counts, (size_t)K, 0u, st);
-        for (int64_t r0 = 0; r0 < n; r0 += CHUNK_ROWS) {
+        // memberships: the GEMM-shaped kernel when there are enough vectors to fill the chip with
+        // 64-vector workgroups, else (or for k-extents it is not built for) the decode-time kernel
+        const bool gemm = n >= 4096 && vpk_kmeans_assign_gemm(x, (long)n, d, cp, cnorm, K, L.kt, L.ctiles, assign, counts, st);
+        for (int64_t r0 = 0; !gemm && r0 < n; r0 += CHUNK_ROWS) {
             const int rows = (int)std::min<int64_t>(CHUNK_ROWS, n - r0);
             vpk_centroid((const char *)x + (size_t)r0 * d * 2, rows, d, cp, cnorm, K, L.kt, L.ctiles, L.tpw, L.parts,
                          cpart, st);

@@ -310,7 +310,7 @@ vp_status run_clustered(const char *fn, const vp_index *I, const void *hidden, i
         const int rgs = ceil_div(N, dispatch);
         const int tpw = vp_tiles_per_wave((long long)rgs * I->L.vtiles, sb_target(I, rt_masked), sb_min(I, rt_masked));
         const int chunks = ceil_div(I->L.vtiles, (long)tpw * VP_WG_WAVES);
-        const int grid_full = rgs > 1 ? ceil_div(chunks, 8) * 8 * rgs : chunks;
+        const int grid_full = (rgs > 1 && chunks >= 8) ? ceil_div(chunks, 8) * 8 * rgs : chunks * rgs;
         const VpMaskInfo mask = {g, I->bitmaps, I->L.bm_words};
         if (rt_masked == 4)
             vpk_project_gemm(I->full, hidden, I->d, perm, items, hdr, grid_full, k, partials, floors + N, &mask, st);
@@ -345,7 +345,7 @@ vp_status run_full(const char *fn, const vp_index *I, const void *hidden, int N,
     const int rgs = ceil_div(N, rpi);
     const int tpw = vp_tiles_per_wave((long long)rgs * I->L.vtiles, sb_target(I, row_tiles), sb_min(I, row_tiles));
     const int chunks = ceil_div(I->L.vtiles, (long)tpw * VP_WG_WAVES);
-    const int grid_items = rgs > 1 ? ceil_div(chunks, 8) * 8 * rgs : chunks;
+    const int grid_items = (rgs > 1 && chunks >= 8) ? ceil_div(chunks, 8) * 8 * rgs : chunks * rgs;
     auto *ev = profile_slot(I);
     if (ev) (void)hipEventRecord(ev->first, st);
     launch_single_bucket(I->full, I, hidden, perm, items, hdr, N, grid_items, row_tiles, k, N <= I->rstar ? I->rstar : 0,

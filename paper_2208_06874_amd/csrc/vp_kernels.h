@@ -73,6 +73,8 @@ void vpk_union_gather(const void *wp, const float *bias_full, int kt, const int3
 void vpk_fill_u32(void *p, size_t n, uint32_t v, hipStream_t st);
 void vpk_kmeans_assign(const void *cpart, int parts, int rows, int K, int32_t *assign, int32_t *counts,
                        hipStream_t st);
+bool vpk_kmeans_assign_gemm(const void *X, long n, int d, const void *cp, const float *cnorm, int K, int kt, int ctiles,
+                            int32_t *assign, int32_t *counts, hipStream_t st);
 void vpk_kmeans_bucket(const int32_t *assign, long n, const int32_t *counts, int K, int32_t *start, int32_t *cursor,
                        int32_t *perm, hipStream_t st);
 void vpk_kmeans_update(const void *X, int d, const int32_t *perm, const int32_t *start, const int32_t *counts, int K,
