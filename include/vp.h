@@ -103,9 +103,14 @@ vp_status vp_get_info(const vp_index *idx, vp_index_info *info);
  *                   its own cluster's active set instead of streaming the occupied
  *                   slabs, when the planner's cost model says that is cheaper (many
  *                   occupied clusters); same results.  Default 0.
- *   "cost_bw_slab_gbs", "cost_bw_full_gbs", "cost_bw_l2_gbs"  GB/s of the cost model
- *   "wide_items"    1 (default): vp_project_full / vp_project_union of more than 16
- *                   rows with k <= 2 put 32 rows in an item; 0: always 16
+ *   "cost_bw_slab_gbs", "cost_bw_full_gbs", "cost_bw_l2_gbs", "cost_bw_gemm_gbs"
+ *                   GB/s of the cost model
+ *   "gemm_min_rows" projections that keep all rows in one bucket (full, masked, union)
+ *                   use the kernel with 64 rows per work item from this many rows on
+ *                   (default 33; 0: never); d_pad must be 256, 512, 1024 or 1536
+ *   "gemm_target_items"  work items of that kernel (default 512)
+ *   "wide_items"    1 (default): below gemm_min_rows, vp_project_full / vp_project_union
+ *                   of more than 16 rows with k <= 2 put 32 rows in an item; 0: always 16
  *   "profile"       1: time the projection kernel with HIP events (vp_get_profile)
  * Unknown name or out-of-range value: VP_ERR_INVALID_ARG. */
 vp_status vp_set_option(vp_index *idx, const char *name, int64_t value);
