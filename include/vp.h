@@ -185,9 +185,10 @@ vp_status vp_get_profile(vp_index *idx, double *kernel_ms_total, int64_t *launch
  * every vector to its nearest centroid (Eq. 2 as at decode time: fp16 inputs, fp32
  * accumulation, ties to the lowest index) and replaces every centroid by the mean
  * of its members; a cluster without members keeps its centroid.  The sums are
- * exact (64-bit integers in units of 2^-24) and each mean is rounded once to fp16
- * (nearest, ties to even), so equal inputs give bit-identical centroids and, given
- * the memberships, the centroids equal the correctly rounded means.
+ * exact (every fp16 value is a multiple of 2^-24; see the bound on x below) and each
+ * mean is rounded once to fp16 (nearest, ties to even), so equal inputs give
+ * bit-identical centroids and, given the memberships, the centroids equal the
+ * correctly rounded means.
  *   x          device, fp16 [n, d] row-major, 16-byte aligned, finite values;
  *              per cluster and coordinate the sum of |x| must stay below 2^29
  *   centroids  device, fp16 [K, d]: starting centroids in, trained centroids out

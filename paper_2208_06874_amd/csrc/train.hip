@@ -2,13 +2,12 @@
 // settings of section 3.1): Lloyd k-means over recorded hidden vectors and the
 // active set of each cluster as the union of its members' recorded tokens.
 //
-// Assignment reuses the Eq. 2 kernel of the decode path (nearest centroid,
-// ties to the lowest index).  The update is exact: every binary16 value is an
-// integer multiple of 2^-24, so the members of a cluster are summed as 64-bit
-// integers in that unit.  Integer sums do not depend on the order of the
-// additions, which makes the result independent of how the atomics below are
-// served, and the mean sum / count is rounded once, in double precision, to
-// binary16 (nearest, ties to even).  A cluster without members keeps its
+// Memberships are Eq. 2 (nearest centroid, ties to the lowest index), for many vectors as a
+// GEMM.  The update is exact: every binary16 value is an integer multiple of 2^-24, so sums
+// of members, kept in double precision while they stay below 2^29 in magnitude, or as 64-bit
+// integers in that unit where the sums of different threads meet, are exact whatever the
+// order of the additions (and of the atomics), and the mean sum / count is rounded once, in
+// double precision, to binary16 (nearest, ties to even).  A cluster without members keeps its
 // centroid.
 #include <hip/hip_runtime.h>
 #include "vp_kernels.h"
@@ -200,27 +199,30 @@ __global__ __launch_bounds__(256) void kmeans_scatter_kernel(const int32_t *__re
     perm[pos] = (int32_t)r;
 }
 
-// A binary16 bit pattern as an integer count of 2^-24 (finite inputs only).
-__device__ inline long long half_units(uint32_t h)
-{
-    const int expo = (h >> 10) & 0x1f;
-    const long long frac = h & 0x3ff;
-    const long long mag = expo ? ((frac | 0x400) << (expo - 1)) : frac;
-    return (h & 0x8000) ? -mag : mag;
-}
+// Running sums of 8 coordinates.  They are kept in double precision: every binary16 value is
+// a multiple of 2^-24, so while a sum stays below 2^29 in magnitude every addition is exact and
+// the order of the additions does not matter.  Where sums of different threads meet they are
+// added as 64-bit integers in units of 2^-24 (exact conversions), which keeps that true under
+// atomics.
+typedef _Float16 half2t __attribute__((ext_vector_type(2)));
 
-__device__ inline void add_units(long long (&s)[8], const uint4 v)
+__device__ inline void add_units(double (&s)[8], const uint4 v)
 {
     const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-        s[2 * e] += half_units(w[e] & 0xffff);
-        s[2 * e + 1] += half_units(w[e] >> 16);
+        const half2t h = __builtin_bit_cast(half2t, w[e]);
+        s[2 * e] += (double)(float)h[0];
+        s[2 * e + 1] += (double)(float)h[1];
     }
 }
 
-// Sum of the members of cluster blockIdx.x, every `splits`-th one starting at blockIdx.y,
-// over 8 coordinates per thread.
+__device__ inline unsigned long long to_units(double sum) { return (unsigned long long)(long long)(sum * 0x1p24); }
+
+// Sum of the members of cluster blockIdx.x that fall to this workgroup (every `splits`-th one
+// starting at blockIdx.y).  A thread owns one 16-byte piece (8 coordinates) of the vectors; when
+// a vector has fewer than 256 pieces the workgroup's threads form several member lanes that take
+// the workgroup's members in turn.  Eight rows are in flight per thread.
 __global__ __launch_bounds__(256) void kmeans_sum_kernel(const uint4 *__restrict__ X, int pieces,
                                                          const int32_t *__restrict__ perm,
                                                          const int32_t *__restrict__ start, int splits,
@@ -228,21 +230,44 @@ __global__ __launch_bounds__(256) void kmeans_sum_kernel(const uint4 *__restrict
 {
     const int j = blockIdx.x;
     const int m0 = start[j], m1 = start[j + 1];
-    for (int piece = threadIdx.x; piece < pieces; piece += 256) {
-        long long s[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-        int m = m0 + blockIdx.y;
-        for (; m + 3 * splits < m1; m += 4 * splits) {   // four rows in flight
-            uint4 v[4];
+    const int lanes = pieces <= 128 ? 256 / pieces : 1;       // member lanes per workgroup
+    const int ml = lanes > 1 ? threadIdx.x / pieces : 0;       // this thread's member lane
+    __shared__ unsigned long long lsum[128 * 8];
+    if (lanes > 1) {
+        for (int e = threadIdx.x; e < pieces * 8; e += 256) lsum[e] = 0ull;
+        __syncthreads();
+    }
+    const int step = splits * lanes;
+    const int first = m0 + blockIdx.y * lanes + ml;
+    for (int piece = lanes > 1 ? threadIdx.x - ml * pieces : threadIdx.x; piece < pieces && ml < lanes; piece += 256) {
+        double s[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        int m = first;
+        for (; m + 7 * step < m1; m += 8 * step) {
+            int r[8];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) v[u] = X[(size_t)perm[m + u * splits] * pieces + piece];
+            for (int u = 0; u < 8; ++u) r[u] = perm[m + u * step];
+            uint4 v[8];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) add_units(s, v[u]);
+            for (int u = 0; u < 8; ++u) v[u] = X[(size_t)r[u] * pieces + piece];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) add_units(s, v[u]);
         }
-        for (; m < m1; m += splits) add_units(s, X[(size_t)perm[m] * pieces + piece]);
-        if (m0 + (int)blockIdx.y < m1) {
+        for (; m < m1; m += step) add_units(s, X[(size_t)perm[m] * pieces + piece]);
+        if (lanes > 1) {
+            // the member lanes meet in LDS; one global addition per coordinate and workgroup
+            unsigned long long *slot = lsum + (size_t)piece * 8;
 #pragma unroll
-            for (int e = 0; e < 8; ++e)
-                atomicAdd(&acc[((size_t)j * pieces + piece) * 8 + e], (unsigned long long)s[e]);
+            for (int e = 0; e < 8; ++e) atomicAdd(slot + e, to_units(s[e]));
+        } else if (first < m1) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) atomicAdd(&acc[((size_t)j * pieces + piece) * 8 + e], to_units(s[e]));
+        }
+    }
+    if (lanes > 1) {
+        __syncthreads();
+        if (m0 + (int)blockIdx.y * lanes < m1) {
+            for (int e = threadIdx.x; e < pieces * 8; e += 256)
+                atomicAdd(&acc[(size_t)j * pieces * 8 + e], lsum[e]);
         }
     }
 }
@@ -279,6 +304,66 @@ __host__ __device__ inline uint16_t double_to_half_bits(double v)
     if (rem > half || (rem == half && (q & 1))) h += 1;        // a carry moves into the exponent field
     if (h >= 0x7c00) h = 0x7c00;
     return (uint16_t)(sign | h);
+}
+
+// One workgroup per cluster: sums all its members and writes the new centroid at once (no
+// sums in memory, no atomics between workgroups).  Used when there are enough clusters to fill
+// the chip this way; the member lanes of the workgroup meet in LDS.
+__global__ __launch_bounds__(1024) void kmeans_mean_kernel(const uint4 *__restrict__ X, int pieces,
+                                                          const int32_t *__restrict__ perm,
+                                                          const int32_t *__restrict__ start, uint4 *__restrict__ C)
+{
+    const int j = blockIdx.x;
+    const int m0 = start[j], m1 = start[j + 1];
+    if (m0 == m1) return;                                      // no members: the centroid stays
+    constexpr int T = 1024;                                   // threads per workgroup
+    const int lanes = pieces <= T / 2 ? T / pieces : 1;       // member lanes
+    const int ml = lanes > 1 ? threadIdx.x / pieces : 0;
+    __shared__ unsigned long long lsum[(T / 2) * 8];
+    if (lanes > 1) {
+        for (int e = threadIdx.x; e < pieces * 8; e += T) lsum[e] = 0ull;
+        __syncthreads();
+    }
+    const double inv_units = 0x1p-24;
+    const double count = (double)(m1 - m0);
+    for (int piece = lanes > 1 ? threadIdx.x - ml * pieces : threadIdx.x; piece < pieces && ml < lanes; piece += T) {
+        double s[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        int m = m0 + ml;
+        for (; m + 7 * lanes < m1; m += 8 * lanes) {
+            // row numbers first, then all eight rows: written as one expression the loads of a row
+            // number and of its row alternate and every one waits for the one before
+            int r[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) r[u] = perm[m + u * lanes];
+            uint4 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = X[(size_t)r[u] * pieces + piece];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) add_units(s, v[u]);
+        }
+        for (; m < m1; m += lanes) add_units(s, X[(size_t)perm[m] * pieces + piece]);
+        if (lanes > 1) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) atomicAdd(lsum + (size_t)piece * 8 + e, to_units(s[e]));
+        } else {
+            uint32_t h[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) h[e] = double_to_half_bits(s[e] / count);
+            C[(size_t)j * pieces + piece] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16),
+                                                       h[6] | (h[7] << 16));
+        }
+    }
+    if (lanes > 1) {
+        __syncthreads();
+        for (int piece = threadIdx.x; piece < pieces; piece += T) {
+            uint32_t h[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                h[e] = double_to_half_bits((double)(long long)lsum[piece * 8 + e] * inv_units / count);
+            C[(size_t)j * pieces + piece] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16),
+                                                       h[6] | (h[7] << 16));
+        }
+    }
 }
 
 // New centroids from the sums; the sums are cleared for the next iteration.
@@ -441,6 +526,12 @@ void vpk_kmeans_bucket(const int32_t *assign, long n, const int32_t *counts, int
 void vpk_kmeans_update(const void *X, int d, const int32_t *perm, const int32_t *start, const int32_t *counts, int K,
                        int splits, void *acc, void *C, hipStream_t st)
 {
+    if (K >= 256) {
+        // enough clusters to fill the chip with one workgroup each: no sums in memory at all
+        hipLaunchKernelGGL(kmeans_mean_kernel, dim3(K), dim3(1024), 0, st, (const uint4 *)X, d / 8, perm, start,
+                           (uint4 *)C);
+        return;
+    }
     hipLaunchKernelGGL(kmeans_sum_kernel, dim3(K, splits), dim3(256), 0, st, (const uint4 *)X, d / 8, perm, start,
                        splits, (unsigned long long *)acc);
     const size_t e = (size_t)K * d;

@@ -81,7 +81,7 @@ vp_status vp_kmeans(const void *x, int64_t n, int32_t d, int32_t K, int32_t iter
     int32_t *start = (int32_t *)(ws + L.start), *cursor = (int32_t *)(ws + L.cursor), *perm = (int32_t *)(ws + L.perm);
     void *acc = ws + L.acc;
     // clusters x splits workgroups of the summing kernel: a few thousand
-    const int splits = std::max(1, std::min(64, 4096 / K));
+    const int splits = std::max(1, std::min(64, 2048 / K));
 
     vpk_fill_u32(acc, (size_t)K * d * 2, 0u, st);
     for (int it = 0; it <= iters; ++it) {

@@ -52,7 +52,8 @@ def _mixture(cfg_name, n, **scale):
 
 @pytest.mark.parametrize("name,n,scale", [("tiny", 4096, {}), ("tiny", 1000, dict(d=72, K=5)),
                                           ("mid", 3000, dict(d=264, K=77)), ("mid", 5000, dict(K=77)),
-                                          ("skewed", 4500, dict(K=50))])
+                                          ("skewed", 4500, dict(K=50)), ("tiny", 6000, dict(K=300)),
+                                          ("mid", 6000, dict(K=260, d=264)), ("mid", 5000, dict(K=256, d=2056))])
 def test_lloyd_steps_match_the_oracle(oracle, name, n, scale):
     cfg, X, _q, C0 = _mixture(name, n, **scale)
     Cb = C0.view(np.uint16).copy()
