@@ -197,7 +197,13 @@ def main():
         mode = int(ws[:64].view(torch.int32)[7].item())
         index.set_option("dispatch", 0)
         result["with_dispatch"] = {"rows_per_s": N / (ms_disp * 1e-3), "ms_per_step": ms_disp,
-                                   "planner_chose": "masked full projection" if mode == 1 else "per-cluster slabs"}
+                                   "planner_chose": "masked full projection" if mode == 1 else "per-cluster slabs",
+                                   "speedup_vs_slabs": ms_step / ms_disp}
+        if mode == 1:
+            # a dense contraction over the whole vocabulary: priced against the matrix cores, whole step
+            tf = 2.0 * N * d * cfg.V / (ms_disp * 1e-3) / 1e12
+            result["with_dispatch"]["roofline"] = {"bound": "mfma", "achieved": tf, "peak": 2500.0, "unit": "TFLOP/s",
+                                                   "frac": tf / 2500.0}
 
     if not args.no_union:
         # the paper's own batched form (union of the active sets of the batch), whole call timed
