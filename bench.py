@@ -29,6 +29,77 @@ MEASURED_TRAFFIC_BYTES = {
 }
 
 
+def cluster_sweep(args, dev):
+    """Synthetic analogue of the hyper-parameter study of section 3.5: number of centroids x recorded likely
+    tokens per training vector -> size of the active sets, how often the full projection's best token lies in
+    the row's active set, and the time of the clustered projection of a decode batch (8 sentences x beam 8)."""
+    import numpy as np
+    import torch
+
+    import paper_2208_06874_amd as P
+    from paper_2208_06874_amd import workloads as wl
+
+    cfg = wl.CONFIGS[args.workload]
+    N, k, n_tr, T_max = 64, 1, args.train_vectors, 5
+    W, b, C_true = wl.make_model(cfg)
+    Wt, bt = torch.from_numpy(W).to(dev), torch.from_numpy(b).to(dev)
+    Xn, _q, _c0 = wl.training_set(cfg, C_true, n_tr)
+    Xt = torch.from_numpy(Xn).to(dev)
+    boot = P.vp_build(Wt, bt, Xt[:1].contiguous(), np.array([0, 1], np.int64), np.array([0], np.int32), k_max=T_max)
+    top = torch.empty((n_tr, T_max), dtype=torch.int32, device=dev)
+    for r0 in range(0, n_tr, 32768):               # recording: top-5 of the full projection, once
+        r1 = min(n_tr, r0 + 32768)
+        ids, _ = boot.project_full(Xt[r0:r1], T_max)
+        top[r0:r1] = ids
+    batches = [torch.from_numpy(wl.make_rows(cfg, C_true, N=N, stream=60 + i)[0]).to(dev) for i in range(8)]
+    full_best = [boot.project_full(h, 1)[0][:, 0].clone() for h in batches]
+
+    def time_ms(fn, steps=40, warmup=8):
+        for i in range(warmup):
+            fn(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            fn(i)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+    wsf = boot.workspace(N)
+    ms_full = time_ms(lambda i: boot.project_full(batches[i % 8], k, workspace=wsf))
+    rows = []
+    rng = np.random.default_rng(220806874 + 1000 * cfg.index + 77)
+    for K in (100, 200, 500, 1000, 1300, 2000):
+        pick = np.sort(rng.choice(n_tr, size=K, replace=False))
+        C0 = Xt[torch.from_numpy(pick).to(dev)].contiguous()
+        Ct = C0.clone()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        assign, counts = P.vp_kmeans(Xt, Ct, 20)
+        torch.cuda.synchronize()
+        ms_train = (time.perf_counter() - t0) * 1e3
+        keep = torch.nonzero(counts > 0)[:, 0]
+        for T in (1, 3, 5):
+            off, ids = P.vp_active_sets(top[:, :T].contiguous(), assign, K, cfg.V)
+            off_h, ids_h, keep_h = off.cpu().numpy(), ids.cpu().numpy(), keep.cpu().numpy()
+            sizes = np.diff(off_h)[keep_h]
+            ids_k = np.concatenate([ids_h[off_h[j]:off_h[j + 1]] for j in keep_h])
+            off_k = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+            index = P.vp_build(Wt, bt, Ct[keep].contiguous(), off_k, ids_k, k_max=8)
+            ws = index.workspace(N)
+            ms = time_ms(lambda i: index.project(batches[i % 8], k, workspace=ws))
+            hit = float(np.mean([(index.project(h, 1, workspace=ws)[0][:, 0] == fb).float().mean().item()
+                                 for h, fb in zip(batches, full_best)]))
+            rows.append({"centroids": K, "clusters_with_members": int(len(keep_h)), "recorded_tokens": T,
+                         "mean_active_fraction": float(sizes.mean() / cfg.V),
+                         "max_active_fraction": float(sizes.max() / cfg.V), "ms_per_step": ms,
+                         "rows_per_s": N / (ms * 1e-3), "speedup_vs_full": ms_full / ms,
+                         "top1_in_active_set": hit, "kmeans_20_iterations_ms": ms_train})
+            del index, ws
+    return {"metric": "cluster sweep: centroids x recorded tokens -> active fraction, rows/s (N=64, top-1)",
+            "workload": cfg.name, "train_vectors": n_tr, "full_vocab_ms_per_step": ms_full, "data": "synthetic",
+            "rows": rows}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -43,6 +114,9 @@ def main():
     ap.add_argument("--no-union", action="store_true")
     ap.add_argument("--no-dispatch", action="store_true")
     ap.add_argument("--no-training", action="store_true")
+    ap.add_argument("--cluster-sweep", action="store_true",
+                    help="instead of the benchmark: train clusters for a grid of centroid counts and recorded tokens "
+                         "per vector (a synthetic analogue of the paper's section 3.5) and time vp_project on each")
     ap.add_argument("--train-vectors", type=int, default=131072, help="recorded vectors of the cluster-training leg")
     ap.add_argument("--option", action="append", default=[], help="library option name=value")
     ap.add_argument("--graph", action="store_true",
@@ -66,6 +140,9 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
+    if args.cluster_sweep:
+        print(json.dumps(cluster_sweep(args, dev)))
+        return
     cfg = wl.CONFIGS[args.workload]
     N = args.rows or cfg.N
     k = args.topk or cfg.k

@@ -229,3 +229,17 @@ def test_trained_index_end_to_end(oracle):
     print("trained index:", st, sf, "top-1 agreement with the full projection %.3f" % hit,
           "clusters kept %d of %d," % (len(keep), cfg.K), "mean active set %.0f of %d" % (len(ids_h) / len(keep), cfg.V))
     assert hit >= 0.6
+
+
+def test_cluster_sweep_of_the_benchmark_runs():
+    """bench.py --cluster-sweep (synthetic analogue of the paper's section 3.5) on the tiny workload."""
+    torch = _torch()
+    import argparse
+    import bench
+    out = bench.cluster_sweep(argparse.Namespace(workload="tiny", train_vectors=8192), torch.device("cuda:0"))
+    rows = out["rows"]
+    assert len(rows) == 18 and all(r["ms_per_step"] > 0 and 0 < r["mean_active_fraction"] <= 1 for r in rows)
+    # more recorded tokens per vector can only enlarge the active sets and the chance to hold the best token
+    for a, b, c in zip(rows[0::3], rows[1::3], rows[2::3]):
+        assert a["mean_active_fraction"] <= b["mean_active_fraction"] <= c["mean_active_fraction"]
+        assert a["top1_in_active_set"] <= b["top1_in_active_set"] + 1e-9 <= c["top1_in_active_set"] + 2e-9
