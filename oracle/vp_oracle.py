@@ -15,7 +15,7 @@ import subprocess
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRCS = [os.path.join(_HERE, "vp_oracle.c"), os.path.join(_HERE, "vp_train_oracle.c")]
+_SRCS = [os.path.join(_HERE, f) for f in ("vp_oracle.c", "vp_train_oracle.c", "vp_search_oracle.c")]
 _SO = os.path.join(_HERE, "libvp_oracle.so")
 _lib = None
 
@@ -267,3 +267,21 @@ def active_sets(top, assign, K: int, V: int):
     ids = np.empty(int(total), np.int32)
     _load().vpo_active_sets(*args, _p(ids))
     return off, ids
+
+
+# ------------------------------------------------------------------ toy search consumer
+def beam_step(cand_ids, cand_logp, scores, B: int):
+    """One beam-search step.  cand_ids int32 [S*B, k], cand_logp float32 [S*B, k], scores float32 [S*B].
+    Returns (out_scores float32 [S*B], out_parent int32 [S*B], out_token int32 [S*B])."""
+    cand_ids = np.ascontiguousarray(cand_ids, np.int32)
+    cand_logp = np.ascontiguousarray(cand_logp, np.float32)
+    scores = np.ascontiguousarray(scores, np.float32)
+    n, k = cand_ids.shape
+    assert n % B == 0 and cand_logp.shape == (n, k) and scores.shape == (n,)
+    S = n // B
+    out_s = np.empty(n, np.float32)
+    out_p = np.empty(n, np.int32)
+    out_t = np.empty(n, np.int32)
+    _load().vpo_beam_step(_p(cand_ids), _p(cand_logp), _p(scores), ctypes.c_int(S), ctypes.c_int(B), ctypes.c_int(k),
+                          _p(out_s), _p(out_p), _p(out_t))
+    return out_s, out_p, out_t
