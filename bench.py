@@ -114,6 +114,7 @@ def main():
     ap.add_argument("--no-union", action="store_true")
     ap.add_argument("--no-dispatch", action="store_true")
     ap.add_argument("--no-training", action="store_true")
+    ap.add_argument("--no-decode-loop", action="store_true")
     ap.add_argument("--cluster-sweep", action="store_true",
                     help="instead of the benchmark: train clusters for a grid of centroid counts and recorded tokens "
                          "per vector (a synthetic analogue of the paper's section 3.5) and time vp_project on each")
@@ -351,6 +352,39 @@ def main():
             "membership_pass_ms": ms0, "record_top%d_ms" % T: ms_rec, "active_sets_ms": ms_sets,
             "active_set_entries": int(a_ids.numel()), "empty_clusters": int((counts == 0).sum().item())}
         del Xt, kws, top, wst
+
+    if not args.no_decode_loop:
+        # toy search consumer: 8 sentences x beam 8, every step = clustered projection (top-8) + one beam
+        # step + the survivors' rows carried to their new slots (a gather; the rows stand in for a decoder)
+        S_d, B_d, k_d, T_d = 8, 8, 8, 32
+        n_d = S_d * B_d
+        pool = torch.from_numpy(wl.make_rows(cfg, C, N=n_d * 4, stream=90)[0]).to(dev)
+        d_ids = torch.empty((n_d, k_d), dtype=torch.int32, device=dev)
+        d_logp = torch.empty((n_d, k_d), dtype=torch.float32, device=dev)
+        d_g = torch.empty((n_d,), dtype=torch.int32, device=dev)
+        wsd = index.workspace(n_d)
+        slot0 = (torch.arange(n_d, device=dev) // B_d) * B_d
+        first = torch.full((n_d,), float("-inf"), device=dev)
+        first[::B_d] = 0.0
+
+        def decode(steps):
+            scores, rows = first.clone(), pool[:n_d]
+            for t in range(steps):
+                index.project(rows, k_d, out_ids=d_ids, out_logp=d_logp, out_cluster=d_g, workspace=wsd)
+                scores, parent, _tok = P.vp_beam_step(d_ids, d_logp, scores, B_d)
+                fresh = pool[(t % 4) * n_d:(t % 4 + 1) * n_d]
+                rows = fresh[slot0 + parent.clamp(min=0)]
+            return scores
+
+        decode(4)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        decode(T_d)
+        torch.cuda.synchronize()
+        ms_dec = (time.perf_counter() - t0) * 1e3 / T_d
+        result["decode_loop"] = {"sentences": S_d, "beam": B_d, "topk": k_d, "steps": T_d, "ms_per_step": ms_dec,
+                                 "rows_per_s": n_d / (ms_dec * 1e-3),
+                                 "note": "vp_project + vp_beam_step + a gather of the next rows per step"}
 
     if not args.no_cpu_baseline:
         # the CPU oracle, as it stands, on the first batch of the same workload

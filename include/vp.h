@@ -222,6 +222,24 @@ vp_status vp_active_sets(const int32_t *top_ids, const int32_t *assign, int64_t 
                          int32_t V, int64_t *cand_offsets, int32_t *cand_ids, int64_t capacity,
                          int64_t *total, void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* ---- Toy search consumer (section 2.1: the sorted probabilities feed beam search,
+ * greedy search or sampling) ----
+ * One beam-search step for S sentences of B hypotheses each.  Row s * B + b of the
+ * inputs belongs to hypothesis b of sentence s.
+ *   cand_ids    device, int32 [S * B, k]: the projection's out_ids (entries < 0: none)
+ *   cand_logp   device, fp32 [S * B, k]: the projection's out_logp
+ *   scores      device, fp32 [S * B]: accumulated log-probability of every hypothesis
+ *               (-inf: dead; a search starts with 0 for hypothesis 0 and -inf elsewhere)
+ *   out_scores  device, fp32 [S * B]: the B largest sums scores[b] + cand_logp[b][j] of
+ *               each sentence, descending; equal sums in order of b, then j
+ *   out_parent  device, int32 [S * B]: the hypothesis b each one continues
+ *   out_token   device, int32 [S * B]: the token that continues it
+ * Missing hypotheses (fewer than B finite sums): -inf, -1, -1.  B = 1 is greedy search.
+ * Limits: B * k <= 2048, k <= 32.  Only enqueues one kernel. */
+vp_status vp_beam_step(const int32_t *cand_ids, const float *cand_logp, const float *scores, int32_t S,
+                       int32_t B, int32_t k, float *out_scores, int32_t *out_parent, int32_t *out_token,
+                       void *hip_stream);
+
 /* Host utility: v rounded to fp16 bits exactly as vp_kmeans rounds a mean. */
 uint16_t vp_round_to_half(double v);
 

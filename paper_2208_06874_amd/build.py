@@ -13,7 +13,7 @@ BUILD = os.path.join(ROOT, "_build")
 LIB = os.path.join(HERE, "libvp.so")
 
 SOURCES = ["vp_api.hip", "build_kernels.hip", "centroid.hip", "plan.hip", "project.hip", "merge.hip", "union.hip",
-           "train.hip", "train_api.hip", "project_gemm.hip"]
+           "train.hip", "train_api.hip", "project_gemm.hip", "search.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

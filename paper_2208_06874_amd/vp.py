@@ -23,7 +23,7 @@ EXPORTS = ("vp_build_bytes", "vp_build", "vp_get_info", "vp_set_option", "vp_wor
            "vp_project", "vp_project_full", "vp_union_workspace_bytes", "vp_project_union",
            "vp_project_debug_logits", "vp_get_profile", "vp_destroy", "vp_last_error",
            "vp_kmeans_workspace_bytes", "vp_kmeans", "vp_active_sets_workspace_bytes", "vp_active_sets",
-           "vp_round_to_half")
+           "vp_round_to_half", "vp_beam_step")
 
 
 class VpError(RuntimeError):
@@ -95,6 +95,8 @@ def lib():
         L.vp_active_sets.restype = ctypes.c_int
         L.vp_active_sets.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp, vp,
                                      ctypes.c_int64, ctypes.POINTER(ctypes.c_int64), vp, ctypes.c_size_t, vp]
+        L.vp_beam_step.restype = ctypes.c_int
+        L.vp_beam_step.argtypes = [vp, vp, vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp, vp, vp, vp]
         L.vp_round_to_half.restype = ctypes.c_uint16
         L.vp_round_to_half.argtypes = [ctypes.c_double]
         _lib = L
@@ -362,3 +364,20 @@ def vp_kmeans_workspace_bytes(n: int, d: int, K: int) -> int:
 
 def vp_active_sets_workspace_bytes(K: int, V: int) -> int:
     return lib().vp_active_sets_workspace_bytes(K, V)
+
+
+def vp_beam_step(cand_ids, cand_logp, scores, B: int, out=None, stream=None):
+    """vp_beam_step: returns (out_scores fp32 [S*B], out_parent int32 [S*B], out_token int32 [S*B])."""
+    import torch
+    assert cand_ids.is_cuda and cand_ids.dtype == torch.int32 and cand_ids.is_contiguous() and cand_ids.dim() == 2
+    assert cand_logp.dtype == torch.float32 and cand_logp.is_contiguous() and cand_logp.shape == cand_ids.shape
+    assert scores.dtype == torch.float32 and scores.is_contiguous() and scores.shape == (cand_ids.shape[0],)
+    n, k = cand_ids.shape
+    assert n % B == 0
+    if out is None:
+        out = (torch.empty(n, dtype=torch.float32, device=cand_ids.device),
+               torch.empty(n, dtype=torch.int32, device=cand_ids.device),
+               torch.empty(n, dtype=torch.int32, device=cand_ids.device))
+    _check(lib().vp_beam_step(cand_ids.data_ptr(), cand_logp.data_ptr(), scores.data_ptr(), n // B, B, k,
+                              out[0].data_ptr(), out[1].data_ptr(), out[2].data_ptr(), _stream(stream)))
+    return out

@@ -32,7 +32,7 @@ def test_python_binding_has_the_same_names():
     for n in ("vp_build", "vp_project", "vp_project_full", "vp_project_debug_logits", "vp_workspace_bytes",
               "vp_set_option", "vp_get_info", "vp_get_profile", "vp_destroy", "vp_last_error", "vp_project_union",
               "vp_union_workspace_bytes", "vp_kmeans", "vp_kmeans_workspace_bytes", "vp_active_sets",
-              "vp_active_sets_workspace_bytes", "vp_round_to_half"):
+              "vp_active_sets_workspace_bytes", "vp_round_to_half", "vp_beam_step"):
         assert callable(getattr(P, n))
 
 
@@ -135,6 +135,14 @@ def test_training_calls_reject_bad_arguments_on_the_host():
                             None) == vp.VP_ERR_INVALID_ARG
     assert L.vp_active_sets(0x1000, 0x1000, 5, 3, 4, 100, 0x1000, 0x1000, 8, ctypes.byref(tot), 0x1000, 16,
                             None) == vp.VP_ERR_WORKSPACE
+
+
+def test_beam_step_rejects_bad_arguments_on_the_host():
+    L = vp.lib()
+    assert L.vp_beam_step(None, None, None, 2, 4, 4, None, None, None, None) == vp.VP_ERR_INVALID_ARG
+    assert L.vp_beam_step(0x1000, 0x1000, 0x1000, 2, 128, 32, 0x1000, 0x1000, 0x1000, None) == vp.VP_ERR_UNSUPPORTED
+    assert L.vp_beam_step(0x1000, 0x1000, 0x1000, 2, 0, 4, 0x1000, 0x1000, 0x1000, None) == vp.VP_ERR_UNSUPPORTED
+    assert L.vp_beam_step(None, None, None, 0, 4, 4, None, None, None, None) == vp.VP_OK   # no sentences: no-op
 
 
 def test_round_to_half_is_the_library_cast():
