@@ -340,6 +340,31 @@ __global__ __launch_bounds__(VP_WG_THREADS) void project_kernel(
                                         dbg_row_off, none);
 }
 
+// The same with 16 loads in flight per wavefront, for k-extents whose staged rows leave room
+// for fewer than four workgroups per CU (d_pad >= 1280): fewer wavefronts, deeper queues
+// (skewed workload, d = 1536: 68.4 % -> 69.9 % of the HBM peak).
+__global__ __launch_bounds__(VP_WG_THREADS) void project_pf16_kernel(
+    VpSlabSet set, const uint4 *__restrict__ hidden, int d, const int32_t *__restrict__ perm,
+    const VpItem *__restrict__ items, const VpPlanHeader *__restrict__ hdr, int k, int rstar,
+    float *__restrict__ partials, unsigned int *__restrict__ floors, float *__restrict__ dbg_logits,
+    const int64_t *__restrict__ dbg_row_off)
+{
+    const VpItem probe = items[blockIdx.x];
+    const int total_items = hdr->total_items;
+    const int tpw = hdr->tiles_per_wave;
+    if (hdr->mode != 0) return;
+    const int it = item_of_workgroup(hdr);
+    if (it < 0 || it >= total_items) return;
+    const VpItem item = it == (int)blockIdx.x ? probe : items[it];
+    const VpMaskInfo none = {nullptr, nullptr, 0};
+    if (item.shared)
+        project_item<false, 1, 16, false>(set, hidden, d, perm, item, it, tpw, k, rstar, partials, floors, dbg_logits,
+                                          dbg_row_off, none);
+    else
+        project_item<true, 1, 16, false>(set, hidden, d, perm, item, it, tpw, k, rstar, partials, floors, dbg_logits,
+                                         dbg_row_off, none);
+}
+
 // Items of up to 32 rows, all sharing their tiles with other row groups: single-bucket
 // projections (full, union) of more than 16 rows.
 __global__ __launch_bounds__(VP_WG_THREADS) void project2_kernel(
@@ -397,6 +422,9 @@ hipError_t vpk_project_prepare()
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(project2_kernel),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e == hipSuccess)
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(project_pf16_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e == hipSuccess)
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(project_masked_kernel),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     return e;
@@ -412,7 +440,14 @@ void vpk_project(const VpSlabSet &set, const void *hidden, int d, const int32_t 
                            partials, floors, dbg_logits, dbg_row_off);
         return;
     }
-    hipLaunchKernelGGL(project_kernel, dim3(grid_items), dim3(VP_WG_THREADS), vpk_project_lds_bytes(set.kt, k, 1), st,
+    const size_t lds = vpk_project_lds_bytes(set.kt, k, 1);
+    if (set.kt % 16 == 0 && lds * 4 > 160 * 1024) {
+        hipLaunchKernelGGL(project_pf16_kernel, dim3(grid_items), dim3(VP_WG_THREADS), lds, st, set,
+                           (const uint4 *)hidden, d, perm, items, hdr, k, rstar, partials, floors, dbg_logits,
+                           dbg_row_off);
+        return;
+    }
+    hipLaunchKernelGGL(project_kernel, dim3(grid_items), dim3(VP_WG_THREADS), lds, st,
                        set, (const uint4 *)hidden, d, perm, items, hdr, k, rstar, partials, floors, dbg_logits,
                        dbg_row_off);
 }
