@@ -519,3 +519,49 @@ def test_many_rows_many_clusters(oracle):
     H = _rows(r, C, 9000)
     ids_g, logp_g, g = B.project(H, 2)
     print("many", pu.check_projection(oracle, W, b, C, off, ids, H, 2, ids_g, logp_g, g))
+
+
+def test_limits_of_one_call(oracle):
+    """The largest shapes the header allows: N = 65536 rows in one call; d = 4096 with K = 4096 clusters.
+    (Not all three at once: the oracle's Eq. 2 alone would be 10^12 double-precision products.)"""
+    r, W, b, C = _small_model(12, 64, 1500, 64)
+    off, ids = _random_lists(r, 64, 1500, 17, 200)
+    B = Built(W, b, C, off, ids, k_max=2)
+    H = _rows(r, C, 65536)
+    print("limits: 65536 rows", flush=True)
+    ids_g, logp_g, g = B.project(H, 2)
+    print("limits rows", pu.check_projection(oracle, W, b, C, off, ids, H, 2, ids_g, logp_g, g), flush=True)
+    f_ids, f_logp = B.project_full(H[:4096], 2)
+    pu.check_full(oracle, W, b, H[:4096], 2, f_ids, f_logp)
+
+    r, W, b, C = _small_model(14, 4096, 1500, 4096)
+    off, ids = _random_lists(r, 4096, 1500, 17, 40)
+    B = Built(W, b, C, off, ids, k_max=2)
+    H = _rows(r, C, 70)
+    print("limits: d 4096, K 4096", flush=True)
+    ids_g, logp_g, g = B.project(H, 2)
+    print("limits d K", pu.check_projection(oracle, W, b, C, off, ids, H, 2, ids_g, logp_g, g), flush=True)
+    f_ids, f_logp = B.project_full(H, 2)
+    pu.check_full(oracle, W, b, H, 2, f_ids, f_logp)
+
+
+def test_largest_topk_on_the_many_row_kernel(oracle):
+    """top-32 through the 64-row kernel (full projection, union form, masked dispatch) with ragged row counts."""
+    r, W, b, C = _small_model(13, 512, 3000, 6)
+    off, ids = _random_lists(r, 6, 3000, 200, 900)
+    B = Built(W, b, C, off, ids, k_max=32)
+    for N in (33, 100, 129):
+        H = _rows(r, C, N)
+        f_ids, f_logp = B.project_full(H, 32)
+        pu.check_full(oracle, W, b, H, 32, f_ids, f_logp)
+        u_ids, u_logp, u_g, u_n = B.project_union(H, 32)
+        pu.check_union(oracle, W, b, C, off, ids, H, 32, u_ids, u_logp, u_g, u_n)
+        B.index.set_option("dispatch", 1)
+        B.index.set_option("cost_bw_slab_gbs", 1)      # force the masked projection
+        try:
+            m_ids, m_logp, m_g = B.project(H, 32)
+            assert _planner_mode(B.index, N) == 1
+        finally:
+            B.index.set_option("cost_bw_slab_gbs", 6800)
+            B.index.set_option("dispatch", 0)
+        pu.check_projection(oracle, W, b, C, off, ids, H, 32, m_ids, m_logp, m_g)
