@@ -4,8 +4,9 @@
 //
 // As in the paper, the union is formed with a boolean list over the vocabulary
 // (bit-packed here): it starts all zero, threads switch on the bits of every
-// active token of every predicted cluster, and a prefix scan over the list
-// yields the reduced column set U in ascending order.  The columns of U are
+// active token of every predicted cluster (by OR-ing the clusters' membership
+// bit lists), and a prefix scan over the list yields the reduced column set U in
+// ascending order.  The columns of U are
 // then gathered from the packed copy of W into a slab in the workspace, and
 // the projection / log-softmax / top-k kernels run on that slab with all rows
 // in one bucket, so every row is normalised over U (tokens outside U are at
@@ -56,70 +57,90 @@ __global__ __launch_bounds__(UNION_THREADS) void union_prepare_kernel(
     if (tid == 0) uh->n_occ = n_occ;
 }
 
-// Switches on the bits of the active tokens of every occupied cluster.
-__global__ __launch_bounds__(256) void union_flag_kernel(
-    const int32_t *__restrict__ occ, const VpUnionHeader *__restrict__ uh, const int32_t *__restrict__ tile_off,
-    const int32_t *__restrict__ n_cand, const int32_t *__restrict__ ids, int chunk, unsigned int *__restrict__ mask)
+// Switches on the bits of the active tokens of every occupied cluster: the index keeps one
+// membership bit list per cluster, so the boolean list is the OR of the occupied clusters'
+// lists.  A thread owns one 32-bit word; blockIdx.y splits the clusters.
+constexpr int UNION_OR_SPLIT = 8;
+constexpr int UNION_BLOCK_WORDS = 256;   // words of the boolean list per workgroup of the scan kernels
+
+__global__ __launch_bounds__(256) void union_flag_kernel(const int32_t *__restrict__ occ,
+                                                         const VpUnionHeader *__restrict__ uh,
+                                                         const uint32_t *__restrict__ bitmaps, int bm_words,
+                                                         int mask_words, unsigned int *__restrict__ mask)
 {
-    if ((int)blockIdx.x >= uh->n_occ) return;
-    const int j = occ[blockIdx.x];
-    const int n = n_cand[j];
-    const int32_t *list = ids + (size_t)tile_off[j] * VP_TILE_ITEMS;
-    const int c1 = min(n, (int)(blockIdx.y + 1) * chunk);
-    for (int c = blockIdx.y * chunk + threadIdx.x; c < c1; c += blockDim.x) {
-        const int v = list[c];
-        const unsigned int bit = 1u << (v & 31);
-        if (!(mask[v >> 5] & bit)) atomicOr(&mask[v >> 5], bit);
+    const int w = blockIdx.x * 256 + threadIdx.x;
+    if (w >= mask_words) return;
+    const int n_occ = uh->n_occ;
+    unsigned int acc = 0;
+    int c = blockIdx.y;
+    for (; c + 3 * UNION_OR_SPLIT < n_occ; c += 4 * UNION_OR_SPLIT) {   // four lists in flight
+        const int j0 = occ[c], j1 = occ[c + UNION_OR_SPLIT], j2 = occ[c + 2 * UNION_OR_SPLIT],
+                  j3 = occ[c + 3 * UNION_OR_SPLIT];
+        const unsigned int b0 = bitmaps[(size_t)j0 * bm_words + w], b1 = bitmaps[(size_t)j1 * bm_words + w],
+                           b2 = bitmaps[(size_t)j2 * bm_words + w], b3 = bitmaps[(size_t)j3 * bm_words + w];
+        acc |= (b0 | b1) | (b2 | b3);
     }
+    for (; c < n_occ; c += UNION_OR_SPLIT) acc |= bitmaps[(size_t)occ[c] * bm_words + w];
+    if (acc) atomicOr(&mask[w], acc);
 }
 
-// Prefix scan over the boolean list -> U (ascending, padded with -1 to whole
-// groups of 16), its size, and the plan of the projection over U.
+// Prefix scan over the boolean list in three steps: set bits per block of the list, scan of
+// the block counts (with the plan of the projection over U), and the ascending ids.
+__global__ __launch_bounds__(256) void union_count_kernel(const unsigned int *__restrict__ mask, int mask_words,
+                                                          int32_t *__restrict__ bsum)
+{
+    __shared__ int part[4];
+    const int w = blockIdx.x * UNION_BLOCK_WORDS + threadIdx.x;
+    int c = w < mask_words ? __popc(mask[w]) : 0;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) c += __shfl_xor(c, off);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = c;
+    __syncthreads();
+    if (threadIdx.x == 0) bsum[blockIdx.x] = part[0] + part[1] + part[2] + part[3];
+}
+
 __global__ __launch_bounds__(UNION_THREADS) void union_compact_kernel(
-    const unsigned int *__restrict__ mask, int mask_words, int V, int N, int rpi, int target_items, int min_items,
-    int max_items, int32_t *__restrict__ uids, VpUnionHeader *__restrict__ uh, int32_t *__restrict__ out_union_size,
+    int32_t *__restrict__ bsum, int blocks, int N, int rpi, int target_items, int min_items, int max_items,
+    int32_t *__restrict__ uids, VpUnionHeader *__restrict__ uh, int32_t *__restrict__ out_union_size,
     int32_t *__restrict__ perm, VpRowPlan *__restrict__ rowplan, unsigned int *__restrict__ floors,
     VpItem *__restrict__ items, VpPlanHeader *__restrict__ hdr)
 {
     __shared__ int wsum[UNION_THREADS / 64 + 1];
-    __shared__ int total_s;
+    __shared__ int carry_s;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int per = (mask_words + UNION_THREADS - 1) / UNION_THREADS;
-    const int w0 = min(tid * per, mask_words), w1 = min(w0 + per, mask_words);
-    int cnt = 0;
-    for (int w = w0; w < w1; ++w) cnt += __popc(mask[w]);
-    // exclusive scan of the per-thread counts
-    int inc = cnt;
+    if (tid == 0) carry_s = 0;
+    __syncthreads();
+    // exclusive scan of the block counts, in place
+    for (int base = 0; base < blocks; base += UNION_THREADS) {
+        const int b = base + tid;
+        const int v = b < blocks ? bsum[b] : 0;
+        int inc = v;
 #pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const int up = __shfl_up(inc, off);
-        if (lane >= off) inc += up;
-    }
-    if (lane == 63) wsum[wave] = inc;
-    __syncthreads();
-    if (tid == 0) {
-        int run = 0;
-        for (int w = 0; w < UNION_THREADS / 64; ++w) {
-            const int t = wsum[w];
-            wsum[w] = run;
-            run += t;
+        for (int off = 1; off < 64; off <<= 1) {
+            const int up = __shfl_up(inc, off);
+            if (lane >= off) inc += up;
         }
-        total_s = run;
-    }
-    __syncthreads();
-    int pos = wsum[wave] + inc - cnt;
-    const int nU = total_s;
-    for (int w = w0; w < w1; ++w) {
-        unsigned int bits = mask[w];
-        while (bits) {
-            const int b = __ffs(bits) - 1;
-            bits &= bits - 1;
-            uids[pos++] = w * 32 + b;
+        if (lane == 63) wsum[wave] = inc;
+        __syncthreads();
+        if (tid == 0) {
+            int run = carry_s;
+            for (int w = 0; w < UNION_THREADS / 64; ++w) {
+                const int t = wsum[w];
+                wsum[w] = run;
+                run += t;
+            }
+            wsum[UNION_THREADS / 64] = run;
         }
+        __syncthreads();
+        if (b < blocks) bsum[b] = wsum[wave] + inc - v;
+        __syncthreads();
+        if (tid == 0) carry_s = wsum[UNION_THREADS / 64];
+        __syncthreads();
     }
+    const int nU = carry_s;
     const int tiles = (nU + VP_TILE_ITEMS - 1) / VP_TILE_ITEMS;
-    for (int c = nU + tid; c < tiles * VP_TILE_ITEMS; c += UNION_THREADS) uids[c] = -1;
+    for (int c = nU + tid; c < tiles * VP_TILE_ITEMS; c += UNION_THREADS) uids[c] = -1;   // pad the last group
     if (tid == 0) {
         uh->n_union = nU;
         uh->tiles = tiles;
@@ -127,6 +148,32 @@ __global__ __launch_bounds__(UNION_THREADS) void union_compact_kernel(
     }
     vp_plan_single_bucket(N, nU, tiles, rpi, target_items, min_items, max_items, perm, rowplan, floors, items, hdr,
                           nullptr, tid, UNION_THREADS);
+}
+
+// U in ascending order: every block of the list writes its ids behind those of the blocks before it.
+__global__ __launch_bounds__(256) void union_emit_kernel(const unsigned int *__restrict__ mask, int mask_words,
+                                                         const int32_t *__restrict__ boff, int32_t *__restrict__ uids)
+{
+    __shared__ int part[4];
+    const int w = blockIdx.x * UNION_BLOCK_WORDS + threadIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    unsigned int bits = w < mask_words ? mask[w] : 0u;
+    const int c = __popc(bits);
+    int inc = c;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int up = __shfl_up(inc, off);
+        if (lane >= off) inc += up;
+    }
+    if (lane == 63) part[wave] = inc;
+    __syncthreads();
+    int pos = boff[blockIdx.x] + inc - c;
+    for (int x = 0; x < wave; ++x) pos += part[x];
+    while (bits) {
+        const int b = __ffs(bits) - 1;
+        bits &= bits - 1;
+        uids[pos++] = w * 32 + b;
+    }
 }
 
 // Gathers the columns of U from the packed copy of W into the union slab (same
@@ -165,21 +212,25 @@ void vpk_union_mark(const void *cpart, int parts, int N, int K, int mask_words, 
                        (const int2 *)cpart, parts, N, K, mask_words, g, out_cluster, occ, uh, mask);
 }
 
-void vpk_union_flags(const int32_t *occ, const VpUnionHeader *uh, const VpSlabSet &clusters, int max_occ,
-                     int n_max, unsigned int *mask, hipStream_t st)
+void vpk_union_flags(const int32_t *occ, const VpUnionHeader *uh, const uint32_t *bitmaps, int bm_words,
+                     int mask_words, unsigned int *mask, hipStream_t st)
 {
-    const int chunk = 4096;
-    dim3 grid(max_occ, (n_max + chunk - 1) / chunk);
-    hipLaunchKernelGGL(union_flag_kernel, grid, dim3(256), 0, st, occ, uh, clusters.tile_off, clusters.n_cand,
-                       clusters.ids, chunk, mask);
+    dim3 grid((mask_words + 255) / 256, UNION_OR_SPLIT);
+    hipLaunchKernelGGL(union_flag_kernel, grid, dim3(256), 0, st, occ, uh, bitmaps, bm_words, mask_words, mask);
 }
 
-void vpk_union_compact(const unsigned int *mask, int mask_words, int V, int N, int rpi, int target_items, int min_items,
-                       int max_items, int32_t *uids, VpUnionHeader *uh, int32_t *out_union_size, int32_t *perm,
-                       VpRowPlan *rowplan, unsigned int *floors, VpItem *items, VpPlanHeader *hdr, hipStream_t st)
+int vpk_union_blocks(int mask_words) { return (mask_words + UNION_BLOCK_WORDS - 1) / UNION_BLOCK_WORDS; }
+
+void vpk_union_compact(const unsigned int *mask, int mask_words, int32_t *bsum, int N, int rpi, int target_items,
+                       int min_items, int max_items, int32_t *uids, VpUnionHeader *uh, int32_t *out_union_size,
+                       int32_t *perm, VpRowPlan *rowplan, unsigned int *floors, VpItem *items, VpPlanHeader *hdr,
+                       hipStream_t st)
 {
-    hipLaunchKernelGGL(union_compact_kernel, dim3(1), dim3(UNION_THREADS), 0, st, mask, mask_words, V, N, rpi,
-                       target_items, min_items, max_items, uids, uh, out_union_size, perm, rowplan, floors, items, hdr);
+    const int blocks = vpk_union_blocks(mask_words);
+    hipLaunchKernelGGL(union_count_kernel, dim3(blocks), dim3(256), 0, st, mask, mask_words, bsum);
+    hipLaunchKernelGGL(union_compact_kernel, dim3(1), dim3(UNION_THREADS), 0, st, bsum, blocks, N, rpi, target_items,
+                       min_items, max_items, uids, uh, out_union_size, perm, rowplan, floors, items, hdr);
+    hipLaunchKernelGGL(union_emit_kernel, dim3(blocks), dim3(256), 0, st, mask, mask_words, bsum, uids);
 }
 
 void vpk_union_gather(const void *wp, const float *bias_full, int kt, const int32_t *uids, const VpUnionHeader *uh,

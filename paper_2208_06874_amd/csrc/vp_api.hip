@@ -358,7 +358,7 @@ vp_status run_full(const char *fn, const vp_index *I, const void *hidden, int N,
 
 // Extra workspace of the batch-union form, placed after the common part.
 struct UnionLayout {
-    size_t base, uh, occ, mask, uids, ubias, uslab, total;
+    size_t base, uh, occ, mask, bsum, uids, ubias, uslab, total;
     int mask_words;
 };
 
@@ -373,6 +373,7 @@ UnionLayout plan_union_workspace(const vp_index *I, int N)
     U.uh = take(sizeof(VpUnionHeader));
     U.occ = take((size_t)I->K * 4);
     U.mask = take((size_t)U.mask_words * 4);
+    U.bsum = take((size_t)vpk_union_blocks(U.mask_words) * 4);
     U.uids = take(vpad * 4);
     U.ubias = take(vpad * 4);
     U.uslab = take((size_t)I->L.vtiles * I->L.kt * VP_TILE_BYTES);
@@ -674,6 +675,7 @@ vp_status vp_project_union(const vp_index *I, const void *hidden, int32_t N, int
     VpUnionHeader *uh = reinterpret_cast<VpUnionHeader *>(ws + U.uh);
     int32_t *occ = reinterpret_cast<int32_t *>(ws + U.occ);
     unsigned int *mask = reinterpret_cast<unsigned int *>(ws + U.mask);
+    int32_t *bsum = reinterpret_cast<int32_t *>(ws + U.bsum);
     int32_t *uids = reinterpret_cast<int32_t *>(ws + U.uids);
     float *ubias = reinterpret_cast<float *>(ws + U.ubias);
     void *uslab = ws + U.uslab;
@@ -686,10 +688,10 @@ vp_status vp_project_union(const vp_index *I, const void *hidden, int32_t N, int
     vpk_centroid(hidden, N, I->d, I->cp, I->cnorm, I->K, I->L.kt, I->L.ctiles, tpw_c, parts, cpart, st);
     // step 2: boolean list over the vocabulary -> reduced column set U
     vpk_union_mark(cpart, parts, N, I->K, U.mask_words, g, out_cluster, occ, uh, mask, st);
-    vpk_union_flags(occ, uh, I->clusters, std::min(N, I->K), I->L.n_max, mask, st);
+    vpk_union_flags(occ, uh, I->bitmaps, I->L.bm_words, U.mask_words, mask, st);
     const int max_items = max_items_full(I, N);
     const int row_tiles_u = single_bucket_row_tiles(I, N, k);
-    vpk_union_compact(mask, U.mask_words, I->V, N, VP_ROWS_PER_ITEM * row_tiles_u, sb_target(I, row_tiles_u), sb_min(I, row_tiles_u), max_items, uids, uh,
+    vpk_union_compact(mask, U.mask_words, bsum, N, VP_ROWS_PER_ITEM * row_tiles_u, sb_target(I, row_tiles_u), sb_min(I, row_tiles_u), max_items, uids, uh,
                       out_union_size, perm, rowplan, floors, items, hdr, st);
     // step 3: the reduced weight matrix and Eq. 1 over it; steps 4-5 fused (no [N, V] array)
     vpk_union_gather(I->full.tiles, I->full.bias, I->L.kt, uids, uh, I->L.vtiles, uslab, ubias, st);
