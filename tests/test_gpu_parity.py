@@ -393,19 +393,31 @@ def test_results_are_deterministic(mid):
 
 
 def test_wide_items_of_the_full_projection(oracle, tiny):
-    """Items of 32 rows (two row tiles per slab tile) are used for k <= 2 and more than 16 rows."""
+    """Below the row count of the 64-row kernel, items of 32 rows (two row tiles per slab tile) are used for
+    k <= 2 and more than 16 rows; with that kernel switched off the same holds for any row count.  All three
+    item shapes must give the same ids."""
     cfg = tiny.cfg
+    for N, no_gemm in ((24, False), (75, True)):
+        H, q = wl.make_rows(cfg, tiny.C, N=N, stream=9)
+        for k in (1, 2):
+            default = tiny.project_full(H, k)      # N = 75: the 64-row kernel
+            if no_gemm:
+                tiny.index.set_option("gemm_min_rows", 0)
+            try:
+                wide = tiny.project_full(H, k)
+                print("wide full", N, k, pu.check_full(oracle, tiny.W, tiny.b, H, k, wide[0], wide[1]))
+                tiny.index.set_option("wide_items", 0)
+                narrow = tiny.project_full(H, k)
+                print("narrow full", N, k, pu.check_full(oracle, tiny.W, tiny.b, H, k, narrow[0], narrow[1]))
+                ids, logp, g, nu = tiny.project_union(H, 2)
+            finally:
+                tiny.index.set_option("wide_items", 1)
+                tiny.index.set_option("gemm_min_rows", 33)
+            for other in (wide, narrow):
+                assert np.array_equal(default[0], other[0])
+                assert np.allclose(default[1], other[1], rtol=0, atol=1e-4)
+            pu.check_union(oracle, tiny.W, tiny.b, tiny.C, tiny.cand_off, tiny.cand_ids, H, 2, ids, logp, g, nu)
     H, q = wl.make_rows(cfg, tiny.C, N=75, stream=9)
-    for k in (1, 2):
-        wide = tiny.project_full(H, k)
-        print("wide full", k, pu.check_full(oracle, tiny.W, tiny.b, H, k, wide[0], wide[1]))
-        tiny.index.set_option("wide_items", 0)
-        try:
-            narrow = tiny.project_full(H, k)
-        finally:
-            tiny.index.set_option("wide_items", 1)
-        assert np.array_equal(wide[0], narrow[0])
-        assert np.allclose(wide[1], narrow[1], rtol=0, atol=1e-4)
     ids, logp, g, nu = tiny.project_union(H, 2)
     pu.check_union(oracle, tiny.W, tiny.b, tiny.C, tiny.cand_off, tiny.cand_ids, H, 2, ids, logp, g, nu)
     _, _, zf = tiny.debug(H[:40], full=True)
