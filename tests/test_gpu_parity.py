@@ -456,6 +456,20 @@ def test_dispatch_to_the_masked_full_projection(oracle, tiny, mid):
         assert np.allclose(got[1], base[1], rtol=0, atol=1e-4)
         assert np.array_equal(g2, base[2])
     assert _planner_mode(mid.index, 8) in (0, 1)
+    # fewer than 33 rows: the 16-row form of the masked projection, forced by making the slabs look slow
+    cfg = wl.scaled(mid.cfg, k=8)
+    H, q = wl.make_rows(cfg, mid.C, N=20, stream=77)
+    base = mid.project(H, 8)
+    mid.index.set_option("dispatch", 1)
+    mid.index.set_option("cost_bw_slab_gbs", 1)
+    try:
+        got = mid.project(H, 8)
+        assert _planner_mode(mid.index, 20) == 1
+    finally:
+        mid.index.set_option("cost_bw_slab_gbs", 6800)
+        mid.index.set_option("dispatch", 0)
+    pu.check_projection(oracle, mid.W, mid.b, mid.C, mid.cand_off, mid.cand_ids, H, 8, got[0], got[1], got[2])
+    assert np.array_equal(got[0], base[0])
 
 
 def test_dispatch_cost_model_constants(mid):
