@@ -591,3 +591,42 @@ def test_largest_topk_on_the_many_row_kernel(oracle):
             B.index.set_option("cost_bw_slab_gbs", 6800)
             B.index.set_option("dispatch", 0)
         pu.check_projection(oracle, W, b, C, off, ids, H, 32, m_ids, m_logp, m_g)
+
+
+def test_shared_workspace_and_side_stream(oracle, mid):
+    """One big workspace reused by calls of different sizes and kinds, all on a stream of their own, must give
+    what fresh workspaces on the default stream give: nothing may survive in the workspace from call to call,
+    and no kernel may run on another stream than the caller's."""
+    import torch
+    cfg = mid.cfg
+    dev = mid.dev
+    big = torch.empty(mid.index.union_workspace_bytes(1024), dtype=torch.uint8, device=dev)
+    side = torch.cuda.Stream(device=dev)             # default priority
+    batches = {N: wl.make_rows(cfg, mid.C, N=N, stream=300 + N)[0] for N in (1024, 5, 70, 33, 17)}
+    want = {}
+    for N, H in batches.items():
+        want[N] = (mid.project(H, 8), mid.project_full(H, 2), mid.project_union(H, 8))
+    mid.index.set_option("dispatch", 1)
+    try:
+        for N, H in batches.items():
+            want[N] += (mid.project(H, 8),)
+        torch.cuda.synchronize()
+        big.fill_(0xA5)                               # stale garbage to start from
+        got = {}
+        with torch.cuda.stream(side):
+            for N, H in batches.items():
+                h = mid.rows(H)
+                a = mid.index.project(h, 8, workspace=big)
+                mid.index.set_option("dispatch", 0)
+                b = mid.index.project(h, 8, workspace=big)
+                c = mid.index.project_full(h, 2, workspace=big)
+                d = mid.index.project_union(h, 8, workspace=big)
+                mid.index.set_option("dispatch", 1)
+                got[N] = (b, c, d, a)
+        side.synchronize()
+    finally:
+        mid.index.set_option("dispatch", 0)
+    for N in batches:
+        for kind, (g, w) in enumerate(zip(got[N], want[N])):
+            assert np.array_equal(pu.to_np(g[0]), w[0]), (N, kind)
+            assert np.array_equal(pu.to_np(g[1]), w[1]), (N, kind)
