@@ -83,16 +83,16 @@ def test_twenty_iterations_and_determinism(oracle):
     assert counts.sum() == X.shape[0] and np.array_equal(counts, np.bincount(assign, minlength=cfg.K))
     if np.array_equal(Cb, ref["C_bits"]):
         assert excused > 0 or np.array_equal(assign, ref["assign"])
-        verdict = "bit-identical centroids"
+        outcome = "bit-identical centroids"
     else:
         # a membership decided differently inside the fp32 tolerance sends the two runs down
         # different paths; both must end at the same quality
         mine = oracle.kmeans_step(X, Cb.view(np.float16).astype(np.float64))["objective"]
         assert abs(mine - ref["objective"][-1]) <= 1e-3 * ref["objective"][-1]
-        verdict = "objective %.6g vs %.6g" % (mine, ref["objective"][-1])
+        outcome = "objective %.6g vs %.6g" % (mine, ref["objective"][-1])
     # the training must have improved on the start
     assert ref["objective"][-1] < ref["objective"][0]
-    print("twenty iterations:", verdict, "excused", excused)
+    print("twenty iterations:", outcome, "excused", excused)
 
 
 def test_ties_round_to_even_for_every_pair_of_neighbours(oracle):
