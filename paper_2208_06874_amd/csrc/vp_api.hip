@@ -232,9 +232,10 @@ std::pair<hipEvent_t, hipEvent_t> *profile_slot(const vp_index *I)
 }
 
 // Row tiles per item for projections that keep all rows in one bucket (full, masked, union).
-// From gemm_min_rows rows on: 4, the GEMM-shaped kernel (64 rows per item, every loaded slab
-// tile feeds four MFMAs).  Below that, two row tiles per loaded slab tile pay off (measured:
-// -10 % at top-1, N = 256) only while the top-k lists are short.
+// From gemm_min_rows rows on (default 17: measured faster than two 16-row passes from there): 4,
+// the GEMM-shaped kernel (64 rows per item, every loaded slab tile feeds four MFMAs).  Where
+// that kernel is not built for the k-extent, two row tiles per loaded slab tile pay off
+// (measured: -10 % at top-1, N = 256) only while the top-k lists are short.
 int single_bucket_row_tiles(const vp_index *I, int N, int k)
 {
     if (I->gemm_min_rows > 0 && N >= I->gemm_min_rows && vpk_project_gemm_supported(I->L.kt)) return 4;
@@ -481,7 +482,7 @@ vp_status vp_build(const vp_build_desc *D, void *hip_stream, vp_index **out)
     I->full_target_items = 2048;
     I->rstar = 0;
     I->wide_items = 1;
-    I->gemm_min_rows = 33;
+    I->gemm_min_rows = 17;
     I->gemm_target_items = 512;
     I->dispatch = 0;
     // measured on MI355X at d = 1024: bytes per second of the three regimes of the cost model

@@ -393,16 +393,15 @@ def test_results_are_deterministic(mid):
 
 
 def test_wide_items_of_the_full_projection(oracle, tiny):
-    """Below the row count of the 64-row kernel, items of 32 rows (two row tiles per slab tile) are used for
-    k <= 2 and more than 16 rows; with that kernel switched off the same holds for any row count.  All three
-    item shapes must give the same ids."""
+    """From 17 rows on, single-bucket projections use the 64-row kernel; with it switched off, items of 32
+    rows (two row tiles per slab tile) for k <= 2, else of 16 rows.  All three must give the same ids."""
     cfg = tiny.cfg
-    for N, no_gemm in ((24, False), (75, True)):
+    for N in (24, 75):
         H, q = wl.make_rows(cfg, tiny.C, N=N, stream=9)
         for k in (1, 2):
-            default = tiny.project_full(H, k)      # N = 75: the 64-row kernel
-            if no_gemm:
-                tiny.index.set_option("gemm_min_rows", 0)
+            default = tiny.project_full(H, k)      # the 64-row kernel
+            print("64-row full", N, k, pu.check_full(oracle, tiny.W, tiny.b, H, k, default[0], default[1]))
+            tiny.index.set_option("gemm_min_rows", 0)
             try:
                 wide = tiny.project_full(H, k)
                 print("wide full", N, k, pu.check_full(oracle, tiny.W, tiny.b, H, k, wide[0], wide[1]))
@@ -412,7 +411,7 @@ def test_wide_items_of_the_full_projection(oracle, tiny):
                 ids, logp, g, nu = tiny.project_union(H, 2)
             finally:
                 tiny.index.set_option("wide_items", 1)
-                tiny.index.set_option("gemm_min_rows", 33)
+                tiny.index.set_option("gemm_min_rows", 17)
             for other in (wide, narrow):
                 assert np.array_equal(default[0], other[0])
                 assert np.allclose(default[1], other[1], rtol=0, atol=1e-4)
@@ -456,15 +455,15 @@ def test_dispatch_to_the_masked_full_projection(oracle, tiny, mid):
         assert np.allclose(got[1], base[1], rtol=0, atol=1e-4)
         assert np.array_equal(g2, base[2])
     assert _planner_mode(mid.index, 8) in (0, 1)
-    # fewer than 33 rows: the 16-row form of the masked projection, forced by making the slabs look slow
+    # up to 16 rows: the 16-row form of the masked projection, forced by making the slabs look slow
     cfg = wl.scaled(mid.cfg, k=8)
-    H, q = wl.make_rows(cfg, mid.C, N=20, stream=77)
+    H, q = wl.make_rows(cfg, mid.C, N=12, stream=77)
     base = mid.project(H, 8)
     mid.index.set_option("dispatch", 1)
     mid.index.set_option("cost_bw_slab_gbs", 1)
     try:
         got = mid.project(H, 8)
-        assert _planner_mode(mid.index, 20) == 1
+        assert _planner_mode(mid.index, 12) == 1
     finally:
         mid.index.set_option("cost_bw_slab_gbs", 6800)
         mid.index.set_option("dispatch", 0)
@@ -576,7 +575,7 @@ def test_largest_topk_on_the_many_row_kernel(oracle):
     r, W, b, C = _small_model(13, 512, 3000, 6)
     off, ids = _random_lists(r, 6, 3000, 200, 900)
     B = Built(W, b, C, off, ids, k_max=32)
-    for N in (33, 100, 129):
+    for N in (17, 33, 100, 129):
         H = _rows(r, C, N)
         f_ids, f_logp = B.project_full(H, 32)
         pu.check_full(oracle, W, b, H, 32, f_ids, f_logp)
