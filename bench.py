@@ -276,7 +276,9 @@ def main():
         index.set_option("dispatch", 0)
         result["with_dispatch"] = {"rows_per_s": N / (ms_disp * 1e-3), "ms_per_step": ms_disp,
                                    "planner_chose": "masked full projection" if mode == 1 else "per-cluster slabs",
-                                   "speedup_vs_slabs": ms_step / ms_disp}
+                                   "speedup_vs_slabs": ms_step / ms_disp,
+                                   "speedup_vs_full": (result["full_vocab"]["ms_per_step"] / ms_disp)
+                                   if "full_vocab" in result else None}
         if mode == 1:
             # a dense contraction over the whole vocabulary: priced against the matrix cores, whole step
             tf = 2.0 * N * d * cfg.V / (ms_disp * 1e-3) / 1e12
