@@ -47,7 +47,9 @@ typedef enum {
 } vp_status;
 
 /* Limits: d % 8 == 0, 8 <= d <= 4096; 1 <= K <= 4096; 1 <= V < 2^31 - 16;
- * 1 <= k <= k_max <= 32; every active set non-empty; N <= 65536 per call. */
+ * 1 <= k <= k_max <= 32; N <= 65536 per call.  An active set may be empty (a cluster
+ * that lost its members in training): rows that fall into it get ids -1 and log-probs
+ * -inf; at least one set must hold a token. */
 #define VP_MAX_TOPK 32
 #define VP_MAX_CLUSTERS 4096
 #define VP_MAX_ROWS 65536
@@ -88,8 +90,8 @@ size_t vp_build_bytes(const vp_build_desc *desc);
  * slab with its active tokens' columns, their bias and their ids.  W, bias and
  * centroids are only read during this call (the index keeps its own copies);
  * the arena must outlive the index.  Synchronises the stream before returning.
- * Unsorted, duplicate or out-of-range ids: VP_ERR_INVALID_ARG.  Empty active
- * set, d % 8 != 0, limits exceeded: VP_ERR_UNSUPPORTED. */
+ * Unsorted, duplicate or out-of-range ids: VP_ERR_INVALID_ARG.  All active sets
+ * empty, d % 8 != 0, limits exceeded: VP_ERR_UNSUPPORTED. */
 vp_status vp_build(const vp_build_desc *desc, void *hip_stream, vp_index **out);
 
 vp_status vp_get_info(const vp_index *idx, vp_index_info *info);
@@ -216,7 +218,7 @@ vp_status vp_kmeans(const void *x, int64_t n, int32_t d, int32_t K, int32_t iter
  *                 nothing is written to cand_ids and VP_ERR_WORKSPACE is returned
  *   workspace     device, 256-byte aligned, >= vp_active_sets_workspace_bytes(K, V)
  * Synchronises the stream once (to learn the total).  A cluster without members
- * gets an empty set. */
+ * gets an empty set (which vp_build accepts). */
 size_t vp_active_sets_workspace_bytes(int32_t K, int32_t V);
 vp_status vp_active_sets(const int32_t *top_ids, const int32_t *assign, int64_t n, int32_t T, int32_t K,
                          int32_t V, int64_t *cand_offsets, int32_t *cand_ids, int64_t capacity,

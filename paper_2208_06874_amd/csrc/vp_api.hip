@@ -110,9 +110,8 @@ vp_status plan_arena(const vp_build_desc *D, bool check_ids, ArenaLayout *L)
         const int64_t a = D->cand_offsets[j], b = D->cand_offsets[j + 1];
         if (b < a) return fail(VP_ERR_INVALID_ARG, "vp_build: cand_offsets decreases at cluster %d", j);
         const int64_t n = b - a;
-        if (n == 0) return fail(VP_ERR_UNSUPPORTED, "vp_build: cluster %d has an empty active set", j);
         if (n > D->V) return fail(VP_ERR_INVALID_ARG, "vp_build: cluster %d lists %lld > V tokens", j, (long long)n);
-        if (check_ids) {
+        if (check_ids && n > 0) {
             const int32_t *ids = D->cand_ids + a;
             if (ids[0] < 0 || ids[n - 1] >= D->V)
                 return fail(VP_ERR_INVALID_ARG, "vp_build: cluster %d has a token id outside [0, V)", j);
@@ -128,6 +127,7 @@ vp_status plan_arena(const vp_build_desc *D, bool check_ids, ArenaLayout *L)
         n_max = std::max<int64_t>(n_max, n);
     }
     if (groups > (1L << 27)) return fail(VP_ERR_UNSUPPORTED, "vp_build: active sets too large in total");
+    if (groups == 0) return fail(VP_ERR_UNSUPPORTED, "vp_build: every active set is empty");
     L->total_groups = groups;
     L->n_total = total;
     L->n_min = n_min;

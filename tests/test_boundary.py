@@ -66,7 +66,7 @@ def test_build_bytes_valid_and_monotone():
     (dict(k_max=0), vp.VP_ERR_UNSUPPORTED),
     (dict(k_max=33), vp.VP_ERR_UNSUPPORTED),
     (dict(flags=1), vp.VP_ERR_INVALID_ARG),
-    (dict(lists=[np.arange(4), np.zeros(0, int), np.arange(3)]), vp.VP_ERR_UNSUPPORTED),   # empty set
+    (dict(lists=[np.zeros(0, int), np.zeros(0, int), np.zeros(0, int)]), vp.VP_ERR_UNSUPPORTED),   # all sets empty
     (dict(lists=[np.array([3, 2]), np.arange(4), np.arange(3)]), vp.VP_ERR_INVALID_ARG),   # unsorted
     (dict(lists=[np.array([2, 2]), np.arange(4), np.arange(3)]), vp.VP_ERR_INVALID_ARG),   # duplicate
     (dict(lists=[np.array([2, 100]), np.arange(4), np.arange(3)]), vp.VP_ERR_INVALID_ARG),  # id >= V

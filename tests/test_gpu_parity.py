@@ -629,3 +629,39 @@ def test_shared_workspace_and_side_stream(oracle, mid):
         for kind, (g, w) in enumerate(zip(got[N], want[N])):
             assert np.array_equal(pu.to_np(g[0]), w[0]), (N, kind)
             assert np.array_equal(pu.to_np(g[1]), w[1]), (N, kind)
+
+
+def test_empty_active_sets(oracle):
+    """A cluster whose active set is empty (a cluster that lost its members in training): rows that fall into
+    it get ids -1 and log-probs -inf in every form of the projection; the other rows are untouched."""
+    r, W, b, C = _small_model(15, 128, 900, 6)
+    lists = [np.sort(r.choice(900, size=n, replace=False)) for n in (40, 0, 170, 0, 33, 5)]
+    off = np.zeros(7, np.int64)
+    np.cumsum([len(x) for x in lists], out=off[1:])
+    ids = np.concatenate(lists).astype(np.int32)
+    B = Built(W, b, C, off, ids, k_max=4)
+    for N in (9, 70):
+        H = _rows(r, C, N, clusters=np.arange(N) % 6)
+        ids_g, logp_g, g = B.project(H, 4)
+        st = pu.check_projection(oracle, W, b, C, off, ids, H, 4, ids_g, logp_g, g)
+        hit = np.isin(g, (1, 3))
+        assert hit.any() and np.all(ids_g[hit] == -1) and np.all(np.isneginf(logp_g[hit]))
+        assert np.all(ids_g[~hit][:, 0] >= 0)
+        g2, offs, z = B.debug(H)
+        assert np.array_equal(offs, oracle.project(W, b, C, off, ids, H, 4, forced_g=g, want_all=True)["all_off"])
+        u_ids, u_logp, u_g, u_n = B.project_union(H, 4)
+        pu.check_union(oracle, W, b, C, off, ids, H, 4, u_ids, u_logp, u_g, u_n)
+        B.index.set_option("dispatch", 1)
+        B.index.set_option("cost_bw_slab_gbs", 1)      # force the masked projection
+        try:
+            m_ids, m_logp, m_g = B.project(H, 4)
+            assert _planner_mode(B.index, N) == 1
+        finally:
+            B.index.set_option("cost_bw_slab_gbs", 6800)
+            B.index.set_option("dispatch", 0)
+        assert np.array_equal(m_ids, ids_g) and np.allclose(m_logp, logp_g, rtol=0, atol=1e-4, equal_nan=True)
+        print("empty sets", N, st)
+    # a batch that only meets empty clusters: the union is empty
+    H = _rows(r, C, 5, clusters=np.array([1, 3, 1, 1, 3]), noise=0.01)
+    u_ids, u_logp, u_g, u_n = B.project_union(H, 4)
+    assert u_n == 0 and np.all(u_ids == -1) and np.all(np.isneginf(u_logp))

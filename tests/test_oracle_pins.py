@@ -240,6 +240,19 @@ def test_duplicate_columns_tie_goes_to_smaller_token(oracle):
         assert ids.index(4) + 1 == ids.index(17)
 
 
+def test_empty_active_set_gives_no_candidates(oracle):
+    W, b, C, H = _small(21, N=6)
+    off = np.array([0, 4, 4, 9, 9, 12], np.int64)            # clusters 1 and 3 list nothing
+    ids = np.array([1, 5, 9, 30, 2, 4, 6, 8, 50, 0, 7, 56], np.int32)
+    forced = np.array([0, 1, 2, 3, 4, 1], np.int32)
+    out = oracle.project(W, b, C, off, ids, H, 3, forced_g=forced, want_all=True)
+    for r in (1, 3, 5):
+        assert out["ids"][r].tolist() == [-1, -1, -1] and np.all(np.isneginf(out["logp"][r]))
+    assert out["all_off"].tolist() == [0, 4, 4, 9, 9, 12, 12]
+    free = oracle.project(W, b, C, off, ids, H[[0, 2, 4]], 3, forced_g=forced[[0, 2, 4]])
+    assert np.array_equal(free["ids"], out["ids"][[0, 2, 4]]) and np.array_equal(free["logp"], out["logp"][[0, 2, 4]])
+
+
 def test_rows_are_independent(oracle):
     W, b, C, H = _small(71, d=24, V=64, K=4, N=12)
     r = np.random.default_rng(71)
