@@ -109,7 +109,7 @@ vp_status vp_get_info(const vp_index *idx, vp_index_info *info);
  *                   GB/s of the cost model
  *   "gemm_min_rows" projections that keep all rows in one bucket (full, masked, union)
  *                   use the kernel with 64 rows per work item from this many rows on
- *                   (default 17; 0: never); d_pad must be 256, 512, 1024 or 1536
+ *                   (default 17; 0: never); d_pad must be 256, 512, 1024, 1536 or 2048
  *   "gemm_target_items"  work items of that kernel (default 512)
  *   "wide_items"    1 (default): below gemm_min_rows, vp_project_full / vp_project_union
  *                   of more than 16 rows with k <= 2 put 32 rows in an item; 0: always 16

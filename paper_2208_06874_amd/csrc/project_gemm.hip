@@ -4,8 +4,9 @@
 // more rows than one 16-row item takes.
 //
 // An item is 64 rows x a range of candidate groups.  The k-extent is split over
-// the four wavefronts of the workgroup: wavefront w keeps the k-slice
-// [w * d_pad / 4, (w + 1) * d_pad / 4) of all 64 rows in registers, already in
+// the wavefronts of the workgroup (four up to d_pad = 1024, eight beyond, so that a
+// slice of the rows still fits the registers twice per SIMD): wavefront w keeps
+// k-slice w of all 64 rows in registers, already in
 // MFMA operand order, and streams only its slice of every slab tile group, so
 // each 1 KiB slab load feeds four v_mfma_f32_16x16x32_f16 (one per row tile) and
 // the hidden rows cost no LDS traffic in the loop.  Per candidate group the four
@@ -30,13 +31,13 @@ namespace {
 constexpr int G_RT = 4;                    // row tiles per item
 constexpr int G_ROWS = 16 * G_RT;          // row slots per item
 
-template <int KW, bool MASKED, bool NT>
+template <int NW, int KW, bool MASKED, bool NT>
 __device__ inline void gemm_item(const VpSlabSet &set, const uint4 *__restrict__ hidden, int d,
                                  const int32_t *__restrict__ perm, const VpItem &item, int it, int k,
                                  float *__restrict__ partials, unsigned int *__restrict__ bounds, int set_id,
                                  const VpMaskInfo &mask)
 {
-    constexpr int KT = KW * 4;
+    constexpr int KT = KW * NW;   // NW wavefronts split the k-extent; the first four also finish a row tile each
     const int tid = threadIdx.x;
     const int wave = tid >> 6;
     const int lane = tid & 63;
@@ -44,10 +45,10 @@ __device__ inline void gemm_item(const VpSlabSet &set, const uint4 *__restrict__
     const int q = lane >> 4;
 
     extern __shared__ uint4 lds[];
-    floatx4 *xbuf = reinterpret_cast<floatx4 *>(lds);                             // [2][G_RT][4 waves][64 lanes]
+    floatx4 *xbuf = reinterpret_cast<floatx4 *>(lds);                             // [2][G_RT][NW waves][64 lanes]
     const int k4 = (k + 3) & ~3;                                                   // slots per lane, padded
-    float *keep_val = reinterpret_cast<float *>(xbuf + 2 * G_RT * 4 * 64);         // [4 waves][k4][64 lanes]
-    int *keep_idx = reinterpret_cast<int *>(keep_val + VP_WG_WAVES * k4 * 64);
+    float *keep_val = reinterpret_cast<float *>(xbuf + 2 * G_RT * NW * 64);        // [4 finishing waves][k4][64 lanes]
+    int *keep_idx = reinterpret_cast<int *>(keep_val + G_RT * k4 * 64);
 
     const int ncand = item.ncand;
     const int toff = item.tile_off;
@@ -81,16 +82,21 @@ __device__ inline void gemm_item(const VpSlabSet &set, const uint4 *__restrict__
         }
     }
 
-    // the rows this wavefront finishes: row tile `wave`
-    const int slot = wave * 16 + n;
-    const bool row_valid = slot < item.nrows;
+    // the rows this wavefront finishes: row tile `wave` (wavefronts 4 .. NW-1 only contribute
+    // their k-slices)
+    const bool finisher = NW == G_RT || wave < G_RT;
+    const int fw = finisher ? wave : 0;
+    const int slot = fw * 16 + n;
+    const bool row_valid = finisher && slot < item.nrows;
     const int myrow = row_valid ? perm[item.perm_start + slot] : -1;
     // this lane's buffer: slot s at mine[s * 64]; slots k .. k4-1 are padding that never loses
-    float *my_val = keep_val + (size_t)wave * k4 * 64 + lane;
-    int *my_idx = keep_idx + (size_t)wave * k4 * 64 + lane;
-    for (int s = 0; s < k4; ++s) {
-        my_val[s * 64] = s < k ? -__builtin_inff() : __builtin_inff();
-        my_idx[s * 64] = VP_IDX_NONE;
+    float *my_val = keep_val + (size_t)fw * k4 * 64 + lane;
+    int *my_idx = keep_idx + (size_t)fw * k4 * 64 + lane;
+    if (finisher) {
+        for (int s = 0; s < k4; ++s) {
+            my_val[s * 64] = s < k ? -__builtin_inff() : __builtin_inff();
+            my_idx[s * 64] = VP_IDX_NONE;
+        }
     }
     float m_run = VP_NEG_BIG;                 // running maximum and sum of exponentials
     float s_run = 0.f;
@@ -134,23 +140,33 @@ __device__ inline void gemm_item(const VpSlabSet &set, const uint4 *__restrict__
 
     // k-slices of group g -> LDS, barrier, this wavefront's row tile summed and folded
     auto finish = [&](int g, int par) {
-        floatx4 *xw = xbuf + (size_t)par * G_RT * 4 * 64;
+        floatx4 *xw = xbuf + (size_t)par * G_RT * NW * 64;
 #pragma unroll
         for (int rt = 0; rt < G_RT; ++rt) {
-            xw[(rt * 4 + wave) * 64 + lane] = acc[rt];
+            xw[(rt * NW + wave) * 64 + lane] = acc[rt];
         }
         const float4 bz4 = bnext;
         const uint32_t mcur = mnext;
-        if (g + 1 < ge) {
+        if (finisher && g + 1 < ge) {
             bnext = *reinterpret_cast<const float4 *>(bias + (g + 1) * VP_TILE_ITEMS);
             if (MASKED) mnext = mrow[((g + 1) * VP_TILE_ITEMS + q * 4) >> 5];
         }
         __syncthreads();
-        const floatx4 p0 = xw[(wave * 4 + 0) * 64 + lane];
-        const floatx4 p1 = xw[(wave * 4 + 1) * 64 + lane];
-        const floatx4 p2 = xw[(wave * 4 + 2) * 64 + lane];
-        const floatx4 p3 = xw[(wave * 4 + 3) * 64 + lane];
-        const floatx4 sum = (p0 + p1) + (p2 + p3);
+        if (!finisher) return;   // wavefronts beyond the fourth go on with the next group's k-slices
+        // fixed order of the partial sums: pairs, then pairs of pairs
+        floatx4 sum;
+        {
+            const floatx4 *pw = xw + (size_t)(fw * NW) * 64 + lane;
+            floatx4 part[NW];
+#pragma unroll
+            for (int w = 0; w < NW; ++w) part[w] = pw[w * 64];
+#pragma unroll
+            for (int step = 1; step < NW; step <<= 1) {
+#pragma unroll
+                for (int w = 0; w < NW; w += 2 * step) part[w] = part[w] + part[w + step];
+            }
+            sum = part[0];
+        }
         const int c0 = g * VP_TILE_ITEMS + q * 4;
         const float bz[4] = {bz4.x, bz4.y, bz4.z, bz4.w};
         float z[4];
@@ -257,6 +273,7 @@ __device__ inline void gemm_item(const VpSlabSet &set, const uint4 *__restrict__
         ++g;
     }
 
+    if (!finisher) return;   // no barrier follows
     // the four lanes of a row (one per candidate quarter) -> one (m, s)
 #pragma unroll
     for (int off = 16; off <= 32; off <<= 1) {
@@ -306,8 +323,8 @@ __device__ inline void gemm_item(const VpSlabSet &set, const uint4 *__restrict__
     }
 }
 
-template <int KW, bool MASKED>
-__global__ __launch_bounds__(VP_WG_THREADS, (KW <= 8 ? 2 : 1)) void project_gemm_kernel(
+template <int NW, int KW, bool MASKED>
+__global__ __launch_bounds__(NW * 64, (NW == 4 && KW <= 8 ? 2 : 1)) void project_gemm_kernel(
     VpSlabSet set, const uint4 *__restrict__ hidden, int d, const int32_t *__restrict__ perm,
     const VpItem *__restrict__ items, const VpPlanHeader *__restrict__ hdr, int k,
     float *__restrict__ partials, unsigned int *__restrict__ bounds, VpMaskInfo mask)
@@ -320,49 +337,73 @@ __global__ __launch_bounds__(VP_WG_THREADS, (KW <= 8 ? 2 : 1)) void project_gemm
     // which set of candidate ranges this item's range belongs to (ranges are 4 * tiles_per_wave groups long)
     const int set_id = (item.tile0 / (hdr->tiles_per_wave * VP_WG_WAVES)) % VP_BOUND_SETS;
     if (item.shared)
-        gemm_item<KW, MASKED, false>(set, hidden, d, perm, item, it, k, partials, bounds, set_id, mask);
+        gemm_item<NW, KW, MASKED, false>(set, hidden, d, perm, item, it, k, partials, bounds, set_id, mask);
     else
-        gemm_item<KW, MASKED, true>(set, hidden, d, perm, item, it, k, partials, bounds, set_id, mask);
+        gemm_item<NW, KW, MASKED, true>(set, hidden, d, perm, item, it, k, partials, bounds, set_id, mask);
 }
 
-template <int KW, bool MASKED>
+template <int NW, int KW, bool MASKED>
 void launch(const VpSlabSet &set, const void *hidden, int d, const int32_t *perm, const VpItem *items,
             const VpPlanHeader *hdr, int grid_items, int k, float *partials, unsigned int *bounds,
             const VpMaskInfo &mask, hipStream_t st)
 {
-    hipLaunchKernelGGL((project_gemm_kernel<KW, MASKED>), dim3(grid_items), dim3(VP_WG_THREADS),
-                       vpk_project_gemm_lds_bytes(k), st, set, (const uint4 *)hidden, d, perm, items, hdr, k, partials,
-                       bounds, mask);
+    hipLaunchKernelGGL((project_gemm_kernel<NW, KW, MASKED>), dim3(grid_items), dim3(NW * 64),
+                       vpk_project_gemm_lds_bytes(k, NW * KW), st, set, (const uint4 *)hidden, d, perm, items, hdr, k,
+                       partials, bounds, mask);
 }
 
 }  // namespace
 
-size_t vpk_project_gemm_lds_bytes(int k)
+// wavefronts that split the k-extent of kt k-tiles: 4 up to d_pad = 1024, 8 beyond
+static int gemm_waves(int kt) { return kt <= 32 ? 4 : 8; }
+
+size_t vpk_project_gemm_lds_bytes(int k, int kt)
 {
     const size_t k4 = (size_t)((k + 3) & ~3);
-    return (size_t)2 * G_RT * 4 * 64 * 16 + (size_t)VP_WG_WAVES * k4 * 64 * 8;
+    return (size_t)2 * G_RT * gemm_waves(kt) * 64 * 16 + (size_t)G_RT * k4 * 64 * 8;
 }
 
+// k-tile counts the kernel is built for (d_pad = 256, 512, 1024, 1536, 2048)
+bool vpk_project_gemm_supported(int kt) { return kt == 8 || kt == 16 || kt == 32 || kt == 48 || kt == 64; }
 
+template <int NW, int KW>
+static hipError_t allow_lds()
+{
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(project_gemm_kernel<NW, KW, false>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(project_gemm_kernel<NW, KW, true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    return e;
+}
 
-// k-tile counts the kernel is built for (d_pad = 256, 512, 1024, 1536)
-bool vpk_project_gemm_supported(int kt) { return kt == 8 || kt == 16 || kt == 32 || kt == 48; }
+// more than 64 KiB of dynamic LDS (eight wavefronts, or long top-k lists) has to be allowed explicitly
+hipError_t vpk_project_gemm_prepare()
+{
+    hipError_t e = allow_lds<4, 2>();
+    if (e == hipSuccess) e = allow_lds<4, 4>();
+    if (e == hipSuccess) e = allow_lds<4, 8>();
+    if (e == hipSuccess) e = allow_lds<8, 6>();
+    if (e == hipSuccess) e = allow_lds<8, 8>();
+    return e;
+}
 
 void vpk_project_gemm(const VpSlabSet &set, const void *hidden, int d, const int32_t *perm, const VpItem *items,
                       const VpPlanHeader *hdr, int grid_items, int k, float *partials, unsigned int *bounds,
                       const VpMaskInfo *mask, hipStream_t st)
 {
     const VpMaskInfo none = {nullptr, nullptr, 0};
-#define VP_GEMM_CASE(KW)                                                                                        \
-    case KW * 4:                                                                                                \
-        if (mask) launch<KW, true>(set, hidden, d, perm, items, hdr, grid_items, k, partials, bounds, *mask, st); \
-        else launch<KW, false>(set, hidden, d, perm, items, hdr, grid_items, k, partials, bounds, none, st);     \
+#define VP_GEMM_CASE(NW, KW)                                                                                       \
+    case NW * KW:                                                                                                  \
+        if (mask) launch<NW, KW, true>(set, hidden, d, perm, items, hdr, grid_items, k, partials, bounds, *mask, st); \
+        else launch<NW, KW, false>(set, hidden, d, perm, items, hdr, grid_items, k, partials, bounds, none, st);     \
         break;
     switch (set.kt) {
-        VP_GEMM_CASE(2)
-        VP_GEMM_CASE(4)
-        VP_GEMM_CASE(8)
-        VP_GEMM_CASE(12)
+        VP_GEMM_CASE(4, 2)
+        VP_GEMM_CASE(4, 4)
+        VP_GEMM_CASE(4, 8)
+        VP_GEMM_CASE(8, 6)
+        VP_GEMM_CASE(8, 8)
         default: break;   // callers check vpk_project_gemm_supported
     }
 #undef VP_GEMM_CASE

@@ -414,6 +414,7 @@ vp_status vp_build(const vp_build_desc *D, void *hip_stream, vp_index **out)
     if (e == hipSuccess) e = vpk_project_prepare();
     if (e == hipSuccess) e = vpk_merge_prepare();
     if (e == hipSuccess) e = vpk_union_prepare();
+    if (e == hipSuccess) e = vpk_project_gemm_prepare();
     if (e != hipSuccess) return fail(VP_ERR_HIP, "vp_build: cannot configure kernels: %s", hipGetErrorString(e));
 
     // host-side metadata: candidate groups per cluster, ids padded to whole groups

@@ -45,8 +45,9 @@ void vpk_project_masked(const VpSlabSet &full, const void *hidden, int d, const 
 
 // GEMM-shaped projection of single-bucket plans with 64 rows per item (mask: nullptr, or the
 // membership lists of the masked full projection)
-size_t vpk_project_gemm_lds_bytes(int k);
+size_t vpk_project_gemm_lds_bytes(int k, int kt);
 bool vpk_project_gemm_supported(int kt);
+hipError_t vpk_project_gemm_prepare();
 void vpk_project_gemm(const VpSlabSet &set, const void *hidden, int d, const int32_t *perm, const VpItem *items,
                       const VpPlanHeader *hdr, int grid_items, int k, float *partials, unsigned int *bounds,
                       const VpMaskInfo *mask, hipStream_t st);

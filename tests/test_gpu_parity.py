@@ -631,6 +631,29 @@ def test_shared_workspace_and_side_stream(oracle, mid):
             assert np.array_equal(pu.to_np(g[1]), w[1]), (N, kind)
 
 
+@pytest.mark.parametrize("d", [1536, 2048])
+def test_many_row_kernel_with_eight_k_slices(oracle, d):
+    """Beyond d = 1024 the 64-row kernel splits the k-extent over eight wavefronts."""
+    r, W, b, C = _small_model(16 + d, d, 1200, 4)
+    off, ids = _random_lists(r, 4, 1200, 100, 500)
+    B = Built(W, b, C, off, ids, k_max=8)
+    for N, k in ((40, 3), (150, 8)):
+        H = _rows(r, C, N)
+        f_ids, f_logp = B.project_full(H, k)
+        print("eight slices full", d, N, pu.check_full(oracle, W, b, H, k, f_ids, f_logp))
+        u_ids, u_logp, u_g, u_n = B.project_union(H, k)
+        pu.check_union(oracle, W, b, C, off, ids, H, k, u_ids, u_logp, u_g, u_n)
+        B.index.set_option("dispatch", 1)
+        B.index.set_option("cost_bw_slab_gbs", 1)      # force the masked projection
+        try:
+            m_ids, m_logp, m_g = B.project(H, k)
+            assert _planner_mode(B.index, N) == 1
+        finally:
+            B.index.set_option("cost_bw_slab_gbs", 6800)
+            B.index.set_option("dispatch", 0)
+        pu.check_projection(oracle, W, b, C, off, ids, H, k, m_ids, m_logp, m_g)
+
+
 def test_empty_active_sets(oracle):
     """A cluster whose active set is empty (a cluster that lost its members in training): rows that fall into
     it get ids -1 and log-probs -inf in every form of the projection; the other rows are untouched."""
