@@ -40,6 +40,8 @@ def cluster_sweep(args, dev):
     from paper_2208_06874_amd import workloads as wl
 
     cfg = wl.CONFIGS[args.workload]
+    if getattr(args, "sweep_noise", None) is not None:
+        cfg = wl.scaled(cfg, noise=args.sweep_noise)
     N, k, n_tr, T_max = 64, 1, args.train_vectors, 5
     W, b, C_true = wl.make_model(cfg)
     Wt, bt = torch.from_numpy(W).to(dev), torch.from_numpy(b).to(dev)
@@ -95,7 +97,7 @@ def cluster_sweep(args, dev):
                          "top1_in_active_set": hit, "kmeans_20_iterations_ms": ms_train})
             del index, ws
     return {"metric": "cluster sweep: centroids x recorded tokens -> active fraction, rows/s (N=64, top-1)",
-            "workload": cfg.name, "train_vectors": n_tr, "full_vocab_ms_per_step": ms_full, "data": "synthetic",
+            "workload": cfg.name, "noise": cfg.noise, "train_vectors": n_tr, "full_vocab_ms_per_step": ms_full, "data": "synthetic",
             "rows": rows}
 
 
@@ -114,6 +116,8 @@ def main():
     ap.add_argument("--no-dispatch", action="store_true")
     ap.add_argument("--no-training", action="store_true")
     ap.add_argument("--no-decode-loop", action="store_true")
+    ap.add_argument("--sweep-noise", type=float, default=None,
+                    help="cluster sweep: noise of the recorded vectors and decode rows (default: the workload's)")
     ap.add_argument("--cluster-sweep", action="store_true",
                     help="instead of the benchmark: train clusters for a grid of centroid counts and recorded tokens "
                          "per vector (a synthetic analogue of the paper's section 3.5) and time vp_project on each")
