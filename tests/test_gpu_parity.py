@@ -688,3 +688,25 @@ def test_empty_active_sets(oracle):
     H = _rows(r, C, 5, clusters=np.array([1, 3, 1, 1, 3]), noise=0.01)
     u_ids, u_logp, u_g, u_n = B.project_union(H, 4)
     assert u_n == 0 and np.all(u_ids == -1) and np.all(np.isneginf(u_logp))
+
+
+def test_non_finite_rows_stay_in_their_lane(tiny):
+    """A row with NaN or infinite entries gets meaningless values, but every index stays in range, the call
+    completes, and the other rows of the batch are exactly what they are without it."""
+    cfg = tiny.cfg
+    H, q = wl.make_rows(cfg, tiny.C, N=40, stream=91)
+    bad = H.copy()
+    bad[3, 5] = np.float16(np.nan)
+    bad[17, :] = np.float16(np.inf)
+    bad[29, 0] = np.float16(-np.inf)
+    good_rows = np.setdiff1d(np.arange(40), [3, 17, 29])
+    for call in ("project", "project_full", "project_union"):
+        want = getattr(tiny, call)(H, 4)
+        got = getattr(tiny, call)(bad, 4)
+        ids = got[0]
+        assert ids.min() >= -1 and ids.max() < cfg.V, call
+        if call != "project_union":      # the union's contents depend on every row's cluster
+            assert np.array_equal(ids[good_rows], want[0][good_rows]), call
+            assert np.array_equal(got[1][good_rows], want[1][good_rows]), call
+        if call == "project":
+            assert got[2].min() >= 0 and got[2].max() < cfg.K
