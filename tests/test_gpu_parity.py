@@ -710,3 +710,45 @@ def test_non_finite_rows_stay_in_their_lane(tiny):
             assert np.array_equal(got[1][good_rows], want[1][good_rows]), call
         if call == "project":
             assert got[2].min() >= 0 and got[2].max() < cfg.K
+
+
+def test_random_shapes(oracle):
+    """Seeded random draws of (d, V, K, N, k) and ragged active sets, some of them empty, through every form
+    of the projection against the oracle."""
+    rs = np.random.default_rng(2208)
+    for case in range(24):
+        d = 8 * int(rs.integers(1, 257)) if case % 3 else int(rs.choice([8, 256, 512, 1024, 1536, 2048]))
+        V = int(rs.integers(17, 5000))
+        K = int(rs.integers(1, 300))
+        N = int(rs.integers(1, 200))
+        k = int(rs.choice([1, 2, 3, 4, 8, 13, 32]))
+        sizes = rs.integers(0, min(V, 600) + 1, K)
+        sizes[rs.random(K) < 0.1] = 0
+        if sizes.sum() == 0:
+            sizes[0] = 1
+        print("random shapes: case %d  d %d V %d K %d N %d k %d" % (case, d, V, K, N, k), flush=True)
+        r, W, b, C = _small_model(1000 + case, d, V, K)
+        lists = [np.sort(r.choice(V, size=int(n), replace=False)) for n in sizes]
+        off = np.zeros(K + 1, np.int64)
+        np.cumsum(sizes, out=off[1:])
+        ids = np.concatenate(lists).astype(np.int32)
+        B = Built(W, b, C, off, ids, k_max=max(k, 1))
+        H = _rows(r, C, N)
+        ids_g, logp_g, g = B.project(H, k)
+        g2, offs, z = B.debug(H)
+        pu.check_projection(oracle, W, b, C, off, ids, H, k, ids_g, logp_g, g, logits_gpu=z, offs_gpu=offs)
+        Hf = H[:64]
+        f_ids, f_logp = B.project_full(Hf, k)
+        pu.check_full(oracle, W, b, Hf, k, f_ids, f_logp)
+        u_ids, u_logp, u_g, u_n = B.project_union(H, k)
+        pu.check_union(oracle, W, b, C, off, ids, H, k, u_ids, u_logp, u_g, u_n)
+        B.index.set_option("dispatch", 1)
+        B.index.set_option("cost_bw_slab_gbs", 1)      # force the masked projection
+        try:
+            m_ids, m_logp, m_g = B.project(H, k)
+            assert _planner_mode(B.index, N) == 1
+        finally:
+            B.index.set_option("cost_bw_slab_gbs", 6800)
+            B.index.set_option("dispatch", 0)
+        pu.check_projection(oracle, W, b, C, off, ids, H, k, m_ids, m_logp, m_g)
+        del B
