@@ -241,3 +241,31 @@ def test_cluster_sweep_of_the_benchmark_runs():
     for a, b, c in zip(rows[0::3], rows[1::3], rows[2::3]):
         assert a["mean_active_fraction"] <= b["mean_active_fraction"] <= c["mean_active_fraction"]
         assert a["top1_in_active_set"] <= b["top1_in_active_set"] + 1e-9 <= c["top1_in_active_set"] + 2e-9
+
+
+def test_random_training_shapes(oracle):
+    """Seeded random (n, d, K): one Lloyd step from the same start must give the oracle's centroids bit for
+    bit for the GPU's memberships, and the active sets of random recordings must match."""
+    torch = _torch()
+    from paper_2208_06874_amd import vp
+    rs = np.random.default_rng(806874)
+    for case in range(12):
+        d = 8 * int(rs.integers(1, 200))
+        K = int(rs.choice([1, 3, 40, 255, 256, 300, 700]))
+        n = int(rs.integers(max(K, 2), 9000))
+        print("random training: case %d  n %d d %d K %d" % (case, n, d, K), flush=True)
+        centres = rs.standard_normal((K, d))
+        q = rs.integers(0, K, n)
+        X = (centres[q] + 0.4 * rs.standard_normal((n, d))).astype(np.float16)
+        C0 = X[np.sort(rs.choice(n, K, replace=False))].copy()
+        _same, a0, c0 = _gpu_kmeans(X, C0, 0)
+        _check_membership(oracle, X, C0.view(np.uint16), a0)
+        new, _a, _c = _gpu_kmeans(X, C0, 1)
+        st = oracle.kmeans_step(X, C0.astype(np.float64), forced=a0)
+        assert np.array_equal(new, st["C"].astype(np.float16).view(np.uint16))
+        T, V = int(rs.integers(1, 6)), int(rs.integers(40, 3000))
+        top = rs.integers(-1, V, (n, T)).astype(np.int32)
+        off, ids = vp.vp_active_sets(_dev(top), _dev(a0), K, V)
+        torch.cuda.synchronize()
+        want_off, want_ids = oracle.active_sets(top, a0, K, V)
+        assert np.array_equal(pu.to_np(off), want_off) and np.array_equal(pu.to_np(ids), want_ids)
