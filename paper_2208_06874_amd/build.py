@@ -11,6 +11,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(ROOT, "_build")
 LIB = os.path.join(HERE, "libvp.so")
+CLI_SRC = os.path.join(ROOT, "examples", "vp_cli.cpp")
+CLI = os.path.join(ROOT, "examples", "vp_cli")
 
 SOURCES = ["vp_api.hip", "build_kernels.hip", "centroid.hip", "plan.hip", "project.hip", "merge.hip", "union.hip",
            "train.hip", "train_api.hip", "project_gemm.hip", "search.hip"]
@@ -55,6 +57,17 @@ def build(verbose: bool = True) -> str:
     os.replace(tmp, LIB)
     if verbose:
         print("built", LIB)
+    # the stand-alone caller of the C ABI (host code only; links against the library just built)
+    if os.path.exists(CLI_SRC):
+        tmp = CLI + ".tmp.%d" % os.getpid()
+        cmd = [_hipcc(), "--offload-arch=gfx950", "-O2", "-std=c++17", "-I", os.path.join(ROOT, "include"), CLI_SRC,
+               "-o", tmp, "-L", HERE, "-lvp", "-Wl,-rpath,$ORIGIN/../paper_2208_06874_amd"]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError("building examples/vp_cli failed:\n%s\n%s" % (r.stdout, r.stderr))
+        os.replace(tmp, CLI)
+        if verbose:
+            print("built", CLI)
     return LIB
 
 
