@@ -238,7 +238,17 @@ def kmeans_step(X, C, forced=None):
     return dict(assign=assign, counts=counts, C=Cn, objective=obj.value)
 
 
-def kmeans(X, C0, iters: int, round_half: bool = True):
+def split_empty(C, counts, round_half: bool = True):
+    """The optional remedy for clusters without members, applied to float64 centroids C [K, d] and the
+    member counts.  Returns the new (C, counts)."""
+    C = np.array(C, np.float64, order="C")
+    counts = np.array(counts, np.int32)
+    K, d = C.shape
+    _load().vpo_split_empty(_p(C), _p(counts), ctypes.c_int(K), ctypes.c_int(d), ctypes.c_int(1 if round_half else 0))
+    return C, counts
+
+
+def kmeans(X, C0, iters: int, round_half: bool = True, split_empty: bool = False):
     """iters Lloyd iterations from the binary16 centroids C0, then the membership against the final
     centroids.  Returns C (float64), C_bits (uint16), assign, counts, objective[iters + 1]."""
     X, C0 = _bits(X), _bits(C0)
@@ -251,7 +261,8 @@ def kmeans(X, C0, iters: int, round_half: bool = True):
     counts = np.empty(K, np.int32)
     obj = np.empty(iters + 1, np.float64)
     _load().vpo_kmeans(_p(X), ctypes.c_int(n), ctypes.c_int(d), _p(C0), ctypes.c_int(K), ctypes.c_int(iters),
-                       ctypes.c_int(1 if round_half else 0), _p(C), _p(Cb), _p(assign), _p(counts), _p(obj))
+                       ctypes.c_int(1 if round_half else 0), ctypes.c_int(1 if split_empty else 0), _p(C), _p(Cb),
+                       _p(assign), _p(counts), _p(obj))
     return dict(C=C, C_bits=Cb, assign=assign, counts=counts, objective=obj)
 
 

@@ -113,6 +113,37 @@ void vpo_kmeans_step(const uint16_t *X, int n, int d, const double *C, int K, co
     }
 }
 
+/* Optional remedy for clusters that lost all their members (the paper names no remedy; k-means
+ * libraries usually split a big cluster).  Deterministic form: the clusters without members are
+ * taken in ascending order; each takes the cluster that currently has the most members (ties: lowest
+ * index; it must have at least two), whose centroid c is replaced by c (1 - eps) and whose copy
+ * c (1 + eps) becomes the empty cluster's centroid, eps = 2^-10; the member count is shared out
+ * (half, rounded down, goes to the new cluster) so that the next empty cluster sees the new sizes.
+ * With round_half the two products are rounded to binary16. */
+void vpo_split_empty(double *C, int32_t *counts, int K, int d, int round_half)
+{
+    const double eps = ldexp(1.0, -10);
+    for (int j = 0; j < K; ++j) {
+        if (counts[j] != 0) continue;
+        int big = 0;
+        for (int i = 1; i < K; ++i)
+            if (counts[i] > counts[big]) big = i;
+        if (counts[big] < 2) return;
+        for (int e = 0; e < d; ++e) {
+            const double c = C[(size_t)big * d + e];
+            double up = c * (1.0 + eps), down = c * (1.0 - eps);
+            if (round_half) {
+                up = vpo_half_to_double(vpo_double_to_half(up));
+                down = vpo_half_to_double(vpo_double_to_half(down));
+            }
+            C[(size_t)j * d + e] = up;
+            C[(size_t)big * d + e] = down;
+        }
+        counts[j] = counts[big] / 2;
+        counts[big] -= counts[j];
+    }
+}
+
 /* iters Lloyd iterations from the binary16 centroids C0, then one more
  * assignment against the final centroids (the membership used to build the
  * active sets).  C_out (double, K x d) and C_out_bits (binary16, may be NULL
@@ -120,7 +151,8 @@ void vpo_kmeans_step(const uint16_t *X, int n, int d, const double *C, int K, co
  * at the start of iteration t (t < iters) and objective[iters] that of the
  * final assignment. */
 void vpo_kmeans(const uint16_t *X, int n, int d, const uint16_t *C0, int K, int iters, int round_half,
-                double *C_out, uint16_t *C_out_bits, int32_t *assign, int32_t *counts, double *objective)
+                int split_empty, double *C_out, uint16_t *C_out_bits, int32_t *assign, int32_t *counts,
+                double *objective)
 {
     double *C = (double *)malloc(sizeof(double) * (size_t)K * d);
     double *Cn = (double *)malloc(sizeof(double) * (size_t)K * d);
@@ -129,6 +161,7 @@ void vpo_kmeans(const uint16_t *X, int n, int d, const uint16_t *C0, int K, int 
         vpo_kmeans_step(X, n, d, C, K, NULL, assign, counts, Cn, objective ? objective + t : NULL);
         for (size_t e = 0; e < (size_t)K * d; ++e)
             C[e] = round_half ? vpo_half_to_double(vpo_double_to_half(Cn[e])) : Cn[e];
+        if (split_empty) vpo_split_empty(C, counts, K, d, round_half);
     }
     vpo_kmeans_step(X, n, d, C, K, NULL, assign, counts, NULL, objective ? objective + iters : NULL);
     for (size_t e = 0; e < (size_t)K * d; ++e) {

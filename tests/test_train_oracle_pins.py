@@ -144,6 +144,37 @@ def test_forced_membership(oracle):
     assert st["objective"] > free["objective"]
 
 
+def test_split_of_empty_clusters(oracle):
+    # hand case: clusters 1 and 3 are empty; 0 has 7 members, 2 has 4.  Cluster 1 splits cluster 0 (7 -> 4 + 3),
+    # then the sizes are 4, 3, 4, 0: cluster 3 splits the lowest of the largest, cluster 0 again (4 -> 2 + 2).
+    C = np.array([[1.0, -2.0], [9.0, 9.0], [0.5, 0.25], [7.0, 7.0]])
+    counts = np.array([7, 0, 4, 0], np.int32)
+    eps = 2.0 ** -10
+    Cn, cn = oracle.split_empty(C, counts, round_half=False)
+    assert cn.tolist() == [2, 3, 4, 2]
+    once = C[0] * (1 - eps)
+    assert np.array_equal(Cn[1], C[0] * (1 + eps)) and np.array_equal(Cn[3], once * (1 + eps))
+    assert np.array_equal(Cn[0], once * (1 - eps)) and np.array_equal(Cn[2], C[2])
+    # rounded form: each product goes through the library cast
+    Ch, _ = oracle.split_empty(C, counts, round_half=True)
+    h = lambda v: v.astype(np.float16).astype(np.float64)
+    assert np.array_equal(Ch[1], h(C[0] * (1 + eps)))
+    assert np.array_equal(Ch[3], h(h(C[0] * (1 - eps)) * (1 + eps)))
+    # nothing to split from: a single member cannot be shared
+    Cs, cs = oracle.split_empty(np.ones((3, 2)), np.array([1, 0, 0], np.int32))
+    assert cs.tolist() == [1, 0, 0] and np.all(Cs == 1.0)
+
+
+def test_training_with_the_split_leaves_no_empty_cluster(oracle):
+    X, C0 = _mixture(9, n=800, d=10, K=8)
+    C0 = np.concatenate([C0, np.full((2, 10), 30.0, np.float16)])        # two centroids nobody is near
+    plain = oracle.kmeans(X, C0, 15, round_half=True, split_empty=False)
+    split = oracle.kmeans(X, C0, 15, round_half=True, split_empty=True)
+    assert (plain["counts"] == 0).sum() == 2 and (split["counts"] == 0).sum() == 0
+    assert split["objective"][-1] < plain["objective"][-1]
+    assert split["counts"].sum() == 800
+
+
 # ------------------------------------------------------------------ active sets
 def test_active_set_worked_example(oracle):
     members, rows = [], {}
