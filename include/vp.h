@@ -197,10 +197,17 @@ vp_status vp_get_profile(vp_index *idx, double *kernel_ms_total, int64_t *launch
  *   assign     device, int32 [n]: cluster of every vector under the final centroids
  *   counts     device, int32 [K]: members per cluster under the final centroids
  *   workspace  device, 256-byte aligned, >= vp_kmeans_workspace_bytes(n, d, K)
+ *   flags      0, or VP_KMEANS_SPLIT_EMPTY: after every iteration the clusters without
+ *              members, in ascending order, each take the cluster with the most members
+ *              at that moment (ties: lowest index; at least two members), whose centroid
+ *              c becomes c (1 - 2^-10) while c (1 + 2^-10), both rounded to fp16, goes to
+ *              the empty cluster, and half of whose member count moves with it (the paper
+ *              names no remedy for such clusters; this is the usual one made deterministic)
  * Only enqueues kernels.  Limits: d % 8 == 0, 8 <= d <= 4096, 1 <= K <= 4096,
  * 1 <= n < 2^31, 0 <= iters <= 1000. */
+#define VP_KMEANS_SPLIT_EMPTY 1u
 size_t vp_kmeans_workspace_bytes(int64_t n, int32_t d, int32_t K);
-vp_status vp_kmeans(const void *x, int64_t n, int32_t d, int32_t K, int32_t iters, void *centroids,
+vp_status vp_kmeans(const void *x, int64_t n, int32_t d, int32_t K, int32_t iters, uint32_t flags, void *centroids,
                     int32_t *assign, int32_t *counts, void *workspace, size_t workspace_bytes,
                     void *hip_stream);
 

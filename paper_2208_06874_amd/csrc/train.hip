@@ -382,6 +382,82 @@ __global__ __launch_bounds__(256) void kmeans_update_kernel(unsigned long long *
     acc[e] = 0ull;
 }
 
+// binary16 bits -> double, exactly
+__device__ inline double half_bits_to_double(uint32_t h)
+{
+    const _Float16 v = __builtin_bit_cast(_Float16, (unsigned short)h);
+    return (double)(float)v;
+}
+
+// Optional remedy for clusters without members: in ascending order each takes the cluster that
+// has the most members at that moment (ties: lowest index; at least two members), whose centroid
+// c becomes c (1 - 2^-10) while c (1 + 2^-10) goes to the empty cluster; half of the members
+// (rounded down) are counted for the new cluster.  One workgroup; cnt lives in LDS.
+__global__ __launch_bounds__(1024) void kmeans_split_kernel(const int32_t *__restrict__ counts, int K, int d,
+                                                            uint16_t *__restrict__ C)
+{
+    extern __shared__ int cnt[];   // [K]
+    __shared__ int red_c[16], red_i[16];
+    __shared__ int big_s, any_empty;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid == 0) any_empty = 0;
+    __syncthreads();
+    for (int j = tid; j < K; j += 1024) {
+        cnt[j] = counts[j];
+        if (cnt[j] == 0) any_empty = 1;
+    }
+    __syncthreads();
+    if (!any_empty) return;
+    const double eps = 0x1p-10;
+    for (int j = 0; j < K; ++j) {
+        if (cnt[j] != 0) continue;          // uniform: every thread reads the same LDS word
+        int bc = -1, bi = 0x7fffffff;       // largest count, lowest index
+        for (int i = tid; i < K; i += 1024) {
+            if (cnt[i] > bc) {
+                bc = cnt[i];
+                bi = i;
+            }
+        }
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int c2 = __shfl_xor(bc, off), i2 = __shfl_xor(bi, off);
+            if (c2 > bc || (c2 == bc && i2 < bi)) {
+                bc = c2;
+                bi = i2;
+            }
+        }
+        if (lane == 0) {
+            red_c[wave] = bc;
+            red_i[wave] = bi;
+        }
+        __syncthreads();
+        if (tid == 0) {
+            for (int w = 1; w < 16; ++w) {
+                if (red_c[w] > bc || (red_c[w] == bc && red_i[w] < bi)) {
+                    bc = red_c[w];
+                    bi = red_i[w];
+                }
+            }
+            big_s = bc >= 2 ? bi : -1;
+        }
+        __syncthreads();
+        const int big = big_s;
+        if (big < 0) return;                // nothing left to split (uniform)
+        for (int e = tid; e < d; e += 1024) {
+            const double c = half_bits_to_double(C[(size_t)big * d + e]);
+            C[(size_t)j * d + e] = double_to_half_bits(c * (1.0 + eps));
+            C[(size_t)big * d + e] = double_to_half_bits(c * (1.0 - eps));
+        }
+        __syncthreads();
+        if (tid == 0) {
+            const int c = cnt[big];
+            cnt[j] = c / 2;
+            cnt[big] = c - c / 2;
+        }
+        __syncthreads();
+    }
+}
+
 __global__ void fill_u32_kernel(uint32_t *__restrict__ p, size_t n, uint32_t v)
 {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -537,6 +613,12 @@ void vpk_kmeans_update(const void *X, int d, const int32_t *perm, const int32_t 
     const size_t e = (size_t)K * d;
     hipLaunchKernelGGL(kmeans_update_kernel, dim3((unsigned)((e + 255) / 256)), dim3(256), 0, st,
                        (unsigned long long *)acc, counts, K, d, (uint16_t *)C);
+}
+
+void vpk_kmeans_split(const int32_t *counts, int K, int d, void *C, hipStream_t st)
+{
+    hipLaunchKernelGGL(kmeans_split_kernel, dim3(1), dim3(1024), (size_t)K * sizeof(int), st, counts, K, d,
+                       (uint16_t *)C);
 }
 
 void vpk_aset_flags(const int32_t *top, const int32_t *assign, long n, int T, int K, int V, int words,

@@ -61,10 +61,11 @@ size_t vp_kmeans_workspace_bytes(int64_t n, int32_t d, int32_t K)
     return L.total;
 }
 
-vp_status vp_kmeans(const void *x, int64_t n, int32_t d, int32_t K, int32_t iters, void *centroids,
+vp_status vp_kmeans(const void *x, int64_t n, int32_t d, int32_t K, int32_t iters, uint32_t flags, void *centroids,
                     int32_t *assign, int32_t *counts, void *workspace, size_t workspace_bytes,
                     void *hip_stream)
 {
+    if (flags & ~(uint32_t)VP_KMEANS_SPLIT_EMPTY) return (vp_status)vpi_fail(VP_ERR_INVALID_ARG, "vp_kmeans: unknown flags 0x%x", flags);
     KmeansLayout L;
     vp_status s = kmeans_layout(n, d, K, &L);
     if (s != VP_OK) return s;
@@ -101,6 +102,7 @@ vp_status vp_kmeans(const void *x, int64_t n, int32_t d, int32_t K, int32_t iter
         if (it == iters) break;   // the last pass only assigns
         vpk_kmeans_bucket(assign, (long)n, counts, K, start, cursor, perm, st);
         vpk_kmeans_update(x, d, perm, start, counts, K, splits, acc, centroids, st);
+        if (flags & VP_KMEANS_SPLIT_EMPTY) vpk_kmeans_split(counts, K, d, centroids, st);
     }
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return (vp_status)vpi_fail(VP_ERR_HIP, "vp_kmeans: %s", hipGetErrorString(e));

@@ -82,6 +82,7 @@ void vpk_kmeans_bucket(const int32_t *assign, long n, const int32_t *counts, int
                        int32_t *perm, hipStream_t st);
 void vpk_kmeans_update(const void *X, int d, const int32_t *perm, const int32_t *start, const int32_t *counts, int K,
                        int splits, void *acc, void *C, hipStream_t st);
+void vpk_kmeans_split(const int32_t *counts, int K, int d, void *C, hipStream_t st);
 void vpk_aset_flags(const int32_t *top, const int32_t *assign, long n, int T, int K, int V, int words,
                     uint32_t *bitmaps, int32_t *sizes, int64_t *cand_off, hipStream_t st);
 void vpk_aset_emit(const uint32_t *bitmaps, int words, int K, const int64_t *cand_off, int32_t *cand_ids,

@@ -88,8 +88,8 @@ def lib():
         L.vp_kmeans_workspace_bytes.restype = ctypes.c_size_t
         L.vp_kmeans_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32]
         L.vp_kmeans.restype = ctypes.c_int
-        L.vp_kmeans.argtypes = [vp, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp, vp, vp, vp,
-                                ctypes.c_size_t, vp]
+        L.vp_kmeans.argtypes = [vp, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_uint32, vp, vp,
+                                vp, vp, ctypes.c_size_t, vp]
         L.vp_active_sets_workspace_bytes.restype = ctypes.c_size_t
         L.vp_active_sets_workspace_bytes.argtypes = [ctypes.c_int32, ctypes.c_int32]
         L.vp_active_sets.restype = ctypes.c_int
@@ -316,7 +316,10 @@ def vp_round_to_half(v: float) -> int:
     return int(lib().vp_round_to_half(float(v)))
 
 
-def vp_kmeans(X, centroids, iters: int = 20, workspace=None, stream=None):
+KMEANS_SPLIT_EMPTY = 1
+
+
+def vp_kmeans(X, centroids, iters: int = 20, workspace=None, stream=None, split_empty: bool = False):
     """vp_kmeans: trains `centroids` (fp16 [K, d], updated in place) on X (fp16 [n, d]).
     Returns (assign int32 [n], counts int32 [K]) under the final centroids."""
     import torch
@@ -332,7 +335,8 @@ def vp_kmeans(X, centroids, iters: int = 20, workspace=None, stream=None):
         workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
     assign = torch.empty(n, dtype=torch.int32, device=X.device)
     counts = torch.empty(K, dtype=torch.int32, device=X.device)
-    _check(lib().vp_kmeans(X.data_ptr(), n, d, K, iters, centroids.data_ptr(), assign.data_ptr(), counts.data_ptr(),
+    _check(lib().vp_kmeans(X.data_ptr(), n, d, K, iters, KMEANS_SPLIT_EMPTY if split_empty else 0, centroids.data_ptr(),
+                           assign.data_ptr(), counts.data_ptr(),
                            workspace.data_ptr(), workspace.numel(), _stream(stream)))
     return assign, counts
 

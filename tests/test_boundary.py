@@ -121,11 +121,12 @@ def test_training_calls_reject_bad_arguments_on_the_host():
     assert L.vp_kmeans_workspace_bytes(0, 64, 10) == 0
     assert L.vp_kmeans_workspace_bytes(1000, 64, 5000) == 0
     assert L.vp_kmeans_workspace_bytes(2000, 64, 10) >= L.vp_kmeans_workspace_bytes(1000, 64, 10)
-    assert L.vp_kmeans(None, 10, 64, 4, 1, None, None, None, None, 0, None) == vp.VP_ERR_INVALID_ARG
-    assert L.vp_kmeans(0x1000, 10, 64, 4, -1, 0x1000, 0x1000, 0x1000, 0x1000, 1 << 30, None) == vp.VP_ERR_INVALID_ARG
-    assert L.vp_kmeans(0x1000, 10, 64, 4, 1, 0x1000, 0x1000, 0x1000, 0x1000, 16, None) == vp.VP_ERR_WORKSPACE
+    assert L.vp_kmeans(None, 10, 64, 4, 1, 0, None, None, None, None, 0, None) == vp.VP_ERR_INVALID_ARG
+    assert L.vp_kmeans(0x1000, 10, 64, 4, 1, 2, 0x1000, 0x1000, 0x1000, 0x1000, 1 << 30, None) == vp.VP_ERR_INVALID_ARG
+    assert L.vp_kmeans(0x1000, 10, 64, 4, -1, 0, 0x1000, 0x1000, 0x1000, 0x1000, 1 << 30, None) == vp.VP_ERR_INVALID_ARG
+    assert L.vp_kmeans(0x1000, 10, 64, 4, 1, 0, 0x1000, 0x1000, 0x1000, 0x1000, 16, None) == vp.VP_ERR_WORKSPACE
     assert "needed" in vp.last_error()
-    assert L.vp_kmeans(0x1008, 10, 64, 4, 1, 0x1000, 0x1000, 0x1000, 0x1000, 1 << 30, None) == vp.VP_ERR_INVALID_ARG
+    assert L.vp_kmeans(0x1008, 10, 64, 4, 1, 0, 0x1000, 0x1000, 0x1000, 0x1000, 1 << 30, None) == vp.VP_ERR_INVALID_ARG
     assert L.vp_active_sets_workspace_bytes(4, 100) > 0
     assert L.vp_active_sets_workspace_bytes(0, 100) == 0
     tot = ctypes.c_int64(0)

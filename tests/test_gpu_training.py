@@ -26,12 +26,12 @@ def _dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
 
 
-def _gpu_kmeans(X, C0, iters):
+def _gpu_kmeans(X, C0, iters, split_empty=False):
     """Returns (centroid bits uint16 [K, d], assign, counts) of vp_kmeans."""
     torch = _torch()
     from paper_2208_06874_amd import vp
     Xt, Ct = _dev(X), _dev(C0.copy())
-    assign, counts = vp.vp_kmeans(Xt, Ct, iters)
+    assign, counts = vp.vp_kmeans(Xt, Ct, iters, split_empty=split_empty)
     torch.cuda.synchronize()
     return pu.to_np(Ct).view(np.uint16), pu.to_np(assign), pu.to_np(counts)
 
@@ -93,6 +93,40 @@ def test_twenty_iterations_and_determinism(oracle):
     # the training must have improved on the start
     assert ref["objective"][-1] < ref["objective"][0]
     print("twenty iterations:", outcome, "excused", excused)
+
+
+@pytest.mark.parametrize("name,n,scale,lost", [("tiny", 3000, dict(d=72, K=9), 3), ("mid", 6000, dict(K=300, d=264), 40),
+                                               ("tiny", 5000, dict(K=1100, d=64), 500), ("tiny", 40, dict(K=30, d=32), 25)])
+def test_split_of_clusters_without_members(oracle, name, n, scale, lost):
+    """Centroids that nobody is near lose their members in the first step; with the option set every
+    iteration ends with the oracle's split of the largest clusters, bit for bit."""
+    cfg, X, _q, C0 = _mixture(name, n, **scale)
+    C0 = C0.copy()
+    far = np.random.default_rng(lost).choice(C0.shape[0], lost, replace=False)
+    C0[far] = np.float16(200.0)
+    Cb = C0.view(np.uint16).copy()
+    K = Cb.shape[0]
+    for step in range(6):
+        print("split", name, n, scale, "step", step, flush=True)
+        _same, assign, counts = _gpu_kmeans(X, Cb.view(np.float16), 0)
+        _check_membership(oracle, X, Cb, assign)
+        new, _a2, _c2 = _gpu_kmeans(X, Cb.view(np.float16), 1, split_empty=True)
+        st = oracle.kmeans_step(X, Cb.view(np.float16).astype(np.float64), forced=assign)
+        rounded = st["C"].astype(np.float16).astype(np.float64)
+        want, cn = oracle.split_empty(rounded, st["counts"], round_half=True)
+        if step == 0:
+            assert (st["counts"] == 0).sum() >= lost
+            plain, _a3, _c3 = _gpu_kmeans(X, Cb.view(np.float16), 1)
+            assert np.array_equal(plain, rounded.astype(np.float16).view(np.uint16)), "flag off: centroids stay"
+        assert cn.sum() == n
+        want = want.astype(np.float16).view(np.uint16)
+        assert np.array_equal(new, want), "step %d: %d coordinates differ" % (step, (new != want).sum())
+        Cb = new
+    _same, assign, counts = _gpu_kmeans(X, Cb.view(np.float16), 0)
+    empty_now = int((counts == 0).sum())
+    print("split", name, "clusters without members after 6 iterations:", empty_now, "of", K)
+    if n >= 2 * K:
+        assert empty_now < lost
 
 
 def test_ties_round_to_even_for_every_pair_of_neighbours(oracle):
