@@ -153,7 +153,8 @@ def main():
     t_gen = time.perf_counter()
     W, b, C = wl.make_model(cfg)
     cand_off, cand_ids = wl.make_candidates(cfg, W, b, C, device="cuda:0")
-    index = P.vp_build(torch.from_numpy(W).to(dev), torch.from_numpy(b).to(dev), torch.from_numpy(C).to(dev),
+    Wt = torch.from_numpy(W).to(dev)   # kept for the library-GEMM reference beside the full projection
+    index = P.vp_build(Wt, torch.from_numpy(b).to(dev), torch.from_numpy(C).to(dev),
                        cand_off, cand_ids, k_max=max(8, k))
     for opt in args.option:
         name, val = opt.split("=")
@@ -269,6 +270,19 @@ def main():
                                 "hbm_frac": full_bytes / (ms_full_kernel * 1e-3) / 1e9 / HBM_PEAK_GBS,
                                 "mfma_tflops": 2.0 * N * d * cfg.V / (ms_full_kernel * 1e-3) / 1e12}
         result["speedup_vs_full"] = ms_full / ms_step
+        # Outside reference, context only: the bare [N, d] x [d, V] product of the vendor GEMM library
+        # (through torch.matmul; it writes [N, V] logits and does no bias, softmax or top-k).
+        lib_out = torch.empty((N, cfg.V), dtype=torch.float16, device=dev)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for i in range(3):
+            torch.matmul(batches[i % len(batches)], Wt, out=lib_out)
+        e0.record()
+        for i in range(fsteps):
+            torch.matmul(batches[i % len(batches)], Wt, out=lib_out)
+        e1.record()
+        torch.cuda.synchronize()
+        result["full_vocab"]["library_gemm_only_ms"] = e0.elapsed_time(e1) / fsteps
+        del lib_out
 
     if not args.no_dispatch:
         # vp_project with the planner allowed to pick the masked full projection (same results)

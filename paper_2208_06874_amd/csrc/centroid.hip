@@ -6,9 +6,13 @@
 // four lane groups of the wavefront are reduced with cross-lane shuffles and
 // the four wavefronts of the workgroup through LDS.  The centroids are split
 // into `parts` ranges handled by different workgroups so that small batches
-// still fill the chip; the planning kernel reduces the per-part minima.
+// still fill the chip; the planner reduces the per-part minima.  For batches
+// of at most 64 rows the planner runs in this kernel, in whichever workgroup
+// finishes last (a device-wide ticket counts them): one launch fewer in the
+// chain of dependent kernels that bounds the time of a small call.
 #include <hip/hip_runtime.h>
 #include "vp_kernels.h"
+#include "plan_common.h"
 
 namespace {
 
@@ -30,7 +34,7 @@ __device__ inline bool score_less(float s, int j, float s2, int j2)
 __global__ __launch_bounds__(256) void centroid_kernel(
     const uint4 *__restrict__ hidden, int N, int d, const uint4 *__restrict__ cp,
     const float *__restrict__ cnorm, int K, int kt_count, int ctiles, int tiles_per_wave, int parts,
-    int2 *__restrict__ cpart)
+    int2 *__restrict__ cpart, VpPlanArgs plan)
 {
     const int wave = threadIdx.x >> 6;
     const int lane = threadIdx.x & 63;
@@ -99,15 +103,39 @@ __global__ __launch_bounds__(256) void centroid_kernel(
         }
         cpart[(size_t)row * parts + part] = make_int2(__float_as_int(best_s), best_j);
     }
+    if (!plan.ticket) return;
+
+    // The workgroup that takes the last ticket plans the projection.  Release: the minima
+    // written above are made visible device-wide before the ticket is taken; acquire: the
+    // last workgroup drops what its caches may hold of the other workgroups' memory.
+    __shared__ int last;
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        __threadfence();
+        const unsigned int t = __hip_atomic_fetch_add(plan.ticket, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        last = t == (unsigned int)plan.total_wgs - 1u;
+        // every workgroup has its ticket: the counter goes back to zero for the next call
+        if (last) __hip_atomic_store(plan.ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    if (!last) return;
+    __threadfence();
+    vp_plan_small(cpart, parts, N, K, plan);
 }
 
 }  // namespace
 
 // parts: workgroups along the centroid axis; each of their 4 wavefronts takes tiles_per_wave tiles.
 void vpk_centroid(const void *hidden, int N, int d, const void *cp, const float *cnorm, int K, int kt,
-                  int ctiles, int tiles_per_wave, int parts, void *cpart, hipStream_t st)
+                  int ctiles, int tiles_per_wave, int parts, void *cpart, const VpPlanArgs *plan, hipStream_t st)
 {
     dim3 grid((N + 15) / 16, parts);
+    VpPlanArgs a = {};
+    if (plan) {
+        a = *plan;
+        a.total_wgs = (int)(grid.x * grid.y);
+    }
     hipLaunchKernelGGL(centroid_kernel, grid, dim3(256), 0, st, (const uint4 *)hidden, N, d, (const uint4 *)cp,
-                       cnorm, K, kt, ctiles, tiles_per_wave, parts, (int2 *)cpart);
+                       cnorm, K, kt, ctiles, tiles_per_wave, parts, (int2 *)cpart, a);
 }

@@ -127,24 +127,12 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(
     int total_tiles;
     block_exscan<int>(my_tiles, &total_tiles, wsum);
 
-    // Cost model: the occupied slabs are streamed once from HBM, further row groups of a
-    // bucket re-read them through the L2; the masked full projection streams W once and
-    // re-reads it through the L2 for every further group of 16 rows.  Both give the same
-    // results, so the cheaper one is taken.
+    // both forms give the same results, so the cheaper one is taken (cost model in plan_common.h)
     if (dispatch) {
         int occ_tiles;
         block_exscan<int>(my_occ_tiles, &occ_tiles, wsum);
         const int rpi_full = dispatch;   // rows per item of the masked projection (16 or 64)
-        const int rgs_full = ceil_div(N, rpi_full);
-        const float t_slab = occ_tiles / cost.bw_slab + (total_tiles - occ_tiles) / cost.bw_l2;
-        // The top-k lists cost the full projection more than the slabs (every lane of every
-        // wavefront is busy there): a margin that grows with k keeps the choice on the safe side.
-        // 64-row items: one pass from HBM, each further row group at the measured rate of the
-        // GEMM-shaped kernel.  16-row items: every row group re-reads W through the L2.
-        const float t_full = rpi_full == 64
-            ? (vtiles / cost.bw_full + (rgs_full - 1) * (vtiles / cost.bw_gemm)) * (1.f + k * 0.0625f)
-            : fmaxf(vtiles / cost.bw_full, (float)rgs_full * vtiles / cost.bw_l2) * (1.f + k * 0.125f);
-        if (t_full < t_slab) {
+        if (vp_full_is_cheaper(occ_tiles, total_tiles, N, rpi_full, vtiles, k, cost)) {
             __syncthreads();
             vp_plan_single_bucket(N, V, vtiles, rpi_full, full_target_items, full_min_items, max_items_full, perm,
                                   rowplan, floors, items, hdr, nullptr, tid, PLAN_THREADS);

@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -29,6 +30,8 @@ vp_status fail(vp_status st, const char *fmt, ...)
 
 constexpr size_t ALIGN = 256;
 constexpr size_t LDS_LIMIT = 160 * 1024;
+constexpr int FUSED_PLAN_MAX_ITEMS = 2048;
+constexpr size_t TICKETS = 1024;   // counters of the fused planner an index owns
 inline size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 inline int ceil_div(long a, long b) { return (int)((a + b - 1) / b); }
@@ -39,7 +42,7 @@ struct ArenaLayout {
     long total_groups;     // candidate groups (of 16) over all clusters
     long n_total;
     int n_min, n_max, max_tiles;
-    size_t wp, biasf, cp, cnorm, full_meta, tile_off, n_cand, ids_pad, sbias, bitmaps, slabs, total;
+    size_t wp, biasf, cp, cnorm, full_meta, tile_off, n_cand, ids_pad, sbias, bitmaps, tickets, slabs, total;
     int bm_words;
 };
 
@@ -77,6 +80,11 @@ struct vp_index {
     int dispatch;    // 1: the planner may choose the masked full projection (same results)
     VpCostModel cost;
     const uint32_t *bitmaps;
+    int fused_plan;   // 1: batches of at most 64 rows are planned inside the Eq. 2 kernel
+    // Counters of finished workgroups for that, zero between calls; calls take them in turn, so
+    // a counter is shared only by calls TICKETS apart.
+    uint32_t *tickets;
+    mutable std::atomic<uint32_t> call_seq;
     VpProfile *prof;
 };
 
@@ -148,6 +156,7 @@ vp_status plan_arena(const vp_build_desc *D, bool check_ids, ArenaLayout *L)
     L->sbias = take((size_t)groups * VP_TILE_ITEMS * sizeof(float));
     L->bm_words = ceil_div((long)L->vtiles * VP_TILE_ITEMS, 32);
     L->bitmaps = take((size_t)D->K * L->bm_words * sizeof(uint32_t));
+    L->tickets = take(TICKETS * sizeof(uint32_t));
     L->slabs = take((size_t)groups * group_bytes);
     L->total = o;
     return VP_OK;
@@ -280,7 +289,6 @@ vp_status run_clustered(const char *fn, const vp_index *I, const void *hidden, i
     int parts = std::min(ceil_div(I->L.ctiles, 4), std::max(1, 2048 / (4 * row_tiles)));
     const int tpw_c = ceil_div(I->L.ctiles, parts * 4);
     parts = ceil_div(I->L.ctiles, tpw_c * 4);
-    vpk_centroid(hidden, N, I->d, I->cp, I->cnorm, I->K, I->L.kt, I->L.ctiles, tpw_c, parts, cpart, st);
 
     const int max_items = max_items_clustered(I, N);
     // the debug entry lays its logits out per cluster list, so it always takes the slabs
@@ -295,13 +303,43 @@ vp_status run_clustered(const char *fn, const vp_index *I, const void *hidden, i
     cost.bw_full /= tile_bytes;
     cost.bw_l2 /= tile_bytes;
     cost.bw_gemm /= tile_bytes;
-    vpk_plan(cpart, parts, N, I->K, I->clusters.n_cand, I->clusters.tile_off, I->target_items, I->min_items, max_items, g,
-             out_cluster, perm, rowplan, floors, items, hdr, dbg_row_off, dispatch, cost, k, I->V, I->L.vtiles,
-             sb_target(I, rt_masked), sb_min(I, rt_masked), max_full, st);
-
     const long row_groups = (long)row_tiles + std::min(N, I->K);
     const long by_tiles = row_groups * ceil_div(I->L.max_tiles, VP_WG_WAVES);
     const int grid_items = (int)std::min<long>(max_items, by_tiles);
+    // Eq. 2, then the plan: inside the same kernel for small batches with few items, where one
+    // workgroup of 256 threads writes the item list as fast as the planning kernel's 1024 (and
+    // not for the debug entry, which also wants the offsets of the rows' logits)
+    if (N <= VP_PLAN_SMALL_ROWS && grid_items <= FUSED_PLAN_MAX_ITEMS && I->fused_plan && !dbg_row_off) {
+        VpPlanArgs a = {};
+        a.n_cand = I->clusters.n_cand;
+        a.tile_off = I->clusters.tile_off;
+        a.target_items = I->target_items;
+        a.min_items = I->min_items;
+        a.max_items = max_items;
+        a.g = g;
+        a.out_cluster = out_cluster;
+        a.perm = perm;
+        a.rowplan = rowplan;
+        a.floors = floors;
+        a.items = items;
+        a.hdr = hdr;
+        a.dispatch = dispatch;
+        a.cost = cost;
+        a.k = k;
+        a.V = I->V;
+        a.vtiles = I->L.vtiles;
+        a.full_target_items = sb_target(I, rt_masked);
+        a.full_min_items = sb_min(I, rt_masked);
+        a.max_items_full = max_full;
+        a.ticket = I->tickets + (I->call_seq.fetch_add(1, std::memory_order_relaxed) % TICKETS);
+        vpk_centroid(hidden, N, I->d, I->cp, I->cnorm, I->K, I->L.kt, I->L.ctiles, tpw_c, parts, cpart, &a, st);
+    } else {
+        vpk_centroid(hidden, N, I->d, I->cp, I->cnorm, I->K, I->L.kt, I->L.ctiles, tpw_c, parts, cpart, nullptr, st);
+        vpk_plan(cpart, parts, N, I->K, I->clusters.n_cand, I->clusters.tile_off, I->target_items, I->min_items, max_items, g,
+                 out_cluster, perm, rowplan, floors, items, hdr, dbg_row_off, dispatch, cost, k, I->V, I->L.vtiles,
+                 sb_target(I, rt_masked), sb_min(I, rt_masked), max_full, st);
+    }
+
     auto *ev = profile_slot(I);
     if (ev) (void)hipEventRecord(ev->first, st);
     vpk_project(I->clusters, hidden, I->d, perm, items, hdr, grid_items, 1, k, I->rstar, partials, floors, dbg_logits,
@@ -446,7 +484,8 @@ vp_status vp_build(const vp_build_desc *D, void *hip_stream, vp_index **out)
     vpk_cnorm(D->centroids, D->K, D->d, L.ctiles * VP_TILE_ITEMS, reinterpret_cast<float *>(A + L.cnorm), st);
     vpk_gather_slabs(A + L.wp, D->bias, L.kt, reinterpret_cast<const int32_t *>(A + L.ids_pad), L.total_groups,
                      A + L.slabs, reinterpret_cast<float *>(A + L.sbias), st);
-    e = hipMemsetAsync(A + L.bitmaps, 0, (size_t)D->K * L.bm_words * sizeof(uint32_t), st);
+    e = hipMemsetAsync(A + L.tickets, 0, TICKETS * sizeof(uint32_t), st);
+    if (e == hipSuccess) e = hipMemsetAsync(A + L.bitmaps, 0, (size_t)D->K * L.bm_words * sizeof(uint32_t), st);
     if (e != hipSuccess) return fail(VP_ERR_HIP, "vp_build: %s", hipGetErrorString(e));
     vpk_bitmaps(reinterpret_cast<const int32_t *>(A + L.ids_pad), reinterpret_cast<const int32_t *>(A + L.tile_off),
                 D->K, L.total_groups, L.bm_words, reinterpret_cast<uint32_t *>(A + L.bitmaps), st);
@@ -492,6 +531,9 @@ vp_status vp_build(const vp_build_desc *D, void *hip_stream, vp_index **out)
     I->cost.bw_l2 = 17.0e12f;
     I->cost.bw_gemm = 12.0e12f;
     I->bitmaps = reinterpret_cast<const uint32_t *>(A + L.bitmaps);
+    I->fused_plan = 1;
+    I->tickets = reinterpret_cast<uint32_t *>(A + L.tickets);
+    I->call_seq.store(0);
     {
         // workgroups of the projection kernel that fit on the chip at once (LDS-limited)
         int dev = 0, cus = 256;
@@ -536,6 +578,11 @@ vp_status vp_set_option(vp_index *I, const char *name, int64_t value)
             return fail(VP_ERR_INVALID_ARG, "vp_set_option: rstar = %lld must be in [0, %d]", (long long)value,
                         VP_GEMV_MAX_ROWS);
         I->rstar = (int)value;
+        return VP_OK;
+    }
+    if (!std::strcmp(name, "fused_plan")) {
+        if (value != 0 && value != 1) return fail(VP_ERR_INVALID_ARG, "vp_set_option: fused_plan must be 0 or 1");
+        I->fused_plan = (int)value;
         return VP_OK;
     }
     if (!std::strcmp(name, "dispatch")) {
@@ -687,7 +734,7 @@ vp_status vp_project_union(const vp_index *I, const void *hidden, int32_t N, int
     int parts = std::min(ceil_div(I->L.ctiles, 4), std::max(1, 2048 / (4 * row_tiles)));
     const int tpw_c = ceil_div(I->L.ctiles, parts * 4);
     parts = ceil_div(I->L.ctiles, tpw_c * 4);
-    vpk_centroid(hidden, N, I->d, I->cp, I->cnorm, I->K, I->L.kt, I->L.ctiles, tpw_c, parts, cpart, st);
+    vpk_centroid(hidden, N, I->d, I->cp, I->cnorm, I->K, I->L.kt, I->L.ctiles, tpw_c, parts, cpart, nullptr, st);
     // step 2: boolean list over the vocabulary -> reduced column set U
     vpk_union_mark(cpart, parts, N, I->K, U.mask_words, g, out_cluster, occ, uh, mask, st);
     vpk_union_flags(occ, uh, I->bitmaps, I->L.bm_words, U.mask_words, mask, st);

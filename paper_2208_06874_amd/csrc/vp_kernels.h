@@ -18,7 +18,7 @@ void vpk_bitmaps(const int32_t *ids_pad, const int32_t *tile_off, int K, long to
 
 // centroid selection (Eq. 2)
 void vpk_centroid(const void *hidden, int N, int d, const void *cp, const float *cnorm, int K, int kt,
-                  int ctiles, int tiles_per_part, int parts, void *cpart, hipStream_t st);
+                  int ctiles, int tiles_per_part, int parts, void *cpart, const VpPlanArgs *plan, hipStream_t st);
 
 // bucketing + planning
 size_t vpk_plan_lds_bytes(int K);

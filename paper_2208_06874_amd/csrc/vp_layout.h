@@ -116,6 +116,27 @@ struct VpCostModel {
     float bw_gemm;   // further passes over W by 64-row items of the GEMM-shaped kernel
 };
 
+#define VP_PLAN_SMALL_ROWS 64   // batches up to this size can be planned inside the Eq. 2 kernel
+
+// Everything the planner needs besides the per-part minima of Eq. 2.
+struct VpPlanArgs {
+    const int32_t *n_cand;
+    const int32_t *tile_off;
+    int target_items, min_items, max_items;
+    int32_t *g;
+    int32_t *out_cluster;
+    int32_t *perm;
+    VpRowPlan *rowplan;
+    unsigned int *floors;
+    VpItem *items;
+    VpPlanHeader *hdr;
+    int32_t dispatch;    // 0, or rows per item of the masked full projection the planner may choose
+    VpCostModel cost;
+    int k, V, vtiles, full_target_items, full_min_items, max_items_full;
+    unsigned int *ticket;   // counts the workgroups of the Eq. 2 kernel that are done (null: separate planning kernel)
+    int total_wgs;
+};
+
 // Size in floats of one partial result: running max, sum of exponentials, then
 // k logits and k candidate positions.
 static inline __host__ __device__ int vp_partial_floats(int k) { return 2 + 2 * k; }
