@@ -123,6 +123,8 @@ def main():
                          "per vector (a synthetic analogue of the paper's section 3.5) and time vp_project on each")
     ap.add_argument("--train-vectors", type=int, default=131072, help="recorded vectors of the cluster-training leg")
     ap.add_argument("--option", action="append", default=[], help="library option name=value")
+    ap.add_argument("--streams", type=int, default=0,
+                    help="also time S independent call chains on S HIP streams (own workspace and outputs each)")
     ap.add_argument("--graph", action="store_true",
                     help="replay each step from a captured HIP graph (one graph per batch) instead of launching it")
     ap.add_argument("--single-cluster", action="store_true",
@@ -258,6 +260,42 @@ def main():
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": ms_kernel, "launches": launches},
     }
+
+    if args.streams > 1:
+        # Independent calls (say, different requests of a server) overlapped on several streams of the
+        # default priority: a call of a few rows leaves most of the chip idle between its dependent kernels.
+        S = args.streams
+        streams = [torch.cuda.Stream(device=dev) for _ in range(S)]
+        # one workspace per chain: index.workspace() hands out the index's one cached buffer, and calls
+        # that share a workspace must not overlap
+        s_ws = [torch.empty(index.workspace_bytes(N), dtype=torch.uint8, device=dev) for _ in range(S)]
+        assert len({w.data_ptr() for w in s_ws} | {ws.data_ptr()}) == S + 1
+        s_ids = [torch.empty((N, k), dtype=torch.int32, device=dev) for _ in range(S)]
+        s_logp = [torch.empty((N, k), dtype=torch.float32, device=dev) for _ in range(S)]
+        s_g = [torch.empty((N,), dtype=torch.int32, device=dev) for _ in range(S)]
+
+        def chains(steps):
+            for i in range(steps):
+                for si, st in enumerate(streams):
+                    with torch.cuda.stream(st):
+                        index.project(batches[(i * S + si) % len(batches)], k, out_ids=s_ids[si], out_logp=s_logp[si],
+                                      out_cluster=s_g[si], workspace=s_ws[si])
+        chains(max(2, args.warmup // 2))
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        chains(args.steps)
+        torch.cuda.synchronize()
+        ms_all = (time.perf_counter() - t0) * 1e3 / args.steps
+        # the last call of chain 0 against the same batch on the default stream
+        j_last = ((args.steps - 1) * S) % len(batches)
+        step(j_last)
+        torch.cuda.synchronize()
+        same = bool(torch.equal(s_ids[0], out_ids[j_last]) and torch.equal(s_logp[0], out_logp[j_last]))
+        result["concurrent_streams"] = {"streams": S, "ms_per_round_of_calls": ms_all,
+                                        "rows_per_s": S * N / (ms_all * 1e-3),
+                                        "speedup_vs_one_stream": S * ms_step / ms_all,
+                                        "matches_single_stream": same}
+        del s_ws, s_ids, s_logp, s_g
 
     if not args.no_full:
         full_ids = torch.empty((N, k), dtype=torch.int32, device=dev)

@@ -137,7 +137,9 @@ size_t vp_workspace_bytes(const vp_index *idx, int32_t N_max);
  *                the lowest index)
  *   workspace    device, 256-byte aligned, >= vp_workspace_bytes(idx, N)
  * N == 0 is a no-op returning VP_OK.  Calls that share a workspace must be
- * ordered on one stream. */
+ * ordered on one stream: a call that overlaps another on the same workspace
+ * reads half-written plans and may access memory out of bounds.  Calls with
+ * workspaces and outputs of their own may overlap on different streams. */
 vp_status vp_project(const vp_index *idx, const void *hidden, int32_t N, int32_t k,
                      int32_t *out_ids, float *out_logp, int32_t *out_cluster,
                      void *workspace, size_t workspace_bytes, void *hip_stream);

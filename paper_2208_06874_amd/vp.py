@@ -183,6 +183,9 @@ class Index:
         return lib().vp_workspace_bytes(self.handle, N)
 
     def workspace(self, N: int):
+        """The index's one cached scratch buffer, grown on demand; the calls below use it when no workspace
+        is passed.  Calls that share a workspace must not overlap: callers that run calls on several streams
+        at once allocate one buffer of workspace_bytes(N) per stream and pass it."""
         import torch
         need = self.workspace_bytes(N)
         if self._ws is None or self._ws.numel() < need:

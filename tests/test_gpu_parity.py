@@ -486,21 +486,25 @@ def test_dispatch_cost_model_constants(mid):
     assert np.array_equal(got[0], base[0])
 
 
-def test_replay_from_a_captured_graph(mid):
+@pytest.mark.parametrize("which,N", [("mid", 48), ("tiny", 7)])
+def test_replay_from_a_captured_graph(mid, tiny, which, N):
     """vp_project only enqueues kernels (no allocation, no synchronisation, no memset), so a call can be
-    captured into a HIP graph; every replay, with eager work in between, must equal the eager result."""
+    captured into a HIP graph; every replay, with eager work in between, must equal the eager result.  (The
+    small case has the planner inside the Eq. 2 kernel: its ticket counter is among the recorded arguments
+    and must be back at zero after every replay.)"""
     import torch
+    mid = mid if which == "mid" else tiny
     cfg = mid.cfg
-    H, q = wl.make_rows(cfg, mid.C, N=48, stream=5)
-    H2, _ = wl.make_rows(cfg, mid.C, N=48, stream=6)
+    H, q = wl.make_rows(cfg, mid.C, N=N, stream=5)
+    H2, _ = wl.make_rows(cfg, mid.C, N=N, stream=6)
     eager = mid.project(H, cfg.k)
     eager2 = mid.project(H2, cfg.k)
     dev = mid.dev
     hbuf = mid.rows(H)
-    ids = torch.empty((48, cfg.k), dtype=torch.int32, device=dev)
-    logp = torch.empty((48, cfg.k), dtype=torch.float32, device=dev)
-    g = torch.empty((48,), dtype=torch.int32, device=dev)
-    ws = torch.empty(mid.index.workspace_bytes(48), dtype=torch.uint8, device=dev)
+    ids = torch.empty((N, cfg.k), dtype=torch.int32, device=dev)
+    logp = torch.empty((N, cfg.k), dtype=torch.float32, device=dev)
+    g = torch.empty((N,), dtype=torch.int32, device=dev)
+    ws = torch.empty(mid.index.workspace_bytes(N), dtype=torch.uint8, device=dev)
     mid.index.project(hbuf, cfg.k, out_ids=ids, out_logp=logp, out_cluster=g, workspace=ws)   # warm-up
     torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()
@@ -798,3 +802,32 @@ def test_planner_inside_the_centroid_kernel(oracle, tiny, mid):
         out = tiny.index.project(Ht, 2)
     torch.cuda.synchronize()
     assert np.array_equal(pu.to_np(out[0]), base[0]) and np.array_equal(pu.to_np(out[1]), base[1])
+
+
+@pytest.mark.gpu
+def test_overlapping_calls_on_several_streams(tiny, mid):
+    """Calls on different streams, each with a workspace and outputs of its own, may overlap on one index
+    (the planner's ticket counters are handed out per call): every result equals the one-stream result."""
+    import torch
+    for B, N, k in ((tiny, 3, 4), (mid, 2, 8), (mid, 40, 8)):
+        dev = B.dev
+        S, rounds = 4, 40
+        Hs = [wl.make_rows(B.cfg, B.C, N=N, stream=500 + i)[0] for i in range(6)]
+        want = [B.project(H, k) for H in Hs]
+        hb = [B.rows(H) for H in Hs]
+        streams = [torch.cuda.Stream(device=dev) for _ in range(S)]       # default priority
+        wss = [torch.empty(B.index.workspace_bytes(N), dtype=torch.uint8, device=dev) for _ in range(S)]
+        assert len({w.data_ptr() for w in wss}) == S
+        outs = [[None] * rounds for _ in range(S)]
+        torch.cuda.synchronize()
+        for i in range(rounds):
+            for si, st in enumerate(streams):
+                with torch.cuda.stream(st):
+                    outs[si][i] = B.index.project(hb[(i * S + si) % len(hb)], k, workspace=wss[si])
+        torch.cuda.synchronize()
+        for i in range(rounds):
+            for si in range(S):
+                w = want[(i * S + si) % len(hb)]
+                got = outs[si][i]
+                assert np.array_equal(pu.to_np(got[0]), w[0]) and np.array_equal(pu.to_np(got[1]), w[1]), (N, i, si)
+                assert np.array_equal(pu.to_np(got[2]), w[2])
