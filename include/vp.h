@@ -113,12 +113,12 @@ vp_status vp_get_info(const vp_index *idx, vp_index_info *info);
  *   "gemm_target_items"  work items of that kernel (default 512)
  *   "wide_items"    1 (default): below gemm_min_rows, vp_project_full / vp_project_union
  *                   of more than 16 rows with k <= 2 put 32 rows in an item; 0: always 16
- *   "fused_plan"    1 (default): for batches of at most 64 rows the Eq. 2 kernel also
- *                   plans the projection (in the workgroup that finishes last), which
- *                   saves a kernel launch; 0: always the separate planning kernel.  Same
- *                   results.  The counters this uses belong to the index and are taken
- *                   in turn by its calls: at most 1024 calls on one index may be in
- *                   flight at once.
+ *   "fused_plan"    batches of at most this many rows (0..64, default 16) whose item list
+ *                   is short are planned inside the Eq. 2 kernel, by the workgroup that
+ *                   finishes last, which saves a kernel launch; 0: always the separate
+ *                   planning kernel.  Same results.  The counters this uses belong to
+ *                   the index and are taken in turn by its calls: at most 1024 calls on
+ *                   one index may be in flight at once.
  *   "profile"       1: time the projection kernel with HIP events (vp_get_profile)
  * Unknown name or out-of-range value: VP_ERR_INVALID_ARG. */
 vp_status vp_set_option(vp_index *idx, const char *name, int64_t value);

@@ -7,7 +7,7 @@
 // the four wavefronts of the workgroup through LDS.  The centroids are split
 // into `parts` ranges handled by different workgroups so that small batches
 // still fill the chip; the planner reduces the per-part minima.  For batches
-// of at most 64 rows the planner runs in this kernel, in whichever workgroup
+// of a few rows (at most 64) the planner can run in this kernel, in whichever workgroup
 // finishes last (a device-wide ticket counts them): one launch fewer in the
 // chain of dependent kernels that bounds the time of a small call.
 #include <hip/hip_runtime.h>

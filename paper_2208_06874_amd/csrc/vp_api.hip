@@ -80,7 +80,7 @@ struct vp_index {
     int dispatch;    // 1: the planner may choose the masked full projection (same results)
     VpCostModel cost;
     const uint32_t *bitmaps;
-    int fused_plan;   // 1: batches of at most 64 rows are planned inside the Eq. 2 kernel
+    int fused_plan;   // batches of at most this many rows (<= 64) are planned inside the Eq. 2 kernel
     // Counters of finished workgroups for that, zero between calls; calls take them in turn, so
     // a counter is shared only by calls TICKETS apart.
     uint32_t *tickets;
@@ -307,9 +307,9 @@ vp_status run_clustered(const char *fn, const vp_index *I, const void *hidden, i
     const long by_tiles = row_groups * ceil_div(I->L.max_tiles, VP_WG_WAVES);
     const int grid_items = (int)std::min<long>(max_items, by_tiles);
     // Eq. 2, then the plan: inside the same kernel for small batches with few items, where one
-    // workgroup of 256 threads writes the item list as fast as the planning kernel's 1024 (and
-    // not for the debug entry, which also wants the offsets of the rows' logits)
-    if (N <= VP_PLAN_SMALL_ROWS && grid_items <= FUSED_PLAN_MAX_ITEMS && I->fused_plan && !dbg_row_off) {
+    // workgroup of 256 threads is as fast as the planning kernel's 1024 and a launch is saved
+    // (not for the debug entry, which also wants the offsets of the rows' logits)
+    if (N <= I->fused_plan && grid_items <= FUSED_PLAN_MAX_ITEMS && !dbg_row_off) {
         VpPlanArgs a = {};
         a.n_cand = I->clusters.n_cand;
         a.tile_off = I->clusters.tile_off;
@@ -531,7 +531,7 @@ vp_status vp_build(const vp_build_desc *D, void *hip_stream, vp_index **out)
     I->cost.bw_l2 = 17.0e12f;
     I->cost.bw_gemm = 12.0e12f;
     I->bitmaps = reinterpret_cast<const uint32_t *>(A + L.bitmaps);
-    I->fused_plan = 1;
+    I->fused_plan = 16;
     I->tickets = reinterpret_cast<uint32_t *>(A + L.tickets);
     I->call_seq.store(0);
     {
@@ -581,7 +581,8 @@ vp_status vp_set_option(vp_index *I, const char *name, int64_t value)
         return VP_OK;
     }
     if (!std::strcmp(name, "fused_plan")) {
-        if (value != 0 && value != 1) return fail(VP_ERR_INVALID_ARG, "vp_set_option: fused_plan must be 0 or 1");
+        if (value < 0 || value > VP_PLAN_SMALL_ROWS)
+            return fail(VP_ERR_INVALID_ARG, "vp_set_option: fused_plan must be in [0, %d]", VP_PLAN_SMALL_ROWS);
         I->fused_plan = (int)value;
         return VP_OK;
     }

@@ -760,9 +760,22 @@ def test_random_shapes(oracle):
 
 @pytest.mark.gpu
 def test_planner_inside_the_centroid_kernel(oracle, tiny, mid):
-    """Batches of at most 64 rows are planned by the last workgroup of the Eq. 2 kernel: same results as with
-    the separate planning kernel and as the oracle, for every bucket structure and many calls in a row."""
+    """Batches of at most 64 rows (by default 16) can be planned by the last workgroup of the Eq. 2 kernel:
+    same results as with the separate planning kernel and as the oracle, for every bucket structure and many
+    calls in a row."""
+    import torch
     r = np.random.default_rng(64)
+
+    def run(B, H, k, fused, dispatch):
+        B.index.set_option("fused_plan", fused)
+        B.index.set_option("dispatch", dispatch)
+        try:
+            out = B.project(H, k)
+            return out, _planner_mode(B.index, H.shape[0])
+        finally:
+            B.index.set_option("fused_plan", 16)
+            B.index.set_option("dispatch", 0)
+
     for B in (tiny, mid):
         K = B.C.shape[0]
         for N, clusters in ((1, None), (2, [3, 3]), (5, None), (16, [1] * 16), (17, [2] * 17), (33, None),
@@ -771,33 +784,22 @@ def test_planner_inside_the_centroid_kernel(oracle, tiny, mid):
             cl = None if clusters is None else [c % K for c in clusters]
             H = _rows(r, B.C, N, clusters=cl)
             for k in (1, 4):
-                B.index.set_option("fused_plan", 0)
-                try:
-                    base = B.project(H, k)
-                finally:
-                    B.index.set_option("fused_plan", 1)
-                got = B.project(H, k)
+                print("fused planner:", B.cfg.name, "N", N, "k", k, flush=True)
+                base, _ = run(B, H, k, 0, 0)
+                got, _ = run(B, H, k, 64, 0)
                 assert np.array_equal(got[2], base[2]) and np.array_equal(got[0], base[0])
                 assert np.array_equal(got[1], base[1]), "same kernels, same item boundaries: same bits"
                 pu.check_projection(oracle, B.W, B.b, B.C, B.cand_off, B.cand_ids, H, k, got[0], got[1], got[2])
                 # with the planner free to choose the masked full projection
-                B.index.set_option("dispatch", 1)
-                try:
-                    d1 = B.project(H, k)
-                    mode = _planner_mode(B.index, N)
-                    B.index.set_option("fused_plan", 0)
-                    d0 = B.project(H, k)
-                    assert _planner_mode(B.index, N) == mode
-                finally:
-                    B.index.set_option("fused_plan", 1)
-                    B.index.set_option("dispatch", 0)
+                d1, mode1 = run(B, H, k, 64, 1)
+                d0, mode0 = run(B, H, k, 0, 1)
+                assert mode1 == mode0
                 assert np.array_equal(d1[0], d0[0]) and np.array_equal(d1[2], base[2])
                 pu.check_projection(oracle, B.W, B.b, B.C, B.cand_off, B.cand_ids, H, k, d1[0], d1[1], d1[2])
     # the counters return to zero: several thousand calls in a row, more than the index owns counters
     H = _rows(r, tiny.C, 7)
     base = tiny.project(H, 2)
     Ht = tiny.rows(H)
-    import torch
     for i in range(2500):
         out = tiny.index.project(Ht, 2)
     torch.cuda.synchronize()
