@@ -235,11 +235,15 @@ def main():
     # algorithmic bytes of one projection-kernel launch: every candidate of every occupied
     # cluster once (fp16 column + fp32 bias), plus the hidden rows
     d = cfg.d
-    per_batch, occupied = {}, {}
+    per_batch, occupied, call_bytes, call_flops = {}, {}, {}, {}
     for j in sorted({i % len(batches) for i in range(args.steps)}):   # the batches the timed steps used
         occ = np.unique(out_g[j].cpu().numpy())
         occupied[j] = occ.size
         per_batch[j] = float(sizes[occ].sum()) * (2 * d + 4) + N * 2 * d
+        # the whole call: slabs with bias and token ids, hidden rows, centroids with norms, outputs;
+        # Eq. 1 over every row's own list plus Eq. 2 over all centroids
+        call_bytes[j] = (float(sizes[occ].sum()) * (2 * d + 8) + N * 2 * d + cfg.K * (2 * d + 4) + N * k * 8)
+        call_flops[j] = 2.0 * d * float(sizes[out_g[j].cpu().numpy()].sum()) + 2.0 * N * cfg.K * d
     used = [per_batch[i % len(batches)] for i in range(args.steps)]
     alg_bytes = float(np.mean(used))
     achieved = alg_bytes / (ms_kernel * 1e-3) / 1e9
@@ -260,6 +264,13 @@ def main():
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": ms_kernel, "launches": launches},
     }
+
+    # lower bound of the whole call at the published peaks, and how close a step comes to it
+    cb = float(np.mean([call_bytes[i % len(batches)] for i in range(args.steps)]))
+    cf = float(np.mean([call_flops[i % len(batches)] for i in range(args.steps)]))
+    bound_ms = max(cb / (HBM_PEAK_GBS * 1e9), cf / 2.5e15) * 1e3
+    result["whole_call"] = {"bytes": cb, "flops": cf, "bound_ms": bound_ms, "frac_of_bound": bound_ms / ms_step,
+                            "bound": "hbm" if cb / (HBM_PEAK_GBS * 1e9) >= cf / 2.5e15 else "mfma"}
 
     if args.streams > 1:
         # Independent calls (say, different requests of a server) overlapped on several streams of the
