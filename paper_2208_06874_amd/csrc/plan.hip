@@ -110,7 +110,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(
 
     // exclusive scan of the histogram -> bucket offsets; total candidate tiles of all row groups
     int carry = 0;
-    int my_tiles = 0, my_occ_tiles = 0;
+    int my_tiles = 0, my_occ_tiles = 0, my_units = 0;
     for (int base = 0; base < K; base += PLAN_THREADS) {
         const int j = base + tid;
         const int c = j < K ? cnt[j] : 0;
@@ -119,13 +119,17 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(
         if (j < K) {
             off[j] = carry + ex;
             my_tiles += ceil_div(c, VP_ROWS_PER_ITEM) * tl[j];
+            my_units += ceil_div(c, VP_ROWS_PER_ITEM);
             if (c > 0) my_occ_tiles += tl[j];
         }
         carry += tot;
     }
     if (tid == 0) off[K] = carry;
-    int total_tiles;
-    block_exscan<int>(my_tiles, &total_tiles, wsum);
+    // (the (bucket, row group) units ride in the upper half of the same sum)
+    long long both;
+    block_exscan<long long>(((long long)my_units << 32) + my_tiles, &both, wsum64);
+    const int total_tiles = (int)(both & 0xffffffffll);
+    const int units = (int)(both >> 32);
 
     // both forms give the same results, so the cheaper one is taken (cost model in plan_common.h)
     if (dispatch) {
@@ -140,7 +144,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(
             return;
         }
     }
-    const int tpw = vp_tiles_per_wave(total_tiles, target_items, min_items);
+    const int tpw = vp_tiles_per_wave_units(total_tiles, units, target_items, min_items);
     const int tpi = tpw * VP_WG_WAVES;
 
     // items per bucket -> item offsets

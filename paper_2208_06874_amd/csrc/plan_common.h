@@ -170,10 +170,12 @@ __device__ inline void vp_plan_small(const int2 *cpart, int parts, int N, int K,
     const int rgs = ceil_div(same_total, VP_ROWS_PER_ITEM);
     int total_tiles = leader ? rgs * tl : 0;
     int occ_tiles = leader ? tl : 0;
+    int units = leader ? rgs : 0;
 #pragma unroll
     for (int off = 1; off < 64; off <<= 1) {
         total_tiles += __shfl_xor(total_tiles, off);
         occ_tiles += __shfl_xor(occ_tiles, off);
+        units += __shfl_xor(units, off);
     }
     if (a.dispatch && vp_full_is_cheaper(occ_tiles, total_tiles, N, a.dispatch, a.vtiles, a.k, a.cost)) {
         vp_plan_single_bucket(N, a.V, a.vtiles, a.dispatch, a.full_target_items, a.full_min_items, a.max_items_full,
@@ -181,7 +183,7 @@ __device__ inline void vp_plan_small(const int2 *cpart, int parts, int N, int K,
         if (tid == 0) a.hdr->mode = 1;
         return;
     }
-    const int tpw = vp_tiles_per_wave(total_tiles, a.target_items, a.min_items);
+    const int tpw = vp_tiles_per_wave_units(total_tiles, units, a.target_items, a.min_items);
     const int tpi = tpw * VP_WG_WAVES;
     const int nit = ceil_div(tl, tpi);
     const int c = leader ? rgs * nit : 0;

@@ -100,6 +100,23 @@ static inline __host__ __device__ int vp_tiles_per_wave(long long total_tiles, i
     return (int)(tpw > 1 ? tpw : 1);
 }
 
+// The same for the clustered plan, which also knows its number of (bucket, row group) units:
+// every unit ends with a partly filled item, so the plan has at most total / (4 tpw) + units
+// items.  When that lies between one and two times the resident workgroup slots (min_items),
+// the second round of workgroups would leave most of the chip idle (measured: 63 % against
+// 72 % of the HBM peak at 1.4 rounds), so the items are made just long enough for one round.
+static inline __host__ __device__ int vp_tiles_per_wave_units(long long total_tiles, int units, int target_items,
+                                                              int min_items)
+{
+    const int tpw = vp_tiles_per_wave(total_tiles, target_items, min_items);
+    const long long per = (long long)VP_WG_WAVES * tpw;
+    const long long items_ub = (total_tiles + per - 1) / per + units;
+    if (items_ub <= min_items || items_ub > 2LL * min_items || 2 * units >= min_items) return tpw;
+    const long long room = (long long)VP_WG_WAVES * (min_items - units);
+    const long long one_round = (total_tiles + room - 1) / room;
+    return (int)(one_round > tpw ? one_round : tpw);
+}
+
 // What the masked full projection needs besides the slab set: each row's cluster
 // and the per-cluster membership bit lists over the vocabulary.
 struct VpMaskInfo {
