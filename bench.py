@@ -90,12 +90,25 @@ def cluster_sweep(args, dev):
             ms = time_ms(lambda i: index.project(batches[i % 8], k, workspace=ws))
             hit = float(np.mean([(index.project(h, 1, workspace=ws)[0][:, 0] == fb).float().mean().item()
                                  for h, fb in zip(batches, full_best)]))
+            # the same batches through the paper's batch-union form and through the planner's choice
+            uws = torch.empty(index.union_workspace_bytes(N), dtype=torch.uint8, device=dev)
+            nu = torch.zeros(1, dtype=torch.int32, device=dev)
+            ms_union = time_ms(lambda i: index.project_union(batches[i % 8], k, out_union_size=nu, workspace=uws))
+            union_sizes = []
+            for h in batches:
+                index.project_union(h, k, out_union_size=nu, workspace=uws)
+                union_sizes.append(int(nu.item()))
+            index.set_option("dispatch", 1)
+            ms_disp = time_ms(lambda i: index.project(batches[i % 8], k, workspace=ws))
+            index.set_option("dispatch", 0)
             rows.append({"centroids": K, "clusters_with_members": with_members, "recorded_tokens": T,
                          "mean_active_fraction": float(sizes.mean() / cfg.V),
                          "max_active_fraction": float(sizes.max() / cfg.V), "ms_per_step": ms,
                          "rows_per_s": N / (ms * 1e-3), "speedup_vs_full": ms_full / ms,
-                         "top1_in_active_set": hit, "kmeans_20_iterations_ms": ms_train})
-            del index, ws
+                         "top1_in_active_set": hit, "kmeans_20_iterations_ms": ms_train,
+                         "union_form_ms_per_step": ms_union, "union_fraction": float(np.mean(union_sizes)) / cfg.V,
+                         "with_dispatch_ms_per_step": ms_disp})
+            del index, ws, uws
     return {"metric": "cluster sweep: centroids x recorded tokens -> active fraction, rows/s (N=64, top-1)",
             "workload": cfg.name, "noise": cfg.noise, "train_vectors": n_tr, "full_vocab_ms_per_step": ms_full, "data": "synthetic",
             "rows": rows}
