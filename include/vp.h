@@ -105,8 +105,11 @@ vp_status vp_get_info(const vp_index *idx, vp_index_info *info);
  *                   its own cluster's active set instead of streaming the occupied
  *                   slabs, when the planner's cost model says that is cheaper (many
  *                   occupied clusters); same results.  Default 0.
- *   "cost_bw_slab_gbs", "cost_bw_full_gbs", "cost_bw_l2_gbs", "cost_bw_gemm_gbs"
- *                   GB/s of the cost model
+ *   "cost_bw_slab_gbs", "cost_bw_full_gbs", "cost_bw_l2_gbs", "cost_bw_gemm_gbs",
+ *   "cost_bw_gather_gbs"   GB/s of the cost model
+ *   "union_dispatch" 1 (default): vp_project_union may skip the gather of U's columns and run
+ *                   the full projection with the batch's boolean list as every row's mask
+ *                   when the cost model says that is cheaper (large unions); same results
  *   "gemm_min_rows" projections that keep all rows in one bucket (full, masked, union)
  *                   use the kernel with 64 rows per work item from this many rows on
  *                   (default 17; 0: never); d_pad must be 256, 512, 1024, 1536 or 2048

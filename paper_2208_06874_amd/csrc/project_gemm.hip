@@ -329,7 +329,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && KW <= 8 ? 2 : 1)) void project
     const VpItem *__restrict__ items, const VpPlanHeader *__restrict__ hdr, int k,
     float *__restrict__ partials, unsigned int *__restrict__ bounds, VpMaskInfo mask)
 {
-    if (MASKED && hdr->mode != 1) return;
+    if (MASKED ? hdr->mode != 1 : hdr->mode != 0) return;   // the planner chose the other form
     const int total_items = hdr->total_items;
     const int it = item_of_workgroup(hdr);
     if (it < 0 || it >= total_items) return;

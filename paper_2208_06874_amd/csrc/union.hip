@@ -25,7 +25,7 @@ constexpr int UNION_THREADS = 1024;
 __global__ __launch_bounds__(UNION_THREADS) void union_prepare_kernel(
     const int2 *__restrict__ cpart, int parts, int N, int K, int mask_words, int32_t *__restrict__ g,
     int32_t *__restrict__ out_cluster, int32_t *__restrict__ occ, VpUnionHeader *__restrict__ uh,
-    unsigned int *__restrict__ mask)
+    unsigned int *__restrict__ mask, int32_t *__restrict__ zero_g)
 {
     extern __shared__ int seen[];   // [K]
     __shared__ int n_occ;
@@ -48,6 +48,7 @@ __global__ __launch_bounds__(UNION_THREADS) void union_prepare_kernel(
         if (bj < 0 || bj >= K) bj = 0;
         g[r] = bj;
         if (out_cluster) out_cluster[r] = bj;
+        zero_g[r] = 0;   // every row reads the one boolean list when the union is projected as a masked full projection
         seen[bj] = 1;
     }
     __syncthreads();
@@ -103,7 +104,8 @@ __global__ __launch_bounds__(UNION_THREADS) void union_compact_kernel(
     int32_t *__restrict__ bsum, int blocks, int N, int rpi, int target_items, int min_items, int max_items,
     int32_t *__restrict__ uids, VpUnionHeader *__restrict__ uh, int32_t *__restrict__ out_union_size,
     int32_t *__restrict__ perm, VpRowPlan *__restrict__ rowplan, unsigned int *__restrict__ floors,
-    VpItem *__restrict__ items, VpPlanHeader *__restrict__ hdr)
+    VpItem *__restrict__ items, VpPlanHeader *__restrict__ hdr, int allow_full, int V, int vtiles, int k,
+    VpCostModel cost, int max_items_full)
 {
     __shared__ int wsum[UNION_THREADS / 64 + 1];
     __shared__ int carry_s;
@@ -145,6 +147,24 @@ __global__ __launch_bounds__(UNION_THREADS) void union_compact_kernel(
         uh->n_union = nU;
         uh->tiles = tiles;
         if (out_union_size) *out_union_size = nU;
+    }
+    // A large union is cheaper projected in place: the full projection with the boolean list as
+    // every row's mask streams W once and gathers nothing (same results: tokens outside U are at
+    // -infinity either way).  Per candidate group the projection costs the same in both forms.
+    if (allow_full) {
+        const int rgs = ceil_div(N, rpi);
+        const float per_group = rpi >= 64 ? (1.f / cost.bw_full + (rgs - 1) / cost.bw_gemm) * (1.f + k * 0.0625f)
+                                          : fmaxf(1.f / cost.bw_full, rgs / cost.bw_l2) * (1.f + k * 0.125f);
+        const float t_union = cost.t_gather + tiles * (1.f / cost.bw_gather + per_group);
+        const float t_full = vtiles * per_group;
+        if (t_full < t_union) {
+            __syncthreads();   // uh->tiles = 0 below must come after the write above
+            if (tid == 0) uh->tiles = 0;   // nothing to gather
+            vp_plan_single_bucket(N, V, vtiles, rpi, target_items, min_items, max_items_full, perm, rowplan, floors,
+                                  items, hdr, nullptr, tid, UNION_THREADS);
+            if (tid == 0) hdr->mode = 1;
+            return;
+        }
     }
     vp_plan_single_bucket(N, nU, tiles, rpi, target_items, min_items, max_items, perm, rowplan, floors, items, hdr,
                           nullptr, tid, UNION_THREADS);
@@ -206,10 +226,10 @@ hipError_t vpk_union_prepare()
 }
 
 void vpk_union_mark(const void *cpart, int parts, int N, int K, int mask_words, int32_t *g, int32_t *out_cluster,
-                    int32_t *occ, VpUnionHeader *uh, unsigned int *mask, hipStream_t st)
+                    int32_t *occ, VpUnionHeader *uh, unsigned int *mask, int32_t *zero_g, hipStream_t st)
 {
     hipLaunchKernelGGL(union_prepare_kernel, dim3(1), dim3(UNION_THREADS), (size_t)K * sizeof(int), st,
-                       (const int2 *)cpart, parts, N, K, mask_words, g, out_cluster, occ, uh, mask);
+                       (const int2 *)cpart, parts, N, K, mask_words, g, out_cluster, occ, uh, mask, zero_g);
 }
 
 void vpk_union_flags(const int32_t *occ, const VpUnionHeader *uh, const uint32_t *bitmaps, int bm_words,
@@ -224,12 +244,14 @@ int vpk_union_blocks(int mask_words) { return (mask_words + UNION_BLOCK_WORDS - 
 void vpk_union_compact(const unsigned int *mask, int mask_words, int32_t *bsum, int N, int rpi, int target_items,
                        int min_items, int max_items, int32_t *uids, VpUnionHeader *uh, int32_t *out_union_size,
                        int32_t *perm, VpRowPlan *rowplan, unsigned int *floors, VpItem *items, VpPlanHeader *hdr,
+                       int allow_full, int V, int vtiles, int k, const VpCostModel &cost, int max_items_full,
                        hipStream_t st)
 {
     const int blocks = vpk_union_blocks(mask_words);
     hipLaunchKernelGGL(union_count_kernel, dim3(blocks), dim3(256), 0, st, mask, mask_words, bsum);
     hipLaunchKernelGGL(union_compact_kernel, dim3(1), dim3(UNION_THREADS), 0, st, bsum, blocks, N, rpi, target_items,
-                       min_items, max_items, uids, uh, out_union_size, perm, rowplan, floors, items, hdr);
+                       min_items, max_items, uids, uh, out_union_size, perm, rowplan, floors, items, hdr, allow_full, V,
+                       vtiles, k, cost, max_items_full);
     hipLaunchKernelGGL(union_emit_kernel, dim3(blocks), dim3(256), 0, st, mask, mask_words, bsum, uids);
 }
 

@@ -80,6 +80,7 @@ struct vp_index {
     int dispatch;    // 1: the planner may choose the masked full projection (same results)
     VpCostModel cost;
     const uint32_t *bitmaps;
+    int union_dispatch;   // 1: vp_project_union may project a large union as a masked full projection
     int fused_plan;   // batches of at most this many rows (<= 64) are planned inside the Eq. 2 kernel
     // Counters of finished workgroups for that, zero between calls; calls take them in turn, so
     // a counter is shared only by calls TICKETS apart.
@@ -397,7 +398,7 @@ vp_status run_full(const char *fn, const vp_index *I, const void *hidden, int N,
 
 // Extra workspace of the batch-union form, placed after the common part.
 struct UnionLayout {
-    size_t base, uh, occ, mask, bsum, uids, ubias, uslab, total;
+    size_t base, uh, occ, mask, zero_g, bsum, uids, ubias, uslab, total;
     int mask_words;
 };
 
@@ -407,11 +408,12 @@ UnionLayout plan_union_workspace(const vp_index *I, int N)
     U.base = plan_workspace(I, N).total;
     size_t o = U.base;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
-    U.mask_words = ceil_div(I->V, 32);
+    U.mask_words = I->L.bm_words;   // one bit per token, padded like the per-cluster membership lists
     const size_t vpad = (size_t)I->L.vtiles * VP_TILE_ITEMS;
     U.uh = take(sizeof(VpUnionHeader));
     U.occ = take((size_t)I->K * 4);
     U.mask = take((size_t)U.mask_words * 4);
+    U.zero_g = take((size_t)std::max(N, 1) * 4);
     U.bsum = take((size_t)vpk_union_blocks(U.mask_words) * 4);
     U.uids = take(vpad * 4);
     U.ubias = take(vpad * 4);
@@ -530,6 +532,11 @@ vp_status vp_build(const vp_build_desc *D, void *hip_stream, vp_index **out)
     I->cost.bw_full = 5.4e12f;
     I->cost.bw_l2 = 17.0e12f;
     I->cost.bw_gemm = 12.0e12f;
+    // batch-union form: the gather of U's columns (16-byte pieces of the packed W; fitted to the
+    // measured crossover at |U| = 12 % of V for 64 rows) and the kernels only the gathered form needs
+    I->cost.bw_gather = 0.8e12f;
+    I->cost.t_gather = 12.0e-6f;
+    I->union_dispatch = 1;
     I->bitmaps = reinterpret_cast<const uint32_t *>(A + L.bitmaps);
     I->fused_plan = 16;
     I->tickets = reinterpret_cast<uint32_t *>(A + L.tickets);
@@ -580,6 +587,11 @@ vp_status vp_set_option(vp_index *I, const char *name, int64_t value)
         I->rstar = (int)value;
         return VP_OK;
     }
+    if (!std::strcmp(name, "union_dispatch")) {
+        if (value != 0 && value != 1) return fail(VP_ERR_INVALID_ARG, "vp_set_option: union_dispatch must be 0 or 1");
+        I->union_dispatch = (int)value;
+        return VP_OK;
+    }
     if (!std::strcmp(name, "fused_plan")) {
         if (value < 0 || value > VP_PLAN_SMALL_ROWS)
             return fail(VP_ERR_INVALID_ARG, "vp_set_option: fused_plan must be in [0, %d]", VP_PLAN_SMALL_ROWS);
@@ -589,6 +601,11 @@ vp_status vp_set_option(vp_index *I, const char *name, int64_t value)
     if (!std::strcmp(name, "dispatch")) {
         if (value != 0 && value != 1) return fail(VP_ERR_INVALID_ARG, "vp_set_option: dispatch must be 0 or 1");
         I->dispatch = (int)value;
+        return VP_OK;
+    }
+    if (!std::strcmp(name, "cost_bw_gather_gbs")) {
+        if (value < 1 || value > 1000000) return fail(VP_ERR_INVALID_ARG, "vp_set_option: %s out of range", name);
+        I->cost.bw_gather = (float)value * 1e9f;
         return VP_OK;
     }
     if (!std::strcmp(name, "cost_bw_slab_gbs") || !std::strcmp(name, "cost_bw_full_gbs") ||
@@ -737,12 +754,21 @@ vp_status vp_project_union(const vp_index *I, const void *hidden, int32_t N, int
     parts = ceil_div(I->L.ctiles, tpw_c * 4);
     vpk_centroid(hidden, N, I->d, I->cp, I->cnorm, I->K, I->L.kt, I->L.ctiles, tpw_c, parts, cpart, nullptr, st);
     // step 2: boolean list over the vocabulary -> reduced column set U
-    vpk_union_mark(cpart, parts, N, I->K, U.mask_words, g, out_cluster, occ, uh, mask, st);
+    int32_t *zero_g = reinterpret_cast<int32_t *>(ws + U.zero_g);
+    vpk_union_mark(cpart, parts, N, I->K, U.mask_words, g, out_cluster, occ, uh, mask, zero_g, st);
     vpk_union_flags(occ, uh, I->bitmaps, I->L.bm_words, U.mask_words, mask, st);
     const int max_items = max_items_full(I, N);
     const int row_tiles_u = single_bucket_row_tiles(I, N, k);
+    // the masked full projection exists for items of 16 and of 64 rows
+    const int allow_full = I->union_dispatch && (row_tiles_u == 1 || row_tiles_u == 4);
+    VpCostModel cost = I->cost;
+    const float tile_bytes = (float)I->L.kt * VP_TILE_BYTES;
+    cost.bw_full /= tile_bytes;
+    cost.bw_l2 /= tile_bytes;
+    cost.bw_gemm /= tile_bytes;
+    cost.bw_gather /= tile_bytes;
     vpk_union_compact(mask, U.mask_words, bsum, N, VP_ROWS_PER_ITEM * row_tiles_u, sb_target(I, row_tiles_u), sb_min(I, row_tiles_u), max_items, uids, uh,
-                      out_union_size, perm, rowplan, floors, items, hdr, st);
+                      out_union_size, perm, rowplan, floors, items, hdr, allow_full, I->V, I->L.vtiles, k, cost, max_items, st);
     // step 3: the reduced weight matrix and Eq. 1 over it; steps 4-5 fused (no [N, V] array)
     vpk_union_gather(I->full.tiles, I->full.bias, I->L.kt, uids, uh, I->L.vtiles, uslab, ubias, st);
     VpSlabSet uset = I->full;
@@ -754,6 +780,17 @@ vp_status vp_project_union(const vp_index *I, const void *hidden, int32_t N, int
     const int grid_items = std::min(max_items, ceil_div(rgs * (long)ceil_div(I->L.vtiles, VP_WG_WAVES), 8) * 8 + 8 * rgs);
     launch_single_bucket(uset, I, hidden, perm, items, hdr, N, grid_items, row_tiles_u, k, 0, partials, floors, nullptr,
                          nullptr, st);
+    if (allow_full) {
+        // launched as well; exactly one of the two does the work, as the planner decided
+        const int tpw = vp_tiles_per_wave((long long)rgs * I->L.vtiles, sb_target(I, row_tiles_u), sb_min(I, row_tiles_u));
+        const int chunks = ceil_div(I->L.vtiles, (long)tpw * VP_WG_WAVES);
+        const int grid_full = (rgs > 1 && chunks >= 8) ? ceil_div(chunks, 8) * 8 * rgs : chunks * rgs;
+        const VpMaskInfo umask = {zero_g, mask, 0};   // every row reads list 0: the boolean list of the batch
+        if (row_tiles_u == 4)
+            vpk_project_gemm(I->full, hidden, I->d, perm, items, hdr, grid_full, k, partials, floors + N, &umask, st);
+        else
+            vpk_project_masked(I->full, hidden, I->d, perm, items, hdr, grid_full, k, partials, floors, umask, st);
+    }
     vpk_merge(uset, rowplan, hdr, partials, k, N, out_ids, out_logp, st);
     return launch_status(fn);
 }

@@ -131,6 +131,8 @@ struct VpCostModel {
     float bw_full;   // one pass over the packed W from HBM
     float bw_l2;     // further passes over tiles already in the L2 (16-row items)
     float bw_gemm;   // further passes over W by 64-row items of the GEMM-shaped kernel
+    float bw_gather; // batch-union form: columns of U gathered from the packed W into the union slab
+    float t_gather;  // ... and the fixed time of the kernels only that gather needs (seconds)
 };
 
 #define VP_PLAN_SMALL_ROWS 64   // batches up to this size can be planned inside the Eq. 2 kernel

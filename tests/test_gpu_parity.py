@@ -833,3 +833,38 @@ def test_overlapping_calls_on_several_streams(tiny, mid):
                 got = outs[si][i]
                 assert np.array_equal(pu.to_np(got[0]), w[0]) and np.array_equal(pu.to_np(got[1]), w[1]), (N, i, si)
                 assert np.array_equal(pu.to_np(got[2]), w[2])
+
+
+def _union_mode(index):
+    """White-box: the planner's decision of the last vp_project_union call (header at the start of the workspace)."""
+    import torch
+    torch.cuda.synchronize()
+    return int(index._uws[:64].view(torch.int32)[7].item())
+
+
+@pytest.mark.gpu
+def test_union_form_either_way(oracle, tiny, mid):
+    """The batch-union form gathers the columns of U, or, when U is large, runs the full projection with the
+    boolean list as every row's mask: same results, both against the oracle's union mode."""
+    r = np.random.default_rng(99)
+    for B, N, k in ((tiny, 5, 4), (tiny, 16, 1), (tiny, 40, 4), (mid, 12, 8), (mid, 70, 8), (mid, 200, 2)):
+        H, _q = wl.make_rows(B.cfg, B.C, N=N, stream=900 + N)
+        print("union either way:", B.cfg.name, "N", N, "k", k, flush=True)
+        B.index.set_option("union_dispatch", 0)
+        try:
+            gathered = B.project_union(H, k)
+            assert _union_mode(B.index) == 0
+        finally:
+            B.index.set_option("union_dispatch", 1)
+        B.index.set_option("cost_bw_gather_gbs", 1)          # make the gather look hopeless
+        try:
+            in_place = B.project_union(H, k)
+            assert _union_mode(B.index) == 1
+        finally:
+            B.index.set_option("cost_bw_gather_gbs", 800)
+        for got in (gathered, in_place):
+            pu.check_union(oracle, B.W, B.b, B.C, B.cand_off, B.cand_ids, H, k, got[0], got[1], got[2], got[3])
+        assert np.array_equal(gathered[0], in_place[0]) and gathered[3] == in_place[3]
+        assert np.allclose(gathered[1], in_place[1], rtol=0, atol=1e-4)
+        default = B.project_union(H, k)
+        assert np.array_equal(default[0], gathered[0])
