@@ -86,6 +86,9 @@ def cluster_sweep(args, dev):
             sizes = np.diff(off_h)
             sizes = sizes[sizes > 0]                 # clusters that lost their members list nothing
             index = P.vp_build(Wt, bt, Ct, off_h, ids_h, k_max=8)
+            for opt in args.option:
+                name, val = opt.split("=")
+                index.set_option(name, int(val))
             ws = index.workspace(N)
             ms = time_ms(lambda i: index.project(batches[i % 8], k, workspace=ws))
             hit = float(np.mean([(index.project(h, 1, workspace=ws)[0][:, 0] == fb).float().mean().item()

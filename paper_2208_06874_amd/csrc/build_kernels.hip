@@ -34,6 +34,19 @@ __global__ __launch_bounds__(64) void pack_w_kernel(const uint16_t *__restrict__
     out[((size_t)group * kt_count + kt) * 64 + lane] = o;
 }
 
+// Packed tiles of the whole vocabulary -> one contiguous row of d_pad k-values per token (the
+// transpose of the paper's W[d, V], zero padded): what a run-time gather of single columns reads.
+__global__ __launch_bounds__(256) void token_major_kernel(const uint4 *__restrict__ wp, int V, int kt_count,
+                                                          uint4 *__restrict__ wt)
+{
+    const int X = kt_count * 4;   // 16-byte pieces per token
+    const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= (size_t)V * X) return;
+    const int v = (int)(e / X);
+    const int x = (int)(e - (size_t)v * X);
+    wt[e] = wp[((size_t)(v >> 4) * kt_count + (x >> 2)) * 64 + (x & 3) * 16 + (v & 15)];
+}
+
 // M[rows, d] row-major (one row per item, e.g. the centroids) -> packed tiles.
 __global__ __launch_bounds__(64) void pack_rows_kernel(const uint16_t *__restrict__ M, int rows, int d,
                                                         int kt_count, uint4 *__restrict__ out)
@@ -131,6 +144,13 @@ void vpk_pack_w(const void *W, int d, int V, int kt, void *out, hipStream_t st)
 {
     dim3 grid((V + VP_TILE_ITEMS - 1) / VP_TILE_ITEMS, kt);
     hipLaunchKernelGGL(pack_w_kernel, grid, dim3(64), 0, st, (const uint16_t *)W, d, V, kt, (uint4 *)out);
+}
+
+void vpk_token_major(const void *wp, int V, int kt, void *wt, hipStream_t st)
+{
+    const size_t pieces = (size_t)V * kt * 4;
+    hipLaunchKernelGGL(token_major_kernel, dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, st, (const uint4 *)wp, V,
+                       kt, (uint4 *)wt);
 }
 
 void vpk_pack_rows(const void *M, int rows, int d, int kt, void *out, hipStream_t st)

@@ -196,24 +196,29 @@ __global__ __launch_bounds__(256) void union_emit_kernel(const unsigned int *__r
     }
 }
 
-// Gathers the columns of U from the packed copy of W into the union slab (same
-// tile layout), with their bias.  One workgroup per group of 16 union tokens.
+// Gathers the columns of U into the union slab (packed tile layout), with their bias.  The
+// columns come from the token-major copy of W, where a token's k-values are one contiguous row
+// (in the packed tiles they are interleaved with those of 15 other tokens, and a gather from
+// there fetches four to eight times the bytes it uses).  A workgroup takes groups of 16 union
+// tokens in turn.
 __global__ __launch_bounds__(256) void union_gather_kernel(
-    const uint4 *__restrict__ wp, const float *__restrict__ bias_full, int kt_count,
+    const uint4 *__restrict__ wt, const float *__restrict__ bias_full, int kt_count,
     const int32_t *__restrict__ uids, const VpUnionHeader *__restrict__ uh, uint4 *__restrict__ slab,
     float *__restrict__ ubias)
 {
-    const int group = blockIdx.x;
-    if (group >= uh->tiles) return;
+    const int tiles = uh->tiles;
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    const int v = uids[group * VP_TILE_ITEMS + (lane & 15)];
-    if (threadIdx.x < 16) ubias[group * VP_TILE_ITEMS + lane] = v >= 0 ? bias_full[v] : 0.f;
     const int q = lane >> 4;
-    for (int kt = wave; kt < kt_count; kt += VP_WG_WAVES) {
-        uint4 o = make_uint4(0, 0, 0, 0);
-        if (v >= 0) o = wp[((size_t)(v >> 4) * kt_count + kt) * 64 + q * 16 + (v & 15)];
-        slab[((size_t)group * kt_count + kt) * 64 + lane] = o;
+    for (int group = blockIdx.x; group < tiles; group += gridDim.x) {
+        const int v = uids[group * VP_TILE_ITEMS + (lane & 15)];
+        if (threadIdx.x < 16) ubias[group * VP_TILE_ITEMS + lane] = v >= 0 ? bias_full[v] : 0.f;
+        const uint4 *row = wt + (size_t)(v >= 0 ? v : 0) * (kt_count * 4) + q;
+        for (int kt = wave; kt < kt_count; kt += VP_WG_WAVES) {
+            uint4 o = make_uint4(0, 0, 0, 0);
+            if (v >= 0) o = row[kt * 4];
+            slab[((size_t)group * kt_count + kt) * 64 + lane] = o;
+        }
     }
 }
 
@@ -255,9 +260,10 @@ void vpk_union_compact(const unsigned int *mask, int mask_words, int32_t *bsum, 
     hipLaunchKernelGGL(union_emit_kernel, dim3(blocks), dim3(256), 0, st, mask, mask_words, bsum, uids);
 }
 
-void vpk_union_gather(const void *wp, const float *bias_full, int kt, const int32_t *uids, const VpUnionHeader *uh,
+void vpk_union_gather(const void *wt, const float *bias_full, int kt, const int32_t *uids, const VpUnionHeader *uh,
                       int max_groups, void *slab, float *ubias, hipStream_t st)
 {
-    hipLaunchKernelGGL(union_gather_kernel, dim3(max_groups), dim3(256), 0, st, (const uint4 *)wp, bias_full, kt, uids,
+    const int grid = max_groups < 4096 ? max_groups : 4096;   // |U| is not known here
+    hipLaunchKernelGGL(union_gather_kernel, dim3(grid), dim3(256), 0, st, (const uint4 *)wt, bias_full, kt, uids,
                        uh, (uint4 *)slab, ubias);
 }

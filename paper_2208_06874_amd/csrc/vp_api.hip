@@ -42,7 +42,7 @@ struct ArenaLayout {
     long total_groups;     // candidate groups (of 16) over all clusters
     long n_total;
     int n_min, n_max, max_tiles;
-    size_t wp, biasf, cp, cnorm, full_meta, tile_off, n_cand, ids_pad, sbias, bitmaps, tickets, slabs, total;
+    size_t wp, wt, biasf, cp, cnorm, full_meta, tile_off, n_cand, ids_pad, sbias, bitmaps, tickets, slabs, total;
     int bm_words;
 };
 
@@ -147,6 +147,7 @@ vp_status plan_arena(const vp_build_desc *D, bool check_ids, ArenaLayout *L)
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
     const size_t group_bytes = (size_t)L->kt * VP_TILE_BYTES;
     L->wp = take((size_t)L->vtiles * group_bytes);
+    L->wt = take((size_t)D->V * L->d_pad * 2);   // token-major copy for the run-time gather of the batch-union form
     L->biasf = take((size_t)L->vtiles * VP_TILE_ITEMS * sizeof(float));
     L->cp = take((size_t)L->ctiles * group_bytes);
     L->cnorm = take((size_t)L->ctiles * VP_TILE_ITEMS * sizeof(float));
@@ -481,6 +482,7 @@ vp_status vp_build(const vp_build_desc *D, void *hip_stream, vp_index **out)
     if (e != hipSuccess) return fail(VP_ERR_HIP, "vp_build: upload failed: %s", hipGetErrorString(e));
 
     vpk_pack_w(D->W, D->d, D->V, L.kt, A + L.wp, st);
+    vpk_token_major(A + L.wp, D->V, L.kt, A + L.wt, st);
     vpk_bias_full(D->bias, D->V, L.vtiles * VP_TILE_ITEMS, reinterpret_cast<float *>(A + L.biasf), st);
     vpk_pack_rows(D->centroids, D->K, D->d, L.kt, A + L.cp, st);
     vpk_cnorm(D->centroids, D->K, D->d, L.ctiles * VP_TILE_ITEMS, reinterpret_cast<float *>(A + L.cnorm), st);
@@ -532,9 +534,10 @@ vp_status vp_build(const vp_build_desc *D, void *hip_stream, vp_index **out)
     I->cost.bw_full = 5.4e12f;
     I->cost.bw_l2 = 17.0e12f;
     I->cost.bw_gemm = 12.0e12f;
-    // batch-union form: the gather of U's columns (16-byte pieces of the packed W; fitted to the
-    // measured crossover at |U| = 12 % of V for 64 rows) and the kernels only the gathered form needs
-    I->cost.bw_gather = 0.8e12f;
+    // batch-union form: the gather of U's columns from the token-major copy into the union slab
+    // (fitted to the measured crossover at |U| = 28 % of V for 64 rows) and the kernels only the
+    // gathered form needs
+    I->cost.bw_gather = 2.4e12f;
     I->cost.t_gather = 12.0e-6f;
     I->union_dispatch = 1;
     I->bitmaps = reinterpret_cast<const uint32_t *>(A + L.bitmaps);
@@ -770,7 +773,7 @@ vp_status vp_project_union(const vp_index *I, const void *hidden, int32_t N, int
     vpk_union_compact(mask, U.mask_words, bsum, N, VP_ROWS_PER_ITEM * row_tiles_u, sb_target(I, row_tiles_u), sb_min(I, row_tiles_u), max_items, uids, uh,
                       out_union_size, perm, rowplan, floors, items, hdr, allow_full, I->V, I->L.vtiles, k, cost, max_items, st);
     // step 3: the reduced weight matrix and Eq. 1 over it; steps 4-5 fused (no [N, V] array)
-    vpk_union_gather(I->full.tiles, I->full.bias, I->L.kt, uids, uh, I->L.vtiles, uslab, ubias, st);
+    vpk_union_gather(I->arena + I->L.wt, I->full.bias, I->L.kt, uids, uh, I->L.vtiles, uslab, ubias, st);
     VpSlabSet uset = I->full;
     uset.tiles = uslab;
     uset.bias = ubias;

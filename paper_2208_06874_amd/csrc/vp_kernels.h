@@ -7,6 +7,7 @@
 
 // index building
 void vpk_pack_w(const void *W, int d, int V, int kt, void *out, hipStream_t st);
+void vpk_token_major(const void *wp, int V, int kt, void *wt, hipStream_t st);
 void vpk_pack_rows(const void *M, int rows, int d, int kt, void *out, hipStream_t st);
 void vpk_cnorm(const void *C, int K, int d, int K_pad, float *cnorm, hipStream_t st);
 void vpk_bias_full(const void *b, int V, int V_pad, float *out, hipStream_t st);
@@ -70,7 +71,7 @@ void vpk_union_compact(const unsigned int *mask, int mask_words, int32_t *bsum, 
                        int32_t *perm, VpRowPlan *rowplan, unsigned int *floors, VpItem *items, VpPlanHeader *hdr,
                        int allow_full, int V, int vtiles, int k, const VpCostModel &cost, int max_items_full,
                        hipStream_t st);
-void vpk_union_gather(const void *wp, const float *bias_full, int kt, const int32_t *uids, const VpUnionHeader *uh,
+void vpk_union_gather(const void *wt, const float *bias_full, int kt, const int32_t *uids, const VpUnionHeader *uh,
                       int max_groups, void *slab, float *ubias, hipStream_t st);
 
 // offline training of the clusters (section 2.2)

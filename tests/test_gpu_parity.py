@@ -861,7 +861,7 @@ def test_union_form_either_way(oracle, tiny, mid):
             in_place = B.project_union(H, k)
             assert _union_mode(B.index) == 1
         finally:
-            B.index.set_option("cost_bw_gather_gbs", 800)
+            B.index.set_option("cost_bw_gather_gbs", 2400)
         for got in (gathered, in_place):
             pu.check_union(oracle, B.W, B.b, B.C, B.cand_off, B.cand_ids, H, k, got[0], got[1], got[2], got[3])
         assert np.array_equal(gathered[0], in_place[0]) and gathered[3] == in_place[3]
