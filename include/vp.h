@@ -86,8 +86,10 @@ typedef struct {
 size_t vp_build_bytes(const vp_build_desc *desc);
 
 /* Packs the index into the arena: ||C_j||^2 per centroid (the precomputed term
- * of Eq. 2), centroids and W re-tiled for the matrix cores, and per cluster a
- * slab with its active tokens' columns, their bias and their ids.  W, bias and
+ * of Eq. 2), centroids and W re-tiled for the matrix cores, W once more with one
+ * contiguous row per token (for the run-time gather of vp_project_union), a
+ * membership bit list per cluster, and per cluster a slab with its active
+ * tokens' columns, their bias and their ids.  W, bias and
  * centroids are only read during this call (the index keeps its own copies);
  * the arena must outlive the index.  Synchronises the stream before returning.
  * Unsorted, duplicate or out-of-range ids: VP_ERR_INVALID_ARG.  All active sets
