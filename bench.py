@@ -460,14 +460,23 @@ def main():
                 rows = fresh[slot0 + parent.clamp(min=0)]
             return scores
 
-        decode(4)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        decode(T_d)
-        torch.cuda.synchronize()
-        ms_dec = (time.perf_counter() - t0) * 1e3 / T_d
+        def timed_decode():
+            decode(4)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            final = decode(T_d)
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) * 1e3 / T_d, final
+
+        ms_dec, final_scores = timed_decode()
+        index.set_option("dispatch", 1)          # the same search with the planner free to choose
+        ms_dec_d, final_scores_d = timed_decode()
+        index.set_option("dispatch", 0)
         result["decode_loop"] = {"sentences": S_d, "beam": B_d, "topk": k_d, "steps": T_d, "ms_per_step": ms_dec,
                                  "rows_per_s": n_d / (ms_dec * 1e-3),
+                                 "with_dispatch_ms_per_step": ms_dec_d,
+                                 "with_dispatch_rows_per_s": n_d / (ms_dec_d * 1e-3),
+                                 "with_dispatch_same_hypotheses": bool(torch.allclose(final_scores, final_scores_d, atol=1e-3)),
                                  "note": "vp_project + vp_beam_step + a gather of the next rows per step"}
 
     if not args.no_cpu_baseline:
