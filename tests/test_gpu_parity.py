@@ -868,3 +868,25 @@ def test_union_form_either_way(oracle, tiny, mid):
         assert np.allclose(gathered[1], in_place[1], rtol=0, atol=1e-4)
         default = B.project_union(H, k)
         assert np.array_equal(default[0], gathered[0])
+
+
+@pytest.mark.gpu
+def test_union_form_over_a_long_boolean_list(oracle):
+    """More than 262,144 tokens: the boolean list spans many blocks of the three-step scan.  Gathered and
+    in-place forms against the oracle."""
+    r, W, b, C = _small_model(271, 16, 270000, 6)
+    off, ids = _random_lists(r, 6, 270000, 300, 3000)
+    B = Built(W, b, C, off, ids, k_max=4)
+    for N, k in ((9, 2), (50, 4)):
+        H = _rows(r, C, N)
+        for dispatch, gbs in ((0, 2400), (1, 1)):
+            print("large vocabulary union: N", N, "k", k, "in place" if dispatch else "gathered", flush=True)
+            B.index.set_option("union_dispatch", dispatch)
+            B.index.set_option("cost_bw_gather_gbs", gbs)
+            try:
+                got = B.project_union(H, k)
+                assert _union_mode(B.index) == dispatch
+            finally:
+                B.index.set_option("union_dispatch", 1)
+                B.index.set_option("cost_bw_gather_gbs", 2400)
+            pu.check_union(oracle, W, b, C, off, ids, H, k, got[0], got[1], got[2], got[3])
