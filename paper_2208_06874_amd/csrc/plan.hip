@@ -69,8 +69,10 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(
     int *tl = ioff + K + 1;     // [K]   candidate tiles of each cluster
     __shared__ int wsum[PLAN_THREADS / 64 + 1];
     __shared__ long long wsum64[PLAN_THREADS / 64 + 1];
+    __shared__ int max_rgs;     // most row groups any bucket has
     const int tid = threadIdx.x;
 
+    if (tid == 0) max_rgs = 0;
     for (int j = tid; j < K; j += PLAN_THREADS) {
         cnt[j] = 0;
         tl[j] = tile_off[j + 1] - tile_off[j];
@@ -120,6 +122,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(
             off[j] = carry + ex;
             my_tiles += ceil_div(c, VP_ROWS_PER_ITEM) * tl[j];
             my_units += ceil_div(c, VP_ROWS_PER_ITEM);
+            if (c > 4 * VP_ROWS_PER_ITEM) atomicMax(&max_rgs, ceil_div(c, VP_ROWS_PER_ITEM));
             if (c > 0) my_occ_tiles += tl[j];
         }
         carry += tot;
@@ -221,7 +224,8 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(
         hdr->tiles_per_wave = tpw;
         hdr->overflow = ioff[K] > max_items;
         hdr->total_tiles = total_tiles;
-        hdr->swz_rgs = 0;
+        // buckets of five row groups and more: keep the row groups of a candidate range on one XCD
+        hdr->swz_rgs = max_rgs > 4 ? -VP_XCD_BLOCK_ITEMS : 0;
         hdr->swz_chunks = 0;
         hdr->rows_per_item = VP_ROWS_PER_ITEM;
         hdr->mode = 0;

@@ -193,7 +193,8 @@ WsLayout plan_workspace(const vp_index *I, int N)
     W.perm = take(n * 4);
     W.rowplan = take(n * sizeof(VpRowPlan));
     W.floors = take(n * 4 * (1 + VP_BOUND_SETS));   // [N] bounds of the 16-row kernels, then [N][sets] of the GEMM kernel
-    W.items = take((size_t)W.max_items * sizeof(VpItem));
+    // (workgroups read the record at their own index before they know the item count)
+    W.items = take((size_t)(W.max_items + 8 * VP_XCD_BLOCK_ITEMS) * sizeof(VpItem));
     W.partials = take((size_t)W.max_items * VP_MAX_ROWS_PER_ITEM * vp_partial_floats(I->k_max) * sizeof(float));
     W.total = o;
     return W;
@@ -307,7 +308,8 @@ vp_status run_clustered(const char *fn, const vp_index *I, const void *hidden, i
     cost.bw_gemm /= tile_bytes;
     const long row_groups = (long)row_tiles + std::min(N, I->K);
     const long by_tiles = row_groups * ceil_div(I->L.max_tiles, VP_WG_WAVES);
-    const int grid_items = (int)std::min<long>(max_items, by_tiles);
+    // (+ one round of blocks: the XCD swizzle of plans with heavy buckets rounds the grid up)
+    const int grid_items = (int)std::min<long>(max_items, by_tiles) + 8 * VP_XCD_BLOCK_ITEMS;
     // Eq. 2, then the plan: inside the same kernel for small batches with few items, where one
     // workgroup of 256 threads is as fast as the planning kernel's 1024 and a launch is saved
     // (not for the debug entry, which also wants the offsets of the rows' logits)

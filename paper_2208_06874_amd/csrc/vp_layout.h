@@ -22,6 +22,7 @@
 #define VP_BOUND_SETS 8          // per row: candidate-range sets whose best logits bound the k-th best (GEMM kernel)
 #define VP_MAX_ROWS_PER_ITEM 64  // four row tiles: the GEMM-shaped kernel of single-bucket projections
 #define VP_GEMV_MAX_ROWS 4
+#define VP_XCD_BLOCK_ITEMS 32    // clustered plans with heavy buckets: consecutive items one XCD takes at a time
 
 // One unit of projection work: up to 16 rows of one bucket against a range of
 // candidate tiles of that bucket's slab.
@@ -56,8 +57,11 @@ struct VpPlanHeader {
     int32_t tiles_per_wave;
     int32_t overflow;        // set if the item list did not fit (never expected)
     int32_t total_tiles;
-    // Workgroup -> item swizzle for a single bucket whose row groups share tiles (the
-    // full-vocabulary projection): 0, or the number of row groups / candidate ranges.
+    // Workgroup -> item swizzle.  > 1: a single bucket whose row groups share tiles (the
+    // full-vocabulary projection): the number of row groups, with swz_chunks candidate ranges.
+    // < 0: a clustered plan with buckets of many row groups: -(items per block), blocks of
+    // consecutive items are dealt to the 8 XCDs in turn and every XCD starts at another place
+    // of the list (see item_of_workgroup).  0: none.
     int32_t swz_rgs;
     int32_t swz_chunks;
     int32_t rows_per_item;   // row slots per item in the partial results (16, or 32 with two row tiles)
