@@ -26,6 +26,8 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, vendor figure
 MEASURED_TRAFFIC_BYTES = {
     # profiles/project_kernel_large_N256.md: 3,421,600 KiB x 1.99989 read + 800 KiB written per launch
     ("large", 256): 7.008e9,
+    # profiles/project_pf16_kernel_skewed_N4096.md: 8,035,252 KiB x 1.99989 read + 8,466 KiB written per launch
+    ("skewed", 4096): 16.46e9,
 }
 
 
@@ -276,7 +278,7 @@ def main():
             "single_cluster_microbenchmark": bool(args.single_cluster), "hip_graph_replay": bool(args.graph),
             "occupied_clusters_per_step": float(np.mean(list(occupied.values()))),
             "setup_seconds": t_gen},
-        "roofline": {"bound": "hbm", "kernel": "project_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
+        "roofline": {"bound": "hbm", "kernel": "project_pf16_kernel" if cfg.d > 1024 else "project_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": ms_kernel, "launches": launches},
     }
