@@ -266,6 +266,11 @@ def main():
     alg_bytes = float(np.mean(used))
     achieved = alg_bytes / (ms_kernel * 1e-3) / 1e9
     traffic = MEASURED_TRAFFIC_BYTES.get((args.workload, N))
+    # which form of the slab kernel the library launches (16 loads in flight per wavefront when the
+    # staged rows leave room for fewer than four workgroups per CU)
+    kt = info["d_pad"] // 32
+    lds = kt * 1024 + 4 * k * 16 * 8 + 4 * 16 * 8 + 16 * 12
+    slab_kernel = "project_pf16_kernel" if kt % 16 == 0 and lds * 4 > 160 * 1024 else "project_kernel"
 
     result = {
         "metric": "projected rows/sec fp16 at V=250K,d=1024; speedup vs full-vocab projection",
@@ -278,7 +283,7 @@ def main():
             "single_cluster_microbenchmark": bool(args.single_cluster), "hip_graph_replay": bool(args.graph),
             "occupied_clusters_per_step": float(np.mean(list(occupied.values()))),
             "setup_seconds": t_gen},
-        "roofline": {"bound": "hbm", "kernel": "project_pf16_kernel" if cfg.d > 1024 else "project_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
+        "roofline": {"bound": "hbm", "kernel": slab_kernel, "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": ms_kernel, "launches": launches},
     }
