@@ -88,7 +88,7 @@ def cluster_sweep(args, dev):
             sizes = np.diff(off_h)
             sizes = sizes[sizes > 0]                 # clusters that lost their members list nothing
             index = P.vp_build(Wt, bt, Ct, off_h, ids_h, k_max=8)
-            for opt in args.option:
+            for opt in getattr(args, "option", None) or []:
                 name, val = opt.split("=")
                 index.set_option(name, int(val))
             ws = index.workspace(N)
