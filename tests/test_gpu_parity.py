@@ -890,3 +890,24 @@ def test_union_form_over_a_long_boolean_list(oracle):
                 B.index.set_option("union_dispatch", 1)
                 B.index.set_option("cost_bw_gather_gbs", 2400)
             pu.check_union(oracle, W, b, C, off, ids, H, k, got[0], got[1], got[2], got[3])
+
+
+@pytest.mark.gpu
+def test_item_order_of_plans_with_heavy_buckets(oracle, tiny, mid):
+    """A bucket of more than four row groups switches the workgroup -> item map to blocks of consecutive items
+    per XCD with different starting points; every item must still be done exactly once."""
+    import torch
+    r = np.random.default_rng(7)
+    for B, N, heavy in ((tiny, 200, 120), (tiny, 1000, 1000), (mid, 300, 90), (mid, 81, 81)):
+        K = B.C.shape[0]
+        clusters = np.concatenate([np.full(heavy, 3 % K), r.integers(0, K, N - heavy)]).astype(np.int64)
+        r.shuffle(clusters)
+        H = _rows(r, B.C, N, clusters=clusters)
+        for k in (1, 4):
+            print("heavy bucket:", B.cfg.name, "N", N, "rows in one cluster", heavy, "k", k, flush=True)
+            ids, logp, g = B.project(H, k)
+            ws = B.index.workspace(N)
+            torch.cuda.synchronize()
+            hdr = ws[:64].view(torch.int32)[:8].tolist()
+            assert hdr[4] == -32 and hdr[7] == 0, hdr          # the swizzle of clustered plans is on
+            pu.check_projection(oracle, B.W, B.b, B.C, B.cand_off, B.cand_ids, H, k, ids, logp, g)
