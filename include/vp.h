@@ -121,9 +121,9 @@ vp_status vp_get_info(const vp_index *idx, vp_index_info *info);
  *   "fused_plan"    batches of at most this many rows (0..64, default 16) whose item list
  *                   is short are planned inside the Eq. 2 kernel, by the workgroup that
  *                   finishes last, which saves a kernel launch; 0: always the separate
- *                   planning kernel.  Same results.  The counters this uses belong to
- *                   the index and are taken in turn by its calls: at most 1024 calls on
- *                   one index may be in flight at once.
+ *                   planning kernel.  Same results.  (The index owns 1024 counters for
+ *                   this, one per workspace it has seen; calls on further workspaces use
+ *                   the planning kernel.)
  *   "profile"       1: time the projection kernel with HIP events (vp_get_profile)
  * Unknown name or out-of-range value: VP_ERR_INVALID_ARG. */
 vp_status vp_set_option(vp_index *idx, const char *name, int64_t value);

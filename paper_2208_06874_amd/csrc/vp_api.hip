@@ -4,7 +4,8 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
-#include <atomic>
+#include <mutex>
+#include <unordered_map>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -82,10 +83,12 @@ struct vp_index {
     const uint32_t *bitmaps;
     int union_dispatch;   // 1: vp_project_union may project a large union as a masked full projection
     int fused_plan;   // batches of at most this many rows (<= 64) are planned inside the Eq. 2 kernel
-    // Counters of finished workgroups for that, zero between calls; calls take them in turn, so
-    // a counter is shared only by calls TICKETS apart.
+    // Counters of finished workgroups for that, zero between calls.  Every workspace seen gets a
+    // counter of its own (calls that share a workspace do not overlap, so neither do the uses of
+    // its counter); when all are taken, calls on further workspaces use the planning kernel.
     uint32_t *tickets;
-    mutable std::atomic<uint32_t> call_seq;
+    mutable std::mutex ticket_mutex;
+    mutable std::unordered_map<const void *, int> ticket_of_workspace;
     VpProfile *prof;
 };
 
@@ -313,7 +316,18 @@ vp_status run_clustered(const char *fn, const vp_index *I, const void *hidden, i
     // Eq. 2, then the plan: inside the same kernel for small batches with few items, where one
     // workgroup of 256 threads is as fast as the planning kernel's 1024 and a launch is saved
     // (not for the debug entry, which also wants the offsets of the rows' logits)
+    int slot = -1;
     if (N <= I->fused_plan && grid_items <= FUSED_PLAN_MAX_ITEMS && !dbg_row_off) {
+        std::lock_guard<std::mutex> lock(I->ticket_mutex);
+        auto found = I->ticket_of_workspace.find(ws);
+        if (found != I->ticket_of_workspace.end()) {
+            slot = found->second;
+        } else if (I->ticket_of_workspace.size() < TICKETS) {
+            slot = (int)I->ticket_of_workspace.size();
+            I->ticket_of_workspace.emplace(ws, slot);
+        }
+    }
+    if (slot >= 0) {
         VpPlanArgs a = {};
         a.n_cand = I->clusters.n_cand;
         a.tile_off = I->clusters.tile_off;
@@ -335,7 +349,7 @@ vp_status run_clustered(const char *fn, const vp_index *I, const void *hidden, i
         a.full_target_items = sb_target(I, rt_masked);
         a.full_min_items = sb_min(I, rt_masked);
         a.max_items_full = max_full;
-        a.ticket = I->tickets + (I->call_seq.fetch_add(1, std::memory_order_relaxed) % TICKETS);
+        a.ticket = I->tickets + slot;
         vpk_centroid(hidden, N, I->d, I->cp, I->cnorm, I->K, I->L.kt, I->L.ctiles, tpw_c, parts, cpart, &a, st);
     } else {
         vpk_centroid(hidden, N, I->d, I->cp, I->cnorm, I->K, I->L.kt, I->L.ctiles, tpw_c, parts, cpart, nullptr, st);
@@ -545,7 +559,6 @@ vp_status vp_build(const vp_build_desc *D, void *hip_stream, vp_index **out)
     I->bitmaps = reinterpret_cast<const uint32_t *>(A + L.bitmaps);
     I->fused_plan = 16;
     I->tickets = reinterpret_cast<uint32_t *>(A + L.tickets);
-    I->call_seq.store(0);
     {
         // workgroups of the projection kernel that fit on the chip at once (LDS-limited)
         int dev = 0, cus = 256;

@@ -796,7 +796,7 @@ def test_planner_inside_the_centroid_kernel(oracle, tiny, mid):
                 assert mode1 == mode0
                 assert np.array_equal(d1[0], d0[0]) and np.array_equal(d1[2], base[2])
                 pu.check_projection(oracle, B.W, B.b, B.C, B.cand_off, B.cand_ids, H, k, d1[0], d1[1], d1[2])
-    # the counters return to zero: several thousand calls in a row, more than the index owns counters
+    # the counter returns to zero: several thousand calls in a row on one workspace
     H = _rows(r, tiny.C, 7)
     base = tiny.project(H, 2)
     Ht = tiny.rows(H)
@@ -804,6 +804,16 @@ def test_planner_inside_the_centroid_kernel(oracle, tiny, mid):
         out = tiny.index.project(Ht, 2)
     torch.cuda.synchronize()
     assert np.array_equal(pu.to_np(out[0]), base[0]) and np.array_equal(pu.to_np(out[1]), base[1])
+    # every workspace gets a counter of its own; beyond the 1,024 the index owns, calls fall back to the
+    # planning kernel: 1,100 workspaces carved from one buffer, garbage in all of them
+    need = (tiny.index.workspace_bytes(7) + 255) // 256 * 256
+    big = torch.empty(1100 * need, dtype=torch.uint8, device=tiny.dev)
+    big.fill_(0x5A)
+    outs = [tiny.index.project(Ht, 2, workspace=big[i * need:(i + 1) * need]) for i in range(1100)]
+    torch.cuda.synchronize()
+    for i in (0, 1, 511, 1023, 1024, 1025, 1099):
+        assert np.array_equal(pu.to_np(outs[i][0]), base[0]) and np.array_equal(pu.to_np(outs[i][1]), base[1]), i
+    del big, outs
 
 
 @pytest.mark.gpu
