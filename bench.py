@@ -300,8 +300,7 @@ def main():
         # default priority: a call of a few rows leaves most of the chip idle between its dependent kernels.
         S = args.streams
         streams = [torch.cuda.Stream(device=dev) for _ in range(S)]
-        # one workspace per chain: index.workspace() hands out the index's one cached buffer, and calls
-        # that share a workspace must not overlap
+        # one workspace per chain: calls that share a workspace must not overlap
         s_ws = [torch.empty(index.workspace_bytes(N), dtype=torch.uint8, device=dev) for _ in range(S)]
         assert len({w.data_ptr() for w in s_ws} | {ws.data_ptr()}) == S + 1
         s_ids = [torch.empty((N, k), dtype=torch.int32, device=dev) for _ in range(S)]

@@ -155,7 +155,8 @@ class Index:
         self.handle = h
         self.device = W.device
         self.d, self.V, self.K, self.k_max = d, V, K, k_max
-        self._ws = None
+        self._ws = {}     # cached scratch buffers, one per stream: calls that share one must not overlap
+        self._uws = {}
 
     def close(self):
         if getattr(self, "handle", None):
@@ -171,7 +172,8 @@ class Index:
 
     def set_option(self, name: str, value: int):
         _check(lib().vp_set_option(self.handle, name.encode(), int(value)))
-        self._ws = None
+        self._ws = {}     # the workspace size depends on the options
+        self._uws = {}
 
     def get_profile(self):
         """(summed projection-kernel milliseconds, launches) since the last call."""
@@ -182,15 +184,18 @@ class Index:
     def workspace_bytes(self, N: int) -> int:
         return lib().vp_workspace_bytes(self.handle, N)
 
-    def workspace(self, N: int):
-        """The index's one cached scratch buffer, grown on demand; the calls below use it when no workspace
-        is passed.  Calls that share a workspace must not overlap: callers that run calls on several streams
-        at once allocate one buffer of workspace_bytes(N) per stream and pass it."""
+    def workspace(self, N: int, stream=None):
+        """The index's cached scratch buffer for calls on this stream (default: torch's current stream), grown
+        on demand; the calls below use it when no workspace is passed.  Calls that share a workspace must not
+        overlap, which calls on one stream never do; callers that want a workspace of their own allocate
+        workspace_bytes(N) bytes and pass it."""
         import torch
         need = self.workspace_bytes(N)
-        if self._ws is None or self._ws.numel() < need:
-            self._ws = torch.empty(max(need, 256), dtype=torch.uint8, device=self.device)
-        return self._ws
+        key = _stream(stream)
+        ws = self._ws.get(key)
+        if ws is None or ws.numel() < need:
+            ws = self._ws[key] = torch.empty(max(need, 256), dtype=torch.uint8, device=self.device)
+        return ws
 
     def project(self, hidden, k: int, out_ids=None, out_logp=None, out_cluster=None, want_cluster=True,
                 workspace=None, stream=None):
@@ -204,7 +209,7 @@ class Index:
             out_logp = torch.empty((N, k), dtype=torch.float32, device=self.device)
         if out_cluster is None and want_cluster:
             out_cluster = torch.empty((N,), dtype=torch.int32, device=self.device)
-        ws = self.workspace(N) if workspace is None else workspace
+        ws = self.workspace(N, stream) if workspace is None else workspace
         _check(lib().vp_project(self.handle, hidden.data_ptr(), N, k, out_ids.data_ptr(), out_logp.data_ptr(),
                                 _ptr(out_cluster), ws.data_ptr(), ws.numel(), _stream(stream)))
         return out_ids, out_logp, out_cluster
@@ -218,7 +223,7 @@ class Index:
             out_ids = torch.empty((N, k), dtype=torch.int32, device=self.device)
         if out_logp is None:
             out_logp = torch.empty((N, k), dtype=torch.float32, device=self.device)
-        ws = self.workspace(N) if workspace is None else workspace
+        ws = self.workspace(N, stream) if workspace is None else workspace
         _check(lib().vp_project_full(self.handle, hidden.data_ptr(), N, k, out_ids.data_ptr(),
                                      out_logp.data_ptr(), ws.data_ptr(), ws.numel(), _stream(stream)))
         return out_ids, out_logp
@@ -242,9 +247,10 @@ class Index:
             out_union_size = torch.zeros((1,), dtype=torch.int32, device=self.device)
         if workspace is None:
             need = self.union_workspace_bytes(N)
-            if getattr(self, "_uws", None) is None or self._uws.numel() < need:
-                self._uws = torch.empty(max(need, 256), dtype=torch.uint8, device=self.device)
-            workspace = self._uws
+            key = _stream(stream)
+            workspace = self._uws.get(key)
+            if workspace is None or workspace.numel() < need:
+                workspace = self._uws[key] = torch.empty(max(need, 256), dtype=torch.uint8, device=self.device)
         _check(lib().vp_project_union(self.handle, hidden.data_ptr(), N, k, out_ids.data_ptr(), out_logp.data_ptr(),
                                       out_cluster.data_ptr(), out_union_size.data_ptr(), workspace.data_ptr(),
                                       workspace.numel(), _stream(stream)))
@@ -258,7 +264,7 @@ class Index:
         cluster = torch.empty((N,), dtype=torch.int32, device=self.device)
         offs = torch.empty((N + 1,), dtype=torch.int64, device=self.device)
         logits = torch.full((max(cap, 1),), float("nan"), dtype=torch.float32, device=self.device)
-        ws = self.workspace(N)
+        ws = self.workspace(N, stream)
         _check(lib().vp_project_debug_logits(self.handle, hidden.data_ptr(), N, int(full), cluster.data_ptr(),
                                              offs.data_ptr(), logits.data_ptr(), cap, ws.data_ptr(), ws.numel(),
                                              _stream(stream)))

@@ -849,7 +849,8 @@ def _union_mode(index):
     """White-box: the planner's decision of the last vp_project_union call (header at the start of the workspace)."""
     import torch
     torch.cuda.synchronize()
-    return int(index._uws[:64].view(torch.int32)[7].item())
+    uws = index._uws[torch.cuda.current_stream().cuda_stream]
+    return int(uws[:64].view(torch.int32)[7].item())
 
 
 @pytest.mark.gpu
