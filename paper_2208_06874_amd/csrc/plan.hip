@@ -52,6 +52,59 @@ __device__ T block_exscan(T v, T *total, T *wsum)
 }
 
 
+// Inclusive prefix sum over the 64 lanes of a wavefront with data-parallel-primitive moves in
+// the vector ALU: shifts by 1, 2, 4, 8 inside each row of 16 lanes, then the last lane of rows
+// 0 and 2 broadcast into rows 1 and 3, then lane 31 into rows 2 and 3.  (A scan by cross-lane
+// shuffles takes six round trips through the LDS crossbar; three such scans were most of this
+// kernel's time.)
+__device__ inline int wave_inclusive_sum(int v)
+{
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false);   // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false);   // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false);   // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false);   // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);   // row_bcast:15 -> rows 1, 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);   // row_bcast:31 -> rows 2, 3
+    return v;
+}
+
+// The same scan for ints, two barriers: every wavefront scans the wavefront totals itself.
+__device__ inline int block_exscan_int(int v, int *total, int *wsum)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int nw = blockDim.x >> 6;
+    const int inc = wave_inclusive_sum(v);
+    __syncthreads();   // wsum may still be read from a previous call
+    if (lane == 63) wsum[wave] = inc;
+    __syncthreads();
+    const int w = lane < nw ? wsum[lane] : 0;
+    const int winc = wave_inclusive_sum(w);
+    *total = __builtin_amdgcn_readlane(winc, nw - 1);
+    return __builtin_amdgcn_readlane(winc - w, wave) + inc - v;
+}
+
+// Sums of three per-thread values over the workgroup, to every thread.  wsum3: 3 x 16 ints.
+__device__ inline void block_sum3(int a, int b, int c, int *ta, int *tb, int *tc, int *wsum3)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int nw = blockDim.x >> 6;
+    a = wave_inclusive_sum(a);
+    b = wave_inclusive_sum(b);
+    c = wave_inclusive_sum(c);
+    __syncthreads();
+    if (lane == 63) {
+        wsum3[wave] = a;
+        wsum3[16 + wave] = b;
+        wsum3[32 + wave] = c;
+    }
+    __syncthreads();
+    *ta = __builtin_amdgcn_readlane(wave_inclusive_sum(lane < nw ? wsum3[lane] : 0), nw - 1);
+    *tb = __builtin_amdgcn_readlane(wave_inclusive_sum(lane < nw ? wsum3[16 + lane] : 0), nw - 1);
+    *tc = __builtin_amdgcn_readlane(wave_inclusive_sum(lane < nw ? wsum3[32 + lane] : 0), nw - 1);
+}
+
 constexpr int RPT = 4;   // rows per thread whose cluster id stays in registers between phases
 
 __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(
@@ -69,6 +122,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(
     int *tl = ioff + K + 1;     // [K]   candidate tiles of each cluster
     __shared__ int wsum[PLAN_THREADS / 64 + 1];
     __shared__ long long wsum64[PLAN_THREADS / 64 + 1];
+    __shared__ int wsum3[48];
     __shared__ int max_rgs;     // most row groups any bucket has
     const int tid = threadIdx.x;
 
@@ -117,7 +171,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(
         const int j = base + tid;
         const int c = j < K ? cnt[j] : 0;
         int tot;
-        const int ex = block_exscan<int>(c, &tot, wsum);
+        const int ex = block_exscan_int(c, &tot, wsum);
         if (j < K) {
             off[j] = carry + ex;
             my_tiles += ceil_div(c, VP_ROWS_PER_ITEM) * tl[j];
@@ -128,16 +182,11 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(
         carry += tot;
     }
     if (tid == 0) off[K] = carry;
-    // (the (bucket, row group) units ride in the upper half of the same sum)
-    long long both;
-    block_exscan<long long>(((long long)my_units << 32) + my_tiles, &both, wsum64);
-    const int total_tiles = (int)(both & 0xffffffffll);
-    const int units = (int)(both >> 32);
+    int total_tiles, units, occ_tiles;
+    block_sum3(my_tiles, my_units, my_occ_tiles, &total_tiles, &units, &occ_tiles, wsum3);
 
     // both forms give the same results, so the cheaper one is taken (cost model in plan_common.h)
     if (dispatch) {
-        int occ_tiles;
-        block_exscan<int>(my_occ_tiles, &occ_tiles, wsum);
         const int rpi_full = dispatch;   // rows per item of the masked projection (16 or 64)
         if (vp_full_is_cheaper(occ_tiles, total_tiles, N, rpi_full, vtiles, k, cost)) {
             __syncthreads();
@@ -157,7 +206,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(
         int c = 0;
         if (j < K) c = ceil_div(cnt[j], VP_ROWS_PER_ITEM) * ceil_div(tl[j], tpi);
         int tot;
-        const int ex = block_exscan<int>(c, &tot, wsum);
+        const int ex = block_exscan_int(c, &tot, wsum);
         if (j < K) ioff[j] = carry + ex;
         carry += tot;
     }
