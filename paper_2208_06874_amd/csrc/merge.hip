@@ -4,6 +4,7 @@
 // descending order (section 2.1), mapped back to token ids.
 #include <hip/hip_runtime.h>
 #include "vp_kernels.h"
+#include "wave_ops.h"
 
 namespace {
 
@@ -105,15 +106,7 @@ __global__ __launch_bounds__(MERGE_THREADS) void merge_kernel(
                 }
             }
         }
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            const float v2 = __shfl_xor(bv, off);
-            const int i2 = __shfl_xor(bi, off);
-            if (entry_before(v2, i2, bv, bi)) {
-                bv = v2;
-                bi = i2;
-            }
-        }
+        wave_best_entry(bv, bi);
         if (lane == 0) {
             red_v[wave] = bv;
             red_i[wave] = bi;

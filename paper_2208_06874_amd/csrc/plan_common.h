@@ -161,7 +161,7 @@ __device__ inline void vp_plan_small(const int2 *cpart, int parts, int N, int K,
     // position of every row in bucket order, size of its bucket
     int before = 0, same_before = 0, same_total = 0;
     for (int s = 0; s < N; ++s) {
-        const int js = __shfl(j, s);
+        const int js = __builtin_amdgcn_readlane(j, s);   // s is the same in every lane: a lane read, no shuffle
         before += (js < j || (js == j && s < r)) ? 1 : 0;
         same_before += (js == j && s < r) ? 1 : 0;
         same_total += (js == j) ? 1 : 0;
@@ -189,9 +189,9 @@ __device__ inline void vp_plan_small(const int2 *cpart, int parts, int N, int K,
     const int c = leader ? rgs * nit : 0;
     int ioff = 0, brank = 0, all_items = 0, nb = 0;
     for (int s = 0; s < N; ++s) {
-        const int js = __shfl(j, s);
-        const int cs = __shfl(c, s);
-        const int ls = __shfl(leader ? 1 : 0, s);
+        const int js = __builtin_amdgcn_readlane(j, s);
+        const int cs = __builtin_amdgcn_readlane(c, s);
+        const int ls = __builtin_amdgcn_readlane(leader ? 1 : 0, s);
         const bool lower = ls && js < j;
         ioff += lower ? cs : 0;
         brank += lower ? 1 : 0;

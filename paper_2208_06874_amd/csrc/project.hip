@@ -23,6 +23,7 @@
 #include <hip/hip_runtime.h>
 #include "vp_kernels.h"
 #include "project_common.h"
+#include "wave_ops.h"
 
 namespace {
 
@@ -296,15 +297,7 @@ __device__ inline void project_item(
                     bi = i;
                 }
             }
-#pragma unroll
-            for (int off = 1; off < 64; off <<= 1) {
-                const float v2 = __shfl_xor(bv, off);
-                const int i2 = __shfl_xor(bi, off);
-                if (entry_before(v2, i2, bv, bi)) {
-                    bv = v2;
-                    bi = i2;
-                }
-            }
+            wave_best_entry(bv, bi);
             if (lane == 0) {
                 out[2 + t] = bv;
                 out[2 + k + t] = __int_as_float(bi);
