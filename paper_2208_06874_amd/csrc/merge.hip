@@ -55,13 +55,7 @@ __global__ __launch_bounds__(MERGE_THREADS) void merge_kernel(
         m = mn;
     }
     // log-sum-exp over all parts
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const float m2 = __shfl_xor(m, off), s2 = __shfl_xor(s, off);
-        const float mn = fmaxf(m, m2);
-        s = s * fast_exp(m - mn) + s2 * fast_exp(m2 - mn);
-        m = mn;
-    }
+    wave_log_sum_exp(m, s);
     if (lane == 0) {
         red_v[wave] = m;
         red_s[wave] = s;

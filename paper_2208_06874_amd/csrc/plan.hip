@@ -13,6 +13,7 @@
 #include <hip/hip_runtime.h>
 #include "vp_kernels.h"
 #include "plan_common.h"
+#include "wave_ops.h"
 
 namespace {
 
@@ -51,22 +52,6 @@ __device__ T block_exscan(T v, T *total, T *wsum)
     return wsum[wave] + inc - v;
 }
 
-
-// Inclusive prefix sum over the 64 lanes of a wavefront with data-parallel-primitive moves in
-// the vector ALU: shifts by 1, 2, 4, 8 inside each row of 16 lanes, then the last lane of rows
-// 0 and 2 broadcast into rows 1 and 3, then lane 31 into rows 2 and 3.  (A scan by cross-lane
-// shuffles takes six round trips through the LDS crossbar; three such scans were most of this
-// kernel's time.)
-__device__ inline int wave_inclusive_sum(int v)
-{
-    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false);   // row_shr:1
-    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false);   // row_shr:2
-    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false);   // row_shr:4
-    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false);   // row_shr:8
-    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);   // row_bcast:15 -> rows 1, 3
-    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);   // row_bcast:31 -> rows 2, 3
-    return v;
-}
 
 // The same scan for ints, two barriers: every wavefront scans the wavefront totals itself.
 __device__ inline int block_exscan_int(int v, int *total, int *wsum)

@@ -8,6 +8,7 @@
 
 #include "vp.h"
 #include "vp_kernels.h"
+#include "wave_ops.h"
 
 namespace {
 
@@ -47,15 +48,7 @@ __global__ __launch_bounds__(BEAM_THREADS) void beam_step_kernel(
                 bc = c;
             }
         }
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            const float v2 = __shfl_xor(bv, off);
-            const int c2 = __shfl_xor(bc, off);
-            if (cont_before(v2, c2, bv, bc)) {
-                bv = v2;
-                bc = c2;
-            }
-        }
+        wave_best_entry(bv, bc);   // (sum descending, continuation ascending)
         __syncthreads();   // the previous round's wv / wc have been read
         if (lane == 0) {
             wv[wave] = bv;

@@ -15,6 +15,7 @@
 #include <hip/hip_fp16.h>
 #include "vp_kernels.h"
 #include "plan_common.h"
+#include "wave_ops.h"
 
 namespace {
 
@@ -93,8 +94,7 @@ __global__ __launch_bounds__(256) void union_count_kernel(const unsigned int *__
     __shared__ int part[4];
     const int w = blockIdx.x * UNION_BLOCK_WORDS + threadIdx.x;
     int c = w < mask_words ? __popc(mask[w]) : 0;
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) c += __shfl_xor(c, off);
+    c = wave_sum(c);
     if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = c;
     __syncthreads();
     if (threadIdx.x == 0) bsum[blockIdx.x] = part[0] + part[1] + part[2] + part[3];
@@ -117,12 +117,7 @@ __global__ __launch_bounds__(UNION_THREADS) void union_compact_kernel(
     for (int base = 0; base < blocks; base += UNION_THREADS) {
         const int b = base + tid;
         const int v = b < blocks ? bsum[b] : 0;
-        int inc = v;
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            const int up = __shfl_up(inc, off);
-            if (lane >= off) inc += up;
-        }
+        const int inc = wave_inclusive_sum(v);
         if (lane == 63) wsum[wave] = inc;
         __syncthreads();
         if (tid == 0) {
@@ -179,12 +174,7 @@ __global__ __launch_bounds__(256) void union_emit_kernel(const unsigned int *__r
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     unsigned int bits = w < mask_words ? mask[w] : 0u;
     const int c = __popc(bits);
-    int inc = c;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const int up = __shfl_up(inc, off);
-        if (lane >= off) inc += up;
-    }
+    const int inc = wave_inclusive_sum(c);
     if (lane == 63) part[wave] = inc;
     __syncthreads();
     int pos = boff[blockIdx.x] + inc - c;

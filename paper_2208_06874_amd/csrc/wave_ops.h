@@ -33,4 +33,42 @@ __device__ inline void wave_best_entry(float &v, int &i)
     i = __builtin_amdgcn_readlane(i, 63);
 }
 
+// Inclusive prefix sum over the 64 lanes of a wavefront (lane 63 ends with the total).
+__device__ inline int wave_inclusive_sum(int v)
+{
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false);   // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false);   // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false);   // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false);   // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);   // row_bcast:15 -> rows 1, 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);   // row_bcast:31 -> rows 2, 3
+    return v;
+}
+
+// Sum over the wavefront, to every lane.
+__device__ inline int wave_sum(int v) { return __builtin_amdgcn_readlane(wave_inclusive_sum(v), 63); }
+
+// Running maximum m and sum of exp(x - m) over the wavefront's (m, s) pairs, to every lane.
+__device__ inline void wave_log_sum_exp(float &m, float &s)
+{
+#define VP_DPP_LSE(ctrl, rows)                                                                                    \
+    {                                                                                                             \
+        const float m2 = __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(-3.0e38f), __float_as_int(m), ctrl, rows, 0xf, false)); \
+        const float s2 = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(s), ctrl, rows, 0xf, false)); \
+        const float mn = fmaxf(m, m2);                                                                            \
+        s = s * __builtin_amdgcn_exp2f((m - mn) * 1.4426950408889634f) +                                          \
+            s2 * __builtin_amdgcn_exp2f((m2 - mn) * 1.4426950408889634f);                                         \
+        m = mn;                                                                                                   \
+    }
+    VP_DPP_LSE(0x111, 0xf)
+    VP_DPP_LSE(0x112, 0xf)
+    VP_DPP_LSE(0x114, 0xf)
+    VP_DPP_LSE(0x118, 0xf)
+    VP_DPP_LSE(0x142, 0xa)
+    VP_DPP_LSE(0x143, 0xc)
+#undef VP_DPP_LSE
+    m = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(m), 63));
+    s = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(s), 63));
+}
+
 }  // namespace
