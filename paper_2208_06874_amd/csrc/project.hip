@@ -37,7 +37,7 @@ __device__ inline void project_item(
     const VpSlabSet &set, const uint4 *__restrict__ hidden, int d, const int32_t *__restrict__ perm,
     const VpItem &item, int it, int tpw, int k, int rstar,
     float *__restrict__ partials, unsigned int *__restrict__ floors, float *__restrict__ dbg_logits,
-    const int64_t *__restrict__ dbg_row_off, const VpMaskInfo &mask)
+    const int64_t *__restrict__ dbg_row_off, const VpMaskInfo &mask, bool raw_ok = false)
 {
     constexpr int ROWS = 16 * RT;               // row slots of an item
     const int KT = set.kt;
@@ -58,6 +58,13 @@ __device__ inline void project_item(
     int *rowid = reinterpret_cast<int *>(hdr_s + VP_WG_WAVES * ROWS);             // [ROWS]
     unsigned int *wg_floor = reinterpret_cast<unsigned int *>(rowid + ROWS);      // [ROWS]
     int *rowcl = reinterpret_cast<int *>(wg_floor + ROWS);                        // [ROWS] (masked projection)
+    // Items of at most two tiles per wavefront (a handful of rows against few candidates: the whole
+    // call is a few tens of microseconds) keep no top-k lists while they stream.  A list that has
+    // seen fewer than a few dozen candidates takes almost every one of them, one LDS insertion
+    // after the other, which cost more than the streaming itself; instead the logits (at most 32
+    // per row and wavefront) go to LDS as they are and the epilogue selects among them.
+    const bool raw = RT == 1 && raw_ok && tpw <= VP_RAW_TILES;
+    float *raw_val = reinterpret_cast<float *>(rowcl + ROWS);   // [4 waves][32 slots][16 rows], only if raw_ok
 
     // this wavefront's run of tiles; its first loads go out before anything else
     const int ncand = item.ncand;
@@ -86,6 +93,8 @@ __device__ inline void project_item(
         list_val[e] = -__builtin_inff();
         list_idx[e] = VP_IDX_NONE;
     }
+    if (raw)
+        for (int e = tid; e < VP_WG_WAVES * VP_RAW_TILES * VP_TILE_ITEMS * 16; e += VP_WG_THREADS) raw_val[e] = -__builtin_inff();
     __syncthreads();
 
     // Stage the item's hidden rows: MFMA operand order, or row-major for the GEMV loop.
@@ -212,7 +221,18 @@ __device__ inline void project_item(
                         for (int i = 0; i < 4; ++i)
                             if (c0 + i < ncand) dbg_logits[dbg_base[rt] + c0 + i] = z[i];
                     }
-                    fold_logits(z, c0, q, k, st[rt], list[rt], wg_floor + rt * 16 + n);
+                    if (raw) {
+                        const float tmax = fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3]));
+                        const float mn = fmaxf(st[rt].m, tmax);
+                        st[rt].s = st[rt].s * fast_exp(st[rt].m - mn) + fast_exp(z[0] - mn) + fast_exp(z[1] - mn) +
+                                   fast_exp(z[2] - mn) + fast_exp(z[3] - mn);
+                        st[rt].m = mn;
+                        float *slot = raw_val + ((wave * VP_RAW_TILES + (tile - tb)) * VP_TILE_ITEMS + q * 4) * 16 + n;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) slot[i * 16] = z[i];
+                    } else {
+                        fold_logits(z, c0, q, k, st[rt], list[rt], wg_floor + rt * 16 + n);
+                    }
                 }
                 if (exchange) {
                     // Every fourth tile the first wavefront trades bounds with the other workgroups
@@ -283,11 +303,34 @@ __device__ inline void project_item(
         // lane -> one of the 4 source lists and a residue class (mod 16) of its slots
         const float *sv = list_val + (lane & 3) * k * ROWS + r;
         const int *si = list_idx + (lane & 3) * k * ROWS + r;
+        // without lists: this lane's two of the row's 4 x 32 stored logits and their candidate positions
+        float rv[2] = {-__builtin_inff(), -__builtin_inff()};
+        int ri[2] = {VP_IDX_NONE, VP_IDX_NONE};
+        if (raw) {
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int e = lane + u * 64;   // wavefront e / 32 of the item, its slot e % 32
+                rv[u] = raw_val[e * 16 + r];
+                if (rv[u] > -__builtin_inff())
+                    ri[u] = (item.tile0 + (e / (VP_RAW_TILES * VP_TILE_ITEMS)) * tpw) * VP_TILE_ITEMS +
+                            e % (VP_RAW_TILES * VP_TILE_ITEMS);
+            }
+        }
         float pv = __builtin_inff();
         int pi = -1;
         for (int t = 0; t < k; ++t) {
             float bv = -__builtin_inff();
             int bi = VP_IDX_NONE;
+            if (raw) {
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    const bool after_prev = rv[u] < pv || (rv[u] == pv && ri[u] > pi);
+                    if (after_prev && entry_before(rv[u], ri[u], bv, bi)) {
+                        bv = rv[u];
+                        bi = ri[u];
+                    }
+                }
+            } else
             for (int p = lane >> 2; p < k; p += 16) {
                 const float v = sv[p * ROWS];
                 const int i = si[p * ROWS];
@@ -313,7 +356,7 @@ __global__ __launch_bounds__(VP_WG_THREADS) void project_kernel(
     VpSlabSet set, const uint4 *__restrict__ hidden, int d, const int32_t *__restrict__ perm,
     const VpItem *__restrict__ items, const VpPlanHeader *__restrict__ hdr, int k, int rstar,
     float *__restrict__ partials, unsigned int *__restrict__ floors, float *__restrict__ dbg_logits,
-    const int64_t *__restrict__ dbg_row_off)
+    const int64_t *__restrict__ dbg_row_off, int raw_ok)
 {
     // without the swizzle the item record does not depend on the header: both loads go out
     // together (the grid never exceeds the item array; records past total_items are unused)
@@ -327,10 +370,10 @@ __global__ __launch_bounds__(VP_WG_THREADS) void project_kernel(
     const VpMaskInfo none = {nullptr, nullptr, 0};
     if (item.shared)
         project_item<false, 1, 8, false>(set, hidden, d, perm, item, it, tpw, k, rstar, partials, floors, dbg_logits,
-                                         dbg_row_off, none);
+                                         dbg_row_off, none, raw_ok != 0);
     else
         project_item<true, 1, 8, false>(set, hidden, d, perm, item, it, tpw, k, rstar, partials, floors, dbg_logits,
-                                        dbg_row_off, none);
+                                        dbg_row_off, none, raw_ok != 0);
 }
 
 // The same with 16 loads in flight per wavefront, for k-extents whose staged rows leave room
@@ -423,9 +466,11 @@ hipError_t vpk_project_prepare()
     return e;
 }
 
+// raw_ok: the plan may consist of items short enough to keep raw logits (see project_item); the
+// workgroups then get 8 KiB more LDS for them
 void vpk_project(const VpSlabSet &set, const void *hidden, int d, const int32_t *perm, const VpItem *items,
                  const VpPlanHeader *hdr, int grid_items, int row_tiles, int k, int rstar, float *partials,
-                 unsigned int *floors, float *dbg_logits, const int64_t *dbg_row_off, hipStream_t st)
+                 unsigned int *floors, float *dbg_logits, const int64_t *dbg_row_off, int raw_ok, hipStream_t st)
 {
     if (row_tiles == 2) {
         hipLaunchKernelGGL(project2_kernel, dim3(grid_items), dim3(VP_WG_THREADS),
@@ -440,9 +485,11 @@ void vpk_project(const VpSlabSet &set, const void *hidden, int d, const int32_t 
                            dbg_row_off);
         return;
     }
-    hipLaunchKernelGGL(project_kernel, dim3(grid_items), dim3(VP_WG_THREADS), lds, st,
+    const size_t raw_bytes = (size_t)VP_WG_WAVES * VP_RAW_TILES * VP_TILE_ITEMS * 16 * sizeof(float);
+    if (lds + raw_bytes > 160 * 1024) raw_ok = 0;
+    hipLaunchKernelGGL(project_kernel, dim3(grid_items), dim3(VP_WG_THREADS), lds + (raw_ok ? raw_bytes : 0), st,
                        set, (const uint4 *)hidden, d, perm, items, hdr, k, rstar, partials, floors, dbg_logits,
-                       dbg_row_off);
+                       dbg_row_off, raw_ok);
 }
 
 void vpk_project_masked(const VpSlabSet &full, const void *hidden, int d, const int32_t *perm, const VpItem *items,

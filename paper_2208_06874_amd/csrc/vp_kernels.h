@@ -38,7 +38,7 @@ size_t vpk_project_lds_bytes(int kt, int k, int row_tiles);
 hipError_t vpk_project_prepare();
 void vpk_project(const VpSlabSet &set, const void *hidden, int d, const int32_t *perm, const VpItem *items,
                  const VpPlanHeader *hdr, int grid_items, int row_tiles, int k, int rstar, float *partials,
-                 unsigned int *floors, float *dbg_logits, const int64_t *dbg_row_off, hipStream_t st);
+                 unsigned int *floors, float *dbg_logits, const int64_t *dbg_row_off, int raw_ok, hipStream_t st);
 
 void vpk_project_masked(const VpSlabSet &full, const void *hidden, int d, const int32_t *perm, const VpItem *items,
                         const VpPlanHeader *hdr, int grid_items, int k, float *partials, unsigned int *floors,

@@ -22,6 +22,7 @@
 #define VP_BOUND_SETS 8          // per row: candidate-range sets whose best logits bound the k-th best (GEMM kernel)
 #define VP_MAX_ROWS_PER_ITEM 64  // four row tiles: the GEMM-shaped kernel of single-bucket projections
 #define VP_GEMV_MAX_ROWS 4
+#define VP_RAW_TILES 2           // slab items of at most this many tiles per wavefront keep raw logits, no top-k lists
 #define VP_XCD_BLOCK_ITEMS 32    // clustered plans with heavy buckets: consecutive items one XCD takes at a time
 
 // One unit of projection work: up to 16 rows of one bucket against a range of

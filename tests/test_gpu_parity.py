@@ -160,6 +160,15 @@ def test_decode_size_sweep(oracle, large, N):
     print("sweep", N, _full_check(oracle, large, H, 1, with_logits=(N <= 64)))
 
 
+@pytest.mark.parametrize("N,k", [(1, 8), (3, 4), (5, 8), (8, 8), (9, 8)])
+def test_few_rows_with_several_candidates_kept(oracle, large, N, k):
+    """Few rows, k >= 4: the slab kernel's items are one or two tiles per wavefront and keep raw
+    logits instead of per-lane lists (N = 9 is the first size past that bound on this index)."""
+    cfg = wl.CONFIGS["sweep"]
+    H, q = wl.make_rows(cfg, large.C, N=N, stream=70 + N)
+    print("few rows", N, k, _full_check(oracle, large, H, k))
+
+
 def test_skewed_config(oracle, skewed):
     cfg = skewed.cfg
     H, q = wl.make_rows(cfg, skewed.C)
