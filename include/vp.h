@@ -124,6 +124,11 @@ vp_status vp_get_info(const vp_index *idx, vp_index_info *info);
  *                   planning kernel.  Same results.  (The index owns 1024 counters for
  *                   this, one per workspace it has seen; calls on further workspaces use
  *                   the planning kernel.)
+ *   "raw_logits"    1 (default): calls with k >= 4 whose rows can meet at most 8,192
+ *                   candidate groups of 16 in all (a few rows, short lists) keep the raw
+ *                   logits of every short work item and select its k best at the end;
+ *                   0: top-k lists are built while streaming, as everywhere else.
+ *                   Same results.
  *   "profile"       1: time the projection kernel with HIP events (vp_get_profile)
  * Unknown name or out-of-range value: VP_ERR_INVALID_ARG. */
 vp_status vp_set_option(vp_index *idx, const char *name, int64_t value);

@@ -11,6 +11,7 @@ namespace {
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 constexpr int MERGE_THREADS = 256;
+constexpr int VP_MAX_TOPK_SLOTS = 32;   // largest k of the C ABI (checked on the host)
 
 __device__ inline float fast_exp(float x) { return __builtin_amdgcn_exp2f(x * LOG2E); }
 __device__ inline bool entry_before(float v, int i, float v2, int i2) { return v > v2 || (v == v2 && i < i2); }
@@ -38,7 +39,10 @@ __global__ __launch_bounds__(MERGE_THREADS) void merge_kernel(
     extern __shared__ float staged[];            // [2k][256]: entries of each thread's first part
     __shared__ float red_v[MERGE_THREADS / 64];
     __shared__ float red_s[MERGE_THREADS / 64];
-    __shared__ int red_i[MERGE_THREADS / 64];
+    __shared__ float rnd_v[2][MERGE_THREADS / 64];    // the wavefronts' offers of a round; rounds alternate between
+    __shared__ int rnd_i[2][MERGE_THREADS / 64];      // two sets, so one barrier per round is enough
+    __shared__ float win_v[VP_MAX_TOPK_SLOTS];        // the winners of the k rounds, written out together at the end
+    __shared__ int win_i[VP_MAX_TOPK_SLOTS];
 
     float m = VP_NEG_BIG, s = 0.f;
     if (tid < nit) {
@@ -67,8 +71,7 @@ __global__ __launch_bounds__(MERGE_THREADS) void merge_kernel(
     float S = 0.f;
 #pragma unroll
     for (int w = 0; w < MERGE_THREADS / 64; ++w) S += red_s[w] * fast_exp(red_v[w] - M);
-    const float lse = M + __builtin_amdgcn_logf(S) * LN2;
-    __syncthreads();
+    const float lse = M + __builtin_amdgcn_logf(S) * LN2;   // (red_v / red_s are not written again)
 
     // (in the masked full projection candidate positions are token ids already)
     const int32_t *ids = (set.ids && hdr->mode == 0) ? set.ids + rp.ids_off : nullptr;
@@ -101,25 +104,25 @@ __global__ __launch_bounds__(MERGE_THREADS) void merge_kernel(
             }
         }
         wave_best_entry(bv, bi);
+        const float *rv = rnd_v[t & 1];
+        const int *ri = rnd_i[t & 1];
         if (lane == 0) {
-            red_v[wave] = bv;
-            red_i[wave] = bi;
+            rnd_v[t & 1][wave] = bv;
+            rnd_i[t & 1][wave] = bi;
         }
-        __syncthreads();
-        bv = red_v[0];
-        bi = red_i[0];
+        __syncthreads();   // (the set written next round was last read before this barrier)
+        bv = rv[0];
+        bi = ri[0];
 #pragma unroll
         for (int w = 1; w < MERGE_THREADS / 64; ++w) {
-            if (entry_before(red_v[w], red_i[w], bv, bi)) {
-                bv = red_v[w];
-                bi = red_i[w];
+            if (entry_before(rv[w], ri[w], bv, bi)) {
+                bv = rv[w];
+                bi = ri[w];
             }
         }
-        __syncthreads();
         if (tid == 0) {
-            const bool real = bi != VP_IDX_NONE;
-            out_ids[(size_t)rp.row * k + t] = real ? (ids ? ids[bi] : bi) : -1;
-            out_logp[(size_t)rp.row * k + t] = real ? bv - lse : -__builtin_inff();
+            win_v[t] = bv;
+            win_i[t] = bi;
         }
         if (bi != VP_IDX_NONE && ci == bi) {      // my first part won: offer its next entry
             ++pos;
@@ -128,6 +131,17 @@ __global__ __launch_bounds__(MERGE_THREADS) void merge_kernel(
         }
         pv = bv;
         pi = bi;
+    }
+    // Positions to token ids and the outputs, one thread per slot: the k look-ups are in flight
+    // together (inside the rounds each would be waited for, k memory latencies one after the other:
+    // 9 us instead of 3.5 us for a top-8 merge).
+    __syncthreads();
+    if (tid < k) {
+        const float bv = win_v[tid];
+        const int bi = win_i[tid];
+        const bool real = bi != VP_IDX_NONE;
+        out_ids[(size_t)rp.row * k + tid] = real ? (ids ? ids[bi] : bi) : -1;
+        out_logp[(size_t)rp.row * k + tid] = real ? bv - lse : -__builtin_inff();
     }
 }
 

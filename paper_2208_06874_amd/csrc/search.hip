@@ -34,6 +34,8 @@ __global__ __launch_bounds__(BEAM_THREADS) void beam_step_kernel(
     }
     __shared__ float wv[4];
     __shared__ int wc[4];
+    __shared__ float win_v[BEAM_THREADS * BEAM_PER_THREAD];   // the winners of the B rounds (B <= B * k <= 2048)
+    __shared__ int win_c[BEAM_THREADS * BEAM_PER_THREAD];
     float pv = __builtin_inff();
     int pc = -1;
     for (int t = 0; t < B; ++t) {
@@ -63,14 +65,23 @@ __global__ __launch_bounds__(BEAM_THREADS) void beam_step_kernel(
             }
         }
         if (threadIdx.x == 0) {
-            const size_t o = (size_t)s * B + t;
-            const bool none = bc == 0x7fffffff || bv == -__builtin_inff();
-            out_scores[o] = none ? -__builtin_inff() : bv;
-            out_parent[o] = none ? -1 : bc / k;
-            out_token[o] = none ? -1 : cand_ids[base + bc];
+            win_v[t] = bv;
+            win_c[t] = bc;
         }
         pv = bv;
         pc = bc;
+    }
+    // the outputs, one thread per hypothesis: the token look-ups are in flight together instead of
+    // one memory latency per round
+    __syncthreads();
+    for (int t = threadIdx.x; t < B; t += BEAM_THREADS) {
+        const float bv = win_v[t];
+        const int bc = win_c[t];
+        const size_t o = (size_t)s * B + t;
+        const bool none = bc == 0x7fffffff || bv == -__builtin_inff();
+        out_scores[o] = none ? -__builtin_inff() : bv;
+        out_parent[o] = none ? -1 : bc / k;
+        out_token[o] = none ? -1 : cand_ids[base + bc];
     }
 }
 

@@ -29,6 +29,7 @@ vp_status fail(vp_status st, const char *fmt, ...)
     return st;
 }
 
+static_assert(VP_MAX_TOPK == 32, "merge_kernel keeps the winners of at most 32 rounds");
 constexpr size_t ALIGN = 256;
 constexpr size_t LDS_LIMIT = 160 * 1024;
 constexpr int FUSED_PLAN_MAX_ITEMS = 2048;
@@ -83,6 +84,7 @@ struct vp_index {
     const uint32_t *bitmaps;
     int union_dispatch;   // 1: vp_project_union may project a large union as a masked full projection
     int fused_plan;   // batches of at most this many rows (<= 64) are planned inside the Eq. 2 kernel
+    int raw_logits;   // 1: short items of small top-k >= 4 calls keep raw logits instead of lists (see run_clustered)
     // Counters of finished workgroups for that, zero between calls.  Every workspace seen gets a
     // counter of its own (calls that share a workspace do not overlap, so neither do the uses of
     // its counter); when all are taken, calls on further workspaces use the planning kernel.
@@ -364,7 +366,7 @@ vp_status run_clustered(const char *fn, const vp_index *I, const void *hidden, i
     // into items of one or two tiles per wavefront (the kernel checks the plan's figure itself).
     // For those, keeping raw logits beats building top-k lists from k = 4 on (measured: N = 1,
     // top-8: 50 -> 40 us per call; top-1: no gain, so the lists stay).
-    const int raw_ok = !dbg_logits && k >= 4 && (long)N * I->L.max_tiles <= 8192;
+    const int raw_ok = I->raw_logits && !dbg_logits && k >= 4 && (long)N * I->L.max_tiles <= 8192;
     vpk_project(I->clusters, hidden, I->d, perm, items, hdr, grid_items, 1, k, I->rstar, partials, floors, dbg_logits,
                 dbg_row_off, raw_ok, st);
     if (dispatch) {
@@ -563,6 +565,7 @@ vp_status vp_build(const vp_build_desc *D, void *hip_stream, vp_index **out)
     I->union_dispatch = 1;
     I->bitmaps = reinterpret_cast<const uint32_t *>(A + L.bitmaps);
     I->fused_plan = 16;
+    I->raw_logits = 1;
     I->tickets = reinterpret_cast<uint32_t *>(A + L.tickets);
     {
         // workgroups of the projection kernel that fit on the chip at once (LDS-limited)
@@ -619,6 +622,11 @@ vp_status vp_set_option(vp_index *I, const char *name, int64_t value)
         if (value < 0 || value > VP_PLAN_SMALL_ROWS)
             return fail(VP_ERR_INVALID_ARG, "vp_set_option: fused_plan must be in [0, %d]", VP_PLAN_SMALL_ROWS);
         I->fused_plan = (int)value;
+        return VP_OK;
+    }
+    if (!std::strcmp(name, "raw_logits")) {
+        if (value != 0 && value != 1) return fail(VP_ERR_INVALID_ARG, "vp_set_option: raw_logits must be 0 or 1");
+        I->raw_logits = (int)value;
         return VP_OK;
     }
     if (!std::strcmp(name, "dispatch")) {

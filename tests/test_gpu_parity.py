@@ -169,6 +169,24 @@ def test_few_rows_with_several_candidates_kept(oracle, large, N, k):
     print("few rows", N, k, _full_check(oracle, large, H, k))
 
 
+def test_raw_logits_and_lists_agree(tiny, large):
+    """The two ways a short item finds its k best (lists built while streaming; raw logits and a selection
+    at the end) walk the same total order: same ids, same log-probs."""
+    r = np.random.default_rng(71)
+    for B, sizes in ((tiny, (1, 7, 16, 40)), (large, (1, 2, 6))):
+        for N in sizes:
+            H = _rows(r, B.C, N)
+            for k in (4, 8):
+                got = B.project(H, k)
+                B.index.set_option("raw_logits", 0)
+                try:
+                    ref = B.project(H, k)
+                finally:
+                    B.index.set_option("raw_logits", 1)
+                assert np.array_equal(got[0], ref[0]) and np.array_equal(got[2], ref[2])
+                assert np.allclose(got[1], ref[1], rtol=0, atol=1e-5)
+
+
 def test_skewed_config(oracle, skewed):
     cfg = skewed.cfg
     H, q = wl.make_rows(cfg, skewed.C)
