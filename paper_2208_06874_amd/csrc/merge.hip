@@ -14,7 +14,8 @@ constexpr int MERGE_THREADS = 256;
 constexpr int VP_MAX_TOPK_SLOTS = 32;   // largest k of the C ABI (checked on the host)
 
 __device__ inline float fast_exp(float x) { return __builtin_amdgcn_exp2f(x * LOG2E); }
-__device__ inline bool entry_before(float v, int i, float v2, int i2) { return v > v2 || (v == v2 && i < i2); }
+// (without short-circuit evaluation: compares and selects instead of branches around the tie case)
+__device__ inline bool entry_before(float v, int i, float v2, int i2) { return (v > v2) | ((v == v2) & (i < i2)); }
 
 // One workgroup per row.  Thread t owns the parts t, t + 256, ...  The entries
 // of its first part are copied to LDS in one batch of loads; every part lists
@@ -115,10 +116,9 @@ __global__ __launch_bounds__(MERGE_THREADS) void merge_kernel(
         bi = ri[0];
 #pragma unroll
         for (int w = 1; w < MERGE_THREADS / 64; ++w) {
-            if (entry_before(rv[w], ri[w], bv, bi)) {
-                bv = rv[w];
-                bi = ri[w];
-            }
+            const bool take = entry_before(rv[w], ri[w], bv, bi);
+            bv = take ? rv[w] : bv;
+            bi = take ? ri[w] : bi;
         }
         if (tid == 0) {
             win_v[t] = bv;

@@ -15,7 +15,8 @@ namespace {
 constexpr int BEAM_THREADS = 256;
 constexpr int BEAM_PER_THREAD = 8;   // B * k <= 2048
 
-__device__ inline bool cont_before(float v, int c, float v2, int c2) { return v > v2 || (v == v2 && c < c2); }
+// (without short-circuit evaluation: compares and selects instead of branches around the tie case)
+__device__ inline bool cont_before(float v, int c, float v2, int c2) { return (v > v2) | ((v == v2) & (c < c2)); }
 
 __global__ __launch_bounds__(BEAM_THREADS) void beam_step_kernel(
     const int32_t *__restrict__ cand_ids, const float *__restrict__ cand_logp, const float *__restrict__ scores, int B,
@@ -44,11 +45,10 @@ __global__ __launch_bounds__(BEAM_THREADS) void beam_step_kernel(
 #pragma unroll
         for (int u = 0; u < BEAM_PER_THREAD; ++u) {
             const int c = threadIdx.x + u * BEAM_THREADS;
-            const bool after_prev = sum[u] < pv || (sum[u] == pv && c > pc);
-            if (c < n && after_prev && cont_before(sum[u], c, bv, bc)) {
-                bv = sum[u];
-                bc = c;
-            }
+            const bool after_prev = (sum[u] < pv) | ((sum[u] == pv) & (c > pc));
+            const bool take = (c < n) & after_prev & cont_before(sum[u], c, bv, bc);
+            bv = take ? sum[u] : bv;
+            bc = take ? c : bc;
         }
         wave_best_entry(bv, bc);   // (sum descending, continuation ascending)
         __syncthreads();   // the previous round's wv / wc have been read
@@ -59,10 +59,9 @@ __global__ __launch_bounds__(BEAM_THREADS) void beam_step_kernel(
         __syncthreads();
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
-            if (cont_before(wv[w], wc[w], bv, bc)) {
-                bv = wv[w];
-                bc = wc[w];
-            }
+            const bool take = cont_before(wv[w], wc[w], bv, bc);
+            bv = take ? wv[w] : bv;
+            bc = take ? wc[w] : bc;
         }
         if (threadIdx.x == 0) {
             win_v[t] = bv;
