@@ -28,7 +28,7 @@ constexpr int CU = 8;   // k-tiles fetched together (k-tile counts are multiples
 
 __device__ inline bool score_less(float s, int j, float s2, int j2)
 {
-    return s < s2 || (s == s2 && j < j2);
+    return (s < s2) | ((s == s2) & (j < j2));   // (no short-circuit: compares and selects, no branches)
 }
 
 __global__ __launch_bounds__(256) void centroid_kernel(
@@ -81,10 +81,9 @@ __global__ __launch_bounds__(256) void centroid_kernel(
     for (int off = 16; off <= 32; off <<= 1) {
         const float s2 = __shfl_xor(best_s, off);
         const int j2 = __shfl_xor(best_j, off);
-        if (score_less(s2, j2, best_s, best_j)) {
-            best_s = s2;
-            best_j = j2;
-        }
+        const bool take = score_less(s2, j2, best_s, best_j);
+        best_s = take ? s2 : best_s;
+        best_j = take ? j2 : best_j;
     }
     __shared__ float ws[4][16];
     __shared__ int wj[4][16];
@@ -96,10 +95,9 @@ __global__ __launch_bounds__(256) void centroid_kernel(
     if (wave == 0 && q == 0 && valid_row) {
 #pragma unroll
         for (int w = 1; w < 4; ++w) {
-            if (score_less(ws[w][n], wj[w][n], best_s, best_j)) {
-                best_s = ws[w][n];
-                best_j = wj[w][n];
-            }
+            const bool take = score_less(ws[w][n], wj[w][n], best_s, best_j);
+            best_s = take ? ws[w][n] : best_s;
+            best_j = take ? wj[w][n] : best_j;
         }
         cpart[(size_t)row * parts + part] = make_int2(__float_as_int(best_s), best_j);
     }
@@ -112,7 +110,7 @@ __global__ __launch_bounds__(256) void centroid_kernel(
     __threadfence();
     __syncthreads();
     if (threadIdx.x == 0) {
-        __threadfence();
+        // (the fetch-and-add releases what the barrier has ordered before it and acquires for the plan)
         const unsigned int t = __hip_atomic_fetch_add(plan.ticket, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
         last = t == (unsigned int)plan.total_wgs - 1u;
         // every workgroup has its ticket: the counter goes back to zero for the next call

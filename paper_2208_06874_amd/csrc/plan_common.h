@@ -121,10 +121,9 @@ __device__ inline void vp_plan_small(const int2 *cpart, int parts, int N, int K,
 #pragma unroll
                 for (int v = 0; v < 8; ++v) {
                     const float s = __int_as_float(ex[v]);
-                    if (s < bs || (s == bs && ey[v] < bj)) {
-                        bs = s;
-                        bj = ey[v];
-                    }
+                    const bool take = (s < bs) | ((s == bs) & (ey[v] < bj));   // (selects, no branches)
+                    bs = take ? s : bs;
+                    bj = take ? ey[v] : bj;
                 }
             }
         }
@@ -140,10 +139,9 @@ __device__ inline void vp_plan_small(const int2 *cpart, int parts, int N, int K,
         for (int w = 1; w < 4; ++w) {
             const float s = ps[w][r];
             const int jj = pj[w][r];
-            if (s < bs || (s == bs && jj < j)) {
-                bs = s;
-                j = jj;
-            }
+            const bool take = (s < bs) | ((s == bs) & (jj < j));
+            bs = take ? s : bs;
+            j = take ? jj : j;
         }
         if (j < 0 || j >= K) j = 0;   // non-finite scores: keep every index in range
     }
