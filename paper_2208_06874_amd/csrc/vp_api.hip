@@ -363,7 +363,8 @@ vp_status run_clustered(const char *fn, const vp_index *I, const void *hidden, i
     auto *ev = profile_slot(I);
     if (ev) (void)hipEventRecord(ev->first, st);
     // Few rows against short lists: at most 8,192 tiles in all, which the default item sizing cuts
-    // into items of one or two tiles per wavefront (the kernel checks the plan's figure itself).
+    // into items of one or two tiles per wavefront (unless the plan lands just past one round of
+    // workgroups and its items are lengthened; the kernel checks the plan's figure itself).
     // For those, keeping raw logits beats building top-k lists from k = 4 on (measured: N = 1,
     // top-8: 50 -> 40 us per call; top-1: no gain, so the lists stay).
     const int raw_ok = I->raw_logits && !dbg_logits && k >= 4 && (long)N * I->L.max_tiles <= 8192;

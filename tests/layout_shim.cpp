@@ -1,0 +1,18 @@
+// Host build of the item-sizing rules in csrc/vp_layout.h, for the CPU tests of the host logic
+// (the same inline functions run in the planning kernels and in the host API).
+#define __host__
+#define __device__
+#include "vp_layout.h"
+
+extern "C" int shim_tiles_per_wave(long long total_tiles, int target_items, int min_items)
+{
+    return vp_tiles_per_wave(total_tiles, target_items, min_items);
+}
+
+extern "C" int shim_tiles_per_wave_units(long long total_tiles, int units, int target_items, int min_items)
+{
+    return vp_tiles_per_wave_units(total_tiles, units, target_items, min_items);
+}
+
+extern "C" int shim_raw_tiles(void) { return VP_RAW_TILES; }
+extern "C" int shim_partial_floats(int k) { return vp_partial_floats(k); }

@@ -179,3 +179,62 @@ def test_product_path_does_not_reach_the_oracle():
             if f.endswith((".py", ".hip", ".h", ".cpp")):
                 text = open(os.path.join(base, f)).read()
                 assert "vp_oracle" not in text and "import oracle" not in text and "from oracle" not in text, f
+
+
+# ------------------------------------------------------------------ host logic: how a projection is cut into work items
+@pytest.fixture(scope="module")
+def layout(tmp_path_factory):
+    import subprocess
+    out = tmp_path_factory.mktemp("layout") / "liblayout_shim.so"
+    src = os.path.join(ROOT, "tests", "layout_shim.cpp")
+    inc = os.path.join(ROOT, "paper_2208_06874_amd", "csrc")
+    subprocess.run(["g++", "-O1", "-shared", "-fPIC", "-I", inc, src, "-o", str(out)], check=True)
+    L = ctypes.CDLL(str(out))
+    L.shim_tiles_per_wave.argtypes = [ctypes.c_longlong, ctypes.c_int, ctypes.c_int]
+    L.shim_tiles_per_wave_units.argtypes = [ctypes.c_longlong, ctypes.c_int, ctypes.c_int, ctypes.c_int]
+    return L
+
+
+def test_item_sizing_rules(layout):
+    """Tiles per wavefront of a plan: at least 1; never more items than asked for; with little work at least
+    one item per resident workgroup slot while items stay >= 4 tiles per wavefront; the clustered variant
+    never shortens items and, when it lengthens them, the plan fits one round of workgroup slots."""
+    r = np.random.default_rng(5)
+    for target, min_items in ((8192, 1024), (2048, 1024), (512, 512), (8192, 768)):
+        for total in [1, 3, 16, 4095, 4096, 4097, 8192, 15625, 16384, 16385, 60800, 250000, 10 ** 7] + \
+                     [int(x) for x in r.integers(1, 400000, 60)]:
+            tpw = layout.shim_tiles_per_wave(total, target, min_items)
+            assert tpw >= 1
+            items = -(-total // (4 * tpw))
+            assert items <= max(target, min_items)
+            if total >= 16 * max(target, min_items):          # plenty of work: about `target` items
+                assert items > max(target, min_items) // 2
+            if total <= 16 * min_items and min_items <= target:   # little work: one item per slot, or short items
+                assert tpw <= max(1, -(-total // (4 * min_items)))
+            for units in (1, 2, 17, 200, 600, 5000):
+                t2 = layout.shim_tiles_per_wave_units(total, units, target, min_items)
+                assert t2 >= tpw
+                if t2 > tpw:
+                    ub_before = -(-total // (4 * tpw)) + units
+                    assert min_items < ub_before <= 2 * min_items and 2 * units < min_items
+                    assert -(-total // (4 * t2)) + units <= min_items + 1
+
+
+def test_short_items_bound_of_the_raw_logit_form(layout):
+    """The host considers raw logits only for calls of at most 8,192 candidate tiles.  With the default
+    sizing (8,192 items asked for, 1,024 workgroup slots) such a plan has at most VP_RAW_TILES tiles per
+    wavefront unless its (bucket, row group) units push it just past one round of workgroups, in which case
+    the items get longer and the kernel, which checks the plan's figure, keeps its lists."""
+    raw = layout.shim_raw_tiles()
+    longer = 0
+    for total in list(range(1, 8193, 7)) + [8192]:
+        for units in (1, 4, 16, 64):
+            tpw = layout.shim_tiles_per_wave_units(total, units, 8192, 1024)
+            if total + 8 * units <= 8192:
+                assert tpw <= raw
+            else:
+                assert tpw <= raw + 1
+                longer += tpw > raw
+    assert longer > 0
+    assert layout.shim_tiles_per_wave_units(8193 + 4096, 1, 8192, 1024) > raw
+    assert layout.shim_partial_floats(8) == 18
