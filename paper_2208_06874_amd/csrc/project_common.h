@@ -141,34 +141,9 @@ __device__ inline uint4 load_piece(const uint4 *p)
 // of the list after the XCD before it.
 __device__ inline int item_of_workgroup(const VpPlanHeader *hdr)
 {
-    int it = blockIdx.x;
     const int swz_rgs = hdr->swz_rgs;
-    if (swz_rgs < 0) {
-        const int B = -swz_rgs;          // items per block
-        const int total = hdr->total_items;
-        const int xcd = it & 7;
-        const int l = it >> 3;           // this XCD's l-th workgroup
-        // Every XCD starts an eighth of the list further on (and wraps round), so that the
-        // workgroups in flight at any time come from eight places of the list: a heavy bucket's
-        // items, served by the L2, then overlap with items that stream from HBM on the other XCDs
-        // instead of forming a phase of their own on the whole chip (skewed workload: 70 -> 77 %
-        // of the HBM peak; most of it from this overlap, blocks of 8 to 32 items do equally well).
-        const int nbx = ((total + B - 1) / B + 7) >> 3;   // blocks per XCD
-        int i = l / B;
-        if (i >= nbx) return -1;
-        i = (i + xcd * ((nbx + 7) >> 3)) % nbx;
-        it = (i * 8 + xcd) * B + l % B;
-        return it < total ? it : -1;
-    }
-    if (swz_rgs > 1) {
-        const int xcd = it & 7;
-        const int t = it >> 3;
-        const int chl = t / swz_rgs;
-        const int ch = chl * 8 + xcd;
-        if (ch >= hdr->swz_chunks) return -1;
-        it = ch * swz_rgs + (t - chl * swz_rgs);
-    }
-    return it;
+    if (swz_rgs == 0 || swz_rgs == 1) return blockIdx.x;
+    return vp_item_of_workgroup(blockIdx.x, hdr->total_items, swz_rgs, hdr->swz_chunks);
 }
 
 }  // namespace

@@ -122,6 +122,38 @@ static inline __host__ __device__ int vp_tiles_per_wave_units(long long total_ti
     return (int)(one_round > tpw ? one_round : tpw);
 }
 
+// The workgroup -> item maps behind VpPlanHeader.swz_rgs (wg = the workgroup's index in the grid;
+// workgroups are handed to the 8 XCDs in turn).  Every item in [0, total_items) is taken by exactly
+// one workgroup of a grid that is large enough (total_items + 8 blocks for the first map, the chunk
+// count rounded up to 8 times the row groups for the second); the others get -1.
+static inline __host__ __device__ int vp_item_of_workgroup(int wg, int total_items, int swz_rgs, int swz_chunks)
+{
+    const int xcd = wg & 7;
+    if (swz_rgs < 0) {
+        const int B = -swz_rgs;          // items per block
+        const int l = wg >> 3;           // this XCD's l-th workgroup
+        // Every XCD starts an eighth of the list further on (and wraps round), so that the
+        // workgroups in flight at any time come from eight places of the list: a heavy bucket's
+        // items, served by the L2, then overlap with items that stream from HBM on the other XCDs
+        // instead of forming a phase of their own on the whole chip (skewed workload: 70 -> 77 %
+        // of the HBM peak; most of it from this overlap, blocks of 8 to 32 items do equally well).
+        const int nbx = ((total_items + B - 1) / B + 7) >> 3;   // blocks per XCD
+        int i = l / B;
+        if (i >= nbx) return -1;
+        i = (i + xcd * ((nbx + 7) >> 3)) % nbx;
+        const int it = (i * 8 + xcd) * B + l % B;
+        return it < total_items ? it : -1;
+    }
+    if (swz_rgs > 1) {
+        const int t = wg >> 3;
+        const int chl = t / swz_rgs;
+        const int ch = chl * 8 + xcd;
+        if (ch >= swz_chunks) return -1;
+        return ch * swz_rgs + (t - chl * swz_rgs);
+    }
+    return wg;
+}
+
 // What the masked full projection needs besides the slab set: each row's cluster
 // and the per-cluster membership bit lists over the vocabulary.
 struct VpMaskInfo {

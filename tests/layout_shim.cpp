@@ -16,3 +16,9 @@ extern "C" int shim_tiles_per_wave_units(long long total_tiles, int units, int t
 
 extern "C" int shim_raw_tiles(void) { return VP_RAW_TILES; }
 extern "C" int shim_partial_floats(int k) { return vp_partial_floats(k); }
+
+extern "C" int shim_item_of_workgroup(int wg, int total_items, int swz_rgs, int swz_chunks)
+{
+    return vp_item_of_workgroup(wg, total_items, swz_rgs, swz_chunks);
+}
+extern "C" int shim_xcd_block_items(void) { return VP_XCD_BLOCK_ITEMS; }

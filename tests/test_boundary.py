@@ -238,3 +238,29 @@ def test_short_items_bound_of_the_raw_logit_form(layout):
     assert longer > 0
     assert layout.shim_tiles_per_wave_units(8193 + 4096, 1, 8192, 1024) > raw
     assert layout.shim_partial_floats(8) == 18
+
+
+def test_workgroup_to_item_maps_take_every_item_once(layout):
+    """The two XCD-aware orders in which workgroups take work items: over a grid of the size the host
+    launches, every item is taken by exactly one workgroup and no workgroup gets an item outside the list."""
+    B = layout.shim_xcd_block_items()
+    r = np.random.default_rng(11)
+    # clustered plans with heavy buckets: blocks of B consecutive items dealt to the XCDs, rotated starts
+    for total in [1, 2, 31, 32, 33, 255, 256, 257, 1000, 2047, 2048, 2049, 8466] + [int(x) for x in r.integers(1, 20000, 40)]:
+        grid = total + 8 * B
+        got = [layout.shim_item_of_workgroup(wg, total, -B, 0) for wg in range(grid)]
+        taken = sorted(x for x in got if x >= 0)
+        assert taken == list(range(total)), total
+        assert all(x == -1 or 0 <= x < total for x in got)
+    # single bucket, several row groups: candidate ranges dealt to the XCDs, a range's row groups together
+    for rgs in (2, 3, 4, 16, 64):
+        for chunks in (8, 9, 15, 16, 17, 100, 977):
+            grid = -(-chunks // 8) * 8 * rgs
+            got = [layout.shim_item_of_workgroup(wg, chunks * rgs, rgs, chunks) for wg in range(grid)]
+            assert sorted(x for x in got if x >= 0) == list(range(chunks * rgs)), (rgs, chunks)
+            # the row groups of one range run on one XCD
+            for wg, it in enumerate(got):
+                if it >= 0:
+                    assert (it // rgs) % 8 == wg % 8
+    # no swizzle
+    assert [layout.shim_item_of_workgroup(wg, 10, 0, 0) for wg in range(10)] == list(range(10))
