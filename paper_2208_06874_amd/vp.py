@@ -159,7 +159,8 @@ class Index:
         self._uws = {}
 
     def close(self):
-        if getattr(self, "handle", None):
+        # (also runs from __del__ at interpreter shutdown, when module globals may already be gone)
+        if getattr(self, "handle", None) and callable(lib):
             lib().vp_destroy(self.handle)
             self.handle = None
 
