@@ -154,6 +154,25 @@ vp_status vp_project(const vp_index *idx, const void *hidden, int32_t N, int32_t
                      int32_t *out_ids, float *out_logp, int32_t *out_cluster,
                      void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* vp_project for callers that cannot allocate device memory and so have no
+ * workspace to pass: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid allocation.  Same arguments, outputs and results as
+ * vp_project, minus the workspace: the call's scratch (plan, per-part minima of
+ * Eq. 2, partial results) lives in an array of VP_STATIC_SCRATCH_BYTES bytes that
+ * is part of the library's device code (every GPU the library runs on holds its
+ * own copy until the process ends).  Nothing is allocated or freed here, on the
+ * device or by any library this calls.
+ *   - N and k must be such that vp_workspace_bytes(idx, N) fits the array
+ *     (about 10 MB at k_max = 8 for small batches); otherwise VP_ERR_WORKSPACE
+ *     and nothing is launched.
+ *   - All calls on one GPU share that GPU's array: calls that overlap on one
+ *     GPU (different streams, or different indexes) race on it and may read
+ *     half-written plans.  Order them on one stream.  The array keeps the last
+ *     call's contents; every call rewrites what it reads. */
+#define VP_STATIC_SCRATCH_BYTES (16u << 20)
+vp_status vp_project_static(const vp_index *idx, const void *hidden, int32_t N, int32_t k,
+                            int32_t *out_ids, float *out_logp, int32_t *out_cluster, void *hip_stream);
+
 /* The default projection of section 2.1 over all V tokens (log-softmax over V,
  * top-k), same output contract; the baseline the speed-up is quoted against. */
 vp_status vp_project_full(const vp_index *idx, const void *hidden, int32_t N, int32_t k,

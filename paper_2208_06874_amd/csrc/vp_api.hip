@@ -16,6 +16,11 @@
 #include "vp.h"
 #include "vp_kernels.h"
 
+// Scratch of vp_project_static: a call's workspace for callers that cannot allocate.  In host
+// code this name is only a handle of the symbol; the array's address on a device comes from
+// hipGetSymbolAddress with that device current (static_scratch_of_current_device).
+static __device__ __align__(256) unsigned char scratch[VP_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 thread_local char g_err[512] = "";
@@ -31,6 +36,30 @@ vp_status fail(vp_status st, const char *fmt, ...)
 
 static_assert(VP_MAX_TOPK == 32, "merge_kernel keeps the winners of at most 32 rounds");
 constexpr size_t ALIGN = 256;
+
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[MAX_DEVICES] = {};   // per device: where its copy of the array lives
+
+// The current device's copy of the scratch array; resolved once per device.  Allocates nothing.
+vp_status static_scratch_of_current_device(const char *fn, void **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(VP_ERR_HIP, "%s: hipGetDevice: %s", fn, hipGetErrorString(e));
+    if (dev < 0 || dev >= MAX_DEVICES)
+        return fail(VP_ERR_UNSUPPORTED, "%s: device %d out of range", fn, dev);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p)
+            return fail(VP_ERR_HIP, "%s: hipGetSymbolAddress: %s", fn, hipGetErrorString(e));
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return VP_OK;
+}
 constexpr size_t LDS_LIMIT = 160 * 1024;
 constexpr int FUSED_PLAN_MAX_ITEMS = 2048;
 constexpr size_t TICKETS = 1024;   // counters of the fused planner an index owns
@@ -200,7 +229,10 @@ WsLayout plan_workspace(const vp_index *I, int N)
     W.floors = take(n * 4 * (1 + VP_BOUND_SETS));   // [N] bounds of the 16-row kernels, then [N][sets] of the GEMM kernel
     // (workgroups read the record at their own index before they know the item count)
     W.items = take((size_t)(W.max_items + 8 * VP_XCD_BLOCK_ITEMS) * sizeof(VpItem));
-    W.partials = take((size_t)W.max_items * VP_MAX_ROWS_PER_ITEM * vp_partial_floats(I->k_max) * sizeof(float));
+    // one partial result per (item, row slot): 16 slots in the clustered plan, up to 64 in single-bucket plans
+    const size_t slots = std::max((size_t)max_items_clustered(I, N) * VP_ROWS_PER_ITEM,
+                                  (size_t)max_items_full(I, N) * VP_MAX_ROWS_PER_ITEM);
+    W.partials = take(slots * vp_partial_floats(I->k_max) * sizeof(float));
     W.total = o;
     return W;
 }
@@ -577,6 +609,14 @@ vp_status vp_build(const vp_build_desc *D, void *hip_stream, vp_index **out)
         I->min_items = std::max(1, cus) * per_cu;
     }
     I->prof = new (std::nothrow) VpProfile();
+    // resolve this device's scratch array now, so that vp_project_static's first call does not have to
+    {
+        void *p = nullptr;
+        if (static_scratch_of_current_device("vp_build", &p) != VP_OK) {
+            vp_destroy(I);
+            return VP_ERR_HIP;
+        }
+    }
     *out = I;
     return VP_OK;
 }
@@ -687,6 +727,25 @@ vp_status vp_project(const vp_index *I, const void *hidden, int32_t N, int32_t k
     if (s != VP_OK || N == 0) return s;
     return run_clustered("vp_project", I, hidden, N, k, out_ids, out_logp, out_cluster, static_cast<char *>(workspace),
                          nullptr, nullptr, reinterpret_cast<hipStream_t>(hip_stream));
+}
+
+vp_status vp_project_static(const vp_index *I, const void *hidden, int32_t N, int32_t k, int32_t *out_ids,
+                            float *out_logp, int32_t *out_cluster, void *hip_stream)
+{
+    const char *fn = "vp_project_static";
+    if (!I) return fail(VP_ERR_INVALID_ARG, "%s: null index", fn);
+    if (N < 0 || N > VP_MAX_ROWS) return fail(VP_ERR_INVALID_ARG, "%s: N = %d must be in [0, %d]", fn, N, VP_MAX_ROWS);
+    const size_t need = plan_workspace(I, N).total;
+    if (need > (size_t)VP_STATIC_SCRATCH_BYTES)
+        return fail(VP_ERR_WORKSPACE, "%s: N = %d needs %zu bytes of scratch, the library's array holds %zu", fn, N,
+                    need, (size_t)VP_STATIC_SCRATCH_BYTES);
+    void *ptr = nullptr;   // the array's address on this device (never the symbol's name)
+    vp_status s = static_scratch_of_current_device(fn, &ptr);
+    if (s != VP_OK) return s;
+    s = check_call(fn, I, hidden, N, k, out_ids, out_logp, ptr, VP_STATIC_SCRATCH_BYTES, true);
+    if (s != VP_OK || N == 0) return s;
+    return run_clustered(fn, I, hidden, N, k, out_ids, out_logp, out_cluster, static_cast<char *>(ptr), nullptr,
+                         nullptr, reinterpret_cast<hipStream_t>(hip_stream));
 }
 
 vp_status vp_project_full(const vp_index *I, const void *hidden, int32_t N, int32_t k, int32_t *out_ids,

@@ -20,7 +20,7 @@ STATUS_NAMES = {0: "VP_OK", 1: "VP_ERR_INVALID_ARG", 2: "VP_ERR_UNSUPPORTED", 3:
                 4: "VP_ERR_HIP"}
 
 EXPORTS = ("vp_build_bytes", "vp_build", "vp_get_info", "vp_set_option", "vp_workspace_bytes",
-           "vp_project", "vp_project_full", "vp_union_workspace_bytes", "vp_project_union",
+           "vp_project", "vp_project_static", "vp_project_full", "vp_union_workspace_bytes", "vp_project_union",
            "vp_project_debug_logits", "vp_get_profile", "vp_destroy", "vp_last_error",
            "vp_kmeans_workspace_bytes", "vp_kmeans", "vp_active_sets_workspace_bytes", "vp_active_sets",
            "vp_round_to_half", "vp_beam_step")
@@ -72,6 +72,8 @@ def lib():
         L.vp_workspace_bytes.argtypes = [vp, ctypes.c_int32]
         L.vp_project.restype = ctypes.c_int
         L.vp_project.argtypes = [vp, vp, ctypes.c_int32, ctypes.c_int32, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.vp_project_static.restype = ctypes.c_int
+        L.vp_project_static.argtypes = [vp, vp, ctypes.c_int32, ctypes.c_int32, vp, vp, vp, vp]
         L.vp_project_full.restype = ctypes.c_int
         L.vp_project_full.argtypes = [vp, vp, ctypes.c_int32, ctypes.c_int32, vp, vp, vp, ctypes.c_size_t, vp]
         L.vp_union_workspace_bytes.restype = ctypes.c_size_t
@@ -215,6 +217,14 @@ class Index:
                                 _ptr(out_cluster), ws.data_ptr(), ws.numel(), _stream(stream)))
         return out_ids, out_logp, out_cluster
 
+    def project_static(self, hidden, k: int, out_ids, out_logp, out_cluster=None, stream=None):
+        """vp_project_static: vp_project on the library's own scratch array; the caller passes every output
+        (nothing is allocated here either)."""
+        N = hidden.shape[0]
+        _check(lib().vp_project_static(self.handle, hidden.data_ptr(), N, k, out_ids.data_ptr(), out_logp.data_ptr(),
+                                       _ptr(out_cluster), _stream(stream)))
+        return out_ids, out_logp, out_cluster
+
     def project_full(self, hidden, k: int, out_ids=None, out_logp=None, workspace=None, stream=None):
         """vp_project_full: the default projection over all V tokens."""
         import torch
@@ -279,6 +289,13 @@ def vp_build(W, bias, centroids, cand_off, cand_ids, k_max: int = 8, stream=None
 
 def vp_project(index: Index, hidden, k: int, **kw):
     return index.project(hidden, k, **kw)
+
+
+def vp_project_static(index: Index, hidden, k: int, out_ids, out_logp, out_cluster=None, stream=None):
+    return index.project_static(hidden, k, out_ids, out_logp, out_cluster, stream=stream)
+
+
+STATIC_SCRATCH_BYTES = 16 << 20
 
 
 def vp_project_full(index: Index, hidden, k: int, **kw):

@@ -32,7 +32,7 @@ def test_python_binding_has_the_same_names():
     for n in ("vp_build", "vp_project", "vp_project_full", "vp_project_debug_logits", "vp_workspace_bytes",
               "vp_set_option", "vp_get_info", "vp_get_profile", "vp_destroy", "vp_last_error", "vp_project_union",
               "vp_union_workspace_bytes", "vp_kmeans", "vp_kmeans_workspace_bytes", "vp_active_sets",
-              "vp_active_sets_workspace_bytes", "vp_round_to_half", "vp_beam_step"):
+              "vp_active_sets_workspace_bytes", "vp_round_to_half", "vp_beam_step", "vp_project_static"):
         assert callable(getattr(P, n))
 
 
