@@ -54,6 +54,7 @@ typedef enum {
 #define VP_MAX_CLUSTERS 4096
 #define VP_MAX_ROWS 65536
 #define VP_MAX_DIM 4096
+#define VP_WS_OVERFLOW_WORD 2 /* index of the overflow flag among the workspace's 32-bit words */
 
 typedef struct {
     int32_t d;             /* embedding dimension                                        */
@@ -118,12 +119,13 @@ vp_status vp_get_info(const vp_index *idx, vp_index_info *info);
  *   "gemm_target_items"  work items of that kernel (default 512)
  *   "wide_items"    1 (default): below gemm_min_rows, vp_project_full / vp_project_union
  *                   of more than 16 rows with k <= 2 put 32 rows in an item; 0: always 16
- *   "fused_plan"    batches of at most this many rows (0..64, default 16) whose item list
- *                   is short are planned inside the Eq. 2 kernel, by the workgroup that
- *                   finishes last, which saves a kernel launch; 0: always the separate
- *                   planning kernel.  Same results.  (The index owns 1024 counters for
- *                   this, one per workspace it has seen; calls on further workspaces use
- *                   the planning kernel.)
+ *   "small_path"    1 (default): batches of at most 16 rows run without a planning kernel;
+ *                   every workgroup of the projection finds its own share of the work
+ *                   from the per-part minima of Eq. 2 (two dependent kernels fewer in
+ *                   front of the first slab byte); 0: always the planning kernel.
+ *                   Same plan, same results, bit for bit.
+ *   "small_pf"      1 KiB loads a wavefront of that path keeps in flight: 8, 16 or 32
+ *                   (0, the default: chosen from the batch size)
  *   "raw_logits"    1 (default): calls with k >= 4 whose rows can meet at most 8,192
  *                   candidate groups of 16 in all (a few rows, short lists) keep the raw
  *                   logits of every short work item and select its k best at the end;
@@ -146,6 +148,12 @@ size_t vp_workspace_bytes(const vp_index *idx, int32_t N_max);
  *   out_cluster  device, int32 [N] or NULL: Eq. 2 cluster of each row (ties to
  *                the lowest index)
  *   workspace    device, 256-byte aligned, >= vp_workspace_bytes(idx, N)
+ * Status word: the plan header at the start of the workspace holds, as its third
+ * 32-bit word (VP_WS_OVERFLOW_WORD), a flag that is non-zero after a call whose
+ * work list did not fit the room the host side reserved for it.  That is never
+ * expected (the room is an upper bound); if it happens, every output of the call
+ * is id -1 / log-prob NaN rather than a result that silently lost candidates,
+ * and the flag can be read once the stream has finished the call.
  * N == 0 is a no-op returning VP_OK.  Calls that share a workspace must be
  * ordered on one stream: a call that overlaps another on the same workspace
  * reads half-written plans and may access memory out of bounds.  Calls with

@@ -30,6 +30,15 @@ __global__ __launch_bounds__(MERGE_THREADS) void merge_kernel(
     const VpRowPlan rp = rowplan[blockIdx.x];
     const int rpi = hdr->rows_per_item;
     const int tid = threadIdx.x;
+    if (hdr->overflow) {
+        // The plan did not fit its item list (a bound of the host side is wrong): rows would silently
+        // lose candidates.  Make the call's results unusable instead; the flag stays in the workspace.
+        if (tid < k) {
+            out_ids[(size_t)rp.row * k + tid] = -1;
+            out_logp[(size_t)rp.row * k + tid] = __builtin_nanf("");
+        }
+        return;
+    }
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const int nit = rp.nit;

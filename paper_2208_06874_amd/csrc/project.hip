@@ -34,11 +34,12 @@ namespace {
 // flight per wavefront.
 template <bool NT, int RT, int PF, bool MASKED>
 __device__ inline void project_item(
-    const VpSlabSet &set, const uint4 *__restrict__ hidden, int d, const int32_t *__restrict__ perm,
+    const VpSlabSet &set, const uint4 *__restrict__ hidden, int d, int row_of_tid,
     const VpItem &item, int it, int tpw, int k, int rstar,
     float *__restrict__ partials, unsigned int *__restrict__ floors, float *__restrict__ dbg_logits,
     const int64_t *__restrict__ dbg_row_off, const VpMaskInfo &mask, bool raw_ok = false)
 {
+    // row_of_tid: for threads tid < 16 * RT, the batch row in row slot tid of the item (-1: none)
     constexpr int ROWS = 16 * RT;               // row slots of an item
     const int KT = set.kt;
     const int X = KT * 4;                       // 16-byte pieces per padded row
@@ -83,7 +84,7 @@ __device__ inline void project_item(
     }
 
     if (tid < ROWS) {
-        const int row = tid < item.nrows ? perm[item.perm_start + tid] : -1;
+        const int row = row_of_tid;
         rowid[tid] = row;
         // buckets walked by several row groups hand their bound from workgroup to workgroup
         wg_floor[tid] = (item.shared && row >= 0) ? floors[row] : VP_FLOOR_NONE;
@@ -141,7 +142,16 @@ __device__ inline void project_item(
         if (MASKED && tb < te) mcur[rt] = mrow[rt][(tb * VP_TILE_ITEMS + q * 4) >> 5];
     }
 
-    const bool exchange = item.shared && wave == 0 && q == 0;
+    // top-1 without lists (not for the masked projection, whose register budget is tight)
+    const bool top1 = !MASKED && k == 1 && !raw;
+    float b1v[RT];
+    int b1i[RT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+        b1v[rt] = -__builtin_inff();
+        b1i[rt] = VP_IDX_NONE;
+    }
+    const bool exchange = item.shared && wave == 0 && q == 0 && !top1;
     unsigned int pending[RT];
     bool has_pending = false;
     if (tb < te) {
@@ -230,6 +240,20 @@ __device__ inline void project_item(
                         float *slot = raw_val + ((wave * VP_RAW_TILES + (tile - tb)) * VP_TILE_ITEMS + q * 4) * 16 + n;
 #pragma unroll
                         for (int i = 0; i < 4; ++i) slot[i * 16] = z[i];
+                    } else if (top1) {
+                        // greedy search: the best (logit, position) of this lane's stream stays in registers;
+                        // positions ascend along the stream, so a strict comparison keeps the smaller one
+                        const float tmax = fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3]));
+                        const float mn = fmaxf(st[rt].m, tmax);
+                        st[rt].s = st[rt].s * fast_exp(st[rt].m - mn) + fast_exp(z[0] - mn) + fast_exp(z[1] - mn) +
+                                   fast_exp(z[2] - mn) + fast_exp(z[3] - mn);
+                        st[rt].m = mn;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const bool take = z[i] > b1v[rt];
+                            b1v[rt] = take ? z[i] : b1v[rt];
+                            b1i[rt] = take ? c0 + i : b1i[rt];
+                        }
                     } else {
                         fold_logits(z, c0, q, k, st[rt], list[rt], wg_floor + rt * 16 + n);
                     }
@@ -281,6 +305,21 @@ __device__ inline void project_item(
         if (q == 0) {
             hdr_m[wave * ROWS + rt * 16 + n] = st[rt].m;
             hdr_s[wave * ROWS + rt * 16 + n] = st[rt].s;
+        }
+        if (top1) {
+            // the row's four lanes -> this wavefront's one-entry list
+#pragma unroll
+            for (int off = 16; off <= 32; off <<= 1) {
+                const float v2 = __shfl_xor(b1v[rt], off);
+                const int i2 = __shfl_xor(b1i[rt], off);
+                const bool take = (v2 > b1v[rt]) | ((v2 == b1v[rt]) & (i2 < b1i[rt]));
+                b1v[rt] = take ? v2 : b1v[rt];
+                b1i[rt] = take ? i2 : b1i[rt];
+            }
+            if (q == 0 && row_valid[rt]) {
+                list_val[wave * k * ROWS + rt * 16 + n] = b1v[rt];
+                list_idx[wave * k * ROWS + rt * 16 + n] = b1i[rt];
+            }
         }
     }
     __syncthreads();
@@ -352,6 +391,13 @@ __device__ inline void project_item(
     if (item.shared && tid < item.nrows) atomicMax(floors + rowid[tid], wg_floor[tid]);
 }
 
+// The batch row in row slot threadIdx.x of an item of the planner's list (-1: no such slot).
+__device__ inline int row_of_slot(const int32_t *__restrict__ perm, const VpItem &item, int slots)
+{
+    const int tid = threadIdx.x;
+    return (tid < slots && tid < item.nrows) ? perm[item.perm_start + tid] : -1;
+}
+
 __global__ __launch_bounds__(VP_WG_THREADS) void project_kernel(
     VpSlabSet set, const uint4 *__restrict__ hidden, int d, const int32_t *__restrict__ perm,
     const VpItem *__restrict__ items, const VpPlanHeader *__restrict__ hdr, int k, int rstar,
@@ -369,11 +415,158 @@ __global__ __launch_bounds__(VP_WG_THREADS) void project_kernel(
     const VpItem item = it == (int)blockIdx.x ? probe : items[it];
     const VpMaskInfo none = {nullptr, nullptr, 0};
     if (item.shared)
-        project_item<false, 1, 8, false>(set, hidden, d, perm, item, it, tpw, k, rstar, partials, floors, dbg_logits,
+        project_item<false, 1, 8, false>(set, hidden, d, row_of_slot(perm, item, 16), item, it, tpw, k, rstar, partials, floors, dbg_logits,
                                          dbg_row_off, none, raw_ok != 0);
     else
-        project_item<true, 1, 8, false>(set, hidden, d, perm, item, it, tpw, k, rstar, partials, floors, dbg_logits,
+        project_item<true, 1, 8, false>(set, hidden, d, row_of_slot(perm, item, 16), item, it, tpw, k, rstar, partials, floors, dbg_logits,
                                         dbg_row_off, none, raw_ok != 0);
+}
+
+// Batches of at most 16 rows: no planning kernel, no item list.  Every workgroup reduces the
+// per-part minima of Eq. 2 itself (lane l: row l / 4, every fourth part; the row's cluster id ends
+// up in all four of its lanes), finds the buckets by comparing cluster ids across lanes, sizes the
+// items with the planner's own rule and takes the item with its own number: bucket = cluster (in
+// ascending order of the cluster id), range of candidate tiles = its chunk of that cluster's slab.
+// The plan is therefore the one plan_kernel would write - same buckets, same item boundaries, same
+// partial results - but nothing waits for a planner, and the only loads in front of the first slab
+// byte are the minima and two words of the cluster's metadata.  The first workgroup of a bucket
+// leaves the merge kernel's records of the bucket's rows, workgroup 0 the header and the clusters.
+template <int PF>
+__device__ inline void project_small(const VpSlabSet &set, const uint4 *__restrict__ hidden, int d, const VpSmallArgs &a,
+                                     int k, int rstar, float *__restrict__ partials, int raw_ok)
+{
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int r = lane >> 2;     // the row this lane stands for
+    const int sub = lane & 3;
+    const int N = a.N;
+
+    // finish Eq. 2: minimum over the centroid parts, ties to the lowest index
+    float bs = __builtin_inff();
+    int bj = VP_IDX_NONE;
+    if (r < N) {
+        const int2 *cp = reinterpret_cast<const int2 *>(a.cpart) + (size_t)r * a.parts;
+        for (int p0 = 0; p0 < a.parts; p0 += 16) {
+            int2 e[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int p = p0 + 4 * u + sub;
+                e[u] = p < a.parts ? cp[p] : make_int2(0x7f800000, VP_IDX_NONE);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float s = __int_as_float(e[u].x);
+                const bool take = (s < bs) | ((s == bs) & (e[u].y < bj));
+                bs = take ? s : bs;
+                bj = take ? e[u].y : bj;
+            }
+        }
+    }
+#define VP_QUAD_MIN(ctrl)                                                                                        \
+    {                                                                                                            \
+        const float s2 = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(bs), ctrl, 0xf, 0xf, false)); \
+        const int j2 = __builtin_amdgcn_update_dpp(0, bj, ctrl, 0xf, 0xf, false);                                \
+        const bool take = (s2 < bs) | ((s2 == bs) & (j2 < bj));                                                  \
+        bs = take ? s2 : bs;                                                                                     \
+        bj = take ? j2 : bj;                                                                                     \
+    }
+    VP_QUAD_MIN(0xB1)   // quad_perm [1, 0, 3, 2]
+    VP_QUAD_MIN(0x4E)   // quad_perm [2, 3, 0, 1]
+#undef VP_QUAD_MIN
+    int j = -1;          // rows beyond N match no bucket
+    int to = 0, nc = 0;
+    if (r < N) {
+        j = (bj < 0 || bj >= a.K) ? 0 : bj;   // non-finite scores: keep every index in range
+        to = a.tile_off[j];
+        nc = a.n_cand[j];
+    }
+    const int tl = (nc + VP_TILE_ITEMS - 1) / VP_TILE_ITEMS;
+
+    // position of every row among the rows of its cluster
+    int same_before = 0, same_total = 0;
+    for (int s = 0; s < N; ++s) {
+        const int js = __builtin_amdgcn_readlane(j, 4 * s);
+        same_before += (js == j && s < r) ? 1 : 0;
+        same_total += (js == j) ? 1 : 0;
+    }
+    const bool leader = r < N && sub == 0 && same_before == 0;   // one lane per bucket
+    const int total_tiles = wave_sum(leader ? tl : 0);
+    const int units = wave_sum(leader ? 1 : 0);
+    const int tpw = vp_tiles_per_wave_units(total_tiles, units, a.target_items, a.min_items);
+    const int tpi = tpw * VP_WG_WAVES;
+    const int nit = (tl + tpi - 1) / tpi;
+    const int c = leader ? nit : 0;
+    int ioff = 0, all_items = 0;
+    for (int s = 0; s < N; ++s) {
+        const int js = __builtin_amdgcn_readlane(j, 4 * s);
+        const int cs = __builtin_amdgcn_readlane(c, 4 * s);
+        ioff += js < j ? cs : 0;
+        all_items += cs;
+    }
+
+    const int it = blockIdx.x;
+    if (it == 0 && tid < 64) {
+        if (sub == 0 && r < N) {
+            a.g[r] = j;
+            if (a.out_cluster) a.out_cluster[r] = j;
+            if (tl == 0) {   // a cluster without candidates has no items: its rows' records come from here
+                VpRowPlan rp = {r, j, 0, 1, 0, 0, to * VP_TILE_ITEMS, 0};
+                a.rowplan[r] = rp;
+            }
+        }
+        if (tid == 0) {
+            a.hdr->total_items = all_items;
+            a.hdr->tiles_per_wave = tpw;
+            a.hdr->overflow = all_items > (int)gridDim.x;
+            a.hdr->total_tiles = total_tiles;
+            a.hdr->swz_rgs = 0;
+            a.hdr->swz_chunks = 0;
+            a.hdr->rows_per_item = VP_ROWS_PER_ITEM;
+            a.hdr->mode = 0;
+        }
+    }
+    if (it >= all_items) return;
+
+    // the bucket this workgroup's item belongs to
+    const unsigned long long owner = __ballot(leader && it >= ioff && it < ioff + c);
+    const int src = __ffsll((long long)owner) - 1;
+    const int jb = __builtin_amdgcn_readlane(j, src);
+    const int ioff_b = __builtin_amdgcn_readlane(ioff, src);
+    VpItem item;
+    item.cluster = jb;
+    item.perm_start = 0;
+    item.nrows = __builtin_amdgcn_readlane(same_total, src);
+    item.tile0 = (it - ioff_b) * tpi;
+    item.ntiles = min(tpi, __builtin_amdgcn_readlane(tl, src) - item.tile0);
+    item.shared = 0;
+    item.tile_off = __builtin_amdgcn_readlane(to, src);
+    item.ncand = __builtin_amdgcn_readlane(nc, src);
+    if (it == ioff_b && tid < 64 && sub == 0 && j == jb) {
+        VpRowPlan rp = {r, j, ioff_b, 1, nit, same_before, to * VP_TILE_ITEMS, 0};
+        a.rowplan[r] = rp;
+    }
+    // row slot s of the item holds the bucket's s-th row
+    int row_of_tid = -1;
+    {
+        int cnt = 0;
+        for (int s = 0; s < N; ++s) {
+            if (__builtin_amdgcn_readlane(j, 4 * s) == jb) {
+                if (tid == cnt) row_of_tid = s;
+                ++cnt;
+            }
+        }
+    }
+    const VpMaskInfo none = {nullptr, nullptr, 0};
+    project_item<true, 1, PF, false>(set, hidden, d, row_of_tid, item, it, tpw, k, rstar, partials, nullptr, nullptr,
+                                     nullptr, none, raw_ok != 0);
+}
+
+template <int PF>
+__global__ __launch_bounds__(VP_WG_THREADS) void project_small_kernel(
+    VpSlabSet set, const uint4 *__restrict__ hidden, int d, VpSmallArgs a, int k, int rstar,
+    float *__restrict__ partials, int raw_ok)
+{
+    project_small<PF>(set, hidden, d, a, k, rstar, partials, raw_ok);
 }
 
 // The same with 16 loads in flight per wavefront, for k-extents whose staged rows leave room
@@ -394,10 +587,10 @@ __global__ __launch_bounds__(VP_WG_THREADS) void project_pf16_kernel(
     const VpItem item = it == (int)blockIdx.x ? probe : items[it];
     const VpMaskInfo none = {nullptr, nullptr, 0};
     if (item.shared)
-        project_item<false, 1, 16, false>(set, hidden, d, perm, item, it, tpw, k, rstar, partials, floors, dbg_logits,
+        project_item<false, 1, 16, false>(set, hidden, d, row_of_slot(perm, item, 16), item, it, tpw, k, rstar, partials, floors, dbg_logits,
                                           dbg_row_off, none);
     else
-        project_item<true, 1, 16, false>(set, hidden, d, perm, item, it, tpw, k, rstar, partials, floors, dbg_logits,
+        project_item<true, 1, 16, false>(set, hidden, d, row_of_slot(perm, item, 16), item, it, tpw, k, rstar, partials, floors, dbg_logits,
                                          dbg_row_off, none);
 }
 
@@ -415,7 +608,7 @@ __global__ __launch_bounds__(VP_WG_THREADS) void project2_kernel(
     if (it < 0 || it >= total_items) return;
     const VpItem item = items[it];
     const VpMaskInfo none = {nullptr, nullptr, 0};
-    project_item<false, 2, 16, false>(set, hidden, d, perm, item, it, tpw, k, 0, partials, floors, dbg_logits,
+    project_item<false, 2, 16, false>(set, hidden, d, row_of_slot(perm, item, 32), item, it, tpw, k, 0, partials, floors, dbg_logits,
                                       dbg_row_off, none);
 }
 
@@ -434,10 +627,10 @@ __global__ __launch_bounds__(VP_WG_THREADS) void project_masked_kernel(
     if (it < 0 || it >= total_items) return;
     const VpItem item = items[it];
     if (item.shared)
-        project_item<false, 1, 8, true>(set, hidden, d, perm, item, it, tpw, k, 0, partials, floors, nullptr, nullptr,
+        project_item<false, 1, 8, true>(set, hidden, d, row_of_slot(perm, item, 16), item, it, tpw, k, 0, partials, floors, nullptr, nullptr,
                                         mask);
     else
-        project_item<true, 1, 8, true>(set, hidden, d, perm, item, it, tpw, k, 0, partials, floors, nullptr, nullptr,
+        project_item<true, 1, 8, true>(set, hidden, d, row_of_slot(perm, item, 16), item, it, tpw, k, 0, partials, floors, nullptr, nullptr,
                                        mask);
 }
 
@@ -462,6 +655,15 @@ hipError_t vpk_project_prepare()
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e == hipSuccess)
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(project_masked_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(project_small_kernel<8>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(project_small_kernel<16>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(project_small_kernel<32>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     return e;
 }
@@ -490,6 +692,25 @@ void vpk_project(const VpSlabSet &set, const void *hidden, int d, const int32_t 
     hipLaunchKernelGGL(project_kernel, dim3(grid_items), dim3(VP_WG_THREADS), lds + (raw_ok ? raw_bytes : 0), st,
                        set, (const uint4 *)hidden, d, perm, items, hdr, k, rstar, partials, floors, dbg_logits,
                        dbg_row_off, raw_ok);
+}
+
+// pf: 1 KiB loads a wavefront keeps in flight (8, 16 or 32; the k-tile count must be a multiple)
+void vpk_project_small(const VpSlabSet &set, const void *hidden, int d, const VpSmallArgs &a, int grid_items, int k,
+                       int rstar, float *partials, int raw_ok, int pf, hipStream_t st)
+{
+    const size_t lds = vpk_project_lds_bytes(set.kt, k, 1);
+    const size_t raw_bytes = (size_t)VP_WG_WAVES * VP_RAW_TILES * VP_TILE_ITEMS * 16 * sizeof(float);
+    if (lds + raw_bytes > 160 * 1024) raw_ok = 0;
+    const size_t bytes = lds + (raw_ok ? raw_bytes : 0);
+    if (pf == 32 && set.kt % 32 == 0)
+        hipLaunchKernelGGL(project_small_kernel<32>, dim3(grid_items), dim3(VP_WG_THREADS), bytes, st, set,
+                           (const uint4 *)hidden, d, a, k, rstar, partials, raw_ok);
+    else if (pf >= 16 && set.kt % 16 == 0)
+        hipLaunchKernelGGL(project_small_kernel<16>, dim3(grid_items), dim3(VP_WG_THREADS), bytes, st, set,
+                           (const uint4 *)hidden, d, a, k, rstar, partials, raw_ok);
+    else
+        hipLaunchKernelGGL(project_small_kernel<8>, dim3(grid_items), dim3(VP_WG_THREADS), bytes, st, set,
+                           (const uint4 *)hidden, d, a, k, rstar, partials, raw_ok);
 }
 
 void vpk_project_masked(const VpSlabSet &full, const void *hidden, int d, const int32_t *perm, const VpItem *items,

@@ -96,7 +96,7 @@ vp_status vp_kmeans(const void *x, int64_t n, int32_t d, int32_t K, int32_t iter
         for (int64_t r0 = 0; !gemm && r0 < n; r0 += CHUNK_ROWS) {
             const int rows = (int)std::min<int64_t>(CHUNK_ROWS, n - r0);
             vpk_centroid((const char *)x + (size_t)r0 * d * 2, rows, d, cp, cnorm, K, L.kt, L.ctiles, L.tpw, L.parts,
-                         cpart, nullptr, st);
+                         cpart, st);
             vpk_kmeans_assign(cpart, L.parts, rows, K, assign + r0, counts, st);
         }
         if (it == iters) break;   // the last pass only assigns

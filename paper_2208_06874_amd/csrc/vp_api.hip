@@ -5,7 +5,6 @@
 
 #include <algorithm>
 #include <mutex>
-#include <unordered_map>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -61,8 +60,6 @@ vp_status static_scratch_of_current_device(const char *fn, void **out)
     return VP_OK;
 }
 constexpr size_t LDS_LIMIT = 160 * 1024;
-constexpr int FUSED_PLAN_MAX_ITEMS = 2048;
-constexpr size_t TICKETS = 1024;   // counters of the fused planner an index owns
 inline size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 inline int ceil_div(long a, long b) { return (int)((a + b - 1) / b); }
@@ -73,7 +70,7 @@ struct ArenaLayout {
     long total_groups;     // candidate groups (of 16) over all clusters
     long n_total;
     int n_min, n_max, max_tiles;
-    size_t wp, wt, biasf, cp, cnorm, full_meta, tile_off, n_cand, ids_pad, sbias, bitmaps, tickets, slabs, total;
+    size_t wp, wt, biasf, cp, cnorm, full_meta, tile_off, n_cand, ids_pad, sbias, bitmaps, slabs, total;
     int bm_words;
 };
 
@@ -105,6 +102,7 @@ struct vp_index {
     const float *cnorm;
     int target_items, full_target_items, rstar;
     int min_items;   // resident workgroup slots of the projection kernel on this GPU
+    int cus;         // compute units of this GPU
     int wide_items;  // 1: single-bucket projections of more than 16 rows use items of 32 rows
     int gemm_target_items;   // work items of the GEMM-shaped kernel: its resident workgroup slots
     int gemm_min_rows;   // single-bucket projections of at least this many rows use the GEMM-shaped kernel (0: never)
@@ -112,14 +110,9 @@ struct vp_index {
     VpCostModel cost;
     const uint32_t *bitmaps;
     int union_dispatch;   // 1: vp_project_union may project a large union as a masked full projection
-    int fused_plan;   // batches of at most this many rows (<= 64) are planned inside the Eq. 2 kernel
+    int small_path;   // 1: batches of at most 16 rows are planned by the projection workgroups themselves
+    int small_pf;     // 1 KiB loads a wavefront of that path keeps in flight (0: chosen from the batch size)
     int raw_logits;   // 1: short items of small top-k >= 4 calls keep raw logits instead of lists (see run_clustered)
-    // Counters of finished workgroups for that, zero between calls.  Every workspace seen gets a
-    // counter of its own (calls that share a workspace do not overlap, so neither do the uses of
-    // its counter); when all are taken, calls on further workspaces use the planning kernel.
-    uint32_t *tickets;
-    mutable std::mutex ticket_mutex;
-    mutable std::unordered_map<const void *, int> ticket_of_workspace;
     VpProfile *prof;
 };
 
@@ -192,7 +185,6 @@ vp_status plan_arena(const vp_build_desc *D, bool check_ids, ArenaLayout *L)
     L->sbias = take((size_t)groups * VP_TILE_ITEMS * sizeof(float));
     L->bm_words = ceil_div((long)L->vtiles * VP_TILE_ITEMS, 32);
     L->bitmaps = take((size_t)D->K * L->bm_words * sizeof(uint32_t));
-    L->tickets = take(TICKETS * sizeof(uint32_t));
     L->slabs = take((size_t)groups * group_bytes);
     L->total = o;
     return VP_OK;
@@ -347,50 +339,58 @@ vp_status run_clustered(const char *fn, const vp_index *I, const void *hidden, i
     const long by_tiles = row_groups * ceil_div(I->L.max_tiles, VP_WG_WAVES);
     // (+ one round of blocks: the XCD swizzle of plans with heavy buckets rounds the grid up)
     const int grid_items = (int)std::min<long>(max_items, by_tiles) + 8 * VP_XCD_BLOCK_ITEMS;
-    // Eq. 2, then the plan: inside the same kernel for small batches with few items, where one
-    // workgroup of 256 threads is as fast as the planning kernel's 1024 and a launch is saved
-    // (not for the debug entry, which also wants the offsets of the rows' logits)
-    int slot = -1;
-    if (N <= I->fused_plan && grid_items <= FUSED_PLAN_MAX_ITEMS && !dbg_row_off) {
-        std::lock_guard<std::mutex> lock(I->ticket_mutex);
-        auto found = I->ticket_of_workspace.find(ws);
-        if (found != I->ticket_of_workspace.end()) {
-            slot = found->second;
-        } else if (I->ticket_of_workspace.size() < TICKETS) {
-            slot = (int)I->ticket_of_workspace.size();
-            I->ticket_of_workspace.emplace(ws, slot);
-        }
+    // Batches of a few rows: no planning kernel; the projection workgroups find their own work
+    // (project_small_kernel).  With dispatch on, only when the slabs are the cheaper form even
+    // if every row sat in a cluster of its own with the longest list (the planner's cost model
+    // on that worst case), so that nothing is lost by not asking it.
+    bool small = I->small_path && N <= VP_SMALL_ROWS && !dbg_row_off && !dbg_logits;
+    if (small && dispatch) {
+        const float worst = (float)N * I->L.max_tiles;
+        const float t_slab = worst / cost.bw_slab;
+        const float t_full = I->L.vtiles / cost.bw_full * (1.f + k * 0.125f);
+        small = t_slab <= t_full;
     }
-    if (slot >= 0) {
-        VpPlanArgs a = {};
-        a.n_cand = I->clusters.n_cand;
+    const int raw_ok_all = I->raw_logits && !dbg_logits && k >= 4 && (long)N * I->L.max_tiles <= 8192;
+    if (small) {
+        // Eq. 2 with one workgroup per centroid tile: one minimum per tile and row
+        vpk_centroid_small(hidden, N, I->d, I->cp, I->cnorm, I->K, I->L.kt, I->L.ctiles, cpart, st);
+        VpSmallArgs a = {};
+        a.cpart = reinterpret_cast<const int32_t *>(cpart);
+        a.parts = I->L.ctiles;
+        a.N = N;
+        a.K = I->K;
         a.tile_off = I->clusters.tile_off;
+        a.n_cand = I->clusters.n_cand;
         a.target_items = I->target_items;
         a.min_items = I->min_items;
-        a.max_items = max_items;
         a.g = g;
         a.out_cluster = out_cluster;
-        a.perm = perm;
         a.rowplan = rowplan;
-        a.floors = floors;
-        a.items = items;
         a.hdr = hdr;
-        a.dispatch = dispatch;
-        a.cost = cost;
-        a.k = k;
-        a.V = I->V;
-        a.vtiles = I->L.vtiles;
-        a.full_target_items = sb_target(I, rt_masked);
-        a.full_min_items = sb_min(I, rt_masked);
-        a.max_items_full = max_full;
-        a.ticket = I->tickets + slot;
-        vpk_centroid(hidden, N, I->d, I->cp, I->cnorm, I->K, I->L.kt, I->L.ctiles, tpw_c, parts, cpart, &a, st);
-    } else {
-        vpk_centroid(hidden, N, I->d, I->cp, I->cnorm, I->K, I->L.kt, I->L.ctiles, tpw_c, parts, cpart, nullptr, st);
-        vpk_plan(cpart, parts, N, I->K, I->clusters.n_cand, I->clusters.tile_off, I->target_items, I->min_items, max_items, g,
-                 out_cluster, perm, rowplan, floors, items, hdr, dbg_row_off, dispatch, cost, k, I->V, I->L.vtiles,
-                 sb_target(I, rt_masked), sb_min(I, rt_masked), max_full, st);
+        // items: at most one per tiles_per_wave * 4 tiles of a bucket plus a partly filled one per
+        // bucket; tiles_per_wave is 1 only while that gives at most min_items items
+        const long worst_tiles = (long)N * I->L.max_tiles;
+        const long eff = std::max<long>(I->min_items, std::min<long>(I->target_items, worst_tiles / (4 * VP_WG_WAVES)));
+        const int grid_small = (int)std::min<long>((long)N * ceil_div(I->L.max_tiles, VP_WG_WAVES), eff + N);
+        // loads in flight per wavefront: 16 (three wavefronts per SIMD) measured best or within 2 %
+        // of the best from 1 to 16 rows, top-1 and top-8 (32: no faster even for one row, whose
+        // wavefronts then hold their whole share in flight; 8: 13 % slower at 4 rows, top-8)
+        int pf = I->small_pf;
+        if (pf == 0) pf = I->L.kt % 16 == 0 ? 16 : 8;
+        // resident workgroups of the kernel with that many loads in flight (2, 3 or 4 wavefronts per SIMD)
+        const int per_cu = std::max(1, I->min_items / I->cus);
+        a.min_items = I->cus * std::min(per_cu, pf == 32 ? 2 : pf == 16 ? 3 : 4);
+        auto *ev = profile_slot(I);
+        if (ev) (void)hipEventRecord(ev->first, st);
+        vpk_project_small(I->clusters, hidden, I->d, a, grid_small, k, I->rstar, partials, raw_ok_all, pf, st);
+        if (ev) (void)hipEventRecord(ev->second, st);
+        vpk_merge(I->clusters, rowplan, hdr, partials, k, N, out_ids, out_logp, st);
+        return launch_status(fn);
     }
+    vpk_centroid(hidden, N, I->d, I->cp, I->cnorm, I->K, I->L.kt, I->L.ctiles, tpw_c, parts, cpart, st);
+    vpk_plan(cpart, parts, N, I->K, I->clusters.n_cand, I->clusters.tile_off, I->target_items, I->min_items, max_items, g,
+             out_cluster, perm, rowplan, floors, items, hdr, dbg_row_off, dispatch, cost, k, I->V, I->L.vtiles,
+             sb_target(I, rt_masked), sb_min(I, rt_masked), max_full, st);
 
     auto *ev = profile_slot(I);
     if (ev) (void)hipEventRecord(ev->first, st);
@@ -399,7 +399,7 @@ vp_status run_clustered(const char *fn, const vp_index *I, const void *hidden, i
     // workgroups and its items are lengthened; the kernel checks the plan's figure itself).
     // For those, keeping raw logits beats building top-k lists from k = 4 on (measured: N = 1,
     // top-8: 50 -> 40 us per call; top-1: no gain, so the lists stay).
-    const int raw_ok = I->raw_logits && !dbg_logits && k >= 4 && (long)N * I->L.max_tiles <= 8192;
+    const int raw_ok = raw_ok_all;
     vpk_project(I->clusters, hidden, I->d, perm, items, hdr, grid_items, 1, k, I->rstar, partials, floors, dbg_logits,
                 dbg_row_off, raw_ok, st);
     if (dispatch) {
@@ -544,8 +544,7 @@ vp_status vp_build(const vp_build_desc *D, void *hip_stream, vp_index **out)
     vpk_cnorm(D->centroids, D->K, D->d, L.ctiles * VP_TILE_ITEMS, reinterpret_cast<float *>(A + L.cnorm), st);
     vpk_gather_slabs(A + L.wp, D->bias, L.kt, reinterpret_cast<const int32_t *>(A + L.ids_pad), L.total_groups,
                      A + L.slabs, reinterpret_cast<float *>(A + L.sbias), st);
-    e = hipMemsetAsync(A + L.tickets, 0, TICKETS * sizeof(uint32_t), st);
-    if (e == hipSuccess) e = hipMemsetAsync(A + L.bitmaps, 0, (size_t)D->K * L.bm_words * sizeof(uint32_t), st);
+    e = hipMemsetAsync(A + L.bitmaps, 0, (size_t)D->K * L.bm_words * sizeof(uint32_t), st);
     if (e != hipSuccess) return fail(VP_ERR_HIP, "vp_build: %s", hipGetErrorString(e));
     vpk_bitmaps(reinterpret_cast<const int32_t *>(A + L.ids_pad), reinterpret_cast<const int32_t *>(A + L.tile_off),
                 D->K, L.total_groups, L.bm_words, reinterpret_cast<uint32_t *>(A + L.bitmaps), st);
@@ -597,9 +596,9 @@ vp_status vp_build(const vp_build_desc *D, void *hip_stream, vp_index **out)
     I->cost.t_gather = 12.0e-6f;
     I->union_dispatch = 1;
     I->bitmaps = reinterpret_cast<const uint32_t *>(A + L.bitmaps);
-    I->fused_plan = 16;
+    I->small_path = 1;
+    I->small_pf = 0;
     I->raw_logits = 1;
-    I->tickets = reinterpret_cast<uint32_t *>(A + L.tickets);
     {
         // workgroups of the projection kernel that fit on the chip at once (LDS-limited)
         int dev = 0, cus = 256;
@@ -607,6 +606,7 @@ vp_status vp_build(const vp_build_desc *D, void *hip_stream, vp_index **out)
         const size_t lds = vpk_project_lds_bytes(L.kt, D->k_max, 1);
         const int per_cu = (int)std::max<size_t>(1, std::min<size_t>(8, LDS_LIMIT / lds));
         I->min_items = std::max(1, cus) * per_cu;
+        I->cus = std::max(1, cus);
     }
     I->prof = new (std::nothrow) VpProfile();
     // resolve this device's scratch array now, so that vp_project_static's first call does not have to
@@ -641,71 +641,47 @@ vp_status vp_get_info(const vp_index *I, vp_index_info *info)
 vp_status vp_set_option(vp_index *I, const char *name, int64_t value)
 {
     if (!I || !name) return fail(VP_ERR_INVALID_ARG, "vp_set_option: null argument");
-    if (!std::strcmp(name, "target_items") || !std::strcmp(name, "full_target_items")) {
-        if (value < 1 || value > (1 << 20))
-            return fail(VP_ERR_INVALID_ARG, "vp_set_option: %s = %lld must be in [1, 2^20]", name, (long long)value);
-        (name[0] == 't' ? I->target_items : I->full_target_items) = (int)value;
-        return VP_OK;
-    }
-    if (!std::strcmp(name, "rstar")) {
-        if (value < 0 || value > VP_GEMV_MAX_ROWS)
-            return fail(VP_ERR_INVALID_ARG, "vp_set_option: rstar = %lld must be in [0, %d]", (long long)value,
-                        VP_GEMV_MAX_ROWS);
-        I->rstar = (int)value;
-        return VP_OK;
-    }
-    if (!std::strcmp(name, "union_dispatch")) {
-        if (value != 0 && value != 1) return fail(VP_ERR_INVALID_ARG, "vp_set_option: union_dispatch must be 0 or 1");
-        I->union_dispatch = (int)value;
-        return VP_OK;
-    }
-    if (!std::strcmp(name, "fused_plan")) {
-        if (value < 0 || value > VP_PLAN_SMALL_ROWS)
-            return fail(VP_ERR_INVALID_ARG, "vp_set_option: fused_plan must be in [0, %d]", VP_PLAN_SMALL_ROWS);
-        I->fused_plan = (int)value;
-        return VP_OK;
-    }
-    if (!std::strcmp(name, "raw_logits")) {
-        if (value != 0 && value != 1) return fail(VP_ERR_INVALID_ARG, "vp_set_option: raw_logits must be 0 or 1");
-        I->raw_logits = (int)value;
-        return VP_OK;
-    }
-    if (!std::strcmp(name, "dispatch")) {
-        if (value != 0 && value != 1) return fail(VP_ERR_INVALID_ARG, "vp_set_option: dispatch must be 0 or 1");
-        I->dispatch = (int)value;
-        return VP_OK;
-    }
-    if (!std::strcmp(name, "cost_bw_gather_gbs")) {
-        if (value < 1 || value > 1000000) return fail(VP_ERR_INVALID_ARG, "vp_set_option: %s out of range", name);
-        I->cost.bw_gather = (float)value * 1e9f;
-        return VP_OK;
-    }
-    if (!std::strcmp(name, "cost_bw_slab_gbs") || !std::strcmp(name, "cost_bw_full_gbs") ||
-        !std::strcmp(name, "cost_bw_l2_gbs") || !std::strcmp(name, "cost_bw_gemm_gbs")) {
-        if (value < 1 || value > 1000000) return fail(VP_ERR_INVALID_ARG, "vp_set_option: %s out of range", name);
-        float &f = name[8] == 's' ? I->cost.bw_slab : name[8] == 'f' ? I->cost.bw_full : name[8] == 'g' ? I->cost.bw_gemm : I->cost.bw_l2;
-        f = (float)value * 1e9f;
-        return VP_OK;
-    }
-    if (!std::strcmp(name, "gemm_target_items")) {
-        if (value < 1 || value > (1 << 20)) return fail(VP_ERR_INVALID_ARG, "vp_set_option: gemm_target_items out of range");
-        I->gemm_target_items = (int)value;
-        return VP_OK;
-    }
-    if (!std::strcmp(name, "gemm_min_rows")) {
-        if (value < 0 || value > VP_MAX_ROWS) return fail(VP_ERR_INVALID_ARG, "vp_set_option: gemm_min_rows out of range");
-        I->gemm_min_rows = (int)value;
-        return VP_OK;
-    }
-    if (!std::strcmp(name, "wide_items")) {
-        if (value != 0 && value != 1) return fail(VP_ERR_INVALID_ARG, "vp_set_option: wide_items must be 0 or 1");
-        I->wide_items = (int)value;
-        return VP_OK;
-    }
+    // one row per option: where it lives, its range, and for the rates of the cost model the
+    // factor from the option's unit (GB/s) to bytes per second
+    struct Option {
+        const char *name;
+        int vp_index::*field;
+        float VpCostModel::*rate;
+        int64_t lo, hi;
+    };
+    static const Option table[] = {
+        {"target_items", &vp_index::target_items, nullptr, 1, 1 << 20},
+        {"full_target_items", &vp_index::full_target_items, nullptr, 1, 1 << 20},
+        {"gemm_target_items", &vp_index::gemm_target_items, nullptr, 1, 1 << 20},
+        {"gemm_min_rows", &vp_index::gemm_min_rows, nullptr, 0, VP_MAX_ROWS},
+        {"rstar", &vp_index::rstar, nullptr, 0, VP_GEMV_MAX_ROWS},
+        {"wide_items", &vp_index::wide_items, nullptr, 0, 1},
+        {"dispatch", &vp_index::dispatch, nullptr, 0, 1},
+        {"union_dispatch", &vp_index::union_dispatch, nullptr, 0, 1},
+        {"small_path", &vp_index::small_path, nullptr, 0, 1},
+        {"small_pf", &vp_index::small_pf, nullptr, 0, 32},
+        {"raw_logits", &vp_index::raw_logits, nullptr, 0, 1},
+        {"cost_bw_slab_gbs", nullptr, &VpCostModel::bw_slab, 1, 1000000},
+        {"cost_bw_full_gbs", nullptr, &VpCostModel::bw_full, 1, 1000000},
+        {"cost_bw_l2_gbs", nullptr, &VpCostModel::bw_l2, 1, 1000000},
+        {"cost_bw_gemm_gbs", nullptr, &VpCostModel::bw_gemm, 1, 1000000},
+        {"cost_bw_gather_gbs", nullptr, &VpCostModel::bw_gather, 1, 1000000},
+    };
     if (!std::strcmp(name, "profile")) {
         if (value != 0 && value != 1) return fail(VP_ERR_INVALID_ARG, "vp_set_option: profile must be 0 or 1");
         if (!I->prof) return fail(VP_ERR_INVALID_ARG, "vp_set_option: profiling unavailable");
         I->prof->on = value == 1;
+        return VP_OK;
+    }
+    for (const Option &o : table) {
+        if (std::strcmp(name, o.name) != 0) continue;
+        if (value < o.lo || value > o.hi)
+            return fail(VP_ERR_INVALID_ARG, "vp_set_option: %s = %lld must be in [%lld, %lld]", name, (long long)value,
+                        (long long)o.lo, (long long)o.hi);
+        if (o.field == &vp_index::small_pf && value != 0 && value != 8 && value != 16 && value != 32)
+            return fail(VP_ERR_INVALID_ARG, "vp_set_option: small_pf must be 0, 8, 16 or 32");
+        if (o.field) I->*o.field = (int)value;
+        else I->cost.*o.rate = (float)value * 1e9f;
         return VP_OK;
     }
     return fail(VP_ERR_INVALID_ARG, "vp_set_option: unknown option '%s'", name);
@@ -843,7 +819,7 @@ vp_status vp_project_union(const vp_index *I, const void *hidden, int32_t N, int
     int parts = std::min(ceil_div(I->L.ctiles, 4), std::max(1, 2048 / (4 * row_tiles)));
     const int tpw_c = ceil_div(I->L.ctiles, parts * 4);
     parts = ceil_div(I->L.ctiles, tpw_c * 4);
-    vpk_centroid(hidden, N, I->d, I->cp, I->cnorm, I->K, I->L.kt, I->L.ctiles, tpw_c, parts, cpart, nullptr, st);
+    vpk_centroid(hidden, N, I->d, I->cp, I->cnorm, I->K, I->L.kt, I->L.ctiles, tpw_c, parts, cpart, st);
     // step 2: boolean list over the vocabulary -> reduced column set U
     int32_t *zero_g = reinterpret_cast<int32_t *>(ws + U.zero_g);
     vpk_union_mark(cpart, parts, N, I->K, U.mask_words, g, out_cluster, occ, uh, mask, zero_g, st);

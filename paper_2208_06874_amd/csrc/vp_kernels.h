@@ -19,7 +19,10 @@ void vpk_bitmaps(const int32_t *ids_pad, const int32_t *tile_off, int K, long to
 
 // centroid selection (Eq. 2)
 void vpk_centroid(const void *hidden, int N, int d, const void *cp, const float *cnorm, int K, int kt,
-                  int ctiles, int tiles_per_part, int parts, void *cpart, const VpPlanArgs *plan, hipStream_t st);
+                  int ctiles, int tiles_per_part, int parts, void *cpart, hipStream_t st);
+
+void vpk_centroid_small(const void *hidden, int N, int d, const void *cp, const float *cnorm, int K, int kt,
+                        int ctiles, void *cpart, hipStream_t st);
 
 // bucketing + planning
 size_t vpk_plan_lds_bytes(int K);
@@ -39,6 +42,9 @@ hipError_t vpk_project_prepare();
 void vpk_project(const VpSlabSet &set, const void *hidden, int d, const int32_t *perm, const VpItem *items,
                  const VpPlanHeader *hdr, int grid_items, int row_tiles, int k, int rstar, float *partials,
                  unsigned int *floors, float *dbg_logits, const int64_t *dbg_row_off, int raw_ok, hipStream_t st);
+
+void vpk_project_small(const VpSlabSet &set, const void *hidden, int d, const VpSmallArgs &a, int grid_items, int k,
+                       int rstar, float *partials, int raw_ok, int pf, hipStream_t st);
 
 void vpk_project_masked(const VpSlabSet &full, const void *hidden, int d, const int32_t *perm, const VpItem *items,
                         const VpPlanHeader *hdr, int grid_items, int k, float *partials, unsigned int *floors,

@@ -172,25 +172,19 @@ struct VpCostModel {
     float t_gather;  // ... and the fixed time of the kernels only that gather needs (seconds)
 };
 
-#define VP_PLAN_SMALL_ROWS 64   // batches up to this size can be planned inside the Eq. 2 kernel
+#define VP_SMALL_ROWS 16   // batches up to this size are planned by the projection workgroups themselves
 
-// Everything the planner needs besides the per-part minima of Eq. 2.
-struct VpPlanArgs {
-    const int32_t *n_cand;
-    const int32_t *tile_off;
-    int target_items, min_items, max_items;
-    int32_t *g;
-    int32_t *out_cluster;
-    int32_t *perm;
-    VpRowPlan *rowplan;
-    unsigned int *floors;
-    VpItem *items;
-    VpPlanHeader *hdr;
-    int32_t dispatch;    // 0, or rows per item of the masked full projection the planner may choose
-    VpCostModel cost;
-    int k, V, vtiles, full_target_items, full_min_items, max_items_full;
-    unsigned int *ticket;   // counts the workgroups of the Eq. 2 kernel that are done (null: separate planning kernel)
-    int total_wgs;
+// What a workgroup of the small-batch projection needs to find its own work (project.hip).
+struct VpSmallArgs {
+    const int32_t *cpart;       // [N][parts][2] per-part (score bits, index) minima of Eq. 2
+    int parts, N, K;
+    const int32_t *tile_off;    // per cluster: first candidate tile of its slab
+    const int32_t *n_cand;      // per cluster: candidates
+    int target_items, min_items;
+    int32_t *g;                 // [N] cluster of each row (out)
+    int32_t *out_cluster;       // [N] or null
+    VpRowPlan *rowplan;         // [N] the merge kernel's records, indexed by row (out)
+    VpPlanHeader *hdr;          // (out)
 };
 
 // Size in floats of one partial result: running max, sum of exponentials, then

@@ -459,6 +459,14 @@ def _planner_mode(index, N):
     return int(ws[:64].view(torch.int32)[7].item())
 
 
+def _overflow(index, N):
+    """White-box: the flag that says the plan did not fit its item list (vp.h: VP_WS_OVERFLOW_WORD)."""
+    import torch
+    ws = index.workspace(N)
+    torch.cuda.synchronize()
+    return int(ws[:64].view(torch.int32)[2].item())
+
+
 def test_dispatch_to_the_masked_full_projection(oracle, tiny, mid):
     """With dispatch on, batches that occupy many clusters run the full projection with every row masked
     to its own active set; the results must be those of the per-cluster projection."""
@@ -517,8 +525,7 @@ def test_dispatch_cost_model_constants(mid):
 def test_replay_from_a_captured_graph(mid, tiny, which, N):
     """vp_project only enqueues kernels (no allocation, no synchronisation, no memset), so a call can be
     captured into a HIP graph; every replay, with eager work in between, must equal the eager result.  (The
-    small case has the planner inside the Eq. 2 kernel: its ticket counter is among the recorded arguments
-    and must be back at zero after every replay.)"""
+    small case has no planning kernel: the projection workgroups find their own work.)"""
     import torch
     mid = mid if which == "mid" else tiny
     cfg = mid.cfg
@@ -786,44 +793,50 @@ def test_random_shapes(oracle):
 
 
 @pytest.mark.gpu
-def test_planner_inside_the_centroid_kernel(oracle, tiny, mid):
-    """Batches of at most 64 rows (by default 16) can be planned by the last workgroup of the Eq. 2 kernel:
-    same results as with the separate planning kernel and as the oracle, for every bucket structure and many
-    calls in a row."""
+def test_small_batches_without_a_planning_kernel(oracle, tiny, mid):
+    """Batches of at most 16 rows are planned by the projection workgroups themselves (no planning kernel,
+    no item list): same plan as the planning kernel's, so the same bits, for every bucket structure, every
+    number of loads in flight (which also sets how long the items are), and many calls in a row."""
     import torch
     r = np.random.default_rng(64)
 
-    def run(B, H, k, fused, dispatch):
-        B.index.set_option("fused_plan", fused)
+    def run(B, H, k, small, dispatch, pf=0):
+        B.index.set_option("small_path", small)
+        B.index.set_option("small_pf", pf)
         B.index.set_option("dispatch", dispatch)
         try:
             out = B.project(H, k)
-            return out, _planner_mode(B.index, H.shape[0])
+            return out, _planner_mode(B.index, H.shape[0]), _overflow(B.index, H.shape[0])
         finally:
-            B.index.set_option("fused_plan", 16)
+            B.index.set_option("small_path", 1)
+            B.index.set_option("small_pf", 0)
             B.index.set_option("dispatch", 0)
 
     for B in (tiny, mid):
         K = B.C.shape[0]
-        for N, clusters in ((1, None), (2, [3, 3]), (5, None), (16, [1] * 16), (17, [2] * 17), (33, None),
-                            (64, None), (64, [K - 1] * 64), (64, [0] * 30 + [K - 1] * 34), (63, list(range(63))),
-                            (48, [5] * 16 + [6] * 16 + [7] * 16)):
+        for N, clusters in ((1, None), (2, [3, 3]), (3, [K - 1, 0, K - 1]), (5, None), (16, [1] * 16), (16, None),
+                            (16, list(range(16))), (15, [7] * 8 + [2] * 7), (9, [4, 4, 4, 1, 1, 9, 9, 9, 9])):
             cl = None if clusters is None else [c % K for c in clusters]
             H = _rows(r, B.C, N, clusters=cl)
-            for k in (1, 4):
-                print("fused planner:", B.cfg.name, "N", N, "k", k, flush=True)
-                base, _ = run(B, H, k, 0, 0)
-                got, _ = run(B, H, k, 64, 0)
-                assert np.array_equal(got[2], base[2]) and np.array_equal(got[0], base[0])
-                assert np.array_equal(got[1], base[1]), "same kernels, same item boundaries: same bits"
+            for k in (1, 4, 8):
+                print("small path:", B.cfg.name, "N", N, "k", k, flush=True)
+                base, _, ovf0 = run(B, H, k, 0, 0)
+                assert ovf0 == 0
+                for pf in (0, 8, 16, 32):
+                    got, _, ovf = run(B, H, k, 1, 0, pf)
+                    assert ovf == 0
+                    assert np.array_equal(got[2], base[2]) and np.array_equal(got[0], base[0])
+                    if pf == 8:
+                        assert np.array_equal(got[1], base[1]), "same item boundaries: same bits"
+                    else:    # items sized for another number of resident workgroups: another order of the sums
+                        assert np.allclose(got[1], base[1], rtol=0, atol=1e-5)
                 pu.check_projection(oracle, B.W, B.b, B.C, B.cand_off, B.cand_ids, H, k, got[0], got[1], got[2])
                 # with the planner free to choose the masked full projection
-                d1, mode1 = run(B, H, k, 64, 1)
-                d0, mode0 = run(B, H, k, 0, 1)
-                assert mode1 == mode0
+                d1, mode1, _ = run(B, H, k, 1, 1)
+                d0, mode0, _ = run(B, H, k, 0, 1)
                 assert np.array_equal(d1[0], d0[0]) and np.array_equal(d1[2], base[2])
                 pu.check_projection(oracle, B.W, B.b, B.C, B.cand_off, B.cand_ids, H, k, d1[0], d1[1], d1[2])
-    # the counter returns to zero: several thousand calls in a row on one workspace
+    # several thousand calls in a row on one workspace
     H = _rows(r, tiny.C, 7)
     base = tiny.project(H, 2)
     Ht = tiny.rows(H)
@@ -831,14 +844,13 @@ def test_planner_inside_the_centroid_kernel(oracle, tiny, mid):
         out = tiny.index.project(Ht, 2)
     torch.cuda.synchronize()
     assert np.array_equal(pu.to_np(out[0]), base[0]) and np.array_equal(pu.to_np(out[1]), base[1])
-    # every workspace gets a counter of its own; beyond the 1,024 the index owns, calls fall back to the
-    # planning kernel: 1,100 workspaces carved from one buffer, garbage in all of them
+    # workspaces full of garbage: nothing in them is read before it is written
     need = (tiny.index.workspace_bytes(7) + 255) // 256 * 256
-    big = torch.empty(1100 * need, dtype=torch.uint8, device=tiny.dev)
+    big = torch.empty(40 * need, dtype=torch.uint8, device=tiny.dev)
     big.fill_(0x5A)
-    outs = [tiny.index.project(Ht, 2, workspace=big[i * need:(i + 1) * need]) for i in range(1100)]
+    outs = [tiny.index.project(Ht, 2, workspace=big[i * need:(i + 1) * need]) for i in range(40)]
     torch.cuda.synchronize()
-    for i in (0, 1, 511, 1023, 1024, 1025, 1099):
+    for i in (0, 1, 20, 39):
         assert np.array_equal(pu.to_np(outs[i][0]), base[0]) and np.array_equal(pu.to_np(outs[i][1]), base[1]), i
     del big, outs
 
@@ -846,7 +858,7 @@ def test_planner_inside_the_centroid_kernel(oracle, tiny, mid):
 @pytest.mark.gpu
 def test_overlapping_calls_on_several_streams(tiny, mid):
     """Calls on different streams, each with a workspace and outputs of its own, may overlap on one index
-    (the planner's ticket counters are handed out per call): every result equals the one-stream result."""
+    (nothing but the workspace and the outputs is written by a call): every result equals the one-stream result."""
     import torch
     for B, N, k in ((tiny, 3, 4), (mid, 2, 8), (mid, 40, 8)):
         dev = B.dev
