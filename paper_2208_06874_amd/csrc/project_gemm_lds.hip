@@ -1,0 +1,469 @@
+// Projection of many rows against one run of slab tiles with the rows held in LDS: the
+// GEMM-shaped case of Eq. 1 (section 2.1) for single-bucket plans (the full projection, the
+// masked full projection, the batch-union form) of more than 16 rows and k-extents up to
+// d_pad = 1024.
+//
+// An item is 64 rows x a range of candidate groups, one workgroup of eight wavefronts.  The 64
+// rows are staged once in LDS in MFMA operand order (4 row tiles x KT KiB) and never move
+// again.  The range is cut into steps of four candidate groups (64 candidates); wavefront w
+// takes steps w, w + 8, ...  A step streams the four groups' tiles straight into registers
+// (a ring of four k-tiles ahead, crossing step boundaries, so the loads never drain), and per
+// k-tile feeds each loaded 1 KiB slab tile to four v_mfma_f32_16x16x32_f16, one per row tile,
+// whose row operands are read from LDS (one 1 KiB read per four MFMAs).  No wavefront waits
+// for another inside the loop: there is no split of the k-extent, so nothing is exchanged and
+// there is no barrier between the staging of the rows and the end of the item.
+//
+// After the 32 x 16 MFMAs of a step a lane holds, for each of the four row tiles, the 16 logits
+// of one row (its quarter of each of the four groups).  They are folded in one go: bias,
+// validity and membership mask, one online log-sum-exp update per row (steps 4-5 of the
+// inference list of section 2.3), and the top-k (section 2.1).  Top-1 stays in registers.  For
+// k >= 2 the workgroup keeps ONE list per row in LDS, shared by all eight wavefronts: k 64-bit
+// keys (the logit's bits made monotone above the complemented position, so a larger key is an
+// earlier entry in (logit descending, position ascending) order), always sorted.  A candidate is
+// inserted without locks or turns by a cascade of LDS atomic maxima: slot 0 takes max(slot, key)
+// and hands the smaller of the two to slot 1, and so on; every step keeps the multiset of keys
+// (slots plus keys on their way) and the order of the slots, slots only ever grow, and a key
+// leaves the far end only if k others are ahead of it - so whatever the interleaving of the
+// lanes and wavefronts, the list ends as the k best keys in order.  The last slot is at all
+// times a lower bound of the row's k-th best: a lane offers only candidates that are not below
+// it (nor below the bound the workgroups that hold the same rows trade through global memory),
+// best first, re-reading the bound after every insertion - so even the first step, which finds
+// the list empty, costs a lane one or two insertions rather than sixteen.
+#include <hip/hip_runtime.h>
+#include <type_traits>
+#include "vp_kernels.h"
+#include "project_common.h"
+#include "wave_ops.h"
+
+namespace {
+
+constexpr int L_NW = 8;        // wavefronts per workgroup
+constexpr int L_G = 4;         // candidate groups per step
+constexpr int L_RT = 4;        // row tiles per item
+constexpr int L_ROWS = 64;     // row slots per item
+constexpr int L_PF = 4;        // k-tiles of the four groups kept in flight
+constexpr int VP_MAX_TOPK_LANES = 32;   // the epilogue writes a row's list with one lane per entry
+
+// (logit descending, position ascending), without branches
+__device__ inline bool before_entry(float v, int i, float v2, int i2) { return (v > v2) | ((v == v2) & (i < i2)); }
+
+template <int KT, bool MASKED, bool NT>
+__device__ inline void gemm_lds_item(const VpSlabSet &set, const uint4 *__restrict__ hidden, int d,
+                                     const int32_t *__restrict__ perm, const VpItem &item, int it, int k,
+                                     float *__restrict__ partials, unsigned int *__restrict__ floors,
+                                     const VpMaskInfo &mask)
+{
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6;
+    const int lane = tid & 63;
+    const int n = lane & 15;
+    const int q = lane >> 4;
+
+    extern __shared__ uint4 lds[];
+    uint4 *ldsB = lds;                                                          // [L_RT][KT][64]: the rows
+    unsigned long long *lkey = reinterpret_cast<unsigned long long *>(lds + L_RT * KT * 64);   // [k][64]: the rows' lists
+    unsigned int *wg_floor = reinterpret_cast<unsigned int *>(lkey + k * L_ROWS);               // [64]
+    // after the loop, in place of the rows:
+    float *hdr_m = reinterpret_cast<float *>(lds);                              // [L_NW][64]
+    float *hdr_s = hdr_m + L_NW * L_ROWS;
+
+    const int ncand = item.ncand;
+    const int gb = item.tile0;
+    const int ge = item.tile0 + item.ntiles;
+    const int nsteps = (item.ntiles + L_G - 1) / L_G;
+    const int last_word = ((ncand + VP_TILE_ITEMS - 1) / VP_TILE_ITEMS * VP_TILE_ITEMS - 1) >> 5;   // of a membership list
+    const uint4 *slab = reinterpret_cast<const uint4 *>(set.tiles) + (size_t)item.tile_off * KT * 64 + lane;
+    const float *bias = set.bias + (size_t)item.tile_off * VP_TILE_ITEMS + q * 4;
+
+    // offsets (in 16-byte pieces) of the four groups of a step; groups past the item's end repeat
+    // its last group (loaded, never looked at)
+    auto group_off = [&](int step, unsigned int (&off)[L_G]) {
+#pragma unroll
+        for (int j = 0; j < L_G; ++j) off[j] = (unsigned int)min(gb + step * L_G + j, ge - 1) * (KT * 64);
+    };
+
+    uint4 ring[L_PF][L_G];
+    unsigned int cur[L_G], nxt[L_G];
+    int step = wave;
+    const bool active = step < nsteps;
+    if (active) {
+        group_off(step, cur);
+#pragma unroll
+        for (int p = 0; p < L_PF; ++p)
+#pragma unroll
+            for (int j = 0; j < L_G; ++j) ring[p][j] = load_piece<NT>(slab + cur[j] + p * 64);
+    }
+
+    // the rows of this item -> LDS, MFMA operand order (row slots beyond nrows: zeros)
+    {
+        constexpr int X = KT * 4;   // 16-byte pieces per padded row
+        const int pieces_per_row = d >> 3;
+        for (int e = tid; e < L_ROWS * X; e += L_NW * 64) {
+            const int r = e / X;
+            const int x = e - r * X;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (r < item.nrows && x < pieces_per_row) {
+                const int row = perm[item.perm_start + r];
+                v = hidden[(size_t)row * pieces_per_row + x];
+            }
+            ldsB[((r >> 4) * KT + (x >> 2)) * 64 + (x & 3) * 16 + (r & 15)] = v;
+        }
+    }
+    for (int e = tid; e < k * L_ROWS; e += L_NW * 64) lkey[e] = 0ull;   // below the key of every logit
+    // this lane's row in each row tile
+    int myrow[L_RT];
+    bool row_valid[L_RT];
+#pragma unroll
+    for (int rt = 0; rt < L_RT; ++rt) {
+        const int slot = rt * 16 + n;
+        row_valid[rt] = slot < item.nrows;
+        myrow[rt] = row_valid[rt] ? perm[item.perm_start + slot] : -1;
+    }
+    if (tid < L_ROWS) {
+        const int row = tid < item.nrows ? perm[item.perm_start + tid] : -1;
+        wg_floor[tid] = row >= 0 ? floors[row] : VP_FLOOR_NONE;
+    }
+    __syncthreads();
+
+    // per row tile: running maximum, sum of exponentials, k-th best of this wavefront's list
+    float m_run[L_RT], s_run[L_RT];
+    float b1v[L_RT];
+    int b1i[L_RT];
+    const uint32_t *mrow[L_RT];
+#pragma unroll
+    for (int rt = 0; rt < L_RT; ++rt) {
+        m_run[rt] = VP_NEG_BIG;
+        s_run[rt] = 0.f;
+        b1v[rt] = -__builtin_inff();
+        b1i[rt] = VP_IDX_NONE;
+        mrow[rt] = MASKED ? mask.bitmaps + (size_t)(row_valid[rt] ? mask.g[myrow[rt]] : 0) * mask.words : nullptr;
+    }
+    const bool top1 = k == 1;
+    unsigned int pending[L_RT];
+    int pending_rt = -1;
+    int done_steps = 0;
+
+    uint4 bnext[L_RT];   // the rows' operands of the k-tile to come
+#pragma unroll
+    for (int rt = 0; rt < L_RT; ++rt) bnext[rt] = ldsB[(rt * KT) * 64 + lane];
+    static_assert((KT & (KT - 1)) == 0, "k-tile counts of this kernel are powers of two");
+
+    while (step < nsteps) {
+        const int g0 = gb + step * L_G;
+        const int next_step = step + L_NW;
+        group_off(next_step < nsteps ? next_step : step, nxt);
+        // bias and membership words of the step, wanted only after its MFMAs
+        float4 bz[L_G];
+#pragma unroll
+        for (int j = 0; j < L_G; ++j) bz[j] = *reinterpret_cast<const float4 *>(bias + (size_t)min(g0 + j, ge - 1) * VP_TILE_ITEMS);
+        uint32_t mw[L_RT][2];
+        if (MASKED) {
+#pragma unroll
+            for (int rt = 0; rt < L_RT; ++rt) {
+                // the step's 64 candidates start at a multiple of 64: two whole 32-bit words
+                const int w0 = (g0 * VP_TILE_ITEMS) >> 5;
+                mw[rt][0] = mrow[rt][w0];
+                mw[rt][1] = mrow[rt][min(w0 + 1, last_word)];
+            }
+        }
+
+        floatx4 acc[L_RT][L_G];
+#pragma unroll
+        for (int rt = 0; rt < L_RT; ++rt)
+#pragma unroll
+            for (int j = 0; j < L_G; ++j) acc[rt][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+        // L_PF k-tiles per pass of the loop body: pass b consumes the ring and refills it with
+        // k-tiles (b + 1) * L_PF ... of this step, the last pass with the first k-tiles of the
+        // wavefront's next step
+#pragma unroll 1
+        for (int b = 0; b < KT / L_PF; ++b) {
+            const bool last = b == KT / L_PF - 1;
+            unsigned int src[L_G];
+#pragma unroll
+            for (int j = 0; j < L_G; ++j) src[j] = last ? nxt[j] : cur[j] + (b + 1) * (L_PF * 64);
+#pragma unroll
+            for (int u = 0; u < L_PF; ++u) {
+                // The rows' operands of the next k-tile are read while this one's MFMAs run (after a
+                // step's last k-tile: the first one again; the rows never change), and a ring slot is
+                // refilled as soon as its MFMAs have been issued: the loads then have three quarters
+                // of a pass, and the other wavefront's share of the matrix cores, to come back.  The
+                // scheduling barrier keeps that order (left alone, the compiler sinks all loads of a
+                // pass to its end, right in front of their first use).
+                Frag bf[L_RT];
+                const int kt_next = (b * L_PF + u + 1) & (KT - 1);
+#pragma unroll
+                for (int rt = 0; rt < L_RT; ++rt) {
+                    bf[rt].u = bnext[rt];
+                    bnext[rt] = ldsB[(rt * KT + kt_next) * 64 + lane];
+                }
+#pragma unroll
+                for (int rt = 0; rt < L_RT; ++rt)
+#pragma unroll
+                    for (int j = 0; j < L_G; ++j) {
+                        Frag a;
+                        a.u = ring[u][j];
+                        acc[rt][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a.h, bf[rt].h, acc[rt][j], 0, 0, 0);
+                    }
+#pragma unroll
+                for (int j = 0; j < L_G; ++j) ring[u][j] = load_piece<NT>(slab + src[j] + u * 64);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+
+        // fold the 16 logits of each of this lane's four rows
+        const int c_first = g0 * VP_TILE_ITEMS + q * 4;           // position of z[0] (j = 0, i = 0) in the slab
+        const bool ragged = (g0 + L_G) * VP_TILE_ITEMS > ncand || g0 + L_G > ge;   // (wavefront-uniform)
+        if (pending_rt >= 0) {
+            // bounds read from the other workgroups a step ago
+#pragma unroll
+            for (int rt = 0; rt < L_RT; ++rt)
+                if (rt == pending_rt && q == 0 && row_valid[rt]) atomicMax(wg_floor + rt * 16 + n, pending[rt]);
+            pending_rt = -1;
+        }
+        // (written per row tile with the tile's number a compile-time constant: the accumulators
+        // and the per-tile state must stay in registers)
+        auto fold_row_tile = [&](auto rt_const) {
+            constexpr int rt = decltype(rt_const)::value;
+            float z[L_G * 4];
+#pragma unroll
+            for (int j = 0; j < L_G; ++j) {
+                z[j * 4 + 0] = acc[rt][j][0] + bz[j].x;
+                z[j * 4 + 1] = acc[rt][j][1] + bz[j].y;
+                z[j * 4 + 2] = acc[rt][j][2] + bz[j].z;
+                z[j * 4 + 3] = acc[rt][j][3] + bz[j].w;
+            }
+            if (ragged) {
+#pragma unroll
+                for (int j = 0; j < L_G; ++j)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if (g0 + j >= ge || c_first + j * VP_TILE_ITEMS + i >= ncand) z[j * 4 + i] = -__builtin_inff();
+            }
+            if (MASKED) {
+#pragma unroll
+                for (int j = 0; j < L_G; ++j) {
+                    const uint32_t nib = (mw[rt][j >> 1] >> ((j & 1) * 16 + q * 4)) & 15u;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if (!((nib >> i) & 1u)) z[j * 4 + i] = -__builtin_inff();
+                }
+            }
+            float tmax = z[0];
+#pragma unroll
+            for (int e = 1; e < L_G * 4; ++e) tmax = fmaxf(tmax, z[e]);
+            const float mn = fmaxf(m_run[rt], tmax);
+            float sum = 0.f;
+#pragma unroll
+            for (int e = 0; e < L_G * 4; ++e) sum += fast_exp(z[e] - mn);
+            s_run[rt] = s_run[rt] * fast_exp(m_run[rt] - mn) + sum;
+            m_run[rt] = mn;
+
+            if (top1) {
+                // positions ascend along a lane's own stream: a strict comparison keeps the smaller one
+#pragma unroll
+                for (int e = 0; e < L_G * 4; ++e) {
+                    const bool take = z[e] > b1v[rt];
+                    b1v[rt] = take ? z[e] : b1v[rt];
+                    b1i[rt] = take ? c_first + (e >> 2) * VP_TILE_ITEMS + (e & 3) : b1i[rt];
+                }
+                return;
+            }
+            const int slot = rt * 16 + n;
+            unsigned long long *list = lkey + slot;              // + p * L_ROWS
+            const float far_floor = key_float(__hip_atomic_load(wg_floor + slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
+            auto row_floor = [&]() {
+                const unsigned long long kth = __hip_atomic_load(list + (k - 1) * L_ROWS, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                return fmaxf(far_floor, kth ? key_float((unsigned int)(kth >> 32)) : -__builtin_inff());
+            };
+            float floor = row_floor();
+            const bool want = row_valid[rt] & (tmax >= floor) & (tmax > -__builtin_inff());
+            if (__ballot(want) != 0) {
+                if (want) {
+                    // this lane's candidates, best first, until one is below the bound (the others,
+                    // which are not better, then are too)
+                    while (true) {
+                        float v = z[0];
+                        int e_best = 0;
+#pragma unroll
+                        for (int e = 1; e < L_G * 4; ++e) {
+                            const bool take = z[e] > v;   // strict: of equal logits the smaller position
+                            v = take ? z[e] : v;
+                            e_best = take ? e : e_best;
+                        }
+                        if (!((v >= floor) & (v > -__builtin_inff()))) break;
+                        const unsigned int c = (unsigned int)(c_first + (e_best >> 2) * VP_TILE_ITEMS + (e_best & 3));
+                        // (-0 becomes +0: equal as logits, they must tie and be ordered by position)
+                        unsigned long long carry = ((unsigned long long)float_key(v + 0.f) << 32) | (unsigned int)~c;
+                        for (int p = 0; p < k && carry != 0ull; ++p) {
+                            const unsigned long long old = __hip_atomic_fetch_max(list + p * L_ROWS, carry, __ATOMIC_RELAXED,
+                                                                                  __HIP_MEMORY_SCOPE_WORKGROUP);
+                            carry = old < carry ? old : carry;
+                        }
+#pragma unroll
+                        for (int e = 0; e < L_G * 4; ++e) z[e] = e == e_best ? -__builtin_inff() : z[e];
+                        floor = row_floor();
+                    }
+                }
+            }
+        };
+        fold_row_tile(std::integral_constant<int, 0>{});
+        fold_row_tile(std::integral_constant<int, 1>{});
+        fold_row_tile(std::integral_constant<int, 2>{});
+        fold_row_tile(std::integral_constant<int, 3>{});
+        // every second step of a wavefront, one row tile in turn: trade bounds with the other
+        // workgroups that project the same rows onto other candidate ranges (one atomicMax
+        // publishes ours and returns theirs, folded into the LDS copy a step later: no wait here)
+        ++done_steps;
+        if (!top1 && (done_steps & 1) == 0) {
+            const int rt_x = ((done_steps >> 1) + wave) & (L_RT - 1);
+#pragma unroll
+            for (int rt = 0; rt < L_RT; ++rt)
+                if (rt == rt_x && q == 0 && row_valid[rt]) {
+                    const unsigned long long kth = __hip_atomic_load(lkey + (k - 1) * L_ROWS + rt * 16 + n, __ATOMIC_RELAXED,
+                                                                     __HIP_MEMORY_SCOPE_WORKGROUP);
+                    const unsigned int mine = max((unsigned int)(kth >> 32),
+                                                  __hip_atomic_load(wg_floor + rt * 16 + n, __ATOMIC_RELAXED,
+                                                                    __HIP_MEMORY_SCOPE_WORKGROUP));
+                    pending[rt] = atomicMax(floors + myrow[rt], max(mine, (unsigned int)VP_FLOOR_NONE));
+                }
+            pending_rt = rt_x;
+        }
+#pragma unroll
+        for (int j = 0; j < L_G; ++j) cur[j] = nxt[j];
+        step = next_step;
+    }
+
+    // the row's four lanes (one per quarter of every group) -> one (m, s); top-1: one entry
+#pragma unroll
+    for (int rt = 0; rt < L_RT; ++rt) {
+#pragma unroll
+        for (int off = 16; off <= 32; off <<= 1) {
+            const float m2 = __shfl_xor(m_run[rt], off);
+            const float s2 = __shfl_xor(s_run[rt], off);
+            const float mn = fmaxf(m_run[rt], m2);
+            s_run[rt] = s_run[rt] * fast_exp(m_run[rt] - mn) + s2 * fast_exp(m2 - mn);
+            m_run[rt] = mn;
+            if (top1) {
+                const float v2 = __shfl_xor(b1v[rt], off);
+                const int i2 = __shfl_xor(b1i[rt], off);
+                const bool take = before_entry(v2, i2, b1v[rt], b1i[rt]);
+                b1v[rt] = take ? v2 : b1v[rt];
+                b1i[rt] = take ? i2 : b1i[rt];
+            }
+        }
+        if (top1 && q == 0 && row_valid[rt] && b1i[rt] != VP_IDX_NONE)
+            __hip_atomic_fetch_max(lkey + rt * 16 + n,
+                                   ((unsigned long long)float_key(b1v[rt] + 0.f) << 32) | (unsigned int)~(unsigned int)b1i[rt],
+                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    }
+    __syncthreads();   // nobody reads the rows any more: their LDS becomes the (m, s) exchange
+#pragma unroll
+    for (int rt = 0; rt < L_RT; ++rt) {
+        if (q == 0) {
+            hdr_m[wave * L_ROWS + rt * 16 + n] = m_run[rt];
+            hdr_s[wave * L_ROWS + rt * 16 + n] = s_run[rt];
+        }
+    }
+    if (!top1 && tid < item.nrows) {
+        const unsigned int kth = (unsigned int)(lkey[(k - 1) * L_ROWS + tid] >> 32);
+        atomicMax(floors + perm[item.perm_start + tid], max(max(kth, wg_floor[tid]), (unsigned int)VP_FLOOR_NONE));
+    }
+    __syncthreads();
+
+    // one partial result per (item, row): the row's list is in order already; wavefront w takes
+    // row slots w, w + 8, ...
+    const int PFL = vp_partial_floats(k);
+    for (int r = wave; r < item.nrows; r += L_NW) {
+        float M = hdr_m[r];
+#pragma unroll
+        for (int w = 1; w < L_NW; ++w) M = fmaxf(M, hdr_m[w * L_ROWS + r]);
+        float S = 0.f;
+#pragma unroll
+        for (int w = 0; w < L_NW; ++w) S += hdr_s[w * L_ROWS + r] * fast_exp(hdr_m[w * L_ROWS + r] - M);
+        float *out = partials + ((size_t)it * L_ROWS + r) * PFL;
+        if (lane == 0) {
+            out[0] = M;
+            out[1] = S;
+        }
+        if (lane < k) {
+            const unsigned long long key = lkey[lane * L_ROWS + r];
+            out[2 + lane] = key ? key_float((unsigned int)(key >> 32)) : -__builtin_inff();
+            out[2 + k + lane] = __int_as_float(key ? (int)~(unsigned int)key : VP_IDX_NONE);
+        }
+    }
+}
+
+template <int KT, bool MASKED>
+__global__ __launch_bounds__(L_NW * 64) void project_gemm_lds_kernel(
+    VpSlabSet set, const uint4 *__restrict__ hidden, int d, const int32_t *__restrict__ perm,
+    const VpItem *__restrict__ items, const VpPlanHeader *__restrict__ hdr, int k,
+    float *__restrict__ partials, unsigned int *__restrict__ floors, VpMaskInfo mask)
+{
+    if (MASKED ? hdr->mode != 1 : hdr->mode != 0) return;   // the planner chose the other form
+    const int total_items = hdr->total_items;
+    const int it = item_of_workgroup(hdr);
+    if (it < 0 || it >= total_items) return;
+    const VpItem item = items[it];
+    if (item.shared)
+        gemm_lds_item<KT, MASKED, false>(set, hidden, d, perm, item, it, k, partials, floors, mask);
+    else
+        gemm_lds_item<KT, MASKED, true>(set, hidden, d, perm, item, it, k, partials, floors, mask);
+}
+
+template <int KT, bool MASKED>
+void launch_lds(const VpSlabSet &set, const void *hidden, int d, const int32_t *perm, const VpItem *items,
+                const VpPlanHeader *hdr, int grid_items, int k, float *partials, unsigned int *floors,
+                const VpMaskInfo &mask, hipStream_t st)
+{
+    hipLaunchKernelGGL((project_gemm_lds_kernel<KT, MASKED>), dim3(grid_items), dim3(L_NW * 64),
+                       vpk_project_rows_lds_bytes(k, KT), st, set, (const uint4 *)hidden, d, perm, items, hdr, k,
+                       partials, floors, mask);
+}
+
+template <int KT>
+hipError_t allow_lds_bytes()
+{
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(project_gemm_lds_kernel<KT, false>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(project_gemm_lds_kernel<KT, true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    return e;
+}
+
+}  // namespace
+
+size_t vpk_project_rows_lds_bytes(int k, int kt)
+{
+    return (size_t)L_RT * kt * VP_TILE_BYTES + (size_t)k * L_ROWS * 8 + L_ROWS * 4;
+}
+
+// built for d_pad = 256, 512 and 1024 (the rows of an item must fit the LDS beside its lists)
+bool vpk_project_rows_lds_supported(int kt, int k) { return (kt == 8 || kt == 16 || kt == 32) && k >= 1 && k <= VP_MAX_TOPK_LANES; }
+
+hipError_t vpk_project_rows_lds_prepare()
+{
+    hipError_t e = allow_lds_bytes<8>();
+    if (e == hipSuccess) e = allow_lds_bytes<16>();
+    if (e == hipSuccess) e = allow_lds_bytes<32>();
+    return e;
+}
+
+void vpk_project_rows_lds(const VpSlabSet &set, const void *hidden, int d, const int32_t *perm, const VpItem *items,
+                          const VpPlanHeader *hdr, int grid_items, int k, float *partials, unsigned int *floors,
+                          const VpMaskInfo *mask, hipStream_t st)
+{
+    const VpMaskInfo none = {nullptr, nullptr, 0};
+#define VP_LDS_CASE(KT)                                                                                          \
+    case KT:                                                                                                     \
+        if (mask) launch_lds<KT, true>(set, hidden, d, perm, items, hdr, grid_items, k, partials, floors, *mask, st); \
+        else launch_lds<KT, false>(set, hidden, d, perm, items, hdr, grid_items, k, partials, floors, none, st);  \
+        break;
+    switch (set.kt) {
+        VP_LDS_CASE(8)
+        VP_LDS_CASE(16)
+        VP_LDS_CASE(32)
+        default: break;   // callers check vpk_project_rows_lds_supported
+    }
+#undef VP_LDS_CASE
+}

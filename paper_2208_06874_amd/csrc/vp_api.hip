@@ -105,6 +105,8 @@ struct vp_index {
     int cus;         // compute units of this GPU
     int wide_items;  // 1: single-bucket projections of more than 16 rows use items of 32 rows
     int gemm_target_items;   // work items of the GEMM-shaped kernel: its resident workgroup slots
+    int gemm_lds;        // 1: items of 64 rows use the kernel that holds the rows in LDS where it is built (d_pad <= 1024, k <= 8)
+    int gemm_lds_items;  // its work items: one per compute unit
     int gemm_min_rows;   // single-bucket projections of at least this many rows use the GEMM-shaped kernel (0: never)
     int dispatch;    // 1: the planner may choose the masked full projection (same results)
     VpCostModel cost;
@@ -203,7 +205,8 @@ int max_items_clustered(const vp_index *I, int N)
 // (the grid of the full projection is padded to 8 candidate ranges at a time, one per XCD)
 int max_items_full(const vp_index *I, int N)
 {
-    return std::max(I->full_target_items, I->gemm_target_items) + 8 * ceil_div(N, VP_ROWS_PER_ITEM) + 2;
+    return std::max(I->full_target_items, std::max(I->gemm_target_items, I->gemm_lds_items)) +
+           8 * ceil_div(N, VP_ROWS_PER_ITEM) + 2;
 }
 
 WsLayout plan_workspace(const vp_index *I, int N)
@@ -285,8 +288,23 @@ int single_bucket_row_tiles(const vp_index *I, int N, int k)
 }
 
 // Item count bounds (target, minimum) of a single-bucket plan with this many row tiles.
-inline int sb_target(const vp_index *I, int row_tiles) { return row_tiles == 4 ? I->gemm_target_items : I->full_target_items; }
-inline int sb_min(const vp_index *I, int row_tiles) { return row_tiles == 4 ? I->gemm_target_items : I->min_items; }
+inline bool use_gemm_lds(const vp_index *I, int row_tiles, int k)
+{
+    return row_tiles == 4 && I->gemm_lds && vpk_project_rows_lds_supported(I->L.kt, k);
+}
+inline int sb_target(const vp_index *I, int row_tiles, int k)
+{
+    return use_gemm_lds(I, row_tiles, k) ? I->gemm_lds_items : row_tiles == 4 ? I->gemm_target_items : I->full_target_items;
+}
+inline int sb_min(const vp_index *I, int row_tiles, int k)
+{
+    return use_gemm_lds(I, row_tiles, k) ? I->gemm_lds_items : row_tiles == 4 ? I->gemm_target_items : I->min_items;
+}
+// candidate tiles per wavefront of a single-bucket plan (the split the planning kernels make)
+inline int sb_tiles_per_wave(const vp_index *I, int rgs, int row_tiles, int k)
+{
+    return vp_tiles_per_wave((long long)rgs * I->L.vtiles, sb_target(I, row_tiles, k), sb_min(I, row_tiles, k));
+}
 
 // Launches the projection kernel that goes with the plan's rows per item.
 void launch_single_bucket(const VpSlabSet &set, const vp_index *I, const void *hidden, const int32_t *perm,
@@ -294,7 +312,9 @@ void launch_single_bucket(const VpSlabSet &set, const vp_index *I, const void *h
                           float *partials, unsigned int *floors, float *dbg_logits, const int64_t *dbg_row_off,
                           hipStream_t st)
 {
-    if (row_tiles == 4)
+    if (use_gemm_lds(I, row_tiles, k))
+        vpk_project_rows_lds(set, hidden, I->d, perm, items, hdr, grid_items, k, partials, floors, nullptr, st);
+    else if (row_tiles == 4)
         vpk_project_gemm(set, hidden, I->d, perm, items, hdr, grid_items, k, partials, floors + N, nullptr, st);
     else
         vpk_project(set, hidden, I->d, perm, items, hdr, grid_items, row_tiles, k, rstar, partials, floors, dbg_logits,
@@ -390,7 +410,7 @@ vp_status run_clustered(const char *fn, const vp_index *I, const void *hidden, i
     vpk_centroid(hidden, N, I->d, I->cp, I->cnorm, I->K, I->L.kt, I->L.ctiles, tpw_c, parts, cpart, st);
     vpk_plan(cpart, parts, N, I->K, I->clusters.n_cand, I->clusters.tile_off, I->target_items, I->min_items, max_items, g,
              out_cluster, perm, rowplan, floors, items, hdr, dbg_row_off, dispatch, cost, k, I->V, I->L.vtiles,
-             sb_target(I, rt_masked), sb_min(I, rt_masked), max_full, st);
+             sb_target(I, rt_masked, k), sb_min(I, rt_masked, k), max_full, st);
 
     auto *ev = profile_slot(I);
     if (ev) (void)hipEventRecord(ev->first, st);
@@ -405,11 +425,13 @@ vp_status run_clustered(const char *fn, const vp_index *I, const void *hidden, i
     if (dispatch) {
         // launched as well; exactly one of the two does the work, as the planner decided
         const int rgs = ceil_div(N, dispatch);
-        const int tpw = vp_tiles_per_wave((long long)rgs * I->L.vtiles, sb_target(I, rt_masked), sb_min(I, rt_masked));
+        const int tpw = sb_tiles_per_wave(I, rgs, rt_masked, k);
         const int chunks = ceil_div(I->L.vtiles, (long)tpw * VP_WG_WAVES);
         const int grid_full = (rgs > 1 && chunks >= 8) ? ceil_div(chunks, 8) * 8 * rgs : chunks * rgs;
         const VpMaskInfo mask = {g, I->bitmaps, I->L.bm_words};
-        if (rt_masked == 4)
+        if (use_gemm_lds(I, rt_masked, k))
+            vpk_project_rows_lds(I->full, hidden, I->d, perm, items, hdr, grid_full, k, partials, floors, &mask, st);
+        else if (rt_masked == 4)
             vpk_project_gemm(I->full, hidden, I->d, perm, items, hdr, grid_full, k, partials, floors + N, &mask, st);
         else
             vpk_project_masked(I->full, hidden, I->d, perm, items, hdr, grid_full, k, partials, floors, mask, st);
@@ -435,12 +457,12 @@ vp_status run_full(const char *fn, const vp_index *I, const void *hidden, int N,
     const int row_tiles = dbg_logits ? 1 : single_bucket_row_tiles(I, N, k);
     const int rpi = VP_ROWS_PER_ITEM * row_tiles;
     const int max_items = max_items_full(I, N);
-    vpk_plan_full(N, I->V, I->L.vtiles, rpi, sb_target(I, row_tiles), sb_min(I, row_tiles), max_items, perm, rowplan, floors,
-                  items, hdr, dbg_row_off, st);
+    vpk_plan_full(N, I->V, I->L.vtiles, rpi, sb_target(I, row_tiles, k), sb_min(I, row_tiles, k), max_items, perm, rowplan,
+                  floors, items, hdr, dbg_row_off, st);
     // the same split the planning kernel makes; with several row groups the projection kernel
     // deals candidate ranges to the XCDs, which needs the grid padded to 8 ranges at a time
     const int rgs = ceil_div(N, rpi);
-    const int tpw = vp_tiles_per_wave((long long)rgs * I->L.vtiles, sb_target(I, row_tiles), sb_min(I, row_tiles));
+    const int tpw = sb_tiles_per_wave(I, rgs, row_tiles, k);
     const int chunks = ceil_div(I->L.vtiles, (long)tpw * VP_WG_WAVES);
     const int grid_items = (rgs > 1 && chunks >= 8) ? ceil_div(chunks, 8) * 8 * rgs : chunks * rgs;
     auto *ev = profile_slot(I);
@@ -512,6 +534,7 @@ vp_status vp_build(const vp_build_desc *D, void *hip_stream, vp_index **out)
     if (e == hipSuccess) e = vpk_merge_prepare();
     if (e == hipSuccess) e = vpk_union_prepare();
     if (e == hipSuccess) e = vpk_project_gemm_prepare();
+    if (e == hipSuccess) e = vpk_project_rows_lds_prepare();
     if (e != hipSuccess) return fail(VP_ERR_HIP, "vp_build: cannot configure kernels: %s", hipGetErrorString(e));
 
     // host-side metadata: candidate groups per cluster, ids padded to whole groups
@@ -583,6 +606,8 @@ vp_status vp_build(const vp_build_desc *D, void *hip_stream, vp_index **out)
     I->wide_items = 1;
     I->gemm_min_rows = 17;
     I->gemm_target_items = 512;
+    I->gemm_lds = 1;
+    I->gemm_lds_items = 256;
     I->dispatch = 0;
     // measured on MI355X at d = 1024: bytes per second of the three regimes of the cost model
     I->cost.bw_slab = 6.8e12f;
@@ -607,6 +632,7 @@ vp_status vp_build(const vp_build_desc *D, void *hip_stream, vp_index **out)
         const int per_cu = (int)std::max<size_t>(1, std::min<size_t>(8, LDS_LIMIT / lds));
         I->min_items = std::max(1, cus) * per_cu;
         I->cus = std::max(1, cus);
+        I->gemm_lds_items = I->cus;
     }
     I->prof = new (std::nothrow) VpProfile();
     // resolve this device's scratch array now, so that vp_project_static's first call does not have to
@@ -654,6 +680,8 @@ vp_status vp_set_option(vp_index *I, const char *name, int64_t value)
         {"full_target_items", &vp_index::full_target_items, nullptr, 1, 1 << 20},
         {"gemm_target_items", &vp_index::gemm_target_items, nullptr, 1, 1 << 20},
         {"gemm_min_rows", &vp_index::gemm_min_rows, nullptr, 0, VP_MAX_ROWS},
+        {"gemm_lds", &vp_index::gemm_lds, nullptr, 0, 1},
+        {"gemm_lds_items", &vp_index::gemm_lds_items, nullptr, 1, 1 << 20},
         {"rstar", &vp_index::rstar, nullptr, 0, VP_GEMV_MAX_ROWS},
         {"wide_items", &vp_index::wide_items, nullptr, 0, 1},
         {"dispatch", &vp_index::dispatch, nullptr, 0, 1},
@@ -834,7 +862,7 @@ vp_status vp_project_union(const vp_index *I, const void *hidden, int32_t N, int
     cost.bw_l2 /= tile_bytes;
     cost.bw_gemm /= tile_bytes;
     cost.bw_gather /= tile_bytes;
-    vpk_union_compact(mask, U.mask_words, bsum, N, VP_ROWS_PER_ITEM * row_tiles_u, sb_target(I, row_tiles_u), sb_min(I, row_tiles_u), max_items, uids, uh,
+    vpk_union_compact(mask, U.mask_words, bsum, N, VP_ROWS_PER_ITEM * row_tiles_u, sb_target(I, row_tiles_u, k), sb_min(I, row_tiles_u, k), max_items, uids, uh,
                       out_union_size, perm, rowplan, floors, items, hdr, allow_full, I->V, I->L.vtiles, k, cost, max_items, st);
     // step 3: the reduced weight matrix and Eq. 1 over it; steps 4-5 fused (no [N, V] array)
     vpk_union_gather(I->arena + I->L.wt, I->full.bias, I->L.kt, uids, uh, I->L.vtiles, uslab, ubias, st);
@@ -849,11 +877,13 @@ vp_status vp_project_union(const vp_index *I, const void *hidden, int32_t N, int
                          nullptr, st);
     if (allow_full) {
         // launched as well; exactly one of the two does the work, as the planner decided
-        const int tpw = vp_tiles_per_wave((long long)rgs * I->L.vtiles, sb_target(I, row_tiles_u), sb_min(I, row_tiles_u));
+        const int tpw = sb_tiles_per_wave(I, rgs, row_tiles_u, k);
         const int chunks = ceil_div(I->L.vtiles, (long)tpw * VP_WG_WAVES);
         const int grid_full = (rgs > 1 && chunks >= 8) ? ceil_div(chunks, 8) * 8 * rgs : chunks * rgs;
         const VpMaskInfo umask = {zero_g, mask, 0};   // every row reads list 0: the boolean list of the batch
-        if (row_tiles_u == 4)
+        if (use_gemm_lds(I, row_tiles_u, k))
+            vpk_project_rows_lds(I->full, hidden, I->d, perm, items, hdr, grid_full, k, partials, floors, &umask, st);
+        else if (row_tiles_u == 4)
             vpk_project_gemm(I->full, hidden, I->d, perm, items, hdr, grid_full, k, partials, floors + N, &umask, st);
         else
             vpk_project_masked(I->full, hidden, I->d, perm, items, hdr, grid_full, k, partials, floors, umask, st);
