@@ -1,12 +1,15 @@
 #!/usr/bin/env python3
 """Benchmark of the clustered vocabulary projection on one MI355X.
 
-A step is one vp_project call (centroid selection, bucketing, slab projection
-with fused log-softmax/top-k, merge) over one batch of synthetic hidden rows,
-inputs already resident in HBM.  The workload is the large multilingual shape
-(d = 1024, V = 250,000, K = 1,000 clusters, N = 256 rows, top-8) the metric is
-quoted on.  Distinct batches are cycled so that consecutive steps touch
-different slabs.  Prints ONE JSON line.
+A step is one vp_project call with the library's default options (centroid
+selection, bucketing, the projection in whichever of its two forms the planner
+picks - per-cluster slabs or the full projection masked to every row's active
+set - with fused log-softmax/top-k, merge) over one batch of synthetic hidden
+rows, inputs already resident in HBM.  The headline workload is the large
+multilingual shape (d = 1024, V = 250,000, K = 1,000 clusters, N = 256 rows,
+top-8) the metric is quoted on; the other configured workloads follow in the
+"configs" array of the same line.  Distinct batches are cycled so that
+consecutive steps touch different slabs.  Prints ONE JSON line.
 """
 import argparse
 import json
@@ -21,13 +24,14 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, vendor figure
 
 # HBM bytes per launch of the projection kernel from rocprofv3 --pmc runs
-# (FETCH_SIZE / WRITE_SIZE scaled by a copy kernel of known size); filled in from
-# the summaries under profiles/ for the workloads that have been profiled.
+# (FETCH_SIZE / WRITE_SIZE scaled by a copy kernel of known size): constants copied
+# from the summaries under profiles/, NOT measured by this run; the JSON line names
+# the summary next to the figure ("traffic_source").  Keyed by (workload, rows, form).
 MEASURED_TRAFFIC_BYTES = {
-    # profiles/project_kernel_large_N256.md: 3,421,600 KiB x 1.99989 read + 800 KiB written per launch
-    ("large", 256): 7.008e9,
-    # profiles/project_pf16_kernel_skewed_N4096.md: 8,035,252 KiB x 1.99989 read + 8,466 KiB written per launch
-    ("skewed", 4096): 16.46e9,
+    # 3,421,600 KiB x 1.99989 read + 800 KiB written per launch
+    ("large", 256, "slabs"): (7.008e9, "profiles/project_kernel_large_N256.md"),
+    # 8,035,252 KiB x 1.99989 read + 8,466 KiB written per launch
+    ("skewed", 4096, "slabs"): (16.46e9, "profiles/project_pf16_kernel_skewed_N4096.md"),
 }
 
 
@@ -92,6 +96,7 @@ def cluster_sweep(args, dev):
                 name, val = opt.split("=")
                 index.set_option(name, int(val))
             ws = index.workspace(N)
+            index.set_option("dispatch", 0)          # the per-cluster slabs; the planner's choice is timed below
             ms = time_ms(lambda i: index.project(batches[i % 8], k, workspace=ws))
             hit = float(np.mean([(index.project(h, 1, workspace=ws)[0][:, 0] == fb).float().mean().item()
                                  for h, fb in zip(batches, full_best)]))
@@ -105,7 +110,6 @@ def cluster_sweep(args, dev):
                 union_sizes.append(int(nu.item()))
             index.set_option("dispatch", 1)
             ms_disp = time_ms(lambda i: index.project(batches[i % 8], k, workspace=ws))
-            index.set_option("dispatch", 0)
             rows.append({"centroids": K, "clusters_with_members": with_members, "recorded_tokens": T,
                          "mean_active_fraction": float(sizes.mean() / cfg.V),
                          "max_active_fraction": float(sizes.max() / cfg.V), "ms_per_step": ms,
@@ -119,21 +123,208 @@ def cluster_sweep(args, dev):
             "rows": rows}
 
 
+HBM_PEAK_BYTES = HBM_PEAK_GBS * 1e9
+MFMA_PEAK_FLOPS = 2.5e15     # dense fp16, vendor figure
+
+
+class Workload:
+    """A configured workload with its packed index on the GPU."""
+
+    def __init__(self, name, dev, options=(), k_max=8, keep_w=False):
+        import numpy as np
+        import torch
+
+        import paper_2208_06874_amd as P
+        from paper_2208_06874_amd import workloads as wl
+        t0 = time.perf_counter()
+        self.name, self.dev = name, dev
+        self.cfg = wl.CONFIGS[name]
+        self.W, self.b, self.C = wl.make_model(self.cfg)
+        self.cand_off, self.cand_ids = wl.make_candidates(self.cfg, self.W, self.b, self.C, device="cuda:0")
+        Wt = torch.from_numpy(self.W).to(dev)
+        self.index = P.vp_build(Wt, torch.from_numpy(self.b).to(dev), torch.from_numpy(self.C).to(dev),
+                                self.cand_off, self.cand_ids, k_max=k_max)
+        self.Wt = Wt if keep_w else None    # for the library-GEMM reference beside the full projection
+        for opt in options:
+            n, v = opt.split("=")
+            self.index.set_option(n, int(v))
+        self.info = self.index.info()
+        self.sizes = np.asarray(self.cand_off[1:] - self.cand_off[:-1])
+        torch.cuda.synchronize()
+        self.setup_seconds = time.perf_counter() - t0
+
+    def close(self):
+        self.index.close()
+        self.Wt = None
+
+
+def timed(index, fn, warmup, steps, profile=True):
+    """(ms per step, ms of the projection kernels per step, launches) of `steps` calls of fn(i).  The step time
+    comes from a pass without the event pairs around the kernel (they cost a small call several microseconds),
+    the kernel time from a second pass with them."""
+    import torch
+    for i in range(warmup):
+        fn(i)
+    torch.cuda.synchronize()
+    index.set_option("profile", 0)
+    t0 = time.perf_counter()
+    for i in range(steps):
+        fn(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    kernel_ms, launches = 0.0, 0
+    if profile:
+        index.get_profile()                      # drop what is left from earlier passes
+        index.set_option("profile", 1)
+        for i in range(steps):
+            fn(i)
+        torch.cuda.synchronize()
+        kernel_ms, launches = index.get_profile()
+        index.set_option("profile", 0)
+    return (t1 - t0) * 1e3 / steps, kernel_ms / max(launches, 1), launches
+
+
+def slab_kernel_name(info, k, N, small):
+    kt = info["d_pad"] // 32
+    lds = kt * 1024 + 4 * k * 16 * 8 + 4 * 16 * 8 + 16 * 12
+    if small and N <= 16:
+        return "project_small_kernel"
+    return "project_pf16_kernel" if kt % 16 == 0 and lds * 4 > 160 * 1024 else "project_kernel"
+
+
+def measure(wk, N, k, steps, warmup, nb=16, want_full=True, oracle_rows=4, single_cluster=False, batches_np=None):
+    """One workload at one batch size: the default call, the same call confined to the per-cluster slabs, the
+    full projection, the bounds of both forms at the published peaks, and a spot check against the CPU oracle."""
+    import numpy as np
+    import torch
+    from paper_2208_06874_amd import workloads as wl
+
+    cfg, index, dev = wk.cfg, wk.index, wk.dev
+    d = cfg.d
+    if batches_np is None:
+        if single_cluster:
+            pick = np.random.default_rng(7).permutation(cfg.K)
+            batches_np = [wl.make_rows(cfg, wk.C, N=N, stream=1 + i, clusters=np.full(N, pick[i % cfg.K]))[0]
+                          for i in range(nb)]
+        else:
+            batches_np = [wl.make_rows(cfg, wk.C, N=N, stream=1 + i)[0] for i in range(nb)]
+    nb = len(batches_np)
+    batches = [torch.from_numpy(h).to(dev) for h in batches_np]
+    out_ids = [torch.empty((N, k), dtype=torch.int32, device=dev) for _ in batches]
+    out_logp = [torch.empty((N, k), dtype=torch.float32, device=dev) for _ in batches]
+    out_g = [torch.empty((N,), dtype=torch.int32, device=dev) for _ in batches]
+    ws = index.workspace(N)
+
+    def step(i):
+        j = i % nb
+        index.project(batches[j], k, out_ids=out_ids[j], out_logp=out_logp[j], out_cluster=out_g[j], workspace=ws)
+
+    # the call as shipped (default options: the planner picks the form)
+    ms_step, ms_kernel, launches = timed(index, step, warmup, steps)
+    torch.cuda.synchronize()
+    mode = int(ws[:64].view(torch.int32)[7].item())
+    overflow = int(ws[:64].view(torch.int32)[2].item())
+    ids0, logp0, g0 = out_ids[0].cpu().numpy(), out_logp[0].cpu().numpy(), out_g[0].cpu().numpy()
+    g_all = {j: out_g[j].cpu().numpy() for j in sorted({i % nb for i in range(steps)})}
+
+    # algorithmic bytes and flops of both forms: the occupied slabs once (fp16 column + fp32 bias per
+    # candidate) plus the rows; or one pass over the packed W (same per token) plus the rows
+    slab_bytes = {j: float(wk.sizes[np.unique(g)].sum()) * (2 * d + 4) + N * 2 * d for j, g in g_all.items()}
+    used = [i % nb for i in range(steps)]
+    alg_slab = float(np.mean([slab_bytes[j] for j in used]))
+    alg_full = cfg.V * (2.0 * d + 4) + N * 2 * d
+    flops_slab = float(np.mean([2.0 * d * float(wk.sizes[g_all[j]].sum()) for j in used])) + 2.0 * N * cfg.K * d
+    flops_full = 2.0 * N * d * cfg.V
+    side = cfg.K * (2 * d + 4) + N * k * 8            # centroids with norms, outputs
+    occupied = float(np.mean([np.unique(g_all[j]).size for j in used]))
+
+    def bound_ms(nbytes, flops):
+        return max(nbytes / HBM_PEAK_BYTES, flops / MFMA_PEAK_FLOPS) * 1e3
+
+    res = {"workload": cfg.name, "N": N, "k": k, "rows_per_s": N / (ms_step * 1e-3), "ms_per_step": ms_step,
+           "planner_chose": "masked full projection" if mode == 1 else "per-cluster slabs",
+           "plan_overflow": overflow, "occupied_clusters_per_step": occupied}
+    if mode == 1:
+        b_ms = bound_ms(alg_full + side, flops_full + 2.0 * N * cfg.K * d)
+        res["kernel"] = {"name": "project_gemm_lds_kernel (masked)" if cfg.d <= 1024 and k <= 32 else "project_gemm_kernel (masked)",
+                         "kernel_ms": ms_kernel, "algorithmic_bytes": alg_full,
+                         "hbm_gbs": alg_full / (ms_kernel * 1e-3) / 1e9,
+                         "hbm_frac": alg_full / (ms_kernel * 1e-3) / HBM_PEAK_BYTES,
+                         "mfma_tflops": flops_full / (ms_kernel * 1e-3) / 1e12,
+                         "mfma_frac": flops_full / (ms_kernel * 1e-3) / MFMA_PEAK_FLOPS,
+                         "bound": "hbm" if alg_full / HBM_PEAK_BYTES >= flops_full / MFMA_PEAK_FLOPS else "mfma"}
+    else:
+        b_ms = bound_ms(alg_slab + side, flops_slab)
+        res["kernel"] = {"name": slab_kernel_name(wk.info, k, N, True), "kernel_ms": ms_kernel,
+                         "algorithmic_bytes": alg_slab, "hbm_gbs": alg_slab / (ms_kernel * 1e-3) / 1e9,
+                         "hbm_frac": alg_slab / (ms_kernel * 1e-3) / HBM_PEAK_BYTES, "bound": "hbm"}
+    res["whole_call"] = {"bound_ms": b_ms, "frac_of_bound": b_ms / ms_step}
+
+    # the same call confined to the per-cluster slabs (the form the method's byte count belongs to)
+    if mode == 1:
+        index.set_option("dispatch", 0)
+        ms_s, ms_sk, _ = timed(index, step, max(2, warmup // 2), max(5, steps // 2))
+        index.set_option("dispatch", 1)
+    else:
+        ms_s, ms_sk = ms_step, ms_kernel
+    sb_ms = bound_ms(alg_slab + side, flops_slab)
+    res["slabs_only"] = {"ms_per_step": ms_s, "rows_per_s": N / (ms_s * 1e-3), "kernel": slab_kernel_name(wk.info, k, N, True),
+                         "kernel_ms": ms_sk, "algorithmic_bytes": alg_slab,
+                         "hbm_gbs": alg_slab / (ms_sk * 1e-3) / 1e9, "hbm_frac": alg_slab / (ms_sk * 1e-3) / HBM_PEAK_BYTES,
+                         "whole_call_bound_ms": sb_ms, "whole_call_frac_of_bound": sb_ms / ms_s}
+
+    if want_full:
+        full_ids = torch.empty((N, k), dtype=torch.int32, device=dev)
+        full_logp = torch.empty((N, k), dtype=torch.float32, device=dev)
+
+        def step_full(i):
+            index.project_full(batches[i % nb], k, out_ids=full_ids, out_logp=full_logp, workspace=ws)
+
+        ms_full, ms_full_kernel, _ = timed(index, step_full, max(2, warmup // 4), max(5, steps // 4))
+        res["full_vocab"] = {"ms_per_step": ms_full, "rows_per_s": N / (ms_full * 1e-3), "kernel_ms": ms_full_kernel,
+                             "hbm_frac": alg_full / (ms_full_kernel * 1e-3) / HBM_PEAK_BYTES,
+                             "mfma_tflops": flops_full / (ms_full_kernel * 1e-3) / 1e12}
+        res["speedup_vs_full"] = ms_full / ms_step
+        res["speedup_vs_full_slabs_only"] = ms_full / ms_s
+
+    if oracle_rows > 0:
+        # spot parity: the first rows of the first batch against the CPU oracle on the same inputs, each
+        # row evaluated in the cluster the GPU chose (clusters are compared separately)
+        from oracle import vp_oracle
+        vp_oracle.build()
+        r = min(oracle_rows, N)
+        Hs = batches_np[0][:r]
+        g_or = vp_oracle.assign(Hs, wk.C)
+        ref = vp_oracle.project(wk.W, wk.b, wk.C, wk.cand_off, wk.cand_ids, Hs, k, forced_g=g0[:r].astype(np.int32))
+        same = (ids0[:r] == ref["ids"]).all(1)
+        fin = np.isfinite(ref["logp"]) & np.isfinite(logp0[:r])
+        err = np.abs(np.where(fin, logp0[:r] - ref["logp"], 0.0))
+        res["parity"] = {"rows_checked": int(r), "clusters_equal": int((g0[:r] == g_or).sum()),
+                         "topk_ids_equal_rows": int(same.sum()),
+                         "max_abs_logp_err": float(err[same].max()) if same.any() else None}
+    res["_first"] = (ids0, logp0, g0, batches_np, batches, ws)
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="large", help="tiny | mid | large | skewed")
+    ap.add_argument("--workload", default="large", help="tiny | mid | large | sweep | skewed")
     ap.add_argument("--rows", type=int, default=None, help="rows per step (default: the workload's N)")
     ap.add_argument("--topk", type=int, default=None)
     ap.add_argument("--batches", type=int, default=16, help="distinct hidden batches cycled through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-full", action="store_true")
     ap.add_argument("--no-union", action="store_true")
-    ap.add_argument("--no-dispatch", action="store_true")
+    ap.add_argument("--no-dispatch", action="store_true", help="skip the comparison of the two forms of the call")
     ap.add_argument("--no-training", action="store_true")
     ap.add_argument("--no-decode-loop", action="store_true")
+    ap.add_argument("--no-configs", action="store_true",
+                    help="skip the other configured workloads (tiny, mid, the decode-size sweep, skewed)")
+    ap.add_argument("--no-ceilings", action="store_true", help="skip the measured ceilings (streaming read, MFMA loop)")
+    ap.add_argument("--ceilings", action="store_true", help="only measure the ceilings and print them")
     ap.add_argument("--sweep-noise", type=float, default=None,
                     help="cluster sweep: noise of the recorded vectors and decode rows (default: the workload's)")
     ap.add_argument("--cluster-sweep", action="store_true",
@@ -167,33 +358,28 @@ def main():
     if args.cluster_sweep:
         print(json.dumps(cluster_sweep(args, dev)))
         return
-    cfg = wl.CONFIGS[args.workload]
+
+    def ceilings():
+        buf = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        read_gbs, mfma_tf = P.vp_measure_ceilings(buf, repeats=5)
+        del buf
+        return {"hbm_read_gbs": read_gbs, "hbm_read_frac_of_published": read_gbs / HBM_PEAK_GBS,
+                "mfma_f16_tflops": mfma_tf, "mfma_frac_of_published": mfma_tf * 1e12 / MFMA_PEAK_FLOPS,
+                "how": "vp_measure_ceilings: 1 GiB streamed with 1 KiB non-temporal loads, 8 per wavefront in flight; "
+                       "v_mfma_f32_16x16x32_f16 on register operands, 2 wavefronts per SIMD; best of 5"}
+
+    if args.ceilings:
+        print(json.dumps({"metric": "measured ceilings of this GPU", "published": {"hbm_gbs": HBM_PEAK_GBS, "mfma_f16_tflops": 2500.0},
+                          "measured_peak": ceilings()}))
+        return
+
+    wk = Workload(args.workload, dev, options=args.option, k_max=max(8, args.topk or 0), keep_w=not args.no_full)
+    cfg, index = wk.cfg, wk.index
     N = args.rows or cfg.N
     k = args.topk or cfg.k
-    t_gen = time.perf_counter()
-    W, b, C = wl.make_model(cfg)
-    cand_off, cand_ids = wl.make_candidates(cfg, W, b, C, device="cuda:0")
-    Wt = torch.from_numpy(W).to(dev)   # kept for the library-GEMM reference beside the full projection
-    index = P.vp_build(Wt, torch.from_numpy(b).to(dev), torch.from_numpy(C).to(dev),
-                       cand_off, cand_ids, k_max=max(8, k))
-    for opt in args.option:
-        name, val = opt.split("=")
-        index.set_option(name, int(val))
-    info = index.info()
-    sizes = cand_off[1:] - cand_off[:-1]
-    if args.single_cluster:
-        pick = np.random.default_rng(7).permutation(cfg.K)
-        batches_np = [wl.make_rows(cfg, C, N=N, stream=1 + i, clusters=np.full(N, pick[i % cfg.K]))[0]
-                      for i in range(args.batches)]
-    else:
-        batches_np = [wl.make_rows(cfg, C, N=N, stream=1 + i)[0] for i in range(args.batches)]
-    batches = [torch.from_numpy(h).to(dev) for h in batches_np]
-    out_ids = [torch.empty((N, k), dtype=torch.int32, device=dev) for _ in batches]
-    out_logp = [torch.empty((N, k), dtype=torch.float32, device=dev) for _ in batches]
-    out_g = [torch.empty((N,), dtype=torch.int32, device=dev) for _ in batches]
-    ws = index.workspace(N)
-    torch.cuda.synchronize()
-    t_gen = time.perf_counter() - t_gen
+    d = cfg.d
+    info = wk.info
+    sizes = wk.sizes
 
     if args.copy_calibration:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
@@ -202,76 +388,39 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    head = measure(wk, N, k, args.steps, args.warmup, nb=args.batches, want_full=not args.no_full,
+                   oracle_rows=0, single_cluster=args.single_cluster)
+    ids0, logp0, g0, batches_np, batches, ws = head.pop("_first")
+    out_ids = [torch.empty((N, k), dtype=torch.int32, device=dev) for _ in batches]
+    out_logp = [torch.empty((N, k), dtype=torch.float32, device=dev) for _ in batches]
+    out_g = [torch.empty((N,), dtype=torch.int32, device=dev) for _ in batches]
+
     def step(i):
         j = i % len(batches)
         index.project(batches[j], k, out_ids=out_ids[j], out_logp=out_logp[j], out_cluster=out_g[j], workspace=ws)
 
-    def step_full(i):
-        j = i % len(batches)
-        index.project_full(batches[j], k, out_ids=full_ids, out_logp=full_logp, workspace=ws)
-
-    graphs = {}
-
-    def graphed(fn):
-        # one captured graph per batch; event recording is not captured, so the kernel
-        # time of the roofline comes from an un-graphed pass
-        def run(i):
-            j = i % len(batches)
-            key = (fn.__name__, j)
-            if key not in graphs:
-                gr = torch.cuda.CUDAGraph()
-                with torch.cuda.graph(gr):
-                    fn(j)
-                graphs[key] = gr
-            graphs[key].replay()
-        return run
-
-    def timed(fn, warmup, steps, profile=True):
-        for i in range(warmup):
-            fn(i)
-        torch.cuda.synchronize()
-        index.get_profile()                      # drop warm-up launches
-        index.set_option("profile", 1 if profile else 0)
-        t0 = time.perf_counter()
-        for i in range(steps):
-            fn(i)
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        kernel_ms, launches = index.get_profile()
-        index.set_option("profile", 0)
-        return (t1 - t0) * 1e3 / steps, kernel_ms / max(launches, 1), launches
-
-    ms_step, ms_kernel, launches = timed(step, args.warmup, args.steps)
+    ms_step = head["ms_per_step"]
     if args.graph:
+        graphs = {}
         for i in range(len(batches)):
             step(i)                               # results of every batch before capture
         torch.cuda.synchronize()
-        gstep = graphed(step)
-        ms_step, _, _ = timed(gstep, max(args.warmup, len(batches)), args.steps, profile=False)
+
+        def gstep(i):
+            j = i % len(batches)
+            if j not in graphs:
+                gr = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(gr):
+                    step(j)
+                graphs[j] = gr
+            graphs[j].replay()
+
+        ms_step, _, _ = timed(index, gstep, max(args.warmup, len(batches)), args.steps, profile=False)
     rows_per_s = N / (ms_step * 1e-3)
 
-    # algorithmic bytes of one projection-kernel launch: every candidate of every occupied
-    # cluster once (fp16 column + fp32 bias), plus the hidden rows
-    d = cfg.d
-    per_batch, occupied, call_bytes, call_flops = {}, {}, {}, {}
-    for j in sorted({i % len(batches) for i in range(args.steps)}):   # the batches the timed steps used
-        occ = np.unique(out_g[j].cpu().numpy())
-        occupied[j] = occ.size
-        per_batch[j] = float(sizes[occ].sum()) * (2 * d + 4) + N * 2 * d
-        # the whole call: slabs with bias and token ids, hidden rows, centroids with norms, outputs;
-        # Eq. 1 over every row's own list plus Eq. 2 over all centroids
-        call_bytes[j] = (float(sizes[occ].sum()) * (2 * d + 8) + N * 2 * d + cfg.K * (2 * d + 4) + N * k * 8)
-        call_flops[j] = 2.0 * d * float(sizes[out_g[j].cpu().numpy()].sum()) + 2.0 * N * cfg.K * d
-    used = [per_batch[i % len(batches)] for i in range(args.steps)]
-    alg_bytes = float(np.mean(used))
-    achieved = alg_bytes / (ms_kernel * 1e-3) / 1e9
-    traffic = MEASURED_TRAFFIC_BYTES.get((args.workload, N))
-    # which form of the slab kernel the library launches (16 loads in flight per wavefront when the
-    # staged rows leave room for fewer than four workgroups per CU)
-    kt = info["d_pad"] // 32
-    lds = kt * 1024 + 4 * k * 16 * 8 + 4 * 16 * 8 + 16 * 12
-    slab_kernel = "project_pf16_kernel" if kt % 16 == 0 and lds * 4 > 160 * 1024 else "project_kernel"
-
+    kern = head["kernel"]
+    form = "masked" if head["planner_chose"].startswith("masked") else "slabs"
+    traffic, traffic_source = MEASURED_TRAFFIC_BYTES.get((args.workload, N, form), (None, "none"))
     result = {
         "metric": "projected rows/sec fp16 at V=250K,d=1024; speedup vs full-vocab projection",
         "value": rows_per_s, "unit": "rows/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -279,21 +428,54 @@ def main():
         "dtype": "f16", "data": "synthetic",
         "config": {"workload": "%s: d=%d V=%d K=%d N=%d top-%d, %d-%d candidates per cluster" % (
             cfg.name, cfg.d, cfg.V, cfg.K, N, k, int(sizes.min()), int(sizes.max())),
-            "batches_cycled": len(batches), "slab_bytes": info["slab_bytes"],
+            "options": "library defaults" + ("" if not args.option else " + " + ",".join(args.option)),
+            "planner_chose": head["planner_chose"],
+            "batches_cycled": len(batches), "slab_bytes": info["slab_bytes"], "arena_bytes": info["arena_bytes_used"],
             "single_cluster_microbenchmark": bool(args.single_cluster), "hip_graph_replay": bool(args.graph),
-            "occupied_clusters_per_step": float(np.mean(list(occupied.values()))),
-            "setup_seconds": t_gen},
-        "roofline": {"bound": "hbm", "kernel": slab_kernel, "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": ms_kernel, "launches": launches},
+            "occupied_clusters_per_step": head["occupied_clusters_per_step"],
+            "setup_seconds": wk.setup_seconds},
+        # the kernel that dominates the call as shipped
+        "roofline": {"bound": kern["bound"], "kernel": kern["name"],
+                     "achieved": kern["hbm_gbs"] if kern["bound"] == "hbm" else kern["mfma_tflops"],
+                     "peak": HBM_PEAK_GBS if kern["bound"] == "hbm" else 2500.0,
+                     "unit": "GB/s" if kern["bound"] == "hbm" else "TFLOP/s",
+                     "frac": kern["hbm_frac"] if kern["bound"] == "hbm" else kern["mfma_frac"],
+                     "traffic": traffic, "traffic_source": traffic_source,
+                     "algorithmic_bytes_per_launch": kern["algorithmic_bytes"], "kernel_ms": kern["kernel_ms"],
+                     "mfma_tflops": kern.get("mfma_tflops"), "mfma_frac": kern.get("mfma_frac")},
+        "whole_call": head["whole_call"],
+        "plan_overflow": head["plan_overflow"],
     }
-
-    # lower bound of the whole call at the published peaks, and how close a step comes to it
-    cb = float(np.mean([call_bytes[i % len(batches)] for i in range(args.steps)]))
-    cf = float(np.mean([call_flops[i % len(batches)] for i in range(args.steps)]))
-    bound_ms = max(cb / (HBM_PEAK_GBS * 1e9), cf / 2.5e15) * 1e3
-    result["whole_call"] = {"bytes": cb, "flops": cf, "bound_ms": bound_ms, "frac_of_bound": bound_ms / ms_step,
-                            "bound": "hbm" if cb / (HBM_PEAK_GBS * 1e9) >= cf / 2.5e15 else "mfma"}
+    # the per-cluster slab form of the same call (dispatch = 0): the form whose byte count is the method's own
+    so = head["slabs_only"]
+    s_traffic, s_source = MEASURED_TRAFFIC_BYTES.get((args.workload, N, "slabs"), (None, "none"))
+    result["value_slabs_only"] = so["rows_per_s"]
+    result["slab_path"] = {"ms_per_step": so["ms_per_step"], "rows_per_s": so["rows_per_s"],
+                           "roofline": {"bound": "hbm", "kernel": so["kernel"], "achieved": so["hbm_gbs"],
+                                        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": so["hbm_frac"],
+                                        "traffic": s_traffic, "traffic_source": s_source,
+                                        "algorithmic_bytes_per_launch": so["algorithmic_bytes"],
+                                        "kernel_ms": so["kernel_ms"]},
+                           "whole_call_bound_ms": so["whole_call_bound_ms"],
+                           "whole_call_frac_of_bound": so["whole_call_frac_of_bound"]}
+    if "full_vocab" in head:
+        result["full_vocab"] = head["full_vocab"]
+        result["speedup_vs_full"] = result["full_vocab"]["ms_per_step"] / ms_step
+        result["speedup_vs_full_slabs_only"] = head["speedup_vs_full_slabs_only"]
+        # Outside reference, context only: the bare [N, d] x [d, V] product of the vendor GEMM library
+        # (through torch.matmul; it writes [N, V] logits and does no bias, softmax or top-k).
+        fsteps = max(5, args.steps // 4)
+        lib_out = torch.empty((N, cfg.V), dtype=torch.float16, device=dev)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for i in range(3):
+            torch.matmul(batches[i % len(batches)], wk.Wt, out=lib_out)
+        e0.record()
+        for i in range(fsteps):
+            torch.matmul(batches[i % len(batches)], wk.Wt, out=lib_out)
+        e1.record()
+        torch.cuda.synchronize()
+        result["full_vocab"]["library_gemm_only_ms"] = e0.elapsed_time(e1) / fsteps
+        del lib_out
 
     if args.streams > 1:
         # Independent calls (say, different requests of a server) overlapped on several streams of the
@@ -330,49 +512,6 @@ def main():
                                         "matches_single_stream": same}
         del s_ws, s_ids, s_logp, s_g
 
-    if not args.no_full:
-        full_ids = torch.empty((N, k), dtype=torch.int32, device=dev)
-        full_logp = torch.empty((N, k), dtype=torch.float32, device=dev)
-        fsteps = max(5, args.steps // 4)
-        ms_full, ms_full_kernel, _ = timed(step_full, max(2, args.warmup // 4), fsteps)
-        full_bytes = cfg.V * (2.0 * d + 4) + N * 2 * d
-        result["full_vocab"] = {"rows_per_s": N / (ms_full * 1e-3), "ms_per_step": ms_full,
-                                "kernel_ms": ms_full_kernel,
-                                "hbm_frac": full_bytes / (ms_full_kernel * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                                "mfma_tflops": 2.0 * N * d * cfg.V / (ms_full_kernel * 1e-3) / 1e12}
-        result["speedup_vs_full"] = ms_full / ms_step
-        # Outside reference, context only: the bare [N, d] x [d, V] product of the vendor GEMM library
-        # (through torch.matmul; it writes [N, V] logits and does no bias, softmax or top-k).
-        lib_out = torch.empty((N, cfg.V), dtype=torch.float16, device=dev)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        for i in range(3):
-            torch.matmul(batches[i % len(batches)], Wt, out=lib_out)
-        e0.record()
-        for i in range(fsteps):
-            torch.matmul(batches[i % len(batches)], Wt, out=lib_out)
-        e1.record()
-        torch.cuda.synchronize()
-        result["full_vocab"]["library_gemm_only_ms"] = e0.elapsed_time(e1) / fsteps
-        del lib_out
-
-    if not args.no_dispatch:
-        # vp_project with the planner allowed to pick the masked full projection (same results)
-        index.set_option("dispatch", 1)
-        dsteps = max(5, args.steps // 4)
-        ms_disp, _, _ = timed(step, max(2, args.warmup // 4), dsteps, profile=False)
-        mode = int(ws[:64].view(torch.int32)[7].item())
-        index.set_option("dispatch", 0)
-        result["with_dispatch"] = {"rows_per_s": N / (ms_disp * 1e-3), "ms_per_step": ms_disp,
-                                   "planner_chose": "masked full projection" if mode == 1 else "per-cluster slabs",
-                                   "speedup_vs_slabs": ms_step / ms_disp,
-                                   "speedup_vs_full": (result["full_vocab"]["ms_per_step"] / ms_disp)
-                                   if "full_vocab" in result else None}
-        if mode == 1:
-            # a dense contraction over the whole vocabulary: priced against the matrix cores, whole step
-            tf = 2.0 * N * d * cfg.V / (ms_disp * 1e-3) / 1e12
-            result["with_dispatch"]["roofline"] = {"bound": "mfma", "achieved": tf, "peak": 2500.0, "unit": "TFLOP/s",
-                                                   "frac": tf / 2500.0}
-
     if not args.no_union:
         # the paper's own batched form (union of the active sets of the batch), whole call timed
         u_ids = torch.empty((N, k), dtype=torch.int32, device=dev)
@@ -387,7 +526,7 @@ def main():
                                 workspace=uws)
 
         usteps = max(5, args.steps // 4)
-        ms_union, _, _ = timed(step_union, max(2, args.warmup // 4), usteps, profile=False)
+        ms_union, _, _ = timed(index, step_union, max(2, args.warmup // 4), usteps, profile=False)
         result["union_form"] = {"rows_per_s": N / (ms_union * 1e-3), "ms_per_step": ms_union,
                                 "union_size_last_step": int(u_n.item()),
                                 "speedup_vs_full": (result["full_vocab"]["ms_per_step"] / ms_union)
@@ -398,7 +537,7 @@ def main():
         # offline training of the clusters (section 2.2) on synthetic recorded vectors of the same mixture:
         # Lloyd iterations (vp_kmeans) and the active sets from recorded top-3 tokens (vp_active_sets)
         n_tr, T = args.train_vectors, 3
-        Xn, _q, C0 = wl.training_set(cfg, C, n_tr)
+        Xn, _q, C0 = wl.training_set(cfg, wk.C, n_tr)
         Xt = torch.from_numpy(Xn).to(dev)
         C0t = torch.from_numpy(C0).to(dev)
         kws = torch.empty(P.vp_kmeans_workspace_bytes(n_tr, cfg.d, cfg.K), dtype=torch.uint8, device=dev)
@@ -439,77 +578,149 @@ def main():
             "roofline": {"bound": "mfma", "achieved": flops / (ms_iter * 1e-3) / 1e12, "peak": 2500.0,
                          "unit": "TFLOP/s", "frac": flops / (ms_iter * 1e-3) / 2.5e15,
                          "note": "2 n K d flop of the membership pass over the whole iteration"},
-            "membership_pass_ms": ms0, "record_top%d_ms" % T: ms_rec, "active_sets_ms": ms_sets,
+            "membership_pass_ms": ms0, "record_top%d_ms" % T: ms_rec,
+            "record_mfma_tflops": 2.0 * n_tr * cfg.d * cfg.V / (ms_rec * 1e-3) / 1e12, "active_sets_ms": ms_sets,
             "active_set_entries": int(a_ids.numel()), "empty_clusters": int((counts == 0).sum().item())}
+
+        if not args.no_decode_loop:
+            # The rows of the scope joined end to end on LEARNED clusters: the centroids just trained and the
+            # active sets just built (sections 2.2 -> 2.3 -> 2.1) are packed into an index of their own and a
+            # beam search decodes on it: vp_kmeans -> vp_active_sets -> vp_build -> vp_project + vp_beam_step.
+            a_off_h, a_ids_h = a_off.cpu().numpy(), a_ids.cpu().numpy()
+            t0 = time.perf_counter()
+            learned = P.vp_build(wk.Wt if wk.Wt is not None else torch.from_numpy(wk.W).to(dev),
+                                 torch.from_numpy(wk.b).to(dev), Ct, a_off_h, a_ids_h, k_max=8)
+            torch.cuda.synchronize()
+            build_s = time.perf_counter() - t0
+            result["learned_clusters_decode"] = decode_loop(P, wl, learned, cfg, wk.C, dev)
+            result["learned_clusters_decode"].update({
+                "index_build_seconds": build_s, "lloyd_iterations": iters_tr,
+                "mean_active_fraction": float(np.diff(a_off_h)[np.diff(a_off_h) > 0].mean() / cfg.V),
+                "note": "vp_kmeans -> vp_active_sets (recorded top-3) -> vp_build -> vp_project (top-8) + vp_beam_step"})
+            learned.close()
         del Xt, kws, top, wst
 
     if not args.no_decode_loop:
-        # toy search consumer: 8 sentences x beam 8, every step = clustered projection (top-8) + one beam
-        # step + the survivors' rows carried to their new slots (a gather; the rows stand in for a decoder)
-        S_d, B_d, k_d, T_d = 8, 8, 8, 32
-        n_d = S_d * B_d
-        pool = torch.from_numpy(wl.make_rows(cfg, C, N=n_d * 4, stream=90)[0]).to(dev)
-        d_ids = torch.empty((n_d, k_d), dtype=torch.int32, device=dev)
-        d_logp = torch.empty((n_d, k_d), dtype=torch.float32, device=dev)
-        d_g = torch.empty((n_d,), dtype=torch.int32, device=dev)
-        wsd = index.workspace(n_d)
-        slot0 = (torch.arange(n_d, device=dev) // B_d) * B_d
-        first = torch.full((n_d,), float("-inf"), device=dev)
-        first[::B_d] = 0.0
+        result["decode_loop"] = decode_loop(P, wl, index, cfg, wk.C, dev)
 
-        def decode(steps):
-            scores, rows = first.clone(), pool[:n_d]
-            for t in range(steps):
-                index.project(rows, k_d, out_ids=d_ids, out_logp=d_logp, out_cluster=d_g, workspace=wsd)
-                scores, parent, _tok = P.vp_beam_step(d_ids, d_logp, scores, B_d)
-                fresh = pool[(t % 4) * n_d:(t % 4 + 1) * n_d]
-                rows = fresh[slot0 + parent.clamp(min=0)]
-            return scores
+    if not args.no_ceilings:
+        result["roofline"]["measured_peak"] = ceilings()
 
-        def timed_decode():
-            decode(4)
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            final = decode(T_d)
-            torch.cuda.synchronize()
-            return (time.perf_counter() - t0) * 1e3 / T_d, final
-
-        ms_dec, _ = timed_decode()
-        # the same search with the planner free to choose (log-probs agree to 1e-4 between the two forms, so
-        # the two searches may part ways at a near-tie; the timing is what is compared)
-        index.set_option("dispatch", 1)
-        ms_dec_d, _ = timed_decode()
-        index.set_option("dispatch", 0)
-        result["decode_loop"] = {"sentences": S_d, "beam": B_d, "topk": k_d, "steps": T_d, "ms_per_step": ms_dec,
-                                 "rows_per_s": n_d / (ms_dec * 1e-3),
-                                 "with_dispatch_ms_per_step": ms_dec_d,
-                                 "with_dispatch_rows_per_s": n_d / (ms_dec_d * 1e-3),
-                                 "note": "vp_project + vp_beam_step + a gather of the next rows per step"}
-
+    cpu_first = None
     if not args.no_cpu_baseline:
-        # the CPU oracle, as it stands, on the first batch of the same workload
+        # the CPU oracle, as it stands, on the first batches of the same workload: all host threads, then one
         from oracle import vp_oracle
         vp_oracle.build()
         threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
         t0 = time.perf_counter()
         reps = 0
         while True:
-            ref = vp_oracle.project(W, b, C, cand_off, cand_ids, batches_np[reps % len(batches_np)], k)
+            ref = vp_oracle.project(wk.W, wk.b, wk.C, wk.cand_off, wk.cand_ids, batches_np[reps % len(batches_np)], k)
             reps += 1
             if reps == 1:
-                first = ref
+                cpu_first = ref
             if time.perf_counter() - t0 > 10.0 or reps >= 8:
                 break
         cpu_s = time.perf_counter() - t0
         result["cpu_baseline"] = {"value": N * reps / cpu_s, "unit": "rows/s", "cores": threads, "kind": "oracle",
                                   "sample": "%d batch(es) of %d rows of the same workload, %.1f s" % (reps, N, cpu_s)}
-        gi, gl, gg = out_ids[0].cpu().numpy(), out_logp[0].cpu().numpy(), out_g[0].cpu().numpy()
-        same_g = gg == first["g"]
-        same_ids = (gi == first["ids"]).all(1) & same_g
-        err = np.abs(gl[same_ids] - first["logp"][same_ids]).max() if same_ids.any() else float("nan")
+        try:
+            import ctypes
+            gomp = ctypes.CDLL("libgomp.so.1")
+            gomp.omp_set_num_threads(1)
+            r1 = min(N, 16)
+            t0 = time.perf_counter()
+            vp_oracle.project(wk.W, wk.b, wk.C, wk.cand_off, wk.cand_ids, batches_np[0][:r1], k)
+            one_s = time.perf_counter() - t0
+            gomp.omp_set_num_threads(threads)
+            result["cpu_baseline"]["single_thread"] = {"value": r1 / one_s, "unit": "rows/s", "cores": 1,
+                                                       "sample": "%d rows of the first batch, %.1f s" % (r1, one_s)}
+        except OSError:
+            result["cpu_baseline"]["single_thread"] = None
+        same_g = g0 == cpu_first["g"]
+        same_ids = (ids0 == cpu_first["ids"]).all(1) & same_g
+        err = np.abs(logp0[same_ids] - cpu_first["logp"][same_ids]).max() if same_ids.any() else float("nan")
         result["parity"] = {"rows": N, "clusters_equal": int(same_g.sum()), "topk_ids_equal_rows": int(same_ids.sum()),
                             "max_abs_logp_err": float(err)}
+
+    if not args.no_configs and args.workload == "large" and args.rows is None and args.topk is None \
+            and not args.single_cluster:
+        # The other configured workloads, reported the same way (each: the call as shipped, the same call
+        # confined to the slabs, the full projection, a spot check of a few rows against the CPU oracle).
+        configs = []
+        csteps, cwarm = max(10, args.steps // 2), max(4, args.warmup // 2)
+        for n_rows in wl.CONFIGS["sweep"].sweep_N:      # the decode-size sweep runs on the large index (same shape)
+            sw = Workload.__new__(Workload)
+            sw.__dict__.update(wk.__dict__)
+            sw.cfg = wl.CONFIGS["sweep"]
+            steps_n = csteps if n_rows < 1024 else max(6, csteps // 4)
+            m = measure(sw, n_rows, 1, steps_n, cwarm, nb=16, oracle_rows=4)
+            m.pop("_first")
+            configs.append(m)
+        wk.close()
+        del batches, out_ids, out_logp, out_g, ws
+        torch.cuda.empty_cache()
+        for name in ("tiny", "mid", "skewed"):
+            w2 = Workload(name, dev, options=args.option)
+            c2 = w2.cfg
+            steps_n = csteps if name != "skewed" else max(6, csteps // 5)
+            m = measure(w2, c2.N, c2.k, steps_n, cwarm, nb=16 if name != "skewed" else 8, oracle_rows=4)
+            m.pop("_first")
+            m["setup_seconds"] = w2.setup_seconds
+            m["arena_bytes"] = w2.info["arena_bytes_used"]
+            configs.append(m)
+            w2.close()
+            del w2
+            torch.cuda.empty_cache()
+        result["configs"] = configs
     print(json.dumps(result))
+
+
+def decode_loop(P, wl, index, cfg, C, dev):
+    """Toy search consumer: 8 sentences x beam 8, every step = clustered projection (top-8) + one beam step +
+    the survivors' rows carried to their new slots (a gather; the rows stand in for a decoder)."""
+    import torch
+    S_d, B_d, k_d, T_d = 8, 8, 8, 32
+    n_d = S_d * B_d
+    pool = torch.from_numpy(wl.make_rows(cfg, C, N=n_d * 4, stream=90)[0]).to(dev)
+    d_ids = torch.empty((n_d, k_d), dtype=torch.int32, device=dev)
+    d_logp = torch.empty((n_d, k_d), dtype=torch.float32, device=dev)
+    d_g = torch.empty((n_d,), dtype=torch.int32, device=dev)
+    wsd = index.workspace(n_d)
+    slot0 = (torch.arange(n_d, device=dev) // B_d) * B_d
+    first = torch.full((n_d,), float("-inf"), device=dev)
+    first[::B_d] = 0.0
+
+    def decode(steps):
+        scores, rows = first.clone(), pool[:n_d]
+        for t in range(steps):
+            index.project(rows, k_d, out_ids=d_ids, out_logp=d_logp, out_cluster=d_g, workspace=wsd)
+            scores, parent, _tok = P.vp_beam_step(d_ids, d_logp, scores, B_d)
+            fresh = pool[(t % 4) * n_d:(t % 4 + 1) * n_d]
+            rows = fresh[slot0 + parent.clamp(min=0)]
+        return scores
+
+    def timed_decode():
+        decode(4)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        final = decode(T_d)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / T_d, final
+
+    ms_dec, final = timed_decode()
+    mode = int(wsd[:64].view(torch.int32)[7].item())
+    # the same search confined to the per-cluster slabs (log-probs agree to 1e-4 between the two forms, so the
+    # two searches may part ways at a near-tie; the timing is what is compared)
+    index.set_option("dispatch", 0)
+    ms_dec_s, _ = timed_decode()
+    index.set_option("dispatch", 1)
+    return {"sentences": S_d, "beam": B_d, "topk": k_d, "steps": T_d, "ms_per_step": ms_dec,
+            "rows_per_s": n_d / (ms_dec * 1e-3),
+            "planner_chose_last_step": "masked full projection" if mode == 1 else "per-cluster slabs",
+            "slabs_only_ms_per_step": ms_dec_s, "slabs_only_rows_per_s": n_d / (ms_dec_s * 1e-3),
+            "finished_hypotheses": int(torch.isfinite(final).sum().item()),
+            "note": "vp_project + vp_beam_step + a gather of the next rows per step"}
 
 
 if __name__ == "__main__":

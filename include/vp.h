@@ -10,7 +10,10 @@
  * candidates (steps 4-5: excluded tokens are at -infinity) plus a descending
  * top-k (section 2.1) are returned.  Unlike the paper's own GPU design, which
  * unions the active sets of a batch and runs one gathered GEMM, rows are
- * bucketed by cluster and each bucket streams its cluster's pre-packed slab.
+ * bucketed by cluster and each bucket streams its cluster's pre-packed slab;
+ * batches that occupy so many clusters that their slabs outweigh the whole of W
+ * run the full projection with every row masked to its own active set instead
+ * (same results; the planner chooses per call).
  *
  * Conventions
  *  - "device" pointers are HIP device memory of the current device, "host"
@@ -104,10 +107,11 @@ vp_status vp_get_info(const vp_index *idx, vp_index_info *info);
  *   "rstar"         buckets with at most this many rows use the dot-product
  *                   GEMV loop, larger ones the MFMA loop (default 0, max 4)
  *   "full_target_items"  same as target_items for vp_project_full
- *   "dispatch"      1: vp_project may run the full projection with every row masked to
- *                   its own cluster's active set instead of streaming the occupied
+ *   "dispatch"      1 (default): vp_project runs the full projection with every row masked
+ *                   to its own cluster's active set instead of streaming the occupied
  *                   slabs, when the planner's cost model says that is cheaper (many
- *                   occupied clusters); same results.  Default 0.
+ *                   occupied clusters whose slabs outweigh one pass over W); same token ids,
+ *                   log-probs equal up to the order of the fp32 sums.  0: always the slabs.
  *   "cost_bw_slab_gbs", "cost_bw_full_gbs", "cost_bw_l2_gbs", "cost_bw_gemm_gbs",
  *   "cost_bw_gather_gbs"   GB/s of the cost model
  *   "union_dispatch" 1 (default): vp_project_union may skip the gather of U's columns and run
@@ -117,6 +121,10 @@ vp_status vp_get_info(const vp_index *idx, vp_index_info *info);
  *                   use the kernel with 64 rows per work item from this many rows on
  *                   (default 17; 0: never); d_pad must be 256, 512, 1024, 1536 or 2048
  *   "gemm_target_items"  work items of that kernel (default 512)
+ *   "gemm_lds"      1 (default): up to d_pad = 1024 those items run on the kernel that keeps
+ *                   their 64 rows in LDS (no split of the k-extent; one lock-free top-k
+ *                   list per row and workgroup); 0: the split-k kernel everywhere
+ *   "gemm_lds_items"  work items of that kernel (default: one per compute unit)
  *   "wide_items"    1 (default): below gemm_min_rows, vp_project_full / vp_project_union
  *                   of more than 16 rows with k <= 2 put 32 rows in an item; 0: always 16
  *   "small_path"    1 (default): batches of at most 16 rows run without a planning kernel;
@@ -223,6 +231,17 @@ vp_status vp_project_debug_logits(const vp_index *idx, const void *hidden, int32
  * the number of launches, and forgets them.  At most 16384 launches are kept
  * between two calls.  Not meant for use under graph capture. */
 vp_status vp_get_profile(vp_index *idx, double *kernel_ms_total, int64_t *launches);
+
+/* Benchmark aid: what this GPU actually sustains, to stand beside the published peaks in a
+ * roofline.  Streams buf once per repeat with a kernel that only reads (1 KiB non-temporal
+ * loads per wavefront, 8 in flight, as the slab kernel issues them) and runs a loop of
+ * v_mfma_f32_16x16x32_f16 on register operands; both timed with HIP events on the stream.
+ *   buf          device, 256-byte aligned, only read; bytes >= 64 MiB
+ *   read_gbs     host, receives the best GB/s over the repeats
+ *   mfma_tflops  host, receives the best dense fp16 TFLOP/s over the repeats
+ * Synchronises the stream.  repeats in [1, 100]. */
+vp_status vp_measure_ceilings(const void *buf, size_t bytes, int32_t repeats, double *read_gbs,
+                              double *mfma_tflops, void *hip_stream);
 
 /* ---- Offline training of the clusters (section 2.2 "Offline Training of Clusters";
  * training settings of section 3.1: k-means, 20 iterations) ----

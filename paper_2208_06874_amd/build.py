@@ -15,7 +15,7 @@ CLI_SRC = os.path.join(ROOT, "examples", "vp_cli.cpp")
 CLI = os.path.join(ROOT, "examples", "vp_cli")
 
 SOURCES = ["vp_api.hip", "build_kernels.hip", "centroid.hip", "plan.hip", "project.hip", "merge.hip", "union.hip",
-           "train.hip", "train_api.hip", "project_gemm.hip", "project_gemm_lds.hip", "search.hip"]
+           "train.hip", "train_api.hip", "project_gemm.hip", "project_gemm_lds.hip", "search.hip", "ceilings.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

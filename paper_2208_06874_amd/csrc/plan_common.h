@@ -69,8 +69,8 @@ __device__ inline void vp_plan_single_bucket(int N, int ncand, int vtiles, int r
 // groups of a bucket re-read them through the L2; the masked full projection streams W once
 // and pays for every further row group.  The top-k lists cost the full projection more than
 // the slabs (every lane of every wavefront is busy there): a margin that grows with k keeps
-// the choice on the safe side.  64-row items: one pass from HBM, each further row group at
-// the measured rate of the GEMM-shaped kernel.  16-row items: every row group re-reads W
+// the choice on the safe side (64-row items: top-8 measured 10 % over top-1).  64-row items:
+// one pass from HBM, each further row group at the measured rate of the GEMM-shaped kernel.  16-row items: every row group re-reads W
 // through the L2.  Tile counts are in candidate groups; the constants are groups per second.
 __device__ inline bool vp_full_is_cheaper(int occ_tiles, int total_tiles, int N, int rpi_full, int vtiles, int k,
                                           const VpCostModel &cost)
@@ -78,7 +78,7 @@ __device__ inline bool vp_full_is_cheaper(int occ_tiles, int total_tiles, int N,
     const int rgs_full = ceil_div(N, rpi_full);
     const float t_slab = occ_tiles / cost.bw_slab + (total_tiles - occ_tiles) / cost.bw_l2;
     const float t_full = rpi_full == 64
-        ? (vtiles / cost.bw_full + (rgs_full - 1) * (vtiles / cost.bw_gemm)) * (1.f + k * 0.0625f)
+        ? (vtiles / cost.bw_full + (rgs_full - 1) * (vtiles / cost.bw_gemm)) * (1.f + k * 0.0125f)
         : fmaxf(vtiles / cost.bw_full, (float)rgs_full * vtiles / cost.bw_l2) * (1.f + k * 0.125f);
     return t_full < t_slab;
 }

@@ -47,14 +47,14 @@ constexpr int VP_MAX_TOPK_LANES = 32;   // the epilogue writes a row's list with
 // (logit descending, position ascending), without branches
 __device__ inline bool before_entry(float v, int i, float v2, int i2) { return (v > v2) | ((v == v2) & (i < i2)); }
 
-template <int KT, bool MASKED, bool NT>
+template <int KT, bool MASKED, bool NT, bool TOP1>
 __device__ inline void gemm_lds_item(const VpSlabSet &set, const uint4 *__restrict__ hidden, int d,
                                      const int32_t *__restrict__ perm, const VpItem &item, int it, int k,
                                      float *__restrict__ partials, unsigned int *__restrict__ floors,
                                      const VpMaskInfo &mask)
 {
     const int tid = threadIdx.x;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // (uniform: step numbers and tile offsets stay in scalar registers)
     const int lane = tid & 63;
     const int n = lane & 15;
     const int q = lane >> 4;
@@ -71,7 +71,6 @@ __device__ inline void gemm_lds_item(const VpSlabSet &set, const uint4 *__restri
     const int gb = item.tile0;
     const int ge = item.tile0 + item.ntiles;
     const int nsteps = (item.ntiles + L_G - 1) / L_G;
-    const int last_word = ((ncand + VP_TILE_ITEMS - 1) / VP_TILE_ITEMS * VP_TILE_ITEMS - 1) >> 5;   // of a membership list
     const uint4 *slab = reinterpret_cast<const uint4 *>(set.tiles) + (size_t)item.tile_off * KT * 64 + lane;
     const float *bias = set.bias + (size_t)item.tile_off * VP_TILE_ITEMS + q * 4;
 
@@ -129,16 +128,16 @@ __device__ inline void gemm_lds_item(const VpSlabSet &set, const uint4 *__restri
     float m_run[L_RT], s_run[L_RT];
     float b1v[L_RT];
     int b1i[L_RT];
-    const uint32_t *mrow[L_RT];
+    unsigned int moff[L_RT];   // first word of the row's membership list
 #pragma unroll
     for (int rt = 0; rt < L_RT; ++rt) {
         m_run[rt] = VP_NEG_BIG;
         s_run[rt] = 0.f;
         b1v[rt] = -__builtin_inff();
         b1i[rt] = VP_IDX_NONE;
-        mrow[rt] = MASKED ? mask.bitmaps + (size_t)(row_valid[rt] ? mask.g[myrow[rt]] : 0) * mask.words : nullptr;
+        moff[rt] = MASKED ? (unsigned int)(row_valid[rt] ? mask.g[myrow[rt]] : 0) * (unsigned int)mask.words : 0u;
     }
-    const bool top1 = k == 1;
+    constexpr bool top1 = TOP1;   // k == 1: the best entry stays in registers, no list traffic in the loop
     unsigned int pending[L_RT];
     int pending_rt = -1;
     int done_steps = 0;
@@ -156,15 +155,13 @@ __device__ inline void gemm_lds_item(const VpSlabSet &set, const uint4 *__restri
         float4 bz[L_G];
 #pragma unroll
         for (int j = 0; j < L_G; ++j) bz[j] = *reinterpret_cast<const float4 *>(bias + (size_t)min(g0 + j, ge - 1) * VP_TILE_ITEMS);
-        uint32_t mw[L_RT][2];
+        uint2 mw[L_RT];
         if (MASKED) {
+            // the step's 64 candidates start at a multiple of 64: one aligned pair of 32-bit words (the
+            // lists are padded to an even number of words)
 #pragma unroll
-            for (int rt = 0; rt < L_RT; ++rt) {
-                // the step's 64 candidates start at a multiple of 64: two whole 32-bit words
-                const int w0 = (g0 * VP_TILE_ITEMS) >> 5;
-                mw[rt][0] = mrow[rt][w0];
-                mw[rt][1] = mrow[rt][min(w0 + 1, last_word)];
-            }
+            for (int rt = 0; rt < L_RT; ++rt)
+                mw[rt] = *reinterpret_cast<const uint2 *>(mask.bitmaps + (moff[rt] + ((g0 * VP_TILE_ITEMS) >> 5)));
         }
 
         floatx4 acc[L_RT][L_G];
@@ -240,12 +237,16 @@ __device__ inline void gemm_lds_item(const VpSlabSet &set, const uint4 *__restri
                         if (g0 + j >= ge || c_first + j * VP_TILE_ITEMS + i >= ncand) z[j * 4 + i] = -__builtin_inff();
             }
             if (MASKED) {
+                // a token outside the row's active set is at -infinity (steps 4-5 of section 2.3's list):
+                // the membership bit, spread over a word, keeps the logit's bits or takes -infinity's
 #pragma unroll
                 for (int j = 0; j < L_G; ++j) {
-                    const uint32_t nib = (mw[rt][j >> 1] >> ((j & 1) * 16 + q * 4)) & 15u;
+                    const uint32_t w = (j >> 1) ? mw[rt].y : mw[rt].x;
 #pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        if (!((nib >> i) & 1u)) z[j * 4 + i] = -__builtin_inff();
+                    for (int i = 0; i < 4; ++i) {
+                        const uint32_t keep = (uint32_t)__builtin_amdgcn_sbfe((int)w, (j & 1) * 16 + q * 4 + i, 1);   // 0 or ~0
+                        z[j * 4 + i] = __uint_as_float((__float_as_uint(z[j * 4 + i]) & keep) | (0xff800000u & ~keep));
+                    }
                 }
             }
             float tmax = z[0];
@@ -393,7 +394,7 @@ __device__ inline void gemm_lds_item(const VpSlabSet &set, const uint4 *__restri
     }
 }
 
-template <int KT, bool MASKED>
+template <int KT, bool MASKED, bool TOP1>
 __global__ __launch_bounds__(L_NW * 64) void project_gemm_lds_kernel(
     VpSlabSet set, const uint4 *__restrict__ hidden, int d, const int32_t *__restrict__ perm,
     const VpItem *__restrict__ items, const VpPlanHeader *__restrict__ hdr, int k,
@@ -405,9 +406,9 @@ __global__ __launch_bounds__(L_NW * 64) void project_gemm_lds_kernel(
     if (it < 0 || it >= total_items) return;
     const VpItem item = items[it];
     if (item.shared)
-        gemm_lds_item<KT, MASKED, false>(set, hidden, d, perm, item, it, k, partials, floors, mask);
+        gemm_lds_item<KT, MASKED, false, TOP1>(set, hidden, d, perm, item, it, TOP1 ? 1 : k, partials, floors, mask);
     else
-        gemm_lds_item<KT, MASKED, true>(set, hidden, d, perm, item, it, k, partials, floors, mask);
+        gemm_lds_item<KT, MASKED, true, TOP1>(set, hidden, d, perm, item, it, TOP1 ? 1 : k, partials, floors, mask);
 }
 
 template <int KT, bool MASKED>
@@ -415,20 +416,28 @@ void launch_lds(const VpSlabSet &set, const void *hidden, int d, const int32_t *
                 const VpPlanHeader *hdr, int grid_items, int k, float *partials, unsigned int *floors,
                 const VpMaskInfo &mask, hipStream_t st)
 {
-    hipLaunchKernelGGL((project_gemm_lds_kernel<KT, MASKED>), dim3(grid_items), dim3(L_NW * 64),
-                       vpk_project_rows_lds_bytes(k, KT), st, set, (const uint4 *)hidden, d, perm, items, hdr, k,
-                       partials, floors, mask);
+    if (k == 1)
+        hipLaunchKernelGGL((project_gemm_lds_kernel<KT, MASKED, true>), dim3(grid_items), dim3(L_NW * 64),
+                           vpk_project_rows_lds_bytes(k, KT), st, set, (const uint4 *)hidden, d, perm, items, hdr, k,
+                           partials, floors, mask);
+    else
+        hipLaunchKernelGGL((project_gemm_lds_kernel<KT, MASKED, false>), dim3(grid_items), dim3(L_NW * 64),
+                           vpk_project_rows_lds_bytes(k, KT), st, set, (const uint4 *)hidden, d, perm, items, hdr, k,
+                           partials, floors, mask);
 }
 
 template <int KT>
 hipError_t allow_lds_bytes()
 {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(project_gemm_lds_kernel<KT, false>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e == hipSuccess)
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(project_gemm_lds_kernel<KT, true>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    return e;
+    const void *fns[] = {reinterpret_cast<const void *>(project_gemm_lds_kernel<KT, false, false>),
+                         reinterpret_cast<const void *>(project_gemm_lds_kernel<KT, false, true>),
+                         reinterpret_cast<const void *>(project_gemm_lds_kernel<KT, true, false>),
+                         reinterpret_cast<const void *>(project_gemm_lds_kernel<KT, true, true>)};
+    for (const void *f : fns) {
+        const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 }  // namespace

@@ -185,7 +185,7 @@ vp_status plan_arena(const vp_build_desc *D, bool check_ids, ArenaLayout *L)
     L->n_cand = take((size_t)D->K * sizeof(int32_t));
     L->ids_pad = take((size_t)groups * VP_TILE_ITEMS * sizeof(int32_t));
     L->sbias = take((size_t)groups * VP_TILE_ITEMS * sizeof(float));
-    L->bm_words = ceil_div((long)L->vtiles * VP_TILE_ITEMS, 32);
+    L->bm_words = (ceil_div((long)L->vtiles * VP_TILE_ITEMS, 32) + 1) & ~1;   // even: a list's words pair up into aligned 64-bit loads
     L->bitmaps = take((size_t)D->K * L->bm_words * sizeof(uint32_t));
     L->slabs = take((size_t)groups * group_bytes);
     L->total = o;
@@ -608,12 +608,19 @@ vp_status vp_build(const vp_build_desc *D, void *hip_stream, vp_index **out)
     I->gemm_target_items = 512;
     I->gemm_lds = 1;
     I->gemm_lds_items = 256;
-    I->dispatch = 0;
-    // measured on MI355X at d = 1024: bytes per second of the three regimes of the cost model
+    // The planner takes whichever of the two forms of the clustered projection its cost model says
+    // is cheaper (same results): per-cluster slabs, or the full projection masked to every row's own
+    // active set.
+    I->dispatch = 1;
+    // measured on MI355X at d = 1024, V = 250,000: bytes per second of the regimes of the cost model.
+    // Slabs stream at 6.8 TB/s.  The masked full projection with 64-row items takes about 100 us for
+    // its first row group (one pass over W from HBM: 5.1 TB/s) and 25 us for every further one
+    // (W from the L2, matrix cores busy: 20 TB/s of W); with 16-row items every row group re-reads
+    // W through the L2 at 17 TB/s.
     I->cost.bw_slab = 6.8e12f;
-    I->cost.bw_full = 5.4e12f;
+    I->cost.bw_full = 5.1e12f;
     I->cost.bw_l2 = 17.0e12f;
-    I->cost.bw_gemm = 12.0e12f;
+    I->cost.bw_gemm = 20.0e12f;
     // batch-union form: the gather of U's columns from the token-major copy into the union slab
     // (fitted to the measured crossover at |U| = 28 % of V for 64 rows) and the kernels only the
     // gathered form needs
@@ -801,6 +808,51 @@ vp_status vp_get_profile(vp_index *I, double *kernel_ms_total, int64_t *launches
     }
     P->used = 0;
     return VP_OK;
+}
+
+vp_status vp_measure_ceilings(const void *buf, size_t bytes, int32_t repeats, double *read_gbs, double *mfma_tflops,
+                              void *hip_stream)
+{
+    const char *fn = "vp_measure_ceilings";
+    if (!buf || !aligned(buf, ALIGN) || !read_gbs || !mfma_tflops) return fail(VP_ERR_INVALID_ARG, "%s: null or misaligned argument", fn);
+    if (bytes < (64u << 20) || repeats < 1 || repeats > 100)
+        return fail(VP_ERR_INVALID_ARG, "%s: bytes must be at least 64 MiB and repeats in [1, 100]", fn);
+    hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+    void *sink = nullptr;
+    vp_status s = static_scratch_of_current_device(fn, &sink);
+    if (s != VP_OK) return s;
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    cus = std::max(1, cus);
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess) return fail(VP_ERR_HIP, "%s: cannot create events", fn);
+    if (hipEventCreate(&e1) != hipSuccess) {
+        (void)hipEventDestroy(e0);
+        return fail(VP_ERR_HIP, "%s: cannot create events", fn);
+    }
+    *read_gbs = 0.0;
+    *mfma_tflops = 0.0;
+    hipError_t e = hipSuccess;
+    const int mfma_iters = 4096;
+    for (int r = 0; r <= repeats && e == hipSuccess; ++r) {   // (the first pass warms up and is not counted)
+        float ms = 0.f;
+        (void)hipEventRecord(e0, st);
+        const size_t read = vpk_ceiling_read(buf, bytes, cus, sink, st);
+        (void)hipEventRecord(e1, st);
+        e = hipEventSynchronize(e1);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+        if (e == hipSuccess && r > 0 && ms > 0.f) *read_gbs = std::max(*read_gbs, (double)read / (ms * 1e-3) / 1e9);
+        (void)hipEventRecord(e0, st);
+        const double flops = vpk_ceiling_mfma(mfma_iters, cus, sink, st);
+        (void)hipEventRecord(e1, st);
+        if (e == hipSuccess) e = hipEventSynchronize(e1);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+        if (e == hipSuccess && r > 0 && ms > 0.f) *mfma_tflops = std::max(*mfma_tflops, flops / (ms * 1e-3) / 1e12);
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (e != hipSuccess) return fail(VP_ERR_HIP, "%s: %s", fn, hipGetErrorString(e));
+    return launch_status(fn);
 }
 
 size_t vp_union_workspace_bytes(const vp_index *I, int32_t N_max)

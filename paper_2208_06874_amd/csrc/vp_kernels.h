@@ -104,6 +104,10 @@ void vpk_aset_flags(const int32_t *top, const int32_t *assign, long n, int T, in
 void vpk_aset_emit(const uint32_t *bitmaps, int words, int K, const int64_t *cand_off, int32_t *cand_ids,
                    hipStream_t st);
 
+// measured ceilings (benchmark aid)
+size_t vpk_ceiling_read(const void *buf, size_t bytes, int cus, void *sink, hipStream_t st);
+double vpk_ceiling_mfma(int iters, int cus, void *sink, hipStream_t st);
+
 // error message of the calling thread (shared by the translation units of the host API)
 int vpi_fail(int status, const char *fmt, ...);
 uint16_t vpk_round_to_half(double v);

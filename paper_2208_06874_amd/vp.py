@@ -23,7 +23,7 @@ EXPORTS = ("vp_build_bytes", "vp_build", "vp_get_info", "vp_set_option", "vp_wor
            "vp_project", "vp_project_static", "vp_project_full", "vp_union_workspace_bytes", "vp_project_union",
            "vp_project_debug_logits", "vp_get_profile", "vp_destroy", "vp_last_error",
            "vp_kmeans_workspace_bytes", "vp_kmeans", "vp_active_sets_workspace_bytes", "vp_active_sets",
-           "vp_round_to_half", "vp_beam_step")
+           "vp_round_to_half", "vp_beam_step", "vp_measure_ceilings")
 
 
 class VpError(RuntimeError):
@@ -99,6 +99,9 @@ def lib():
                                      ctypes.c_int64, ctypes.POINTER(ctypes.c_int64), vp, ctypes.c_size_t, vp]
         L.vp_beam_step.restype = ctypes.c_int
         L.vp_beam_step.argtypes = [vp, vp, vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp, vp, vp, vp]
+        L.vp_measure_ceilings.restype = ctypes.c_int
+        L.vp_measure_ceilings.argtypes = [vp, ctypes.c_size_t, ctypes.c_int32, ctypes.POINTER(ctypes.c_double),
+                                          ctypes.POINTER(ctypes.c_double), vp]
         L.vp_round_to_half.restype = ctypes.c_uint16
         L.vp_round_to_half.argtypes = [ctypes.c_double]
         _lib = L
@@ -118,6 +121,39 @@ def _ptr(t) -> Optional[int]:
     return None if t is None else t.data_ptr()
 
 
+def _want(t, name: str, dtype, shape=None, device=None, optional: bool = False):
+    """Checks a tensor argument before its address crosses the C ABI: a host pointer, a view with
+    strides or a buffer of the wrong size would make the kernels read or write out of bounds."""
+    import torch
+    if t is None:
+        if optional:
+            return None
+        raise ValueError("%s is required" % name)
+    if not isinstance(t, torch.Tensor):
+        raise TypeError("%s must be a torch.Tensor, got %s" % (name, type(t).__name__))
+    if t.dtype != dtype:
+        raise ValueError("%s must be %s, got %s" % (name, dtype, t.dtype))
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError("%s must have shape %s, got %s" % (name, tuple(shape), tuple(t.shape)))
+    if not t.is_cuda:
+        raise ValueError("%s must live in GPU memory (got a %s tensor)" % (name, t.device))
+    if device is not None and t.device != device:
+        raise ValueError("%s is on %s, the index on %s" % (name, t.device, device))
+    return t
+
+
+def _want_bytes(t, name: str, need: int, device=None):
+    """A workspace: flat uint8, contiguous, on the GPU.  (Its size is checked by the library itself, on the
+    host and before anything is launched: a short one gives VP_ERR_WORKSPACE.)"""
+    import torch
+    _want(t, name, torch.uint8, None, device)
+    if t.dim() != 1:
+        raise ValueError("%s must be a flat uint8 tensor, got shape %s" % (name, tuple(t.shape)))
+    return t
+
+
 def _stream(stream=None) -> int:
     import torch
     s = torch.cuda.current_stream() if stream is None else stream
@@ -135,13 +171,23 @@ class Index:
 
     def __init__(self, W, bias, centroids, cand_off, cand_ids, k_max: int = 8, stream=None):
         import torch
-        assert W.is_cuda and W.dtype == torch.float16 and W.is_contiguous()
-        assert bias.dtype == torch.float16 and centroids.dtype == torch.float16
+        if not isinstance(W, torch.Tensor) or W.dim() != 2:
+            raise ValueError("W must be a [d, V] tensor")
         d, V = W.shape
+        if not isinstance(centroids, torch.Tensor) or centroids.dim() != 2 or centroids.shape[1] != d:
+            raise ValueError("centroids must be a [K, d] tensor")
         K = centroids.shape[0]
+        _want(W, "W", torch.float16)
+        _want(bias, "bias", torch.float16, (V,), W.device)
+        # (contiguous copies, if any were needed, must stay alive until vp_build has read them)
+        self._C = _want(centroids.contiguous(), "centroids", torch.float16, (K, d), W.device)
         self._off = np.ascontiguousarray(cand_off, np.int64)
         self._ids = np.ascontiguousarray(cand_ids, np.int32)
-        desc = make_desc(d, V, K, W.data_ptr(), bias.data_ptr(), centroids.contiguous().data_ptr(), self._off,
+        if self._off.shape != (K + 1,):
+            raise ValueError("cand_off must have K + 1 = %d entries, got %s" % (K + 1, self._off.shape))
+        if self._ids.ndim != 1 or (len(self._off) and self._ids.shape[0] != int(self._off[-1])):
+            raise ValueError("cand_ids must hold cand_off[K] = %d entries, got %s" % (int(self._off[-1]), self._ids.shape))
+        desc = make_desc(d, V, K, W.data_ptr(), bias.data_ptr(), self._C.data_ptr(), self._off,
                          self._ids, None, 0, k_max)
         need = lib().vp_build_bytes(ctypes.byref(desc))
         if need == 0:
@@ -155,6 +201,7 @@ class Index:
         h = ctypes.c_void_p()
         _check(lib().vp_build(ctypes.byref(desc), _stream(stream), ctypes.byref(h)))
         self.handle = h
+        self._C = None    # vp_build has synchronised: the index holds its own packed copy
         self.device = W.device
         self.d, self.V, self.K, self.k_max = d, V, K, k_max
         self._ws = {}     # cached scratch buffers, one per stream: calls that share one must not overlap
@@ -204,37 +251,52 @@ class Index:
                 workspace=None, stream=None):
         """vp_project: hidden[N, d] fp16 -> (ids[N, k] int32, logp[N, k] fp32, cluster[N] int32)."""
         import torch
-        N = hidden.shape[0]
-        assert hidden.dtype == torch.float16 and hidden.is_contiguous() and hidden.shape[1] == self.d
-        if out_ids is None:
-            out_ids = torch.empty((N, k), dtype=torch.int32, device=self.device)
-        if out_logp is None:
-            out_logp = torch.empty((N, k), dtype=torch.float32, device=self.device)
+        N = self._rows(hidden)
+        out_ids, out_logp = self._outputs(N, k, out_ids, out_logp)
         if out_cluster is None and want_cluster:
             out_cluster = torch.empty((N,), dtype=torch.int32, device=self.device)
-        ws = self.workspace(N, stream) if workspace is None else workspace
+        _want(out_cluster, "out_cluster", torch.int32, (N,), self.device, optional=True)
+        ws = self.workspace(N, stream) if workspace is None else _want_bytes(workspace, "workspace",
+                                                                           self.workspace_bytes(N), self.device)
         _check(lib().vp_project(self.handle, hidden.data_ptr(), N, k, out_ids.data_ptr(), out_logp.data_ptr(),
                                 _ptr(out_cluster), ws.data_ptr(), ws.numel(), _stream(stream)))
         return out_ids, out_logp, out_cluster
 
+    def _rows(self, hidden) -> int:
+        import torch
+        if not isinstance(hidden, torch.Tensor) or hidden.dim() != 2:
+            raise ValueError("hidden must be an [N, d] tensor")
+        _want(hidden, "hidden", torch.float16, (hidden.shape[0], self.d), self.device)
+        return hidden.shape[0]
+
+    def _outputs(self, N: int, k: int, out_ids, out_logp):
+        import torch
+        if out_ids is None:
+            out_ids = torch.empty((N, k), dtype=torch.int32, device=self.device)
+        if out_logp is None:
+            out_logp = torch.empty((N, k), dtype=torch.float32, device=self.device)
+        _want(out_ids, "out_ids", torch.int32, (N, k), self.device)
+        _want(out_logp, "out_logp", torch.float32, (N, k), self.device)
+        return out_ids, out_logp
+
     def project_static(self, hidden, k: int, out_ids, out_logp, out_cluster=None, stream=None):
         """vp_project_static: vp_project on the library's own scratch array; the caller passes every output
         (nothing is allocated here either)."""
-        N = hidden.shape[0]
+        import torch
+        N = self._rows(hidden)
+        _want(out_ids, "out_ids", torch.int32, (N, k), self.device)
+        _want(out_logp, "out_logp", torch.float32, (N, k), self.device)
+        _want(out_cluster, "out_cluster", torch.int32, (N,), self.device, optional=True)
         _check(lib().vp_project_static(self.handle, hidden.data_ptr(), N, k, out_ids.data_ptr(), out_logp.data_ptr(),
                                        _ptr(out_cluster), _stream(stream)))
         return out_ids, out_logp, out_cluster
 
     def project_full(self, hidden, k: int, out_ids=None, out_logp=None, workspace=None, stream=None):
         """vp_project_full: the default projection over all V tokens."""
-        import torch
-        N = hidden.shape[0]
-        assert hidden.dtype == torch.float16 and hidden.is_contiguous() and hidden.shape[1] == self.d
-        if out_ids is None:
-            out_ids = torch.empty((N, k), dtype=torch.int32, device=self.device)
-        if out_logp is None:
-            out_logp = torch.empty((N, k), dtype=torch.float32, device=self.device)
-        ws = self.workspace(N, stream) if workspace is None else workspace
+        N = self._rows(hidden)
+        out_ids, out_logp = self._outputs(N, k, out_ids, out_logp)
+        ws = self.workspace(N, stream) if workspace is None else _want_bytes(workspace, "workspace",
+                                                                           self.workspace_bytes(N), self.device)
         _check(lib().vp_project_full(self.handle, hidden.data_ptr(), N, k, out_ids.data_ptr(),
                                      out_logp.data_ptr(), ws.data_ptr(), ws.numel(), _stream(stream)))
         return out_ids, out_logp
@@ -246,22 +308,22 @@ class Index:
                       workspace=None, stream=None):
         """vp_project_union: the paper's batched form -> (ids, logp, cluster, union_size[1])."""
         import torch
-        N = hidden.shape[0]
-        assert hidden.dtype == torch.float16 and hidden.is_contiguous() and hidden.shape[1] == self.d
-        if out_ids is None:
-            out_ids = torch.empty((N, k), dtype=torch.int32, device=self.device)
-        if out_logp is None:
-            out_logp = torch.empty((N, k), dtype=torch.float32, device=self.device)
+        N = self._rows(hidden)
+        out_ids, out_logp = self._outputs(N, k, out_ids, out_logp)
         if out_cluster is None:
             out_cluster = torch.empty((N,), dtype=torch.int32, device=self.device)
         if out_union_size is None:
             out_union_size = torch.zeros((1,), dtype=torch.int32, device=self.device)
+        _want(out_cluster, "out_cluster", torch.int32, (N,), self.device)
+        _want(out_union_size, "out_union_size", torch.int32, (1,), self.device)
+        need = self.union_workspace_bytes(N)
         if workspace is None:
-            need = self.union_workspace_bytes(N)
             key = _stream(stream)
             workspace = self._uws.get(key)
             if workspace is None or workspace.numel() < need:
                 workspace = self._uws[key] = torch.empty(max(need, 256), dtype=torch.uint8, device=self.device)
+        else:
+            _want_bytes(workspace, "workspace", need, self.device)
         _check(lib().vp_project_union(self.handle, hidden.data_ptr(), N, k, out_ids.data_ptr(), out_logp.data_ptr(),
                                       out_cluster.data_ptr(), out_union_size.data_ptr(), workspace.data_ptr(),
                                       workspace.numel(), _stream(stream)))
@@ -270,7 +332,7 @@ class Index:
     def debug_logits(self, hidden, full: bool = False, stream=None):
         """vp_project_debug_logits -> (cluster[N], row_offsets[N+1] int64, logits fp32)."""
         import torch
-        N = hidden.shape[0]
+        N = self._rows(hidden)
         cap = N * (self.V if full else self.info()["n_max"])
         cluster = torch.empty((N,), dtype=torch.int32, device=self.device)
         offs = torch.empty((N + 1,), dtype=torch.int64, device=self.device)
@@ -338,6 +400,16 @@ def vp_last_error() -> str:
     return last_error()
 
 
+def vp_measure_ceilings(buf, repeats: int = 5, stream=None):
+    """vp_measure_ceilings on a uint8 GPU buffer -> (streaming-read GB/s, dense fp16 MFMA TFLOP/s)."""
+    import torch
+    _want(buf, "buf", torch.uint8)
+    r, m = ctypes.c_double(), ctypes.c_double()
+    _check(lib().vp_measure_ceilings(buf.data_ptr(), buf.numel(), int(repeats), ctypes.byref(r), ctypes.byref(m),
+                                     _stream(stream)))
+    return r.value, m.value
+
+
 # ---------------------------------------------------------------- offline training of the clusters
 def vp_round_to_half(v: float) -> int:
     return int(lib().vp_round_to_half(float(v)))
@@ -350,16 +422,19 @@ def vp_kmeans(X, centroids, iters: int = 20, workspace=None, stream=None, split_
     """vp_kmeans: trains `centroids` (fp16 [K, d], updated in place) on X (fp16 [n, d]).
     Returns (assign int32 [n], counts int32 [K]) under the final centroids."""
     import torch
-    assert X.is_cuda and X.dtype == torch.float16 and X.is_contiguous() and X.dim() == 2
-    assert centroids.is_cuda and centroids.dtype == torch.float16 and centroids.is_contiguous()
+    if not isinstance(X, torch.Tensor) or X.dim() != 2 or not isinstance(centroids, torch.Tensor) or centroids.dim() != 2:
+        raise ValueError("X must be an [n, d] and centroids a [K, d] tensor")
     n, d = X.shape
     K = centroids.shape[0]
-    assert centroids.shape[1] == d
+    _want(X, "X", torch.float16)
+    _want(centroids, "centroids", torch.float16, (K, d), X.device)
     need = lib().vp_kmeans_workspace_bytes(n, d, K)
     if need == 0:
         raise VpError(VP_ERR_UNSUPPORTED, last_error())
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
+    else:
+        _want_bytes(workspace, "workspace", need, X.device)
     assign = torch.empty(n, dtype=torch.int32, device=X.device)
     counts = torch.empty(K, dtype=torch.int32, device=X.device)
     _check(lib().vp_kmeans(X.data_ptr(), n, d, K, iters, KMEANS_SPLIT_EMPTY if split_empty else 0, centroids.data_ptr(),
@@ -371,10 +446,11 @@ def vp_kmeans(X, centroids, iters: int = 20, workspace=None, stream=None, split_
 def vp_active_sets(top_ids, assign, K: int, V: int, capacity: Optional[int] = None, stream=None):
     """vp_active_sets: returns (cand_offsets int64 [K+1], cand_ids int32 [total]) on the device."""
     import torch
-    assert top_ids.is_cuda and top_ids.dtype == torch.int32 and top_ids.is_contiguous() and top_ids.dim() == 2
-    assert assign.is_cuda and assign.dtype == torch.int32 and assign.is_contiguous()
+    if not isinstance(top_ids, torch.Tensor) or top_ids.dim() != 2:
+        raise ValueError("top_ids must be an [n, T] tensor")
     n, T = top_ids.shape
-    assert assign.shape[0] == n
+    _want(top_ids, "top_ids", torch.int32)
+    _want(assign, "assign", torch.int32, (n,), top_ids.device)
     need = lib().vp_active_sets_workspace_bytes(K, V)
     if need == 0:
         raise VpError(VP_ERR_UNSUPPORTED, last_error())
@@ -400,11 +476,18 @@ def vp_active_sets_workspace_bytes(K: int, V: int) -> int:
 def vp_beam_step(cand_ids, cand_logp, scores, B: int, out=None, stream=None):
     """vp_beam_step: returns (out_scores fp32 [S*B], out_parent int32 [S*B], out_token int32 [S*B])."""
     import torch
-    assert cand_ids.is_cuda and cand_ids.dtype == torch.int32 and cand_ids.is_contiguous() and cand_ids.dim() == 2
-    assert cand_logp.dtype == torch.float32 and cand_logp.is_contiguous() and cand_logp.shape == cand_ids.shape
-    assert scores.dtype == torch.float32 and scores.is_contiguous() and scores.shape == (cand_ids.shape[0],)
+    if not isinstance(cand_ids, torch.Tensor) or cand_ids.dim() != 2:
+        raise ValueError("cand_ids must be an [S * B, k] tensor")
     n, k = cand_ids.shape
-    assert n % B == 0
+    _want(cand_ids, "cand_ids", torch.int32)
+    _want(cand_logp, "cand_logp", torch.float32, (n, k), cand_ids.device)
+    _want(scores, "scores", torch.float32, (n,), cand_ids.device)
+    if B < 1 or n % B != 0:
+        raise ValueError("the %d rows are not a whole number of sentences of %d hypotheses" % (n, B))
+    if out is not None:
+        _want(out[0], "out_scores", torch.float32, (n,), cand_ids.device)
+        _want(out[1], "out_parent", torch.int32, (n,), cand_ids.device)
+        _want(out[2], "out_token", torch.int32, (n,), cand_ids.device)
     if out is None:
         out = (torch.empty(n, dtype=torch.float32, device=cand_ids.device),
                torch.empty(n, dtype=torch.int32, device=cand_ids.device),

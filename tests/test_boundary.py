@@ -32,7 +32,7 @@ def test_python_binding_has_the_same_names():
     for n in ("vp_build", "vp_project", "vp_project_full", "vp_project_debug_logits", "vp_workspace_bytes",
               "vp_set_option", "vp_get_info", "vp_get_profile", "vp_destroy", "vp_last_error", "vp_project_union",
               "vp_union_workspace_bytes", "vp_kmeans", "vp_kmeans_workspace_bytes", "vp_active_sets",
-              "vp_active_sets_workspace_bytes", "vp_round_to_half", "vp_beam_step", "vp_project_static"):
+              "vp_active_sets_workspace_bytes", "vp_round_to_half", "vp_beam_step", "vp_project_static", "vp_measure_ceilings"):
         assert callable(getattr(P, n))
 
 
@@ -264,3 +264,65 @@ def test_workgroup_to_item_maps_take_every_item_once(layout):
                     assert (it // rgs) % 8 == wg % 8
     # no swizzle
     assert [layout.shim_item_of_workgroup(wg, 10, 0, 0) for wg in range(10)] == list(range(10))
+
+
+def _fake_index(d=64, k_max=4):
+    """An Index object without a library handle: the binding's own checks run before any C call."""
+    import torch
+    idx = vp.Index.__new__(vp.Index)
+    idx.handle = None
+    idx.device = torch.device("cuda:0")
+    idx.d, idx.V, idx.K, idx.k_max = d, 100, 3, k_max
+    idx._ws, idx._uws = {}, {}
+    return idx
+
+
+def test_binding_rejects_host_tensors_and_wrong_shapes_before_any_c_call():
+    """A CPU tensor, a strided view or an output of the wrong size would hand the kernels a host pointer or
+    a short buffer: the binding raises first (handle is None here, so reaching the C call would fail differently)."""
+    import torch
+    idx = _fake_index()
+    H = torch.zeros((5, 64), dtype=torch.float16)            # host memory
+    for call in (lambda: idx.project(H, 2), lambda: idx.project_full(H, 2), lambda: idx.project_union(H, 2),
+                 lambda: idx.debug_logits(H),
+                 lambda: idx.project_static(H, 2, torch.zeros((5, 2), dtype=torch.int32),
+                                            torch.zeros((5, 2), dtype=torch.float32))):
+        with pytest.raises(ValueError, match="GPU memory"):
+            call()
+    with pytest.raises(ValueError, match="hidden must be"):
+        idx.project(torch.zeros(64, dtype=torch.float16), 2)
+    with pytest.raises(ValueError, match="shape"):
+        idx.project(torch.zeros((5, 32), dtype=torch.float16), 2)
+    # the checks themselves, on tensors that claim nothing about the GPU
+    t = torch.zeros((4, 6), dtype=torch.float32)
+    with pytest.raises(ValueError, match="GPU memory"):
+        vp._want(t, "t", torch.float32)
+    with pytest.raises(TypeError):
+        vp._want([1, 2], "t", torch.float32)
+    with pytest.raises(ValueError, match="required"):
+        vp._want(None, "t", torch.float32)
+    assert vp._want(None, "t", torch.float32, optional=True) is None
+    with pytest.raises(ValueError, match="contiguous"):
+        vp._want(t.t(), "t", torch.float32)
+    with pytest.raises(ValueError, match="float16"):
+        idx.project(torch.zeros((5, 64), dtype=torch.float32), 2)
+
+
+def test_build_rejects_bad_tensors_before_any_c_call():
+    import torch
+    W = torch.zeros((64, 100), dtype=torch.float16)
+    b = torch.zeros(100, dtype=torch.float16)
+    C = torch.zeros((3, 64), dtype=torch.float16)
+    off = np.array([0, 1, 2, 3], np.int64)
+    ids = np.array([0, 1, 2], np.int32)
+    with pytest.raises(ValueError, match="GPU memory"):
+        vp.Index(W, b, C, off, ids)
+    with pytest.raises(ValueError, match="W must be"):
+        vp.Index(b, b, C, off, ids)
+    with pytest.raises(ValueError, match="centroids must be"):
+        vp.Index(W, b, torch.zeros((3, 32), dtype=torch.float16), off, ids)
+    for fn in (lambda: vp.vp_kmeans(W, C), lambda: vp.vp_active_sets(torch.zeros((4, 2), dtype=torch.int32),
+                                                                      torch.zeros(4, dtype=torch.int32), 3, 100),
+               lambda: vp.vp_beam_step(torch.zeros((4, 2), dtype=torch.int32), torch.zeros((4, 2)), torch.zeros(4), 2)):
+        with pytest.raises(ValueError, match="GPU memory"):
+            fn()

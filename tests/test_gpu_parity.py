@@ -31,6 +31,9 @@ class Built:
         bt = torch.from_numpy(b).to(dev)
         Ct = torch.from_numpy(C).to(dev)
         self.index = vp.vp_build(Wt, bt, Ct, self.cand_off, self.cand_ids, k_max=k_max)
+        # the tests of this file look at the per-cluster slabs unless they say otherwise: the planner's
+        # choice (on by default in the library) is switched on where it is the subject of a test
+        self.index.set_option("dispatch", 0)
         torch.cuda.synchronize()
         del Wt, bt, Ct   # the index keeps its own packed copies
 
@@ -515,7 +518,7 @@ def test_dispatch_cost_model_constants(mid):
         got = mid.project(H, cfg.k)
         assert _planner_mode(mid.index, 64) == 0
     finally:
-        mid.index.set_option("cost_bw_full_gbs", 5400)
+        mid.index.set_option("cost_bw_full_gbs", 5100)
         mid.index.set_option("dispatch", 0)
     base = mid.project(H, cfg.k)
     assert np.array_equal(got[0], base[0])
