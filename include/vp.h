@@ -113,7 +113,8 @@ vp_status vp_get_info(const vp_index *idx, vp_index_info *info);
  *                   occupied clusters whose slabs outweigh one pass over W); same token ids,
  *                   log-probs equal up to the order of the fp32 sums.  0: always the slabs.
  *   "cost_bw_slab_gbs", "cost_bw_full_gbs", "cost_bw_l2_gbs", "cost_bw_gemm_gbs",
- *   "cost_bw_gather_gbs"   GB/s of the cost model
+ *   "cost_bw_gemm_split_gbs", "cost_bw_gather_gbs"   GB/s of the cost model
+ *   "cost_row_slab_ns"   its time per row of the slab form beyond the bytes (default 60)
  *   "union_dispatch" 1 (default): vp_project_union may skip the gather of U's columns and run
  *                   the full projection with the batch's boolean list as every row's mask
  *                   when the cost model says that is cheaper (large unions); same results

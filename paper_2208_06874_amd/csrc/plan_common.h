@@ -65,20 +65,23 @@ __device__ inline void vp_plan_single_bucket(int N, int ncand, int vtiles, int r
     }
 }
 
-// Cost model of the planner: the occupied slabs are streamed once from HBM and further row
-// groups of a bucket re-read them through the L2; the masked full projection streams W once
-// and pays for every further row group.  The top-k lists cost the full projection more than
-// the slabs (every lane of every wavefront is busy there): a margin that grows with k keeps
-// the choice on the safe side (64-row items: top-8 measured 10 % over top-1).  64-row items:
-// one pass from HBM, each further row group at the measured rate of the GEMM-shaped kernel.  16-row items: every row group re-reads W
-// through the L2.  Tile counts are in candidate groups; the constants are groups per second.
+// Cost model of the planner.  Slabs: the occupied slabs are streamed once from HBM, further row
+// groups of a bucket re-read them through the L2, and every row costs a little beyond its bytes
+// (staging, top-k lists, partial results: what a batch of many rows against short lists is made
+// of).  Masked full projection with 64-row items: one pass over W from HBM, or the matrix cores'
+// time for all row groups, whichever is longer (W is then served by the L2; the rate of the
+// matrix cores is expressed in bytes of W per second).  With 16-row items every row group
+// re-reads W through the L2.  The top-k lists cost the full projection more than the slabs
+// (every lane of every wavefront is busy there): a margin that grows with k keeps the choice on
+// the safe side (64-row items: top-8 measured 10 % over top-1).  Tile counts are in candidate
+// groups; the rates are groups per second.
 __device__ inline bool vp_full_is_cheaper(int occ_tiles, int total_tiles, int N, int rpi_full, int vtiles, int k,
                                           const VpCostModel &cost)
 {
     const int rgs_full = ceil_div(N, rpi_full);
-    const float t_slab = occ_tiles / cost.bw_slab + (total_tiles - occ_tiles) / cost.bw_l2;
+    const float t_slab = occ_tiles / cost.bw_slab + (total_tiles - occ_tiles) / cost.bw_l2 + N * cost.t_row_slab;
     const float t_full = rpi_full == 64
-        ? (vtiles / cost.bw_full + (rgs_full - 1) * (vtiles / cost.bw_gemm)) * (1.f + k * 0.0125f)
+        ? fmaxf(vtiles / cost.bw_full, rgs_full * (vtiles / cost.bw_gemm)) * (1.f + k * 0.0125f)
         : fmaxf(vtiles / cost.bw_full, (float)rgs_full * vtiles / cost.bw_l2) * (1.f + k * 0.125f);
     return t_full < t_slab;
 }

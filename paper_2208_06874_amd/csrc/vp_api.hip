@@ -354,6 +354,7 @@ vp_status run_clustered(const char *fn, const vp_index *I, const void *hidden, i
     cost.bw_slab /= tile_bytes;
     cost.bw_full /= tile_bytes;
     cost.bw_l2 /= tile_bytes;
+    if (rt_masked == 4 && !use_gemm_lds(I, rt_masked, k)) cost.bw_gemm = cost.bw_gemm_split;
     cost.bw_gemm /= tile_bytes;
     const long row_groups = (long)row_tiles + std::min(N, I->K);
     const long by_tiles = row_groups * ceil_div(I->L.max_tiles, VP_WG_WAVES);
@@ -613,14 +614,17 @@ vp_status vp_build(const vp_build_desc *D, void *hip_stream, vp_index **out)
     // active set.
     I->dispatch = 1;
     // measured on MI355X at d = 1024, V = 250,000: bytes per second of the regimes of the cost model.
-    // Slabs stream at 6.8 TB/s.  The masked full projection with 64-row items takes about 100 us for
-    // its first row group (one pass over W from HBM: 5.1 TB/s) and 25 us for every further one
-    // (W from the L2, matrix cores busy: 20 TB/s of W); with 16-row items every row group re-reads
-    // W through the L2 at 17 TB/s.
+    // Slabs stream at 6.8 TB/s, and a row costs about 60 ns beyond its bytes (512 rows against 32
+    // short lists: 72 us for 10 us of bytes).  The masked full projection with 64-row items takes
+    // about 100 us for one pass over W from HBM (5.1 TB/s) or, with more row groups, 35 us per row
+    // group on the matrix cores (14 TB/s of W; the split-k kernel at d = 1536: 98 us per row group
+    // over 0.77 GB, 8 TB/s); with 16-row items every row group re-reads W through the L2 at 17 TB/s.
     I->cost.bw_slab = 6.8e12f;
     I->cost.bw_full = 5.1e12f;
     I->cost.bw_l2 = 17.0e12f;
-    I->cost.bw_gemm = 20.0e12f;
+    I->cost.bw_gemm = 14.0e12f;
+    I->cost.bw_gemm_split = 8.0e12f;
+    I->cost.t_row_slab = 60.0e-9f;
     // batch-union form: the gather of U's columns from the token-major copy into the union slab
     // (fitted to the measured crossover at |U| = 28 % of V for 64 rows) and the kernels only the
     // gathered form needs
@@ -700,7 +704,9 @@ vp_status vp_set_option(vp_index *I, const char *name, int64_t value)
         {"cost_bw_full_gbs", nullptr, &VpCostModel::bw_full, 1, 1000000},
         {"cost_bw_l2_gbs", nullptr, &VpCostModel::bw_l2, 1, 1000000},
         {"cost_bw_gemm_gbs", nullptr, &VpCostModel::bw_gemm, 1, 1000000},
+        {"cost_bw_gemm_split_gbs", nullptr, &VpCostModel::bw_gemm_split, 1, 1000000},
         {"cost_bw_gather_gbs", nullptr, &VpCostModel::bw_gather, 1, 1000000},
+        {"cost_row_slab_ns", nullptr, &VpCostModel::t_row_slab, 0, 100000},
     };
     if (!std::strcmp(name, "profile")) {
         if (value != 0 && value != 1) return fail(VP_ERR_INVALID_ARG, "vp_set_option: profile must be 0 or 1");
@@ -716,6 +722,7 @@ vp_status vp_set_option(vp_index *I, const char *name, int64_t value)
         if (o.field == &vp_index::small_pf && value != 0 && value != 8 && value != 16 && value != 32)
             return fail(VP_ERR_INVALID_ARG, "vp_set_option: small_pf must be 0, 8, 16 or 32");
         if (o.field) I->*o.field = (int)value;
+        else if (o.rate == &VpCostModel::t_row_slab) I->cost.t_row_slab = (float)value * 1e-9f;
         else I->cost.*o.rate = (float)value * 1e9f;
         return VP_OK;
     }
@@ -912,6 +919,7 @@ vp_status vp_project_union(const vp_index *I, const void *hidden, int32_t N, int
     const float tile_bytes = (float)I->L.kt * VP_TILE_BYTES;
     cost.bw_full /= tile_bytes;
     cost.bw_l2 /= tile_bytes;
+    if (row_tiles_u == 4 && !use_gemm_lds(I, row_tiles_u, k)) cost.bw_gemm = cost.bw_gemm_split;
     cost.bw_gemm /= tile_bytes;
     cost.bw_gather /= tile_bytes;
     vpk_union_compact(mask, U.mask_words, bsum, N, VP_ROWS_PER_ITEM * row_tiles_u, sb_target(I, row_tiles_u, k), sb_min(I, row_tiles_u, k), max_items, uids, uh,

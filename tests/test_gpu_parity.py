@@ -964,3 +964,178 @@ def test_item_order_of_plans_with_heavy_buckets(oracle, tiny, mid):
             hdr = ws[:64].view(torch.int32)[:8].tolist()
             assert hdr[4] == -32 and hdr[7] == 0, hdr          # the swizzle of clustered plans is on
             pu.check_projection(oracle, B.W, B.b, B.C, B.cand_off, B.cand_ids, H, k, ids, logp, g)
+
+
+# ------------------------------------------------- the largest shapes, every form, and repeatability
+def _points_check(oracle, B, H, k, ids, logp):
+    """Every returned (row, token) against the oracle's own logit of that pair (Eq. 1): each row's logits
+    descend, equal logits keep ascending token ids, and log-prob differences within a row equal logit
+    differences (the log-sum-exp cancels).  Works at any size: one inner product per returned entry."""
+    N = H.shape[0]
+    rows = np.repeat(np.arange(N, dtype=np.int32), k)
+    toks = ids.reshape(-1).astype(np.int32)
+    assert np.all((toks >= 0) & (toks < B.W.shape[1]))
+    z = oracle.logit_points(B.W, B.b, H, rows, toks).reshape(N, k)
+    assert np.all(z[:, :-1] >= z[:, 1:] - pu.TAU), "logits of a row's entries do not descend"
+    tie = z[:, :-1] == z[:, 1:]
+    assert np.all(ids[:, :-1][tie] < ids[:, 1:][tie])
+    for r in range(N):
+        assert len(set(ids[r].tolist())) == k
+    d_logp = logp[:, :1].astype(np.float64) - logp.astype(np.float64)
+    d_z = z[:, :1] - z
+    err = np.abs(d_logp - d_z).max()
+    assert err <= pu.SANITY, "log-prob differences off by %g" % err
+    return float(err)
+
+
+def test_full_projection_at_the_largest_shapes(oracle, large, skewed):
+    """vp_project_full at the sweep's 1,024 rows and at the skewed workload's 4,096 rows of d = 1,536: every
+    returned entry against the oracle's logit of that (row, token), and whole rows (log-softmax over V, top-k)
+    for a sample the oracle can afford."""
+    cases = ((large, wl.CONFIGS["sweep"], 1024, 1), (large, wl.CONFIGS["sweep"], 1024, 8),
+             (skewed, skewed.cfg, skewed.cfg.N, skewed.cfg.k))
+    for B, cfg, N, k in cases:
+        H, q = wl.make_rows(cfg, B.C, N=N, stream=33)
+        ids, logp = B.project_full(H, k)
+        assert _overflow(B.index, N) == 0
+        err = _points_check(oracle, B, H, k, ids, logp)
+        sample = np.array([0, 1, N // 3, N // 2, N - 65, N - 64, N - 2, N - 1])
+        st = pu.check_full(oracle, B.W, B.b, H[sample], k, ids[sample], logp[sample])
+        print("full projection", cfg.name, N, k, "points err", err, st, flush=True)
+        ids2, logp2 = B.project_full(H, k)
+        assert np.array_equal(ids, ids2) and np.array_equal(logp, logp2), "two runs differ"
+
+
+def _masked(B, H, k, force=True):
+    """vp_project with the planner switched on; force: the slabs made to look hopeless, so that the masked
+    full projection is taken whatever the batch."""
+    B.index.set_option("dispatch", 1)
+    if force:
+        B.index.set_option("cost_bw_slab_gbs", 1)
+    try:
+        out = B.project(H, k)
+        return out, _planner_mode(B.index, H.shape[0]), _overflow(B.index, H.shape[0])
+    finally:
+        B.index.set_option("cost_bw_slab_gbs", 6800)
+        B.index.set_option("dispatch", 0)
+
+
+def test_every_form_on_the_large_and_skewed_indexes(oracle, large, skewed):
+    """The masked full projection and the batch-union form at the sizes the benchmark runs them: N = 256 on the
+    large index (items of 64 rows, rows in LDS) and N = 4,096 at d = 1,536 (the split-k kernel).  Same token ids
+    as the per-cluster slabs, log-probs within 1e-4 of them, sampled rows against the oracle; the union of 226
+    active sets with random top-up ids is the whole vocabulary, so that form must equal the full projection."""
+    for B, cfg in ((large, large.cfg), (skewed, skewed.cfg)):
+        N, k = cfg.N, cfg.k
+        H, q = wl.make_rows(cfg, B.C, N=N, stream=44)
+        base = B.project(H, k)
+        assert _overflow(B.index, N) == 0
+        (m_ids, m_logp, m_g), mode, ovf = _masked(B, H, k)
+        assert mode == 1 and ovf == 0
+        assert np.array_equal(m_g, base[2]) and np.array_equal(m_ids, base[0])
+        assert np.allclose(m_logp, base[1], rtol=0, atol=1e-4)
+        sample = np.array([0, 5, N // 2, N - 1, int(np.argmax(np.bincount(q)[q]))])   # incl. a row of the fullest bucket
+        st = pu.check_projection(oracle, B.W, B.b, B.C, B.cand_off, B.cand_ids, H[sample], k, m_ids[sample],
+                                 m_logp[sample], m_g[sample])
+        print("masked", cfg.name, st, flush=True)
+        # the planner left to itself: whichever form it takes, the same results
+        (d_ids, d_logp, d_g), mode, ovf = _masked(B, H, k, force=False)
+        assert ovf == 0 and np.array_equal(d_ids, base[0]) and np.allclose(d_logp, base[1], rtol=0, atol=1e-4)
+        print("planner chose", cfg.name, mode, flush=True)
+        # twice the same call: the same bits, in every form
+        for fn in (lambda: B.project(H, k), lambda: _masked(B, H, k)[0], lambda: B.project_union(H, k)[:2]):
+            a, b2 = fn(), fn()
+            assert np.array_equal(a[0], b2[0]) and np.array_equal(a[1], b2[1]), "two runs differ"
+        u_ids, u_logp, u_g, nu = B.project_union(H, k)
+        lists = [B.cand_ids[B.cand_off[j]:B.cand_off[j + 1]] for j in np.unique(u_g)]
+        U = np.unique(np.concatenate(lists))
+        assert nu == U.size and np.array_equal(u_g, base[2])
+        if U.size == B.W.shape[1]:
+            f_ids, f_logp = B.project_full(H, k)
+            assert np.array_equal(u_ids, f_ids) and np.allclose(u_logp, f_logp, rtol=0, atol=1e-4)
+        else:
+            _points_check(oracle, B, H, k, u_ids, u_logp)
+            assert np.all(np.isin(u_ids, U))
+
+
+def test_debug_logits_on_skewed_rows(oracle, skewed):
+    """Candidate logits at d = 1,536, element by element, for rows of the fullest and of ordinary buckets."""
+    cfg = skewed.cfg
+    H, q = wl.make_rows(cfg, skewed.C)
+    heavy = int(np.argmax(np.bincount(q, minlength=cfg.K)))
+    pick = np.concatenate([np.nonzero(q == heavy)[0][:20], np.nonzero(q != heavy)[0][:12]])
+    print("skewed logits", _full_check(oracle, skewed, H[pick], cfg.k, with_logits=True))
+
+
+def test_library_defaults_on_all_five_workloads(oracle, tiny, mid, large, skewed):
+    """The call as shipped (the planner free to choose the form) on every configured workload: all rows against
+    the oracle where it can afford them, a sample elsewhere, plus the returned entries' own logits for all rows."""
+    sweep = wl.CONFIGS["sweep"]
+    for B, cfg, N, k in ((tiny, tiny.cfg, None, None), (mid, mid.cfg, None, None), (large, large.cfg, None, None),
+                         (large, sweep, 64, 1), (large, sweep, 1024, 1), (skewed, skewed.cfg, None, None)):
+        N, k = N or cfg.N, k or cfg.k
+        H, q = wl.make_rows(cfg, B.C, N=N, stream=55)
+        (ids, logp, g), mode, ovf = _masked(B, H, k, force=False)
+        assert ovf == 0
+        sample = np.arange(N) if N <= 64 else np.unique(np.linspace(0, N - 1, 12).astype(int))
+        st = pu.check_projection(oracle, B.W, B.b, B.C, B.cand_off, B.cand_ids, H[sample], k, ids[sample],
+                                 logp[sample], g[sample])
+        g_or, excused = pu.check_clusters(oracle, H, B.C, g)
+        err = _points_check(oracle, B, H, k, ids, logp) if min(B.cand_off[1:] - B.cand_off[:-1]) >= k else None
+        print("defaults", cfg.name, N, k, "mode", mode, st, "excused clusters", excused, "points", err, flush=True)
+
+
+def _time_calls(B, Ht, k, steps=20):
+    import time
+    import torch
+    ws = B.index.workspace(Ht.shape[0])
+    best = float("inf")
+    for rep in range(3):
+        for i in range(3):
+            B.index.project(Ht, k, workspace=ws)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            B.index.project(Ht, k, workspace=ws)
+        torch.cuda.synchronize()
+        best = min(best, (time.perf_counter() - t0) / steps)
+    return best
+
+
+def test_planner_picks_the_faster_form(tiny, mid, large, skewed):
+    """The cost model against the clock, over k-extents 512 / 1,024 / 1,536, batch sizes and occupancies (rows
+    spread over the clusters, or crowded into a few): the planner's own choice must run within 10 % (plus a few
+    microseconds of timer noise) of the faster of the two forms, each forced through the same planner."""
+    r = np.random.default_rng(91)
+    report = []
+    for B, sizes in ((tiny, (16, 64, 512)), (mid, (24, 64, 200)), (large, (20, 32, 256)), (skewed, (64, 1024, 4096))):
+        K = B.C.shape[0]
+        for N in sizes:
+            for spread in ("all clusters", "four clusters"):
+                clusters = None if spread == "all clusters" else r.integers(0, K, 4)[r.integers(0, 4, N)]
+                Ht = B.rows(_rows(r, B.C, N, clusters=clusters))
+                k = B.cfg.k
+                t = {}
+                B.index.set_option("dispatch", 1)
+                try:
+                    t["planner"] = _time_calls(B, Ht, k)
+                    mode = _planner_mode(B.index, N)
+                    B.index.set_option("cost_bw_slab_gbs", 1)          # slabs look hopeless: masked full projection
+                    t["masked"] = _time_calls(B, Ht, k)
+                    assert _planner_mode(B.index, N) == 1 or N <= 16
+                    B.index.set_option("cost_bw_slab_gbs", 6800)
+                    full = (5100, 17000, 14000, 8000)
+                    for name in ("cost_bw_full_gbs", "cost_bw_l2_gbs", "cost_bw_gemm_gbs", "cost_bw_gemm_split_gbs"):
+                        B.index.set_option(name, 1)                    # the full projection looks hopeless: slabs
+                    t["slabs"] = _time_calls(B, Ht, k)
+                    assert _planner_mode(B.index, N) == 0
+                finally:
+                    for name, v in zip(("cost_bw_full_gbs", "cost_bw_l2_gbs", "cost_bw_gemm_gbs", "cost_bw_gemm_split_gbs"),
+                                       (5100, 17000, 14000, 8000)):
+                        B.index.set_option(name, v)
+                    B.index.set_option("cost_bw_slab_gbs", 6800)
+                    B.index.set_option("dispatch", 0)
+                best = min(t["masked"], t["slabs"])
+                report.append((B.cfg.name, N, spread, mode, t))
+                print("planner", B.cfg.name, N, spread, "chose", mode, {n: round(v * 1e6, 1) for n, v in t.items()}, flush=True)
+                assert t["planner"] <= 1.10 * best + 4e-6, (B.cfg.name, N, spread, mode, t)
