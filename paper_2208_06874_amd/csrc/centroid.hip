@@ -100,8 +100,8 @@ __global__ __launch_bounds__(256) void centroid_kernel(
     }
 }
 
-// The same for batches of at most 16 rows, where the time is one memory latency after the
-// other rather than bytes: one workgroup per tile of 16 centroids, the k-extent split over its
+// The same for small and medium batches, where the time is one memory latency after the
+// other rather than bytes: one workgroup per (tile of 16 centroids, tile of 16 rows), the k-extent split over its
 // four wavefronts, so that every wavefront has all of its loads in flight at once (a quarter of
 // the tile's k-tiles, and the matching pieces of the rows); the four partial products meet in
 // LDS and are added in a fixed order.  cpart then holds one minimum per tile: parts = ctiles.
@@ -115,9 +115,10 @@ __global__ __launch_bounds__(256) void centroid_small_kernel(
     const int q = lane >> 4;
     const int t = blockIdx.x;
     const int parts = gridDim.x;
-    const bool valid_row = n < N;
+    const int row = blockIdx.y * 16 + n;
+    const bool valid_row = row < N;
     const int pieces_per_row = d >> 3;
-    const uint4 *hrow = hidden + (size_t)(valid_row ? n : 0) * pieces_per_row;
+    const uint4 *hrow = hidden + (size_t)(valid_row ? row : 0) * pieces_per_row;
     const int kq = kt_count >> 2;            // k-tiles per wavefront (k-tile counts are multiples of 8)
     const int k0 = wave * kq;
     const uint4 *ap = cp + ((size_t)t * kt_count + k0) * 64 + lane;
@@ -164,16 +165,16 @@ __global__ __launch_bounds__(256) void centroid_small_kernel(
         best_s = take ? s2 : best_s;
         best_j = take ? j2 : best_j;
     }
-    if (q == 0 && valid_row) cpart[(size_t)n * parts + t] = make_int2(__float_as_int(best_s), best_j);
+    if (q == 0 && valid_row) cpart[(size_t)row * parts + t] = make_int2(__float_as_int(best_s), best_j);
 }
 
 }  // namespace
 
-// Batches of at most 16 rows: one workgroup per centroid tile, parts = ctiles (see above).
+// One workgroup per (centroid tile, row tile), parts = ctiles (see above).
 void vpk_centroid_small(const void *hidden, int N, int d, const void *cp, const float *cnorm, int K, int kt,
                         int ctiles, void *cpart, hipStream_t st)
 {
-    hipLaunchKernelGGL(centroid_small_kernel, dim3(ctiles), dim3(256), 0, st, (const uint4 *)hidden, N, d,
+    hipLaunchKernelGGL(centroid_small_kernel, dim3(ctiles, (N + 15) / 16), dim3(256), 0, st, (const uint4 *)hidden, N, d,
                        (const uint4 *)cp, cnorm, K, kt, (int2 *)cpart);
 }
 

@@ -90,8 +90,6 @@ __device__ inline void block_sum3(int a, int b, int c, int *ta, int *tb, int *tc
     *tc = __builtin_amdgcn_readlane(wave_inclusive_sum(lane < nw ? wsum3[32 + lane] : 0), nw - 1);
 }
 
-constexpr int RPT = 4;   // rows per thread whose cluster id stays in registers between phases
-
 __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(
     const int2 *__restrict__ cpart, int parts, int N, int K, const int32_t *__restrict__ n_cand,
     const int32_t *__restrict__ tile_off, int target_items, int min_items, int max_items, int32_t *__restrict__ g,
@@ -119,34 +117,12 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(
     __syncthreads();
 
     // finish Eq. 2: minimum over the centroid parts, ties to the lowest index
-    int myj[RPT];
-#pragma unroll
-    for (int u = 0; u < RPT; ++u) myj[u] = 0;
-    for (int r = tid, u = 0; r < N; r += PLAN_THREADS, ++u) {
-        float bs = __builtin_inff();
-        int bj = VP_IDX_NONE;
-        const int2 *cp = cpart + (size_t)r * parts;
-        for (int p0 = 0; p0 < parts; p0 += 8) {
-            int2 e[8];
-#pragma unroll
-            for (int v = 0; v < 8; ++v) e[v] = p0 + v < parts ? cp[p0 + v] : make_int2(0x7f800000, VP_IDX_NONE);
-#pragma unroll
-            for (int v = 0; v < 8; ++v) {
-                const float s = __int_as_float(e[v].x);
-                if (s < bs || (s == bs && e[v].y < bj)) {
-                    bs = s;
-                    bj = e[v].y;
-                }
-            }
-        }
-        if (bj < 0 || bj >= K) bj = 0;   // non-finite scores: keep every index in range
-        g[r] = bj;
-        if (out_cluster) out_cluster[r] = bj;
-        atomicAdd(&cnt[bj], 1);
-#pragma unroll
-        for (int v = 0; v < RPT; ++v)
-            if (v == u) myj[v] = bj;
-    }
+    vp_finish_eq2(cpart, parts, N, K, tid, PLAN_THREADS, [&](int r, int j) {
+        g[r] = j;
+        if (out_cluster) out_cluster[r] = j;
+        atomicAdd(&cnt[j], 1);
+    });
+    __threadfence_block();   // the scatter below reads g[] written by other threads of this workgroup
     __syncthreads();
 
     // exclusive scan of the histogram -> bucket offsets; total candidate tiles of all row groups
@@ -203,15 +179,8 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(
     // merge kernel where the partial results of each row will be
     for (int j = tid; j < K; j += PLAN_THREADS) cnt[j] = 0;
     __syncthreads();
-    for (int r = tid, u = 0; r < N; r += PLAN_THREADS, ++u) {
-        int j = 0;
-        if (u < RPT) {
-#pragma unroll
-            for (int v = 0; v < RPT; ++v)
-                if (v == u) j = myj[v];
-        } else {
-            j = g[r];
-        }
+    for (int r = tid; r < N; r += PLAN_THREADS) {
+        const int j = g[r];
         const int local = atomicAdd(&cnt[j], 1);
         const int p = off[j] + local;
         perm[p] = r;

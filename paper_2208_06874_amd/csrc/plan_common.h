@@ -5,6 +5,49 @@
 
 __device__ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
+// Finishes Eq. 2 for rows 0 .. N-1: the minimum over a row's `parts` per-part minima (score bits,
+// centroid index), ties to the lowest index.  Called by all `nthreads` threads of a workgroup (a
+// multiple of 64).  With few rows several lanes share a row (a power of two, at most a wavefront,
+// each taking every T-th part) so that the loads of a row are in flight together instead of one
+// batch after the other; emit(r, j) is called once per row, by the first of its lanes.
+template <typename Emit>
+__device__ inline void vp_finish_eq2(const int2 *__restrict__ cpart, int parts, int N, int K, int tid, int nthreads,
+                                     Emit emit)
+{
+    int T = 1;
+    while (T < 64 && 2 * T * N <= nthreads && 2 * T <= parts) T *= 2;
+    const int rows_per_pass = nthreads / T;
+    const int sub = tid & (T - 1);
+    for (int r0 = 0; r0 < N; r0 += rows_per_pass) {
+        const int r = r0 + tid / T;
+        float bs = __builtin_inff();
+        int bj = VP_IDX_NONE;
+        if (r < N) {
+            const int2 *cp = cpart + (size_t)r * parts;
+            for (int p0 = sub; p0 < parts; p0 += 8 * T) {
+                int2 e[8];
+#pragma unroll
+                for (int v = 0; v < 8; ++v) e[v] = p0 + v * T < parts ? cp[p0 + v * T] : make_int2(0x7f800000, VP_IDX_NONE);
+#pragma unroll
+                for (int v = 0; v < 8; ++v) {
+                    const float s = __int_as_float(e[v].x);
+                    const bool take = (s < bs) | ((s == bs) & (e[v].y < bj));
+                    bs = take ? s : bs;
+                    bj = take ? e[v].y : bj;
+                }
+            }
+        }
+        for (int off = 1; off < T; off <<= 1) {   // (T is the same in every lane)
+            const float s2 = __shfl_xor(bs, off);
+            const int j2 = __shfl_xor(bj, off);
+            const bool take = (s2 < bs) | ((s2 == bs) & (j2 < bj));
+            bs = take ? s2 : bs;
+            bj = take ? j2 : bj;
+        }
+        if (r < N && sub == 0) emit(r, (bj < 0 || bj >= K) ? 0 : bj);   // non-finite scores: keep every index in range
+    }
+}
+
 // Plan for one bucket that holds all N rows in their own order against one slab
 // of ncand candidates in vtiles tiles (the full vocabulary, or the union of the
 // batch's active sets), rpi (16, 32 or 64) rows per item.  Called by every thread gtid of

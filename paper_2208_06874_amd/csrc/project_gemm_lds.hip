@@ -47,7 +47,7 @@ constexpr int VP_MAX_TOPK_LANES = 32;   // the epilogue writes a row's list with
 // (logit descending, position ascending), without branches
 __device__ inline bool before_entry(float v, int i, float v2, int i2) { return (v > v2) | ((v == v2) & (i < i2)); }
 
-template <int KT, bool MASKED, bool NT, bool TOP1>
+template <int KT, bool MASKED, bool NT, bool TOP1, bool GATHER>
 __device__ inline void gemm_lds_item(const VpSlabSet &set, const uint4 *__restrict__ hidden, int d,
                                      const int32_t *__restrict__ perm, const VpItem &item, int it, int k,
                                      float *__restrict__ partials, unsigned int *__restrict__ floors,
@@ -71,14 +71,29 @@ __device__ inline void gemm_lds_item(const VpSlabSet &set, const uint4 *__restri
     const int gb = item.tile0;
     const int ge = item.tile0 + item.ntiles;
     const int nsteps = (item.ntiles + L_G - 1) / L_G;
-    const uint4 *slab = reinterpret_cast<const uint4 *>(set.tiles) + (size_t)item.tile_off * KT * 64 + lane;
+    // Where the slab operands come from.  Packed slab: group after group of KT tiles of 1 KiB, lane l
+    // at piece l of a tile.  GATHER (the batch-union form without a gathered copy, as the paper's
+    // gathered GEMM reads its columns): the candidate's row of the token-major copy of W, whose
+    // k-tile kt holds this lane's 16 bytes at piece kt * 4 + q; the candidates' token ids are U.
+    constexpr int KSTEP = GATHER ? 4 : 64;   // pieces from one k-tile to the next
+    const uint4 *slab = GATHER ? reinterpret_cast<const uint4 *>(set.tiles)
+                               : reinterpret_cast<const uint4 *>(set.tiles) + (size_t)item.tile_off * KT * 64 + lane;
     const float *bias = set.bias + (size_t)item.tile_off * VP_TILE_ITEMS + q * 4;
+    const int32_t *tokens = GATHER ? set.ids + (size_t)item.tile_off * VP_TILE_ITEMS + n : nullptr;
 
     // offsets (in 16-byte pieces) of the four groups of a step; groups past the item's end repeat
     // its last group (loaded, never looked at)
     auto group_off = [&](int step, unsigned int (&off)[L_G]) {
 #pragma unroll
-        for (int j = 0; j < L_G; ++j) off[j] = (unsigned int)min(gb + step * L_G + j, ge - 1) * (KT * 64);
+        for (int j = 0; j < L_G; ++j) {
+            const int g = min(gb + step * L_G + j, ge - 1);
+            if (GATHER) {
+                const int tok = tokens[(size_t)g * VP_TILE_ITEMS];   // -1 in the padding of U's last group
+                off[j] = (unsigned int)max(tok, 0) * (KT * 4) + q;
+            } else {
+                off[j] = (unsigned int)g * (KT * 64);
+            }
+        }
     };
 
     uint4 ring[L_PF][L_G];
@@ -90,7 +105,7 @@ __device__ inline void gemm_lds_item(const VpSlabSet &set, const uint4 *__restri
 #pragma unroll
         for (int p = 0; p < L_PF; ++p)
 #pragma unroll
-            for (int j = 0; j < L_G; ++j) ring[p][j] = load_piece<NT>(slab + cur[j] + p * 64);
+            for (int j = 0; j < L_G; ++j) ring[p][j] = load_piece<NT>(slab + cur[j] + p * KSTEP);
     }
 
     // the rows of this item -> LDS, MFMA operand order (row slots beyond nrows: zeros)
@@ -177,7 +192,7 @@ __device__ inline void gemm_lds_item(const VpSlabSet &set, const uint4 *__restri
             const bool last = b == KT / L_PF - 1;
             unsigned int src[L_G];
 #pragma unroll
-            for (int j = 0; j < L_G; ++j) src[j] = last ? nxt[j] : cur[j] + (b + 1) * (L_PF * 64);
+            for (int j = 0; j < L_G; ++j) src[j] = last ? nxt[j] : cur[j] + (b + 1) * (L_PF * KSTEP);
 #pragma unroll
             for (int u = 0; u < L_PF; ++u) {
                 // The rows' operands of the next k-tile are read while this one's MFMAs run (after a
@@ -202,7 +217,7 @@ __device__ inline void gemm_lds_item(const VpSlabSet &set, const uint4 *__restri
                         acc[rt][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a.h, bf[rt].h, acc[rt][j], 0, 0, 0);
                     }
 #pragma unroll
-                for (int j = 0; j < L_G; ++j) ring[u][j] = load_piece<NT>(slab + src[j] + u * 64);
+                for (int j = 0; j < L_G; ++j) ring[u][j] = load_piece<NT>(slab + src[j] + u * KSTEP);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -394,7 +409,7 @@ __device__ inline void gemm_lds_item(const VpSlabSet &set, const uint4 *__restri
     }
 }
 
-template <int KT, bool MASKED, bool TOP1>
+template <int KT, bool MASKED, bool TOP1, bool GATHER>
 __global__ __launch_bounds__(L_NW * 64) void project_gemm_lds_kernel(
     VpSlabSet set, const uint4 *__restrict__ hidden, int d, const int32_t *__restrict__ perm,
     const VpItem *__restrict__ items, const VpPlanHeader *__restrict__ hdr, int k,
@@ -405,23 +420,23 @@ __global__ __launch_bounds__(L_NW * 64) void project_gemm_lds_kernel(
     const int it = item_of_workgroup(hdr);
     if (it < 0 || it >= total_items) return;
     const VpItem item = items[it];
-    if (item.shared)
-        gemm_lds_item<KT, MASKED, false, TOP1>(set, hidden, d, perm, item, it, TOP1 ? 1 : k, partials, floors, mask);
+    if (item.shared || GATHER)
+        gemm_lds_item<KT, MASKED, false, TOP1, GATHER>(set, hidden, d, perm, item, it, TOP1 ? 1 : k, partials, floors, mask);
     else
-        gemm_lds_item<KT, MASKED, true, TOP1>(set, hidden, d, perm, item, it, TOP1 ? 1 : k, partials, floors, mask);
+        gemm_lds_item<KT, MASKED, true, TOP1, false>(set, hidden, d, perm, item, it, TOP1 ? 1 : k, partials, floors, mask);
 }
 
-template <int KT, bool MASKED>
+template <int KT, bool MASKED, bool GATHER>
 void launch_lds(const VpSlabSet &set, const void *hidden, int d, const int32_t *perm, const VpItem *items,
                 const VpPlanHeader *hdr, int grid_items, int k, float *partials, unsigned int *floors,
                 const VpMaskInfo &mask, hipStream_t st)
 {
     if (k == 1)
-        hipLaunchKernelGGL((project_gemm_lds_kernel<KT, MASKED, true>), dim3(grid_items), dim3(L_NW * 64),
+        hipLaunchKernelGGL((project_gemm_lds_kernel<KT, MASKED, true, GATHER>), dim3(grid_items), dim3(L_NW * 64),
                            vpk_project_rows_lds_bytes(k, KT), st, set, (const uint4 *)hidden, d, perm, items, hdr, k,
                            partials, floors, mask);
     else
-        hipLaunchKernelGGL((project_gemm_lds_kernel<KT, MASKED, false>), dim3(grid_items), dim3(L_NW * 64),
+        hipLaunchKernelGGL((project_gemm_lds_kernel<KT, MASKED, false, GATHER>), dim3(grid_items), dim3(L_NW * 64),
                            vpk_project_rows_lds_bytes(k, KT), st, set, (const uint4 *)hidden, d, perm, items, hdr, k,
                            partials, floors, mask);
 }
@@ -429,10 +444,12 @@ void launch_lds(const VpSlabSet &set, const void *hidden, int d, const int32_t *
 template <int KT>
 hipError_t allow_lds_bytes()
 {
-    const void *fns[] = {reinterpret_cast<const void *>(project_gemm_lds_kernel<KT, false, false>),
-                         reinterpret_cast<const void *>(project_gemm_lds_kernel<KT, false, true>),
-                         reinterpret_cast<const void *>(project_gemm_lds_kernel<KT, true, false>),
-                         reinterpret_cast<const void *>(project_gemm_lds_kernel<KT, true, true>)};
+    const void *fns[] = {reinterpret_cast<const void *>(project_gemm_lds_kernel<KT, false, false, false>),
+                         reinterpret_cast<const void *>(project_gemm_lds_kernel<KT, false, true, false>),
+                         reinterpret_cast<const void *>(project_gemm_lds_kernel<KT, true, false, false>),
+                         reinterpret_cast<const void *>(project_gemm_lds_kernel<KT, true, true, false>),
+                         reinterpret_cast<const void *>(project_gemm_lds_kernel<KT, false, false, true>),
+                         reinterpret_cast<const void *>(project_gemm_lds_kernel<KT, false, true, true>)};
     for (const void *f : fns) {
         const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
@@ -458,15 +475,19 @@ hipError_t vpk_project_rows_lds_prepare()
     return e;
 }
 
+// mask: nullptr, or the membership lists of the masked full projection.  gather: the set's tiles
+// are the token-major copy of W and its ids the batch's union U (no mask then); the slab operands
+// are read through U instead of from a packed copy.
 void vpk_project_rows_lds(const VpSlabSet &set, const void *hidden, int d, const int32_t *perm, const VpItem *items,
                           const VpPlanHeader *hdr, int grid_items, int k, float *partials, unsigned int *floors,
-                          const VpMaskInfo *mask, hipStream_t st)
+                          const VpMaskInfo *mask, bool gather, hipStream_t st)
 {
     const VpMaskInfo none = {nullptr, nullptr, 0};
-#define VP_LDS_CASE(KT)                                                                                          \
-    case KT:                                                                                                     \
-        if (mask) launch_lds<KT, true>(set, hidden, d, perm, items, hdr, grid_items, k, partials, floors, *mask, st); \
-        else launch_lds<KT, false>(set, hidden, d, perm, items, hdr, grid_items, k, partials, floors, none, st);  \
+#define VP_LDS_CASE(KT)                                                                                                   \
+    case KT:                                                                                                              \
+        if (mask) launch_lds<KT, true, false>(set, hidden, d, perm, items, hdr, grid_items, k, partials, floors, *mask, st); \
+        else if (gather) launch_lds<KT, false, true>(set, hidden, d, perm, items, hdr, grid_items, k, partials, floors, none, st); \
+        else launch_lds<KT, false, false>(set, hidden, d, perm, items, hdr, grid_items, k, partials, floors, none, st);     \
         break;
     switch (set.kt) {
         VP_LDS_CASE(8)

@@ -313,12 +313,31 @@ void launch_single_bucket(const VpSlabSet &set, const vp_index *I, const void *h
                           hipStream_t st)
 {
     if (use_gemm_lds(I, row_tiles, k))
-        vpk_project_rows_lds(set, hidden, I->d, perm, items, hdr, grid_items, k, partials, floors, nullptr, st);
+        vpk_project_rows_lds(set, hidden, I->d, perm, items, hdr, grid_items, k, partials, floors, nullptr, false, st);
     else if (row_tiles == 4)
         vpk_project_gemm(set, hidden, I->d, perm, items, hdr, grid_items, k, partials, floors + N, nullptr, st);
     else
         vpk_project(set, hidden, I->d, perm, items, hdr, grid_items, row_tiles, k, rstar, partials, floors, dbg_logits,
                     dbg_row_off, 0, st);
+}
+
+// Eq. 2 for a decode batch: up to VP_KSPLIT_ROWS rows with one workgroup per (centroid tile, row
+// tile) and the k-extent split over its wavefronts (every load in flight at once: 3-4 us instead
+// of 7-9 at 64-256 rows), beyond that the kernel whose workgroups walk several centroid tiles.
+// Returns the number of per-row minima left in cpart.
+constexpr int VP_KSPLIT_ROWS = 256;
+int launch_eq2(const vp_index *I, const void *hidden, int N, void *cpart, hipStream_t st)
+{
+    if (N <= VP_KSPLIT_ROWS) {
+        vpk_centroid_small(hidden, N, I->d, I->cp, I->cnorm, I->K, I->L.kt, I->L.ctiles, cpart, st);
+        return I->L.ctiles;
+    }
+    const int row_tiles = ceil_div(N, 16);
+    int parts = std::min(ceil_div(I->L.ctiles, 4), std::max(1, 2048 / (4 * row_tiles)));
+    const int tpw_c = ceil_div(I->L.ctiles, parts * 4);
+    parts = ceil_div(I->L.ctiles, tpw_c * 4);
+    vpk_centroid(hidden, N, I->d, I->cp, I->cnorm, I->K, I->L.kt, I->L.ctiles, tpw_c, parts, cpart, st);
+    return parts;
 }
 
 // The kernel sequence shared by vp_project and the clustered debug entry.
@@ -336,17 +355,12 @@ vp_status run_clustered(const char *fn, const vp_index *I, const void *hidden, i
     VpItem *items = reinterpret_cast<VpItem *>(ws + W.items);
     float *partials = reinterpret_cast<float *>(ws + W.partials);
 
-    // Eq. 2 in parts so that a handful of rows still occupies many wavefronts
     const int row_tiles = ceil_div(N, 16);
-    int parts = std::min(ceil_div(I->L.ctiles, 4), std::max(1, 2048 / (4 * row_tiles)));
-    const int tpw_c = ceil_div(I->L.ctiles, parts * 4);
-    parts = ceil_div(I->L.ctiles, tpw_c * 4);
-
     const int max_items = max_items_clustered(I, N);
     // the debug entry lays its logits out per cluster list, so it always takes the slabs
     // with dispatch: rows per item of the masked full projection the planner may choose
     const int rt_masked = single_bucket_row_tiles(I, N, VP_MAX_TOPK) == 4 ? 4 : 1;
-    const int dispatch = (I->dispatch && !dbg_logits) ? VP_ROWS_PER_ITEM * rt_masked : 0;
+    int dispatch = (I->dispatch && !dbg_logits) ? VP_ROWS_PER_ITEM * rt_masked : 0;
     const int max_full = max_items_full(I, N);
     // the tile counts of the cost model are in tiles of kt KiB: fold that into the constants
     VpCostModel cost = I->cost;
@@ -360,24 +374,29 @@ vp_status run_clustered(const char *fn, const vp_index *I, const void *hidden, i
     const long by_tiles = row_groups * ceil_div(I->L.max_tiles, VP_WG_WAVES);
     // (+ one round of blocks: the XCD swizzle of plans with heavy buckets rounds the grid up)
     const int grid_items = (int)std::min<long>(max_items, by_tiles) + 8 * VP_XCD_BLOCK_ITEMS;
-    // Batches of a few rows: no planning kernel; the projection workgroups find their own work
-    // (project_small_kernel).  With dispatch on, only when the slabs are the cheaper form even
-    // if every row sat in a cluster of its own with the longest list (the planner's cost model
-    // on that worst case), so that nothing is lost by not asking it.
-    bool small = I->small_path && N <= VP_SMALL_ROWS && !dbg_row_off && !dbg_logits;
-    if (small && dispatch) {
-        const float worst = (float)N * I->L.max_tiles;
-        const float t_slab = worst / cost.bw_slab;
-        const float t_full = I->L.vtiles / cost.bw_full * (1.f + k * 0.125f);
-        small = t_slab <= t_full;
+    // If the slabs are the cheaper form even when every row sits in a cluster of its own with the
+    // longest list (the planner's cost model on that worst case), the planner has nothing to
+    // decide and the masked full projection is not launched at all (learned active sets of a
+    // fraction of a percent of V: the common case).
+    if (dispatch) {
+        const int buckets = std::min(N, I->K);
+        const float occ = (float)buckets * I->L.max_tiles;
+        const float total = (float)(buckets + row_tiles) * I->L.max_tiles;
+        const float t_slab = occ / cost.bw_slab + (total - occ) / cost.bw_l2 + N * cost.t_row_slab;
+        const int rgs_full = ceil_div(N, dispatch);
+        const float t_full = dispatch == 64
+            ? std::max(I->L.vtiles / cost.bw_full, rgs_full * (I->L.vtiles / cost.bw_gemm)) * (1.f + k * 0.0125f)
+            : std::max(I->L.vtiles / cost.bw_full, (float)rgs_full * I->L.vtiles / cost.bw_l2) * (1.f + k * 0.125f);
+        if (t_slab <= t_full) dispatch = 0;
     }
+    // Batches of a few rows: no planning kernel; the projection workgroups find their own work
+    // (project_small_kernel) - unless the planner has a choice to make.
+    const bool small = I->small_path && N <= VP_SMALL_ROWS && !dbg_row_off && !dbg_logits && !dispatch;
     const int raw_ok_all = I->raw_logits && !dbg_logits && k >= 4 && (long)N * I->L.max_tiles <= 8192;
     if (small) {
-        // Eq. 2 with one workgroup per centroid tile: one minimum per tile and row
-        vpk_centroid_small(hidden, N, I->d, I->cp, I->cnorm, I->K, I->L.kt, I->L.ctiles, cpart, st);
         VpSmallArgs a = {};
         a.cpart = reinterpret_cast<const int32_t *>(cpart);
-        a.parts = I->L.ctiles;
+        a.parts = launch_eq2(I, hidden, N, cpart, st);
         a.N = N;
         a.K = I->K;
         a.tile_off = I->clusters.tile_off;
@@ -408,7 +427,7 @@ vp_status run_clustered(const char *fn, const vp_index *I, const void *hidden, i
         vpk_merge(I->clusters, rowplan, hdr, partials, k, N, out_ids, out_logp, st);
         return launch_status(fn);
     }
-    vpk_centroid(hidden, N, I->d, I->cp, I->cnorm, I->K, I->L.kt, I->L.ctiles, tpw_c, parts, cpart, st);
+    const int parts = launch_eq2(I, hidden, N, cpart, st);
     vpk_plan(cpart, parts, N, I->K, I->clusters.n_cand, I->clusters.tile_off, I->target_items, I->min_items, max_items, g,
              out_cluster, perm, rowplan, floors, items, hdr, dbg_row_off, dispatch, cost, k, I->V, I->L.vtiles,
              sb_target(I, rt_masked, k), sb_min(I, rt_masked, k), max_full, st);
@@ -431,7 +450,7 @@ vp_status run_clustered(const char *fn, const vp_index *I, const void *hidden, i
         const int grid_full = (rgs > 1 && chunks >= 8) ? ceil_div(chunks, 8) * 8 * rgs : chunks * rgs;
         const VpMaskInfo mask = {g, I->bitmaps, I->L.bm_words};
         if (use_gemm_lds(I, rt_masked, k))
-            vpk_project_rows_lds(I->full, hidden, I->d, perm, items, hdr, grid_full, k, partials, floors, &mask, st);
+            vpk_project_rows_lds(I->full, hidden, I->d, perm, items, hdr, grid_full, k, partials, floors, &mask, false, st);
         else if (rt_masked == 4)
             vpk_project_gemm(I->full, hidden, I->d, perm, items, hdr, grid_full, k, partials, floors + N, &mask, st);
         else
@@ -478,7 +497,7 @@ vp_status run_full(const char *fn, const vp_index *I, const void *hidden, int N,
 
 // Extra workspace of the batch-union form, placed after the common part.
 struct UnionLayout {
-    size_t base, uh, occ, mask, zero_g, bsum, uids, ubias, uslab, total;
+    size_t base, uh, mask, zero_g, bsum, uids, ubias, uslab, total;
     int mask_words;
 };
 
@@ -491,7 +510,6 @@ UnionLayout plan_union_workspace(const vp_index *I, int N)
     U.mask_words = I->L.bm_words;   // one bit per token, padded like the per-cluster membership lists
     const size_t vpad = (size_t)I->L.vtiles * VP_TILE_ITEMS;
     U.uh = take(sizeof(VpUnionHeader));
-    U.occ = take((size_t)I->K * 4);
     U.mask = take((size_t)U.mask_words * 4);
     U.zero_g = take((size_t)std::max(N, 1) * 4);
     U.bsum = take((size_t)vpk_union_blocks(U.mask_words) * 4);
@@ -894,7 +912,6 @@ vp_status vp_project_union(const vp_index *I, const void *hidden, int32_t N, int
     VpItem *items = reinterpret_cast<VpItem *>(ws + W.items);
     float *partials = reinterpret_cast<float *>(ws + W.partials);
     VpUnionHeader *uh = reinterpret_cast<VpUnionHeader *>(ws + U.uh);
-    int32_t *occ = reinterpret_cast<int32_t *>(ws + U.occ);
     unsigned int *mask = reinterpret_cast<unsigned int *>(ws + U.mask);
     int32_t *bsum = reinterpret_cast<int32_t *>(ws + U.bsum);
     int32_t *uids = reinterpret_cast<int32_t *>(ws + U.uids);
@@ -902,19 +919,14 @@ vp_status vp_project_union(const vp_index *I, const void *hidden, int32_t N, int
     void *uslab = ws + U.uslab;
 
     // step 1: predicted centroids (Eq. 2)
-    const int row_tiles = ceil_div(N, 16);
-    int parts = std::min(ceil_div(I->L.ctiles, 4), std::max(1, 2048 / (4 * row_tiles)));
-    const int tpw_c = ceil_div(I->L.ctiles, parts * 4);
-    parts = ceil_div(I->L.ctiles, tpw_c * 4);
-    vpk_centroid(hidden, N, I->d, I->cp, I->cnorm, I->K, I->L.kt, I->L.ctiles, tpw_c, parts, cpart, st);
+    const int parts = launch_eq2(I, hidden, N, cpart, st);
     // step 2: boolean list over the vocabulary -> reduced column set U
     int32_t *zero_g = reinterpret_cast<int32_t *>(ws + U.zero_g);
-    vpk_union_mark(cpart, parts, N, I->K, U.mask_words, g, out_cluster, occ, uh, mask, zero_g, st);
-    vpk_union_flags(occ, uh, I->bitmaps, I->L.bm_words, U.mask_words, mask, st);
+    vpk_union_mark(cpart, parts, N, I->K, I->bitmaps, I->L.bm_words, U.mask_words, g, out_cluster, zero_g, mask, bsum, st);
     const int max_items = max_items_full(I, N);
     const int row_tiles_u = single_bucket_row_tiles(I, N, k);
     // the masked full projection exists for items of 16 and of 64 rows
-    const int allow_full = I->union_dispatch && (row_tiles_u == 1 || row_tiles_u == 4);
+    int allow_full = I->union_dispatch && (row_tiles_u == 1 || row_tiles_u == 4);
     VpCostModel cost = I->cost;
     const float tile_bytes = (float)I->L.kt * VP_TILE_BYTES;
     cost.bw_full /= tile_bytes;
@@ -922,19 +934,39 @@ vp_status vp_project_union(const vp_index *I, const void *hidden, int32_t N, int
     if (row_tiles_u == 4 && !use_gemm_lds(I, row_tiles_u, k)) cost.bw_gemm = cost.bw_gemm_split;
     cost.bw_gemm /= tile_bytes;
     cost.bw_gather /= tile_bytes;
+    if (allow_full) {
+        // the in-place form cannot win if the gathered form is cheaper even for the largest union this
+        // batch can have (every row in a cluster of its own with the longest list): then it is not launched
+        const int rpi_u = VP_ROWS_PER_ITEM * row_tiles_u;
+        const int rgs_u = ceil_div(N, rpi_u);
+        const float per_group = rpi_u >= 64 ? std::max(1.f / cost.bw_full, rgs_u / cost.bw_gemm) * (1.f + k * 0.0125f)
+                                            : std::max(1.f / cost.bw_full, rgs_u / cost.bw_l2) * (1.f + k * 0.125f);
+        const long u_max = std::min<long>(I->V, (long)std::min(N, I->K) * I->L.n_max);
+        const float tiles_max = (float)ceil_div(u_max, VP_TILE_ITEMS);
+        if (cost.t_gather + tiles_max * (1.f / cost.bw_gather + per_group) <= I->L.vtiles * per_group) allow_full = 0;
+    }
     vpk_union_compact(mask, U.mask_words, bsum, N, VP_ROWS_PER_ITEM * row_tiles_u, sb_target(I, row_tiles_u, k), sb_min(I, row_tiles_u, k), max_items, uids, uh,
-                      out_union_size, perm, rowplan, floors, items, hdr, allow_full, I->V, I->L.vtiles, k, cost, max_items, st);
-    // step 3: the reduced weight matrix and Eq. 1 over it; steps 4-5 fused (no [N, V] array)
-    vpk_union_gather(I->arena + I->L.wt, I->full.bias, I->L.kt, uids, uh, I->L.vtiles, uslab, ubias, st);
+                      out_union_size, perm, rowplan, floors, items, hdr, allow_full, I->V, I->L.vtiles, k, cost, max_items, I->full.bias, ubias, st);
+    // step 3: the reduced weight matrix and Eq. 1 over it; steps 4-5 fused (no [N, V] array).  With
+    // 64-row items on the rows-in-LDS kernel the columns of U are read where they lie, through U,
+    // from the token-major copy of W (the bias of U's tokens was collected with U); otherwise they
+    // are first gathered into a packed slab in the workspace.
+    const bool fused_gather = use_gemm_lds(I, row_tiles_u, k) && (long)I->V * I->L.kt * 4 < (1L << 31);
     VpSlabSet uset = I->full;
-    uset.tiles = uslab;
     uset.bias = ubias;
     uset.ids = uids;
     // grid: the largest split the planner can choose for |U| <= V
     const int rgs = ceil_div(N, VP_ROWS_PER_ITEM * row_tiles_u);
     const int grid_items = std::min(max_items, ceil_div(rgs * (long)ceil_div(I->L.vtiles, VP_WG_WAVES), 8) * 8 + 8 * rgs);
-    launch_single_bucket(uset, I, hidden, perm, items, hdr, N, grid_items, row_tiles_u, k, 0, partials, floors, nullptr,
-                         nullptr, st);
+    if (fused_gather) {
+        uset.tiles = I->arena + I->L.wt;
+        vpk_project_rows_lds(uset, hidden, I->d, perm, items, hdr, grid_items, k, partials, floors, nullptr, true, st);
+    } else {
+        vpk_union_gather(I->arena + I->L.wt, I->L.kt, uids, uh, I->L.vtiles, uslab, st);
+        uset.tiles = uslab;
+        launch_single_bucket(uset, I, hidden, perm, items, hdr, N, grid_items, row_tiles_u, k, 0, partials, floors,
+                             nullptr, nullptr, st);
+    }
     if (allow_full) {
         // launched as well; exactly one of the two does the work, as the planner decided
         const int tpw = sb_tiles_per_wave(I, rgs, row_tiles_u, k);
@@ -942,7 +974,7 @@ vp_status vp_project_union(const vp_index *I, const void *hidden, int32_t N, int
         const int grid_full = (rgs > 1 && chunks >= 8) ? ceil_div(chunks, 8) * 8 * rgs : chunks * rgs;
         const VpMaskInfo umask = {zero_g, mask, 0};   // every row reads list 0: the boolean list of the batch
         if (use_gemm_lds(I, row_tiles_u, k))
-            vpk_project_rows_lds(I->full, hidden, I->d, perm, items, hdr, grid_full, k, partials, floors, &umask, st);
+            vpk_project_rows_lds(I->full, hidden, I->d, perm, items, hdr, grid_full, k, partials, floors, &umask, false, st);
         else if (row_tiles_u == 4)
             vpk_project_gemm(I->full, hidden, I->d, perm, items, hdr, grid_full, k, partials, floors + N, &umask, st);
         else

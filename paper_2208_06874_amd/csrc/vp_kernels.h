@@ -65,7 +65,7 @@ bool vpk_project_rows_lds_supported(int kt, int k);
 hipError_t vpk_project_rows_lds_prepare();
 void vpk_project_rows_lds(const VpSlabSet &set, const void *hidden, int d, const int32_t *perm, const VpItem *items,
                           const VpPlanHeader *hdr, int grid_items, int k, float *partials, unsigned int *floors,
-                          const VpMaskInfo *mask, hipStream_t st);
+                          const VpMaskInfo *mask, bool gather, hipStream_t st);
 
 // per-row merge
 size_t vpk_merge_lds_bytes(int k);
@@ -75,18 +75,17 @@ void vpk_merge(const VpSlabSet &set, const VpRowPlan *rowplan, const VpPlanHeade
 
 // the paper's batch-union form
 hipError_t vpk_union_prepare();
-void vpk_union_mark(const void *cpart, int parts, int N, int K, int mask_words, int32_t *g, int32_t *out_cluster,
-                    int32_t *occ, VpUnionHeader *uh, unsigned int *mask, int32_t *zero_g, hipStream_t st);
-void vpk_union_flags(const int32_t *occ, const VpUnionHeader *uh, const uint32_t *bitmaps, int bm_words,
-                     int mask_words, unsigned int *mask, hipStream_t st);
+void vpk_union_mark(const void *cpart, int parts, int N, int K, const uint32_t *bitmaps, int bm_words, int mask_words,
+                    int32_t *g, int32_t *out_cluster, int32_t *zero_g, unsigned int *mask, int32_t *bsum,
+                    hipStream_t st);
 int vpk_union_blocks(int mask_words);
-void vpk_union_compact(const unsigned int *mask, int mask_words, int32_t *bsum, int N, int rpi, int target_items,
+void vpk_union_compact(const unsigned int *mask, int mask_words, const int32_t *bsum, int N, int rpi, int target_items,
                        int min_items, int max_items, int32_t *uids, VpUnionHeader *uh, int32_t *out_union_size,
                        int32_t *perm, VpRowPlan *rowplan, unsigned int *floors, VpItem *items, VpPlanHeader *hdr,
                        int allow_full, int V, int vtiles, int k, const VpCostModel &cost, int max_items_full,
-                       hipStream_t st);
-void vpk_union_gather(const void *wt, const float *bias_full, int kt, const int32_t *uids, const VpUnionHeader *uh,
-                      int max_groups, void *slab, float *ubias, hipStream_t st);
+                       const float *bias_full, float *ubias, hipStream_t st);
+void vpk_union_gather(const void *wt, int kt, const int32_t *uids, const VpUnionHeader *uh, int max_groups, void *slab,
+                      hipStream_t st);
 
 // offline training of the clusters (section 2.2)
 void vpk_fill_u32(void *p, size_t n, uint32_t v, hipStream_t st);
