@@ -59,6 +59,11 @@ typedef enum {
 #define VP_MAX_DIM 4096
 #define VP_WS_OVERFLOW_WORD 2 /* index of the overflow flag among the workspace's 32-bit words */
 
+/* vp_build_desc.flags: leave out the copy of W with one contiguous row per token (V * d_pad * 2
+ * bytes, as much again as the packed W) that only vp_project_union reads; that call then returns
+ * VP_ERR_UNSUPPORTED for the index. */
+#define VP_BUILD_NO_UNION 1u
+
 typedef struct {
     int32_t d;             /* embedding dimension                                        */
     int32_t V;             /* vocabulary size                                            */
@@ -72,7 +77,7 @@ typedef struct {
     void *arena;           /* device, 256-byte aligned, >= vp_build_bytes()              */
     size_t arena_bytes;
     int32_t k_max;         /* largest top-k that will be requested                       */
-    uint32_t flags;        /* must be 0                                                  */
+    uint32_t flags;        /* 0, or VP_BUILD_NO_UNION                                    */
 } vp_build_desc;
 
 typedef struct {
@@ -91,7 +96,7 @@ size_t vp_build_bytes(const vp_build_desc *desc);
 
 /* Packs the index into the arena: ||C_j||^2 per centroid (the precomputed term
  * of Eq. 2), centroids and W re-tiled for the matrix cores, W once more with one
- * contiguous row per token (for the run-time gather of vp_project_union), a
+ * contiguous row per token (for vp_project_union; not with VP_BUILD_NO_UNION), a
  * membership bit list per cluster, and per cluster a slab with its active
  * tokens' columns, their bias and their ids.  W, bias and
  * centroids are only read during this call (the index keeps its own copies);

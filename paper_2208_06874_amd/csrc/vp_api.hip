@@ -112,6 +112,7 @@ struct vp_index {
     VpCostModel cost;
     const uint32_t *bitmaps;
     int union_dispatch;   // 1: vp_project_union may project a large union as a masked full projection
+    bool has_token_major;   // the copy of W vp_project_union reads is part of the arena
     int small_path;   // 1: batches of at most 16 rows are planned by the projection workgroups themselves
     int small_pf;     // 1 KiB loads a wavefront of that path keeps in flight (0: chosen from the batch size)
     int raw_logits;   // 1: short items of small top-k >= 4 calls keep raw logits instead of lists (see run_clustered)
@@ -124,7 +125,7 @@ namespace {
 vp_status plan_arena(const vp_build_desc *D, bool check_ids, ArenaLayout *L)
 {
     if (!D) return fail(VP_ERR_INVALID_ARG, "vp_build: null description");
-    if (D->flags != 0) return fail(VP_ERR_INVALID_ARG, "vp_build: flags must be 0");
+    if (D->flags & ~VP_BUILD_NO_UNION) return fail(VP_ERR_INVALID_ARG, "vp_build: unknown flag bits %#x", D->flags);
     if (D->d < 8 || D->d > VP_MAX_DIM || D->d % 8 != 0)
         return fail(VP_ERR_UNSUPPORTED, "vp_build: d = %d must be a multiple of 8 in [8, %d]", D->d, VP_MAX_DIM);
     if (D->K < 1 || D->K > VP_MAX_CLUSTERS)
@@ -176,7 +177,8 @@ vp_status plan_arena(const vp_build_desc *D, bool check_ids, ArenaLayout *L)
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
     const size_t group_bytes = (size_t)L->kt * VP_TILE_BYTES;
     L->wp = take((size_t)L->vtiles * group_bytes);
-    L->wt = take((size_t)D->V * L->d_pad * 2);   // token-major copy for the run-time gather of the batch-union form
+    // token-major copy for the batch-union form (left out on request)
+    L->wt = take((D->flags & VP_BUILD_NO_UNION) ? 0 : (size_t)D->V * L->d_pad * 2);
     L->biasf = take((size_t)L->vtiles * VP_TILE_ITEMS * sizeof(float));
     L->cp = take((size_t)L->ctiles * group_bytes);
     L->cnorm = take((size_t)L->ctiles * VP_TILE_ITEMS * sizeof(float));
@@ -580,7 +582,7 @@ vp_status vp_build(const vp_build_desc *D, void *hip_stream, vp_index **out)
     if (e != hipSuccess) return fail(VP_ERR_HIP, "vp_build: upload failed: %s", hipGetErrorString(e));
 
     vpk_pack_w(D->W, D->d, D->V, L.kt, A + L.wp, st);
-    vpk_token_major(A + L.wp, D->V, L.kt, A + L.wt, st);
+    if (!(D->flags & VP_BUILD_NO_UNION)) vpk_token_major(A + L.wp, D->V, L.kt, A + L.wt, st);
     vpk_bias_full(D->bias, D->V, L.vtiles * VP_TILE_ITEMS, reinterpret_cast<float *>(A + L.biasf), st);
     vpk_pack_rows(D->centroids, D->K, D->d, L.kt, A + L.cp, st);
     vpk_cnorm(D->centroids, D->K, D->d, L.ctiles * VP_TILE_ITEMS, reinterpret_cast<float *>(A + L.cnorm), st);
@@ -649,6 +651,7 @@ vp_status vp_build(const vp_build_desc *D, void *hip_stream, vp_index **out)
     I->cost.bw_gather = 2.4e12f;
     I->cost.t_gather = 12.0e-6f;
     I->union_dispatch = 1;
+    I->has_token_major = !(D->flags & VP_BUILD_NO_UNION);
     I->bitmaps = reinterpret_cast<const uint32_t *>(A + L.bitmaps);
     I->small_path = 1;
     I->small_pf = 0;
@@ -895,7 +898,9 @@ vp_status vp_project_union(const vp_index *I, const void *hidden, int32_t N, int
 {
     const char *fn = "vp_project_union";
     vp_status s = check_call(fn, I, hidden, N, k, out_ids, out_logp, workspace, workspace_bytes, true);
-    if (s != VP_OK || N == 0) return s;
+    if (s != VP_OK) return s;
+    if (!I->has_token_major) return fail(VP_ERR_UNSUPPORTED, "%s: the index was built with VP_BUILD_NO_UNION", fn);
+    if (N == 0) return VP_OK;
     const UnionLayout U = plan_union_workspace(I, N);
     if (workspace_bytes < U.total)
         return fail(VP_ERR_WORKSPACE, "%s: workspace of %zu bytes, %zu needed for N = %d", fn, workspace_bytes,

@@ -169,7 +169,7 @@ def make_desc(d, V, K, W, bias, centroids, cand_off: np.ndarray, cand_ids: np.nd
 class Index:
     """A packed index living in a torch uint8 arena on the GPU."""
 
-    def __init__(self, W, bias, centroids, cand_off, cand_ids, k_max: int = 8, stream=None):
+    def __init__(self, W, bias, centroids, cand_off, cand_ids, k_max: int = 8, stream=None, flags: int = 0):
         import torch
         if not isinstance(W, torch.Tensor) or W.dim() != 2:
             raise ValueError("W must be a [d, V] tensor")
@@ -188,7 +188,7 @@ class Index:
         if self._ids.ndim != 1 or (len(self._off) and self._ids.shape[0] != int(self._off[-1])):
             raise ValueError("cand_ids must hold cand_off[K] = %d entries, got %s" % (int(self._off[-1]), self._ids.shape))
         desc = make_desc(d, V, K, W.data_ptr(), bias.data_ptr(), self._C.data_ptr(), self._off,
-                         self._ids, None, 0, k_max)
+                         self._ids, None, 0, k_max, flags)
         need = lib().vp_build_bytes(ctypes.byref(desc))
         if need == 0:
             # let vp_build report the precise status
@@ -345,8 +345,11 @@ class Index:
 
 
 # ---- the C-ABI entry points under their own names --------------------------------------------
-def vp_build(W, bias, centroids, cand_off, cand_ids, k_max: int = 8, stream=None) -> Index:
-    return Index(W, bias, centroids, cand_off, cand_ids, k_max=k_max, stream=stream)
+BUILD_NO_UNION = 1
+
+
+def vp_build(W, bias, centroids, cand_off, cand_ids, k_max: int = 8, stream=None, flags: int = 0) -> Index:
+    return Index(W, bias, centroids, cand_off, cand_ids, k_max=k_max, stream=stream, flags=flags)
 
 
 def vp_project(index: Index, hidden, k: int, **kw):

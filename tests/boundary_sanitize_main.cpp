@@ -73,7 +73,7 @@ int main()
     D.K = 0;
     CHECK(vp_build_bytes(&D) == 0);
     D = good;
-    D.flags = 1;
+    D.flags = 2;   // an unknown flag bit
     CHECK(vp_build_bytes(&D) == 0);
     D = good;
     D.cand_ids = nullptr;

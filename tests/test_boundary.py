@@ -65,7 +65,7 @@ def test_build_bytes_valid_and_monotone():
     (dict(K=0, lists=[]), vp.VP_ERR_UNSUPPORTED),
     (dict(k_max=0), vp.VP_ERR_UNSUPPORTED),
     (dict(k_max=33), vp.VP_ERR_UNSUPPORTED),
-    (dict(flags=1), vp.VP_ERR_INVALID_ARG),
+    (dict(flags=2), vp.VP_ERR_INVALID_ARG),            # an unknown flag bit
     (dict(lists=[np.zeros(0, int), np.zeros(0, int), np.zeros(0, int)]), vp.VP_ERR_UNSUPPORTED),   # all sets empty
     (dict(lists=[np.array([3, 2]), np.arange(4), np.arange(3)]), vp.VP_ERR_INVALID_ARG),   # unsorted
     (dict(lists=[np.array([2, 2]), np.arange(4), np.arange(3)]), vp.VP_ERR_INVALID_ARG),   # duplicate
@@ -326,3 +326,14 @@ def test_build_rejects_bad_tensors_before_any_c_call():
                lambda: vp.vp_beam_step(torch.zeros((4, 2), dtype=torch.int32), torch.zeros((4, 2)), torch.zeros(4), 2)):
         with pytest.raises(ValueError, match="GPU memory"):
             fn()
+
+
+def test_build_flag_drops_the_token_major_copy():
+    """VP_BUILD_NO_UNION: the arena shrinks by V * d_pad * 2 bytes; other flag bits are refused."""
+    L = vp.lib()
+    d0, *_k0 = _desc()
+    d1, *_k1 = _desc(flags=vp.BUILD_NO_UNION)
+    n0, n1 = L.vp_build_bytes(ctypes.byref(d0)), L.vp_build_bytes(ctypes.byref(d1))
+    assert n0 - n1 >= 100 * 256 * 2 and n1 > 0
+    d2, *_k2 = _desc(flags=2)
+    assert L.vp_build_bytes(ctypes.byref(d2)) == 0 and "flag" in vp.last_error()

@@ -1139,3 +1139,29 @@ def test_planner_picks_the_faster_form(tiny, mid, large, skewed):
                 report.append((B.cfg.name, N, spread, mode, t))
                 print("planner", B.cfg.name, N, spread, "chose", mode, {n: round(v * 1e6, 1) for n, v in t.items()}, flush=True)
                 assert t["planner"] <= 1.10 * best + 4e-6, (B.cfg.name, N, spread, mode, t)
+
+
+def test_index_without_the_token_major_copy(oracle):
+    """VP_BUILD_NO_UNION: a smaller arena, vp_project and vp_project_full as ever, vp_project_union refused."""
+    torch = _torch()
+    from paper_2208_06874_amd import vp
+    r, W, b, C = _small_model(21, 256, 4000, 6)
+    off, ids = _random_lists(r, 6, 4000, 100, 600)
+    dev = torch.device("cuda:0")
+    Wt, bt, Ct = (torch.from_numpy(a).to(dev) for a in (W, b, C))
+    full = vp.vp_build(Wt, bt, Ct, off, ids, k_max=4)
+    lean = vp.vp_build(Wt, bt, Ct, off, ids, k_max=4, flags=vp.BUILD_NO_UNION)
+    assert full.info()["arena_bytes_used"] - lean.info()["arena_bytes_used"] >= 4000 * 256 * 2
+    H = _rows(r, C, 40)
+    Ht = torch.from_numpy(H).to(dev)
+    a_ids, a_logp, a_g = full.project(Ht, 4)
+    b_ids, b_logp, b_g = lean.project(Ht, 4)
+    torch.cuda.synchronize()
+    assert torch.equal(a_ids, b_ids) and torch.equal(a_logp, b_logp) and torch.equal(a_g, b_g)
+    pu.check_projection(oracle, W, b, C, off, ids, H, 4, pu.to_np(b_ids), pu.to_np(b_logp), pu.to_np(b_g))
+    f_ids, f_logp = lean.project_full(Ht, 4)
+    torch.cuda.synchronize()
+    pu.check_full(oracle, W, b, H, 4, pu.to_np(f_ids), pu.to_np(f_logp))
+    with pytest.raises(vp.VpError) as e:
+        lean.project_union(Ht, 4)
+    assert e.value.status == vp.VP_ERR_UNSUPPORTED and "NO_UNION" in str(e.value)

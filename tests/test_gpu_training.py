@@ -303,3 +303,68 @@ def test_random_training_shapes(oracle):
         torch.cuda.synchronize()
         want_off, want_ids = oracle.active_sets(top, a0, K, V)
         assert np.array_equal(pu.to_np(off), want_off) and np.array_equal(pu.to_np(ids), want_ids)
+
+
+def test_train_build_decode_joined_at_the_mid_shape(oracle):
+    """The rows of the scope end to end at the mid shape (d = 1,024, V = 128,000, K = 200), every stage
+    against its own oracle: clusters trained by vp_kmeans (Lloyd steps bit for bit, final memberships
+    against brute force), active sets from recorded top-3 tokens (section 2.2), the index packed from them,
+    and a beam search of 8 sentences x beam 8 that decodes on it with vp_project (section 2.3) and
+    vp_beam_step (section 2.1), with the library's default options."""
+    torch = _torch()
+    from paper_2208_06874_amd import vp
+    cfg = wl.CONFIGS["mid"]
+    W, b, C_true = wl.make_model(cfg)
+    n, T = 12000, 3
+    X, _q, C0 = wl.training_set(cfg, C_true, n)
+    Wt, bt, Xt = _dev(W), _dev(b), _dev(X)
+    # recording: the full projection's top-T of every vector (sampled rows against the oracle)
+    boot = vp.vp_build(Wt, bt, _dev(C0[:1]), np.array([0, 1], np.int64), np.array([0], np.int32), k_max=T)
+    top, top_lp = boot.project_full(Xt, T)
+    torch.cuda.synchronize()
+    sample = np.array([0, 1, n // 2, n - 1])
+    pu.check_full(oracle, W, b, X[sample], T, pu.to_np(top)[sample], pu.to_np(top_lp)[sample])
+    # training: every Lloyd step the oracle's, given the GPU's memberships
+    Cb = C0.view(np.uint16).copy()
+    for step in range(3):
+        _same, a, _c = _gpu_kmeans(X, Cb.view(np.float16), 0)
+        _check_membership(oracle, X, Cb, a)
+        new, _a2, _c2 = _gpu_kmeans(X, Cb.view(np.float16), 1)
+        want = oracle.kmeans_step(X, Cb.view(np.float16).astype(np.float64), forced=a)["C"].astype(np.float16)
+        assert np.array_equal(new, want.view(np.uint16)), "Lloyd step %d" % step
+        Cb = new
+    Ct = _dev(C0.copy())
+    assign, counts = vp.vp_kmeans(Xt, Ct, 20)
+    torch.cuda.synchronize()
+    C_new = pu.to_np(Ct)
+    excused = _check_membership(oracle, X, C_new.view(np.uint16), pu.to_np(assign))
+    # active sets: the oracle's union of the recorded tokens of every cluster's members
+    off, ids = vp.vp_active_sets(top, assign, cfg.K, cfg.V)
+    torch.cuda.synchronize()
+    off_h, ids_h = pu.to_np(off), pu.to_np(ids)
+    want_off, want_ids = oracle.active_sets(pu.to_np(top), pu.to_np(assign), cfg.K, cfg.V)
+    assert np.array_equal(off_h, want_off) and np.array_equal(ids_h, want_ids)
+    # the index from the learned clusters, and a search that decodes on it
+    index = vp.vp_build(Wt, bt, Ct, off_h, ids_h, k_max=8)
+    S, B, k = 8, 8, 8
+    scores = np.tile(np.array([0.0] + [-np.inf] * (B - 1), np.float32), S)
+    parent = np.tile(np.arange(B, dtype=np.int32), S)
+    for step in range(3):
+        fresh, _ = wl.make_rows(cfg, C_true, N=S * B, stream=300 + step)
+        gather = (np.arange(S * B) // B) * B + np.maximum(parent, 0)
+        H = np.ascontiguousarray(fresh[gather])
+        out_ids, out_logp, g = index.project(_dev(H), k)
+        torch.cuda.synchronize()
+        st = pu.check_projection(oracle, W, b, C_new, off_h, ids_h, H, k, pu.to_np(out_ids), pu.to_np(out_logp),
+                                 pu.to_np(g))
+        new = vp.vp_beam_step(out_ids, out_logp, _dev(scores), B)
+        torch.cuda.synchronize()
+        got = tuple(pu.to_np(o) for o in new)
+        want = oracle.beam_step(pu.to_np(out_ids), pu.to_np(out_logp), scores, B)
+        for a, w in zip(got, want):
+            assert np.array_equal(a, w)
+        scores, parent = got[0], got[1]
+    sizes = np.diff(off_h)
+    print("joined: clusters with members %d of %d, mean active set %.0f tokens, excused memberships %d, last step %s"
+          % (int((pu.to_np(counts) > 0).sum()), cfg.K, sizes[sizes > 0].mean(), excused, st))
+    assert np.isfinite(scores).sum() == S * B
