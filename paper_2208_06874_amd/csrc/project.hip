@@ -446,15 +446,16 @@ __device__ inline void project_small(const VpSlabSet &set, const uint4 *__restri
     int bj = VP_IDX_NONE;
     if (r < N) {
         const int2 *cp = reinterpret_cast<const int2 *>(a.cpart) + (size_t)r * a.parts;
-        for (int p0 = 0; p0 < a.parts; p0 += 16) {
-            int2 e[4];
+        // (up to 64 parts in one batch of loads: one round trip, not one per four parts)
+        for (int p0 = 0; p0 < a.parts; p0 += 64) {
+            int2 e[16];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < 16; ++u) {
                 const int p = p0 + 4 * u + sub;
                 e[u] = p < a.parts ? cp[p] : make_int2(0x7f800000, VP_IDX_NONE);
             }
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < 16; ++u) {
                 const float s = __int_as_float(e[u].x);
                 const bool take = (s < bs) | ((s == bs) & (e[u].y < bj));
                 bs = take ? s : bs;

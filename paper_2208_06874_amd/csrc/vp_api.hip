@@ -324,10 +324,11 @@ void launch_single_bucket(const VpSlabSet &set, const vp_index *I, const void *h
 }
 
 // Eq. 2 for a decode batch: up to VP_KSPLIT_ROWS rows with one workgroup per (centroid tile, row
-// tile) and the k-extent split over its wavefronts (every load in flight at once: 3-4 us instead
-// of 7-9 at 64-256 rows), beyond that the kernel whose workgroups walk several centroid tiles.
-// Returns the number of per-row minima left in cpart.
-constexpr int VP_KSPLIT_ROWS = 256;
+// tile) and the k-extent split over its wavefronts (every load in flight at once: 4.6 us instead
+// of 9.3 at 64 rows; at 256 rows its thousand small workgroups take 9.2 us against 7-8), beyond
+// that the kernel whose workgroups walk several centroid tiles.  Returns the number of per-row
+// minima left in cpart.
+constexpr int VP_KSPLIT_ROWS = 64;
 int launch_eq2(const vp_index *I, const void *hidden, int N, void *cpart, hipStream_t st)
 {
     if (N <= VP_KSPLIT_ROWS) {
