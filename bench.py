@@ -32,6 +32,8 @@ MEASURED_TRAFFIC_BYTES = {
     ("large", 256, "slabs"): (7.008e9, "profiles/project_kernel_large_N256.md"),
     # 8,035,252 KiB x 1.99989 read + 8,466 KiB written per launch
     ("skewed", 4096, "slabs"): (16.46e9, "profiles/project_pf16_kernel_skewed_N4096.md"),
+    # 329,484 KiB x 2.000 read + 2,698.5 KiB written per launch
+    ("large", 256, "masked"): (677.5e6, "profiles/project_gemm_lds_kernel_large_N256_and_sweep_N1024.md"),
 }
 
 

@@ -116,6 +116,9 @@ struct vp_index {
     int small_path;   // 1: batches of at most 16 rows are planned by the projection workgroups themselves
     int small_pf;     // 1 KiB loads a wavefront of that path keeps in flight (0: chosen from the batch size)
     int raw_logits;   // 1: short items of small top-k >= 4 calls keep raw logits instead of lists (see run_clustered)
+    // [n] = candidate groups of the n longest active sets together, n = 0 .. K: the most slab
+    // bytes n rows can occupy (host-side bound of the planner's choice)
+    std::vector<int64_t> longest_tiles;
     VpProfile *prof;
 };
 
@@ -377,14 +380,14 @@ vp_status run_clustered(const char *fn, const vp_index *I, const void *hidden, i
     const long by_tiles = row_groups * ceil_div(I->L.max_tiles, VP_WG_WAVES);
     // (+ one round of blocks: the XCD swizzle of plans with heavy buckets rounds the grid up)
     const int grid_items = (int)std::min<long>(max_items, by_tiles) + 8 * VP_XCD_BLOCK_ITEMS;
-    // If the slabs are the cheaper form even when every row sits in a cluster of its own with the
-    // longest list (the planner's cost model on that worst case), the planner has nothing to
+    // If the slabs are the cheaper form even when every row sits in a cluster of its own and those
+    // are the clusters with the longest lists (the planner's cost model on that worst case), the planner has nothing to
     // decide and the masked full projection is not launched at all (learned active sets of a
     // fraction of a percent of V: the common case).
     if (dispatch) {
         const int buckets = std::min(N, I->K);
-        const float occ = (float)buckets * I->L.max_tiles;
-        const float total = (float)(buckets + row_tiles) * I->L.max_tiles;
+        const float occ = (float)I->longest_tiles[buckets];
+        const float total = occ + (float)row_tiles * I->L.max_tiles;
         const float t_slab = occ / cost.bw_slab + (total - occ) / cost.bw_l2 + N * cost.t_row_slab;
         const int rgs_full = ceil_div(N, dispatch);
         const float t_full = dispatch == 64
@@ -622,6 +625,16 @@ vp_status vp_build(const vp_build_desc *D, void *hip_stream, vp_index **out)
     I->full.n_cand = reinterpret_cast<const int32_t *>(A + L.full_meta) + 2;
     I->full.entries = 1;
     I->full.kt = L.kt;
+    try {
+        I->longest_tiles.assign((size_t)D->K + 1, 0);
+        for (int j = 0; j < D->K; ++j)
+            I->longest_tiles[j + 1] = ceil_div((long)(D->cand_offsets[j + 1] - D->cand_offsets[j]), VP_TILE_ITEMS);
+        std::sort(I->longest_tiles.begin() + 1, I->longest_tiles.end(), [](int64_t a, int64_t b) { return a > b; });
+        for (int j = 0; j < D->K; ++j) I->longest_tiles[j + 1] += I->longest_tiles[j];
+    } catch (...) {
+        delete I;
+        return fail(VP_ERR_INVALID_ARG, "vp_build: out of host memory");
+    }
     I->target_items = 8192;
     I->full_target_items = 2048;
     I->rstar = 0;
