@@ -6,11 +6,11 @@
 // (bit-packed here): the bits of every active token of every predicted cluster
 // are switched on (by OR-ing the clusters' membership bit lists), and a prefix
 // scan over the list yields the reduced column set U in ascending order.  Two
-// launches do all of that (clusters + list + counts; scan + ids + plan).  The columns of U are
-// then gathered from the packed copy of W into a slab in the workspace, and
-// the projection / log-softmax / top-k kernels run on that slab with all rows
-// in one bucket, so every row is normalised over U (tokens outside U are at
-// -infinity, steps 4-5).
+// launches do all of that (clusters + list + counts; scan + ids + plan).  The projection /
+// log-softmax / top-k kernels then run with all rows in one bucket over the columns of U, so
+// every row is normalised over U (tokens outside U are at -infinity, steps 4-5): the 64-row
+// kernel reads the columns in place from the copy of W that holds one contiguous row per
+// token; where that kernel is not built they are first gathered into a slab in the workspace.
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 #include "vp_kernels.h"
