@@ -123,7 +123,7 @@ __device__ inline bool vp_full_is_cheaper(int occ_tiles, int total_tiles, int N,
 {
     const int rgs_full = ceil_div(N, rpi_full);
     const float t_slab = occ_tiles / cost.bw_slab + (total_tiles - occ_tiles) / cost.bw_l2 + N * cost.t_row_slab;
-    const float t_full = rpi_full == 64
+    const float t_full = rpi_full >= 48
         ? fmaxf(vtiles / cost.bw_full, rgs_full * (vtiles / cost.bw_gemm)) * (1.f + k * 0.0125f)
         : fmaxf(vtiles / cost.bw_full, (float)rgs_full * vtiles / cost.bw_l2) * (1.f + k * 0.125f);
     return t_full < t_slab;

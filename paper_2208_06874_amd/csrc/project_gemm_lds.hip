@@ -39,8 +39,8 @@ namespace {
 
 constexpr int L_NW = 8;        // wavefronts per workgroup
 constexpr int L_G = 4;         // candidate groups per step
-constexpr int L_RT = 4;        // row tiles per item
-constexpr int L_ROWS = 64;     // row slots per item
+// row tiles per item: four (64 rows), or three where four do not fit the LDS (d_pad = 1536: 48 rows, 144 KiB)
+constexpr int lds_row_tiles(int kt) { return kt == 48 ? 3 : 4; }
 constexpr int L_PF = 4;        // k-tiles of the four groups kept in flight
 constexpr int VP_MAX_TOPK_LANES = 32;   // the epilogue writes a row's list with one lane per entry
 
@@ -53,6 +53,8 @@ __device__ inline void gemm_lds_item(const VpSlabSet &set, const uint4 *__restri
                                      float *__restrict__ partials, unsigned int *__restrict__ floors,
                                      const VpMaskInfo &mask)
 {
+    constexpr int L_RT = lds_row_tiles(KT);
+    constexpr int L_ROWS = 16 * L_RT;
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // (uniform: step numbers and tile offsets stay in scalar registers)
     const int lane = tid & 63;
@@ -160,7 +162,6 @@ __device__ inline void gemm_lds_item(const VpSlabSet &set, const uint4 *__restri
     uint4 bnext[L_RT];   // the rows' operands of the k-tile to come
 #pragma unroll
     for (int rt = 0; rt < L_RT; ++rt) bnext[rt] = ldsB[(rt * KT) * 64 + lane];
-    static_assert((KT & (KT - 1)) == 0, "k-tile counts of this kernel are powers of two");
 
     while (step < nsteps) {
         const int g0 = gb + step * L_G;
@@ -202,7 +203,7 @@ __device__ inline void gemm_lds_item(const VpSlabSet &set, const uint4 *__restri
                 // scheduling barrier keeps that order (left alone, the compiler sinks all loads of a
                 // pass to its end, right in front of their first use).
                 Frag bf[L_RT];
-                const int kt_next = (b * L_PF + u + 1) & (KT - 1);
+                const int kt_next = (b * L_PF + u + 1) == KT ? 0 : b * L_PF + u + 1;
 #pragma unroll
                 for (int rt = 0; rt < L_RT; ++rt) {
                     bf[rt].u = bnext[rt];
@@ -325,13 +326,13 @@ __device__ inline void gemm_lds_item(const VpSlabSet &set, const uint4 *__restri
         fold_row_tile(std::integral_constant<int, 0>{});
         fold_row_tile(std::integral_constant<int, 1>{});
         fold_row_tile(std::integral_constant<int, 2>{});
-        fold_row_tile(std::integral_constant<int, 3>{});
+        if constexpr (L_RT > 3) fold_row_tile(std::integral_constant<int, 3>{});
         // every second step of a wavefront, one row tile in turn: trade bounds with the other
         // workgroups that project the same rows onto other candidate ranges (one atomicMax
         // publishes ours and returns theirs, folded into the LDS copy a step later: no wait here)
         ++done_steps;
         if (!top1 && (done_steps & 1) == 0) {
-            const int rt_x = ((done_steps >> 1) + wave) & (L_RT - 1);
+            const int rt_x = ((done_steps >> 1) + wave) % L_RT;
 #pragma unroll
             for (int rt = 0; rt < L_RT; ++rt)
                 if (rt == rt_x && q == 0 && row_valid[rt]) {
@@ -461,17 +462,24 @@ hipError_t allow_lds_bytes()
 
 size_t vpk_project_rows_lds_bytes(int k, int kt)
 {
-    return (size_t)L_RT * kt * VP_TILE_BYTES + (size_t)k * L_ROWS * 8 + L_ROWS * 4;
+    const int rows = 16 * lds_row_tiles(kt);
+    return (size_t)rows * kt * (VP_TILE_BYTES / 16) + (size_t)k * rows * 8 + rows * 4;
 }
 
-// built for d_pad = 256, 512 and 1024 (the rows of an item must fit the LDS beside its lists)
-bool vpk_project_rows_lds_supported(int kt, int k) { return (kt == 8 || kt == 16 || kt == 32) && k >= 1 && k <= VP_MAX_TOPK_LANES; }
+// built for d_pad = 256, 512, 1024 and 1536 (the rows of an item must fit the LDS beside its lists)
+bool vpk_project_rows_lds_supported(int kt, int k)
+{
+    return (kt == 8 || kt == 16 || kt == 32 || kt == 48) && k >= 1 && k <= VP_MAX_TOPK_LANES;
+}
+// row tiles of an item of that kernel
+int vpk_project_rows_lds_row_tiles(int kt) { return lds_row_tiles(kt); }
 
 hipError_t vpk_project_rows_lds_prepare()
 {
     hipError_t e = allow_lds_bytes<8>();
     if (e == hipSuccess) e = allow_lds_bytes<16>();
     if (e == hipSuccess) e = allow_lds_bytes<32>();
+    if (e == hipSuccess) e = allow_lds_bytes<48>();
     return e;
 }
 
@@ -493,6 +501,7 @@ void vpk_project_rows_lds(const VpSlabSet &set, const void *hidden, int d, const
         VP_LDS_CASE(8)
         VP_LDS_CASE(16)
         VP_LDS_CASE(32)
+        VP_LDS_CASE(48)
         default: break;   // callers check vpk_project_rows_lds_supported
     }
 #undef VP_LDS_CASE

@@ -127,7 +127,7 @@ __global__ __launch_bounds__(UNION_THREADS) void union_emit_kernel(
     // -infinity either way).  Per candidate group the projection costs the same in both forms.
     if (allow_full) {
         const int rgs = ceil_div(N, rpi);
-        const float per_group = rpi >= 64 ? fmaxf(1.f / cost.bw_full, rgs / cost.bw_gemm) * (1.f + k * 0.0125f)
+        const float per_group = rpi >= 48 ? fmaxf(1.f / cost.bw_full, rgs / cost.bw_gemm) * (1.f + k * 0.0125f)
                                           : fmaxf(1.f / cost.bw_full, rgs / cost.bw_l2) * (1.f + k * 0.125f);
         const float t_union = cost.t_gather + tiles * (1.f / cost.bw_gather + per_group);
         const float t_full = vtiles * per_group;

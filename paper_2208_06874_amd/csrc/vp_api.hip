@@ -210,7 +210,8 @@ int max_items_clustered(const vp_index *I, int N)
 // (the grid of the full projection is padded to 8 candidate ranges at a time, one per XCD)
 int max_items_full(const vp_index *I, int N)
 {
-    return std::max(I->full_target_items, std::max(I->gemm_target_items, I->gemm_lds_items)) +
+    // (the kernel with the rows in LDS takes up to eight rounds of its one item per compute unit)
+    return std::max(I->full_target_items, std::max(I->gemm_target_items, 8 * I->gemm_lds_items)) +
            8 * ceil_div(N, VP_ROWS_PER_ITEM) + 2;
 }
 
@@ -287,7 +288,11 @@ std::pair<hipEvent_t, hipEvent_t> *profile_slot(const vp_index *I)
 // (measured: -10 % at top-1, N = 256) only while the top-k lists are short.
 int single_bucket_row_tiles(const vp_index *I, int N, int k)
 {
-    if (I->gemm_min_rows > 0 && N >= I->gemm_min_rows && vpk_project_gemm_supported(I->L.kt)) return 4;
+    if (I->gemm_min_rows > 0 && N >= I->gemm_min_rows) {
+        // (the kernel that keeps the rows in LDS has room for three row tiles at d_pad = 1536)
+        if (I->gemm_lds && vpk_project_rows_lds_supported(I->L.kt, k)) return vpk_project_rows_lds_row_tiles(I->L.kt);
+        if (vpk_project_gemm_supported(I->L.kt)) return 4;
+    }
     if (!I->wide_items || k > 2 || N <= VP_ROWS_PER_ITEM || I->L.kt % 16 != 0) return 1;
     return vpk_project_lds_bytes(I->L.kt, k, 2) <= LDS_LIMIT / 2 ? 2 : 1;
 }
@@ -295,20 +300,45 @@ int single_bucket_row_tiles(const vp_index *I, int N, int k)
 // Item count bounds (target, minimum) of a single-bucket plan with this many row tiles.
 inline bool use_gemm_lds(const vp_index *I, int row_tiles, int k)
 {
-    return row_tiles == 4 && I->gemm_lds && vpk_project_rows_lds_supported(I->L.kt, k);
+    return row_tiles >= 3 && I->gemm_lds && vpk_project_rows_lds_supported(I->L.kt, k) &&
+           row_tiles == vpk_project_rows_lds_row_tiles(I->L.kt);
 }
-inline int sb_target(const vp_index *I, int row_tiles, int k)
+// The kernel that keeps an item's rows in LDS runs one workgroup per compute unit, so its plan
+// should fill whole rounds of the chip: row groups x candidate ranges as close below a multiple of
+// the compute units as up to eight rounds allow (4,096 rows of d = 1,536 are 86 row groups: three
+// ranges each would be 258 items, a second round for two of them; 23 ranges are 7.7 rounds).
+inline int gemm_lds_item_count(const vp_index *I, int N, int row_tiles)
 {
-    return use_gemm_lds(I, row_tiles, k) ? I->gemm_lds_items : row_tiles == 4 ? I->gemm_target_items : I->full_target_items;
+    const int rgs = ceil_div(N, VP_ROWS_PER_ITEM * row_tiles);
+    const int slots = std::max(1, I->gemm_lds_items);
+    int best = rgs;   // one range per row group at the least
+    double best_fill = 0.0;
+    for (int rounds = 1; rounds <= 8; ++rounds) {
+        const int ranges = (int)std::min<long>((long)rounds * slots / rgs, I->L.vtiles);
+        if (ranges < 1) continue;
+        const double fill = (double)rgs * ranges / ((double)ceil_div((long)rgs * ranges, slots) * slots);
+        if (fill > best_fill + 1e-9) {
+            best_fill = fill;
+            best = rgs * ranges;
+        }
+        if (fill > 0.97) break;
+    }
+    return best;
 }
-inline int sb_min(const vp_index *I, int row_tiles, int k)
+inline int sb_target(const vp_index *I, int N, int row_tiles, int k)
 {
-    return use_gemm_lds(I, row_tiles, k) ? I->gemm_lds_items : row_tiles == 4 ? I->gemm_target_items : I->min_items;
+    return use_gemm_lds(I, row_tiles, k) ? gemm_lds_item_count(I, N, row_tiles)
+                                         : row_tiles >= 3 ? I->gemm_target_items : I->full_target_items;
+}
+inline int sb_min(const vp_index *I, int N, int row_tiles, int k)
+{
+    return use_gemm_lds(I, row_tiles, k) ? gemm_lds_item_count(I, N, row_tiles)
+                                         : row_tiles >= 3 ? I->gemm_target_items : I->min_items;
 }
 // candidate tiles per wavefront of a single-bucket plan (the split the planning kernels make)
-inline int sb_tiles_per_wave(const vp_index *I, int rgs, int row_tiles, int k)
+inline int sb_tiles_per_wave(const vp_index *I, int N, int rgs, int row_tiles, int k)
 {
-    return vp_tiles_per_wave((long long)rgs * I->L.vtiles, sb_target(I, row_tiles, k), sb_min(I, row_tiles, k));
+    return vp_tiles_per_wave((long long)rgs * I->L.vtiles, sb_target(I, N, row_tiles, k), sb_min(I, N, row_tiles, k));
 }
 
 // Launches the projection kernel that goes with the plan's rows per item.
@@ -365,7 +395,8 @@ vp_status run_clustered(const char *fn, const vp_index *I, const void *hidden, i
     const int max_items = max_items_clustered(I, N);
     // the debug entry lays its logits out per cluster list, so it always takes the slabs
     // with dispatch: rows per item of the masked full projection the planner may choose
-    const int rt_masked = single_bucket_row_tiles(I, N, VP_MAX_TOPK) == 4 ? 4 : 1;
+    const int rt_single = single_bucket_row_tiles(I, N, VP_MAX_TOPK);
+    const int rt_masked = rt_single >= 3 ? rt_single : 1;
     int dispatch = (I->dispatch && !dbg_logits) ? VP_ROWS_PER_ITEM * rt_masked : 0;
     const int max_full = max_items_full(I, N);
     // the tile counts of the cost model are in tiles of kt KiB: fold that into the constants
@@ -374,7 +405,7 @@ vp_status run_clustered(const char *fn, const vp_index *I, const void *hidden, i
     cost.bw_slab /= tile_bytes;
     cost.bw_full /= tile_bytes;
     cost.bw_l2 /= tile_bytes;
-    if (rt_masked == 4 && !use_gemm_lds(I, rt_masked, k)) cost.bw_gemm = cost.bw_gemm_split;
+    if (rt_masked >= 3 && !use_gemm_lds(I, rt_masked, k)) cost.bw_gemm = cost.bw_gemm_split;
     cost.bw_gemm /= tile_bytes;
     const long row_groups = (long)row_tiles + std::min(N, I->K);
     const long by_tiles = row_groups * ceil_div(I->L.max_tiles, VP_WG_WAVES);
@@ -390,7 +421,7 @@ vp_status run_clustered(const char *fn, const vp_index *I, const void *hidden, i
         const float total = occ + (float)row_tiles * I->L.max_tiles;
         const float t_slab = occ / cost.bw_slab + (total - occ) / cost.bw_l2 + N * cost.t_row_slab;
         const int rgs_full = ceil_div(N, dispatch);
-        const float t_full = dispatch == 64
+        const float t_full = dispatch >= 48
             ? std::max(I->L.vtiles / cost.bw_full, rgs_full * (I->L.vtiles / cost.bw_gemm)) * (1.f + k * 0.0125f)
             : std::max(I->L.vtiles / cost.bw_full, (float)rgs_full * I->L.vtiles / cost.bw_l2) * (1.f + k * 0.125f);
         if (t_slab <= t_full) dispatch = 0;
@@ -436,7 +467,7 @@ vp_status run_clustered(const char *fn, const vp_index *I, const void *hidden, i
     const int parts = launch_eq2(I, hidden, N, cpart, st);
     vpk_plan(cpart, parts, N, I->K, I->clusters.n_cand, I->clusters.tile_off, I->target_items, I->min_items, max_items, g,
              out_cluster, perm, rowplan, floors, items, hdr, dbg_row_off, dispatch, cost, k, I->V, I->L.vtiles,
-             sb_target(I, rt_masked, k), sb_min(I, rt_masked, k), max_full, st);
+             sb_target(I, N, rt_masked, k), sb_min(I, N, rt_masked, k), max_full, st);
 
     auto *ev = profile_slot(I);
     if (ev) (void)hipEventRecord(ev->first, st);
@@ -451,7 +482,7 @@ vp_status run_clustered(const char *fn, const vp_index *I, const void *hidden, i
     if (dispatch) {
         // launched as well; exactly one of the two does the work, as the planner decided
         const int rgs = ceil_div(N, dispatch);
-        const int tpw = sb_tiles_per_wave(I, rgs, rt_masked, k);
+        const int tpw = sb_tiles_per_wave(I, N, rgs, rt_masked, k);
         const int chunks = ceil_div(I->L.vtiles, (long)tpw * VP_WG_WAVES);
         const int grid_full = (rgs > 1 && chunks >= 8) ? ceil_div(chunks, 8) * 8 * rgs : chunks * rgs;
         const VpMaskInfo mask = {g, I->bitmaps, I->L.bm_words};
@@ -483,12 +514,12 @@ vp_status run_full(const char *fn, const vp_index *I, const void *hidden, int N,
     const int row_tiles = dbg_logits ? 1 : single_bucket_row_tiles(I, N, k);
     const int rpi = VP_ROWS_PER_ITEM * row_tiles;
     const int max_items = max_items_full(I, N);
-    vpk_plan_full(N, I->V, I->L.vtiles, rpi, sb_target(I, row_tiles, k), sb_min(I, row_tiles, k), max_items, perm, rowplan,
+    vpk_plan_full(N, I->V, I->L.vtiles, rpi, sb_target(I, N, row_tiles, k), sb_min(I, N, row_tiles, k), max_items, perm, rowplan,
                   floors, items, hdr, dbg_row_off, st);
     // the same split the planning kernel makes; with several row groups the projection kernel
     // deals candidate ranges to the XCDs, which needs the grid padded to 8 ranges at a time
     const int rgs = ceil_div(N, rpi);
-    const int tpw = sb_tiles_per_wave(I, rgs, row_tiles, k);
+    const int tpw = sb_tiles_per_wave(I, N, rgs, row_tiles, k);
     const int chunks = ceil_div(I->L.vtiles, (long)tpw * VP_WG_WAVES);
     const int grid_items = (rgs > 1 && chunks >= 8) ? ceil_div(chunks, 8) * 8 * rgs : chunks * rgs;
     auto *ev = profile_slot(I);
@@ -945,12 +976,12 @@ vp_status vp_project_union(const vp_index *I, const void *hidden, int32_t N, int
     const int max_items = max_items_full(I, N);
     const int row_tiles_u = single_bucket_row_tiles(I, N, k);
     // the masked full projection exists for items of 16 and of 64 rows
-    int allow_full = I->union_dispatch && (row_tiles_u == 1 || row_tiles_u == 4);
+    int allow_full = I->union_dispatch && (row_tiles_u == 1 || row_tiles_u >= 3);
     VpCostModel cost = I->cost;
     const float tile_bytes = (float)I->L.kt * VP_TILE_BYTES;
     cost.bw_full /= tile_bytes;
     cost.bw_l2 /= tile_bytes;
-    if (row_tiles_u == 4 && !use_gemm_lds(I, row_tiles_u, k)) cost.bw_gemm = cost.bw_gemm_split;
+    if (row_tiles_u >= 3 && !use_gemm_lds(I, row_tiles_u, k)) cost.bw_gemm = cost.bw_gemm_split;
     cost.bw_gemm /= tile_bytes;
     cost.bw_gather /= tile_bytes;
     if (allow_full) {
@@ -958,13 +989,13 @@ vp_status vp_project_union(const vp_index *I, const void *hidden, int32_t N, int
         // batch can have (every row in a cluster of its own with the longest list): then it is not launched
         const int rpi_u = VP_ROWS_PER_ITEM * row_tiles_u;
         const int rgs_u = ceil_div(N, rpi_u);
-        const float per_group = rpi_u >= 64 ? std::max(1.f / cost.bw_full, rgs_u / cost.bw_gemm) * (1.f + k * 0.0125f)
+        const float per_group = rpi_u >= 48 ? std::max(1.f / cost.bw_full, rgs_u / cost.bw_gemm) * (1.f + k * 0.0125f)
                                             : std::max(1.f / cost.bw_full, rgs_u / cost.bw_l2) * (1.f + k * 0.125f);
         const long u_max = std::min<long>(I->V, (long)std::min(N, I->K) * I->L.n_max);
         const float tiles_max = (float)ceil_div(u_max, VP_TILE_ITEMS);
         if (cost.t_gather + tiles_max * (1.f / cost.bw_gather + per_group) <= I->L.vtiles * per_group) allow_full = 0;
     }
-    vpk_union_compact(mask, U.mask_words, bsum, N, VP_ROWS_PER_ITEM * row_tiles_u, sb_target(I, row_tiles_u, k), sb_min(I, row_tiles_u, k), max_items, uids, uh,
+    vpk_union_compact(mask, U.mask_words, bsum, N, VP_ROWS_PER_ITEM * row_tiles_u, sb_target(I, N, row_tiles_u, k), sb_min(I, N, row_tiles_u, k), max_items, uids, uh,
                       out_union_size, perm, rowplan, floors, items, hdr, allow_full, I->V, I->L.vtiles, k, cost, max_items, I->full.bias, ubias, st);
     // step 3: the reduced weight matrix and Eq. 1 over it; steps 4-5 fused (no [N, V] array).  With
     // 64-row items on the rows-in-LDS kernel the columns of U are read where they lie, through U,
@@ -988,7 +1019,7 @@ vp_status vp_project_union(const vp_index *I, const void *hidden, int32_t N, int
     }
     if (allow_full) {
         // launched as well; exactly one of the two does the work, as the planner decided
-        const int tpw = sb_tiles_per_wave(I, rgs, row_tiles_u, k);
+        const int tpw = sb_tiles_per_wave(I, N, rgs, row_tiles_u, k);
         const int chunks = ceil_div(I->L.vtiles, (long)tpw * VP_WG_WAVES);
         const int grid_full = (rgs > 1 && chunks >= 8) ? ceil_div(chunks, 8) * 8 * rgs : chunks * rgs;
         const VpMaskInfo umask = {zero_g, mask, 0};   // every row reads list 0: the boolean list of the batch

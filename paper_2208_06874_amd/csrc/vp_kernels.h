@@ -62,6 +62,7 @@ void vpk_project_gemm(const VpSlabSet &set, const void *hidden, int d, const int
 // the same with the 64 rows of an item held in LDS (d_pad <= 1024, k <= 8); floors: [N] per-row bounds
 size_t vpk_project_rows_lds_bytes(int k, int kt);
 bool vpk_project_rows_lds_supported(int kt, int k);
+int vpk_project_rows_lds_row_tiles(int kt);
 hipError_t vpk_project_rows_lds_prepare();
 void vpk_project_rows_lds(const VpSlabSet &set, const void *hidden, int d, const int32_t *perm, const VpItem *items,
                           const VpPlanHeader *hdr, int grid_items, int k, float *partials, unsigned int *floors,
