@@ -127,10 +127,11 @@ vp_status vp_get_info(const vp_index *idx, vp_index_info *info);
  *                   use the kernel with 64 rows per work item from this many rows on
  *                   (default 17; 0: never); d_pad must be 256, 512, 1024, 1536 or 2048
  *   "gemm_target_items"  work items of that kernel (default 512)
- *   "gemm_lds"      1 (default): up to d_pad = 1024 those items run on the kernel that keeps
- *                   their 64 rows in LDS (no split of the k-extent; one lock-free top-k
- *                   list per row and workgroup); 0: the split-k kernel everywhere
- *   "gemm_lds_items"  work items of that kernel (default: one per compute unit)
+ *   "gemm_lds"      1 (default): up to d_pad = 1536 those items run on the kernel that keeps
+ *                   their rows in LDS (64 rows, 48 at d_pad = 1536; no split of the k-extent;
+ *                   one lock-free top-k list per row and workgroup); 0: the split-k kernel
+ *                   everywhere
+ *   "gemm_lds_items"  work items of that kernel per round (default: one per compute unit)
  *   "wide_items"    1 (default): below gemm_min_rows, vp_project_full / vp_project_union
  *                   of more than 16 rows with k <= 2 put 32 rows in an item; 0: always 16
  *   "small_path"    1 (default): batches of at most 16 rows run without a planning kernel;
