@@ -672,13 +672,17 @@ def test_shared_workspace_and_side_stream(oracle, mid):
             assert np.array_equal(pu.to_np(g[1]), w[1]), (N, kind)
 
 
-@pytest.mark.parametrize("d", [1536, 2048])
-def test_many_row_kernel_with_eight_k_slices(oracle, d):
-    """Beyond d = 1024 the 64-row kernel splits the k-extent over eight wavefronts."""
+@pytest.mark.parametrize("d,gemm_lds", [(1536, 0), (2048, 1), (1536, 1)])
+def test_many_row_kernels_beyond_d_1024(oracle, d, gemm_lds):
+    """Beyond d = 1024: the split-k kernel with eight wavefronts (d = 2048, or d = 1536 with the other kernel
+    switched off), and at d = 1536 the kernel with the rows in LDS, 48 rows per item (ragged row counts around
+    multiples of 48, top-1 to top-32)."""
     r, W, b, C = _small_model(16 + d, d, 1200, 4)
     off, ids = _random_lists(r, 4, 1200, 100, 500)
-    B = Built(W, b, C, off, ids, k_max=8)
-    for N, k in ((40, 3), (150, 8)):
+    B = Built(W, b, C, off, ids, k_max=32)
+    B.index.set_option("gemm_lds", gemm_lds)
+    cases = ((40, 3), (150, 8)) if not (d == 1536 and gemm_lds) else ((17, 1), (48, 8), (49, 32), (97, 2), (150, 8))
+    for N, k in cases:
         H = _rows(r, C, N)
         f_ids, f_logp = B.project_full(H, k)
         print("eight slices full", d, N, pu.check_full(oracle, W, b, H, k, f_ids, f_logp))
@@ -1022,7 +1026,7 @@ def _masked(B, H, k, force=True):
 
 def test_every_form_on_the_large_and_skewed_indexes(oracle, large, skewed):
     """The masked full projection and the batch-union form at the sizes the benchmark runs them: N = 256 on the
-    large index (items of 64 rows, rows in LDS) and N = 4,096 at d = 1,536 (the split-k kernel).  Same token ids
+    large index (items of 64 rows, rows in LDS) and N = 4,096 at d = 1,536 (items of 48 rows).  Same token ids
     as the per-cluster slabs, log-probs within 1e-4 of them, sampled rows against the oracle; the union of 226
     active sets with random top-up ids is the whole vocabulary, so that form must equal the full projection."""
     for B, cfg in ((large, large.cfg), (skewed, skewed.cfg)):
