@@ -1,15 +1,15 @@
 // Projection of many rows against one run of slab tiles with the rows held in LDS: the
 // GEMM-shaped case of Eq. 1 (section 2.1) for single-bucket plans (the full projection, the
 // masked full projection, the batch-union form) of more than 16 rows and k-extents up to
-// d_pad = 1024.
+// d_pad = 1536.
 //
-// An item is 64 rows x a range of candidate groups, one workgroup of eight wavefronts.  The 64
-// rows are staged once in LDS in MFMA operand order (4 row tiles x KT KiB) and never move
-// again.  The range is cut into steps of four candidate groups (64 candidates); wavefront w
+// An item is 64 rows (48 at d_pad = 1536, where 64 do not fit) x a range of candidate groups, one
+// workgroup of eight wavefronts.  The rows are staged once in LDS in MFMA operand order (4 or 3
+// row tiles x KT KiB) and never move again.  The range is cut into steps of four candidate groups (64 candidates); wavefront w
 // takes steps w, w + 8, ...  A step streams the four groups' tiles straight into registers
 // (a ring of four k-tiles ahead, crossing step boundaries, so the loads never drain), and per
-// k-tile feeds each loaded 1 KiB slab tile to four v_mfma_f32_16x16x32_f16, one per row tile,
-// whose row operands are read from LDS (one 1 KiB read per four MFMAs).  No wavefront waits
+// k-tile feeds each loaded 1 KiB slab tile to one v_mfma_f32_16x16x32_f16 per row tile,
+// whose row operands are read from LDS (one 1 KiB read per four MFMAs: four groups per step).  No wavefront waits
 // for another inside the loop: there is no split of the k-extent, so nothing is exchanged and
 // there is no barrier between the staging of the rows and the end of the item.
 //

@@ -105,7 +105,7 @@ struct vp_index {
     int cus;         // compute units of this GPU
     int wide_items;  // 1: single-bucket projections of more than 16 rows use items of 32 rows
     int gemm_target_items;   // work items of the GEMM-shaped kernel: its resident workgroup slots
-    int gemm_lds;        // 1: items of 64 rows use the kernel that holds the rows in LDS where it is built (d_pad <= 1024, k <= 8)
+    int gemm_lds;        // 1: many-row items use the kernel that holds the rows in LDS where it is built (d_pad <= 1536, k <= 32)
     int gemm_lds_items;  // its work items: one per compute unit
     int gemm_min_rows;   // single-bucket projections of at least this many rows use the GEMM-shaped kernel (0: never)
     int dispatch;    // 1: the planner may choose the masked full projection (same results)
@@ -283,8 +283,9 @@ std::pair<hipEvent_t, hipEvent_t> *profile_slot(const vp_index *I)
 
 // Row tiles per item for projections that keep all rows in one bucket (full, masked, union).
 // From gemm_min_rows rows on (default 17: measured faster than two 16-row passes from there): 4,
-// the GEMM-shaped kernel (64 rows per item, every loaded slab tile feeds four MFMAs).  Where
-// that kernel is not built for the k-extent, two row tiles per loaded slab tile pay off
+// the GEMM-shaped kernels (64 rows per item, every loaded slab tile feeds four MFMAs), or 3 where
+// the one that keeps the rows in LDS has room for 48 only.  Where
+// neither is built for the k-extent, two row tiles per loaded slab tile pay off
 // (measured: -10 % at top-1, N = 256) only while the top-k lists are short.
 int single_bucket_row_tiles(const vp_index *I, int N, int k)
 {
@@ -975,7 +976,7 @@ vp_status vp_project_union(const vp_index *I, const void *hidden, int32_t N, int
     vpk_union_mark(cpart, parts, N, I->K, I->bitmaps, I->L.bm_words, U.mask_words, g, out_cluster, zero_g, mask, bsum, st);
     const int max_items = max_items_full(I, N);
     const int row_tiles_u = single_bucket_row_tiles(I, N, k);
-    // the masked full projection exists for items of 16 and of 64 rows
+    // the masked full projection exists for items of 16 rows and of 48 / 64 rows
     int allow_full = I->union_dispatch && (row_tiles_u == 1 || row_tiles_u >= 3);
     VpCostModel cost = I->cost;
     const float tile_bytes = (float)I->L.kt * VP_TILE_BYTES;
@@ -998,7 +999,7 @@ vp_status vp_project_union(const vp_index *I, const void *hidden, int32_t N, int
     vpk_union_compact(mask, U.mask_words, bsum, N, VP_ROWS_PER_ITEM * row_tiles_u, sb_target(I, N, row_tiles_u, k), sb_min(I, N, row_tiles_u, k), max_items, uids, uh,
                       out_union_size, perm, rowplan, floors, items, hdr, allow_full, I->V, I->L.vtiles, k, cost, max_items, I->full.bias, ubias, st);
     // step 3: the reduced weight matrix and Eq. 1 over it; steps 4-5 fused (no [N, V] array).  With
-    // 64-row items on the rows-in-LDS kernel the columns of U are read where they lie, through U,
+    // the items of the rows-in-LDS kernel the columns of U are read where they lie, through U,
     // from the token-major copy of W (the bias of U's tokens was collected with U); otherwise they
     // are first gathered into a packed slab in the workspace.
     const bool fused_gather = use_gemm_lds(I, row_tiles_u, k) && (long)I->V * I->L.kt * 4 < (1L << 31);

@@ -167,8 +167,8 @@ struct VpCostModel {
     float bw_slab;   // slabs streamed once from HBM
     float bw_full;   // one pass over the packed W from HBM
     float bw_l2;     // further passes over tiles already in the L2 (16-row items)
-    float bw_gemm;   // further passes over W by 64-row items of the GEMM-shaped kernel (rows in LDS)
-    float bw_gemm_split;   // the same for the split-k kernel (k-extents beyond d_pad = 1024, k > 32)
+    float bw_gemm;   // further passes over W by the 48- / 64-row items of the GEMM-shaped kernel (rows in LDS)
+    float bw_gemm_split;   // the same for the split-k kernel (k-extents beyond d_pad = 1536, k > 32)
     float bw_gather; // batch-union form: columns of U gathered from the packed W into the union slab
     float t_gather;  // ... and the fixed time of the kernels only that gather needs (seconds)
     float t_row_slab;  // per-cluster slabs: time per row beyond the bytes (staging, lists, partial results; seconds)
