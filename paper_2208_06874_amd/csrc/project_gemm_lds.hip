@@ -49,7 +49,7 @@ __device__ inline bool before_entry(float v, int i, float v2, int i2) { return (
 
 template <int KT, bool MASKED, bool NT, bool TOP1, bool GATHER>
 __device__ inline void gemm_lds_item(const VpSlabSet &set, const uint4 *__restrict__ hidden, int d,
-                                     const int32_t *__restrict__ perm, const VpItem &item, int it, int k,
+                                     const VpItem &item, int it, int k,
                                      float *__restrict__ partials, unsigned int *__restrict__ floors,
                                      const VpMaskInfo &mask)
 {
@@ -98,6 +98,26 @@ __device__ inline void gemm_lds_item(const VpSlabSet &set, const uint4 *__restri
         }
     };
 
+    // The rows of this item -> LDS, MFMA operand order (row slots beyond nrows: zeros).  A
+    // single-bucket plan keeps the rows in their own order: slot r of the item is row perm_start + r.
+    // All of a thread's pieces are fetched in one batch, in front of the first slab loads (loads
+    // return in order: behind them, the rows would wait for bytes from HBM they do not depend on).
+    constexpr int X = KT * 4;   // 16-byte pieces per padded row
+    constexpr int PER = L_ROWS * X / (L_NW * 64);   // pieces per thread
+    static_assert(PER * L_NW * 64 == L_ROWS * X, "the rows' pieces divide evenly over the threads");
+    uint4 piece[PER];
+    {
+        const int pieces_per_row = d >> 3;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int e = tid + i * (L_NW * 64);
+            const int r = e / X;
+            const int x = e - r * X;
+            piece[i] = make_uint4(0, 0, 0, 0);
+            if (r < item.nrows && x < pieces_per_row) piece[i] = hidden[(size_t)(item.perm_start + r) * pieces_per_row + x];
+        }
+    }
+
     uint4 ring[L_PF][L_G];
     unsigned int cur[L_G], nxt[L_G];
     int step = wave;
@@ -110,20 +130,12 @@ __device__ inline void gemm_lds_item(const VpSlabSet &set, const uint4 *__restri
             for (int j = 0; j < L_G; ++j) ring[p][j] = load_piece<NT>(slab + cur[j] + p * KSTEP);
     }
 
-    // the rows of this item -> LDS, MFMA operand order (row slots beyond nrows: zeros)
-    {
-        constexpr int X = KT * 4;   // 16-byte pieces per padded row
-        const int pieces_per_row = d >> 3;
-        for (int e = tid; e < L_ROWS * X; e += L_NW * 64) {
-            const int r = e / X;
-            const int x = e - r * X;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (r < item.nrows && x < pieces_per_row) {
-                const int row = perm[item.perm_start + r];
-                v = hidden[(size_t)row * pieces_per_row + x];
-            }
-            ldsB[((r >> 4) * KT + (x >> 2)) * 64 + (x & 3) * 16 + (r & 15)] = v;
-        }
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        const int e = tid + i * (L_NW * 64);
+        const int r = e / X;
+        const int x = e - r * X;
+        ldsB[((r >> 4) * KT + (x >> 2)) * 64 + (x & 3) * 16 + (r & 15)] = piece[i];
     }
     for (int e = tid; e < k * L_ROWS; e += L_NW * 64) lkey[e] = 0ull;   // below the key of every logit
     // this lane's row in each row tile
@@ -133,12 +145,9 @@ __device__ inline void gemm_lds_item(const VpSlabSet &set, const uint4 *__restri
     for (int rt = 0; rt < L_RT; ++rt) {
         const int slot = rt * 16 + n;
         row_valid[rt] = slot < item.nrows;
-        myrow[rt] = row_valid[rt] ? perm[item.perm_start + slot] : -1;
+        myrow[rt] = row_valid[rt] ? item.perm_start + slot : -1;
     }
-    if (tid < L_ROWS) {
-        const int row = tid < item.nrows ? perm[item.perm_start + tid] : -1;
-        wg_floor[tid] = row >= 0 ? floors[row] : VP_FLOOR_NONE;
-    }
+    if (tid < L_ROWS) wg_floor[tid] = (!TOP1 && tid < item.nrows) ? floors[item.perm_start + tid] : VP_FLOOR_NONE;
     __syncthreads();
 
     // per row tile: running maximum, sum of exponentials, k-th best of this wavefront's list
@@ -383,7 +392,7 @@ __device__ inline void gemm_lds_item(const VpSlabSet &set, const uint4 *__restri
     }
     if (!top1 && tid < item.nrows) {
         const unsigned int kth = (unsigned int)(lkey[(k - 1) * L_ROWS + tid] >> 32);
-        atomicMax(floors + perm[item.perm_start + tid], max(max(kth, wg_floor[tid]), (unsigned int)VP_FLOOR_NONE));
+        atomicMax(floors + item.perm_start + tid, max(max(kth, wg_floor[tid]), (unsigned int)VP_FLOOR_NONE));
     }
     __syncthreads();
 
@@ -412,7 +421,7 @@ __device__ inline void gemm_lds_item(const VpSlabSet &set, const uint4 *__restri
 
 template <int KT, bool MASKED, bool TOP1, bool GATHER>
 __global__ __launch_bounds__(L_NW * 64) void project_gemm_lds_kernel(
-    VpSlabSet set, const uint4 *__restrict__ hidden, int d, const int32_t *__restrict__ perm,
+    VpSlabSet set, const uint4 *__restrict__ hidden, int d,
     const VpItem *__restrict__ items, const VpPlanHeader *__restrict__ hdr, int k,
     float *__restrict__ partials, unsigned int *__restrict__ floors, VpMaskInfo mask)
 {
@@ -422,23 +431,23 @@ __global__ __launch_bounds__(L_NW * 64) void project_gemm_lds_kernel(
     if (it < 0 || it >= total_items) return;
     const VpItem item = items[it];
     if (item.shared || GATHER)
-        gemm_lds_item<KT, MASKED, false, TOP1, GATHER>(set, hidden, d, perm, item, it, TOP1 ? 1 : k, partials, floors, mask);
+        gemm_lds_item<KT, MASKED, false, TOP1, GATHER>(set, hidden, d, item, it, TOP1 ? 1 : k, partials, floors, mask);
     else
-        gemm_lds_item<KT, MASKED, true, TOP1, false>(set, hidden, d, perm, item, it, TOP1 ? 1 : k, partials, floors, mask);
+        gemm_lds_item<KT, MASKED, true, TOP1, false>(set, hidden, d, item, it, TOP1 ? 1 : k, partials, floors, mask);
 }
 
 template <int KT, bool MASKED, bool GATHER>
-void launch_lds(const VpSlabSet &set, const void *hidden, int d, const int32_t *perm, const VpItem *items,
+void launch_lds(const VpSlabSet &set, const void *hidden, int d, const VpItem *items,
                 const VpPlanHeader *hdr, int grid_items, int k, float *partials, unsigned int *floors,
                 const VpMaskInfo &mask, hipStream_t st)
 {
     if (k == 1)
         hipLaunchKernelGGL((project_gemm_lds_kernel<KT, MASKED, true, GATHER>), dim3(grid_items), dim3(L_NW * 64),
-                           vpk_project_rows_lds_bytes(k, KT), st, set, (const uint4 *)hidden, d, perm, items, hdr, k,
+                           vpk_project_rows_lds_bytes(k, KT), st, set, (const uint4 *)hidden, d, items, hdr, k,
                            partials, floors, mask);
     else
         hipLaunchKernelGGL((project_gemm_lds_kernel<KT, MASKED, false, GATHER>), dim3(grid_items), dim3(L_NW * 64),
-                           vpk_project_rows_lds_bytes(k, KT), st, set, (const uint4 *)hidden, d, perm, items, hdr, k,
+                           vpk_project_rows_lds_bytes(k, KT), st, set, (const uint4 *)hidden, d, items, hdr, k,
                            partials, floors, mask);
 }
 
@@ -485,7 +494,8 @@ hipError_t vpk_project_rows_lds_prepare()
 
 // mask: nullptr, or the membership lists of the masked full projection.  gather: the set's tiles
 // are the token-major copy of W and its ids the batch's union U (no mask then); the slab operands
-// are read through U instead of from a packed copy.
+// are read through U instead of from a packed copy.  (perm is not read: a single-bucket plan keeps
+// the rows in their own order.)
 void vpk_project_rows_lds(const VpSlabSet &set, const void *hidden, int d, const int32_t *perm, const VpItem *items,
                           const VpPlanHeader *hdr, int grid_items, int k, float *partials, unsigned int *floors,
                           const VpMaskInfo *mask, bool gather, hipStream_t st)
@@ -493,9 +503,9 @@ void vpk_project_rows_lds(const VpSlabSet &set, const void *hidden, int d, const
     const VpMaskInfo none = {nullptr, nullptr, 0};
 #define VP_LDS_CASE(KT)                                                                                                   \
     case KT:                                                                                                              \
-        if (mask) launch_lds<KT, true, false>(set, hidden, d, perm, items, hdr, grid_items, k, partials, floors, *mask, st); \
-        else if (gather) launch_lds<KT, false, true>(set, hidden, d, perm, items, hdr, grid_items, k, partials, floors, none, st); \
-        else launch_lds<KT, false, false>(set, hidden, d, perm, items, hdr, grid_items, k, partials, floors, none, st);     \
+        if (mask) launch_lds<KT, true, false>(set, hidden, d, items, hdr, grid_items, k, partials, floors, *mask, st); \
+        else if (gather) launch_lds<KT, false, true>(set, hidden, d, items, hdr, grid_items, k, partials, floors, none, st); \
+        else launch_lds<KT, false, false>(set, hidden, d, items, hdr, grid_items, k, partials, floors, none, st);     \
         break;
     switch (set.kt) {
         VP_LDS_CASE(8)
