@@ -101,15 +101,31 @@ __device__ inline void project_item(
     // Stage the item's hidden rows: MFMA operand order, or row-major for the GEMV loop.
     // Row slots beyond nrows are left as they are: an MFMA output column depends on its
     // own operand column only, and those columns are never looked at.
+    // (four pieces per thread are fetched together: a full item's 8 to 12 pieces per thread cost two or
+    // three trips to the L2, not one each)
     {
         const int pieces_per_row = d >> 3;
-        for (int e = tid; e < item.nrows * X; e += VP_WG_THREADS) {
-            const int r = e / X;
-            const int x = e - r * X;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (x < pieces_per_row) v = hidden[(size_t)rowid[r] * pieces_per_row + x];
-            if (gemv) ldsA[r * X + x] = v;
-            else ldsA[((r >> 4) * KT + (x >> 2)) * 64 + (x & 3) * 16 + (r & 15)] = v;
+        const int total = item.nrows * X;
+        for (int e0 = tid; e0 < total; e0 += 4 * VP_WG_THREADS) {
+            uint4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int e = e0 + u * VP_WG_THREADS;
+                const int r = e / X;
+                const int x = e - r * X;
+                v[u] = make_uint4(0, 0, 0, 0);
+                if (e < total && x < pieces_per_row) v[u] = hidden[(size_t)rowid[r] * pieces_per_row + x];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int e = e0 + u * VP_WG_THREADS;
+                const int r = e / X;
+                const int x = e - r * X;
+                if (e < total) {
+                    if (gemv) ldsA[r * X + x] = v[u];
+                    else ldsA[((r >> 4) * KT + (x >> 2)) * 64 + (x & 3) * 16 + (r & 15)] = v[u];
+                }
+            }
         }
     }
     __syncthreads();
