@@ -304,27 +304,11 @@ inline bool use_gemm_lds(const vp_index *I, int row_tiles, int k)
     return row_tiles >= 3 && I->gemm_lds && vpk_project_rows_lds_supported(I->L.kt, k) &&
            row_tiles == vpk_project_rows_lds_row_tiles(I->L.kt);
 }
-// The kernel that keeps an item's rows in LDS runs one workgroup per compute unit, so its plan
-// should fill whole rounds of the chip: row groups x candidate ranges as close below a multiple of
-// the compute units as up to eight rounds allow (4,096 rows of d = 1,536 are 86 row groups: three
-// ranges each would be 258 items, a second round for two of them; 23 ranges are 7.7 rounds).
+// Item count of the kernel that keeps an item's rows in LDS: whole rounds of its one workgroup per
+// compute unit (vp_rounds_item_count).
 inline int gemm_lds_item_count(const vp_index *I, int N, int row_tiles)
 {
-    const int rgs = ceil_div(N, VP_ROWS_PER_ITEM * row_tiles);
-    const int slots = std::max(1, I->gemm_lds_items);
-    int best = rgs;   // one range per row group at the least
-    double best_fill = 0.0;
-    for (int rounds = 1; rounds <= 8; ++rounds) {
-        const int ranges = (int)std::min<long>((long)rounds * slots / rgs, I->L.vtiles);
-        if (ranges < 1) continue;
-        const double fill = (double)rgs * ranges / ((double)ceil_div((long)rgs * ranges, slots) * slots);
-        if (fill > best_fill + 1e-9) {
-            best_fill = fill;
-            best = rgs * ranges;
-        }
-        if (fill > 0.97) break;
-    }
-    return best;
+    return vp_rounds_item_count(ceil_div(N, VP_ROWS_PER_ITEM * row_tiles), I->gemm_lds_items, I->L.vtiles);
 }
 inline int sb_target(const vp_index *I, int N, int row_tiles, int k)
 {

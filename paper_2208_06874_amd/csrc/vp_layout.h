@@ -105,6 +105,32 @@ static inline __host__ __device__ int vp_tiles_per_wave(long long total_tiles, i
     return (int)(tpw > 1 ? tpw : 1);
 }
 
+// Items of a single-bucket plan for the kernel that keeps an item's rows in LDS and runs one
+// workgroup per compute unit (`slots` at a time): row groups x candidate ranges as close below a
+// multiple of the slots as up to eight rounds allow, so that no round is left nearly empty (86 row
+// groups on 256 slots: three ranges each would be 258 items, a second round for two of them; 23
+// ranges are 7.7 rounds).  At least one range per row group.
+static inline __host__ __device__ int vp_rounds_item_count(int rgs, int slots, int vtiles)
+{
+    if (slots < 1) slots = 1;
+    int best = rgs;
+    double best_fill = 0.0;
+    for (int rounds = 1; rounds <= 8; ++rounds) {
+        long long ranges = (long long)rounds * slots / rgs;
+        if (ranges > vtiles) ranges = vtiles;
+        if (ranges < 1) continue;
+        const long long items = (long long)rgs * ranges;
+        const long long full = (items + slots - 1) / slots * slots;
+        const double fill = (double)items / (double)full;
+        if (fill > best_fill + 1e-9) {
+            best_fill = fill;
+            best = (int)items;
+        }
+        if (fill > 0.97) break;
+    }
+    return best;
+}
+
 // The same for the clustered plan, which also knows its number of (bucket, row group) units:
 // every unit ends with a partly filled item, so the plan has at most total / (4 tpw) + units
 // items.  When that lies between one and two times the resident workgroup slots (min_items),

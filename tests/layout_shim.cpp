@@ -22,3 +22,4 @@ extern "C" int shim_item_of_workgroup(int wg, int total_items, int swz_rgs, int 
     return vp_item_of_workgroup(wg, total_items, swz_rgs, swz_chunks);
 }
 extern "C" int shim_xcd_block_items(void) { return VP_XCD_BLOCK_ITEMS; }
+extern "C" int shim_rounds_item_count(int rgs, int slots, int vtiles) { return vp_rounds_item_count(rgs, slots, vtiles); }

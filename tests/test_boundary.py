@@ -220,6 +220,38 @@ def test_item_sizing_rules(layout):
                     assert -(-total // (4 * t2)) + units <= min_items + 1
 
 
+def test_round_filling_item_count_of_the_many_row_kernel(layout):
+    """Items of the kernel that runs one workgroup per compute unit: a whole number of candidate ranges per
+    row group, at least one; at most eight rounds of the slots (unless there are more row groups than that);
+    the plan the planning kernels then make (tiles per wavefront from that count) has no more items than
+    asked for; and no choice of fewer rounds would have filled its rounds better."""
+    r = np.random.default_rng(9)
+    cases = [(1, 256, 15625), (4, 256, 15625), (16, 256, 15625), (86, 256, 15625), (6, 256, 15625), (1024, 256, 15625),
+             (3000, 256, 15625), (5, 256, 3), (86, 304, 8000)]
+    cases += [(int(a), int(b), int(c)) for a, b, c in zip(r.integers(1, 1500, 200), r.choice([64, 104, 256, 304], 200),
+                                                           r.integers(1, 40000, 200))]
+    for rgs, slots, vtiles in cases:
+        items = layout.shim_rounds_item_count(rgs, slots, vtiles)
+        assert items >= rgs and items % rgs == 0
+        ranges = items // rgs
+        assert ranges <= max(1, vtiles)
+        assert items <= 8 * slots or ranges == 1
+        # what the planning kernels make of it: ranges of 4 * tpw tiles
+        tpw = layout.shim_tiles_per_wave(rgs * vtiles, items, items)
+        chunks = -(-vtiles // (4 * tpw))
+        assert chunks * rgs <= items
+        fill = items / (-(-items // slots) * slots)
+        for rounds in range(1, 9):
+            rg2 = min(rounds * slots // rgs, vtiles)
+            if rg2 < 1:
+                continue
+            it2 = rgs * rg2
+            f2 = it2 / (-(-it2 // slots) * slots)
+            assert f2 <= fill + 1e-9 or fill > 0.97, (rgs, slots, vtiles, items, rounds)
+            if f2 > 0.97:
+                break
+
+
 def test_short_items_bound_of_the_raw_logit_form(layout):
     """The host considers raw logits only for calls of at most 8,192 candidate tiles.  With the default
     sizing (8,192 items asked for, 1,024 workgroup slots) such a plan has at most VP_RAW_TILES tiles per
